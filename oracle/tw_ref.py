@@ -1,0 +1,146 @@
+"""Python side of the CPU oracle (TEST INFRASTRUCTURE ONLY, never on the product path).
+
+* ``masked_gemm``      - ctypes call into ``tw_oracle.c`` (fp64 masked product, the definition).
+* ``tile_structure``   - the TW format's integer side written out from the paper's description
+                         (Sec. IV-A): column pruning first, surviving columns re-grouped G at a
+                         time, each group keeping its own ascending list of K rows; a tile owns
+                         the stretch of original columns up to the next tile's first column
+                         (the "G+4, G+3, G+2, G-9" stretches of the worked example).
+* ``masked_weight_bits`` - what pack -> unpack must give back: B where kept, +0 elsewhere.
+
+Nothing here imports the HIP package, and the HIP package imports nothing from here.
+Parity status: pinned by tests/test_oracle_pins.py and tests/test_tile_structure_pins.py.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tw_oracle.c")
+_LIB = os.path.join(_HERE, "libtw_oracle.so")
+_DT = {"f16": 0, "bf16": 1}
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no fast-math, no FMA contraction: the sum is the plain one)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        lib.two_masked_gemm.restype = ctypes.c_int
+        lib.two_masked_gemm.argtypes = [u16p, ctypes.c_long, u16p, ctypes.c_long,
+                                        ctypes.POINTER(ctypes.c_uint8), ctypes.c_long, ctypes.c_long,
+                                        ctypes.c_long, ctypes.c_int,
+                                        ctypes.POINTER(ctypes.c_double), ctypes.c_long]
+        lib.two_decode.restype = ctypes.c_int
+        lib.two_decode.argtypes = [u16p, ctypes.c_long, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+        lib.two_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().two_num_threads())
+
+
+def decode(bits: np.ndarray, dtype: str) -> np.ndarray:
+    """16-bit patterns -> float64 through the oracle's own decoder."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.empty(b.shape, dtype=np.float64)
+    rc = _load().two_decode(b.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), b.size, _DT[dtype],
+                            out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    if rc != 0:
+        raise RuntimeError("two_decode failed")
+    return out
+
+
+def masked_gemm(A_bits: np.ndarray, B_bits: np.ndarray, mask: np.ndarray, dtype: str) -> np.ndarray:
+    """C = A . (B * mask) in fp64 from 16-bit inputs.  A [M,K] (row stride may exceed K), B [K,N], mask [K,N]."""
+    assert A_bits.dtype == np.uint16 and B_bits.dtype == np.uint16
+    assert A_bits.ndim == 2 and B_bits.ndim == 2 and mask.shape == B_bits.shape
+    assert A_bits.strides[1] == 2 and B_bits.strides[1] == 2
+    M, K = A_bits.shape
+    K2, N = B_bits.shape
+    assert K == K2
+    lda = A_bits.strides[0] // 2 if M > 1 else K
+    ldb = B_bits.strides[0] // 2 if K > 1 else N
+    mk = np.ascontiguousarray(mask, dtype=np.uint8)
+    C = np.empty((M, N), dtype=np.float64)
+    rc = _load().two_masked_gemm(
+        A_bits.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), lda,
+        B_bits.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), ldb,
+        mk.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), M, K, N, _DT[dtype],
+        C.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), N)
+    if rc != 0:
+        raise RuntimeError(f"two_masked_gemm failed: {rc}")
+    return C
+
+
+class NotTileWise(ValueError):
+    pass
+
+
+def tile_structure(mask: np.ndarray, G: int) -> Dict[str, np.ndarray]:
+    """Integer description of a TW mask.
+
+    1. A column survives iff it keeps at least one weight (column pruning comes first).
+    2. Surviving columns, ascending, are swept left to right; a tile is closed when it holds G
+       columns or when the next column keeps a different set of rows.
+    3. Tile t keeps the ascending rows of that shared set; it owns original columns
+       [span[t], span[t+1]) with span[0] = 0, span[t] = its first column, span[T] = N.
+    4. More than 2*ceil(N/G) tiles means the mask is not tile-wise for this G.
+    """
+    mask = np.asarray(mask)
+    K, N = mask.shape
+    m = mask != 0
+    col_idx = np.flatnonzero(m.any(axis=0)).astype(np.int32)
+    tile_col_ptr = [0]
+    rows = []
+    i = 0
+    while i < len(col_idx):
+        pat = m[:, col_idx[i]]
+        j = i + 1
+        while j < len(col_idx) and j - i < G and np.array_equal(m[:, col_idx[j]], pat):
+            j += 1
+        rows.append(np.flatnonzero(pat).astype(np.int32))
+        tile_col_ptr.append(j)
+        i = j
+    T = len(rows)
+    if T > 2 * ((N + G - 1) // G):
+        raise NotTileWise(f"{T} tiles for N={N}, G={G}")
+    tile_row_ptr = np.zeros(T + 1, dtype=np.int32)
+    for t, r in enumerate(rows):
+        tile_row_ptr[t + 1] = tile_row_ptr[t] + len(r)
+    span = np.zeros(T + 1, dtype=np.int32)
+    for t in range(1, T):
+        span[t] = col_idx[tile_col_ptr[t]]
+    span[T] = N if T > 0 else 0
+    return dict(
+        K=K, N=N, G=G, T=T,
+        col_idx=col_idx,
+        tile_col_ptr=np.asarray(tile_col_ptr, dtype=np.int32),
+        tile_row_ptr=tile_row_ptr,
+        row_idx=(np.concatenate(rows).astype(np.int32) if rows else np.zeros(0, np.int32)),
+        tile_span=span,
+        nnz=int(m.sum()),
+    )
+
+
+def masked_weight_bits(B_bits: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """B where the mask keeps it, the +0 pattern elsewhere."""
+    return np.where(np.asarray(mask) != 0, B_bits, np.uint16(0)).astype(np.uint16)
