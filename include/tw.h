@@ -1,0 +1,131 @@
+/*
+ * libtw - tile-wise (TW) sparse GEMM for AMD MI355X (gfx950).  C ABI.
+ *
+ * The operation (paper Sec. IV-A and Sec. VI): a weight matrix B (K x N) is cut into column tiles
+ * of granularity G; whole columns may be pruned first, the surviving columns are re-grouped G at
+ * a time, and every tile then keeps its own subset of the K rows.  With M the 0/1 mask of kept
+ * weights the product is
+ *
+ *        C (M x N)  =  A (M x K) . (B * mask)
+ *
+ * which runs as one reduced-K dense GEMM per tile over the activation columns that tile keeps
+ * (Fig. 4 step 4).  A and C stay dense (Sec. VI "Tiling"); B is compacted offline.
+ *
+ * Conventions
+ *   - All matrices are row-major; ld* are row strides in ELEMENTS.  Elements of A, B, C are
+ *     16-bit: IEEE binary16 (TW_F16) or bfloat16 (TW_BF16).  Products are accumulated in fp32
+ *     and rounded to nearest-even once, at the store.
+ *   - "host" pointers are ordinary memory, "device" pointers are HIP device memory of the
+ *     current device.  The library never allocates or frees device memory and never
+ *     synchronises: every device call only enqueues work on the given stream.
+ *   - Every function returns TW_OK (0) or a negative tw_status; on error nothing is written
+ *     to output buffers and nothing is enqueued.  No exceptions cross the boundary.
+ *   - The packed weight is one relocatable byte blob (offsets, no pointers).  The same bytes
+ *     are used on the host (launch parameters, tw_info, tw_unpack) and, copied by the caller,
+ *     on the device.  Alignment of a blob buffer: 256 bytes on the device, 16 on the host.
+ *   - Functions are thread-safe; the library keeps no mutable global state apart from the
+ *     per-device kernel attributes it sets once.
+ *   - Non-finite activations at positions a tile does NOT keep never reach the result (they
+ *     are skipped, not multiplied by zero).
+ */
+#ifndef TW_H_
+#define TW_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { TW_F16 = 0, TW_BF16 = 1 } tw_dtype;
+
+typedef enum {
+    TW_OK = 0,
+    TW_ERR_ARG = -1,           /* null pointer, non-positive size, ld too small, unknown dtype   */
+    TW_ERR_NOT_TILEWISE = -2,  /* the mask needs more than 2*ceil(N/G) tiles                     */
+    TW_ERR_BUF = -3,           /* blob / workspace buffer too small, or not a blob               */
+    TW_ERR_ALIGN = -4,         /* pointer or ld not aligned as required                          */
+    TW_ERR_HIP = -5,           /* a HIP runtime call failed                                      */
+    TW_ERR_UNSUPPORTED = -6    /* granularity or shape the kernels do not cover                  */
+} tw_status;
+
+/* Description of a packed weight.  The off_* members are byte offsets from the start of the blob
+ * to int32 arrays in canonical form (exactly one correct value each):
+ *   col_idx[n_kept_cols]  original index of every surviving column, ascending
+ *   tile_col_ptr[T+1]     tile t holds surviving columns [tile_col_ptr[t], tile_col_ptr[t+1])
+ *   tile_row_ptr[T+1]     tile t keeps rows row_idx[tile_row_ptr[t] .. tile_row_ptr[t+1])
+ *   row_idx[sum k_t]      kept K rows of every tile, ascending within the tile
+ *   tile_span[T+1]        tile t owns original columns [tile_span[t], tile_span[t+1]); pruned
+ *                         columns inside are written as zeros by tw_gemm (tile_span[0] = 0,
+ *                         tile_span[T] = N; a single 0 when T = 0)
+ *   sched_order[T]        tiles by kept rows, descending (stable): the load-balancing order  */
+typedef struct tw_info_t {
+    int32_t version;
+    int32_t dtype;
+    int32_t K, N, G, T;
+    int32_t n_kept_cols;
+    int32_t k_chunk;           /* K rows of A staged in LDS at a time by tw_gemm                  */
+    int64_t nnz;               /* kept weights                                                   */
+    int64_t padded_macs_per_row; /* multiply-adds per row of A the kernel really issues (>= nnz)  */
+    uint64_t blob_bytes;
+    uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
+             off_sched_order;
+} tw_info_t;
+
+/* ---- host side, offline (Sec. VI "Tiling": pruned rows/columns of B are removed before inference) ---- */
+
+/* Size in bytes of the blob tw_pack would write for this mask.
+ * mask: host, K x N bytes, row-major, N per row; nonzero = kept.  G: tile granularity (32, 64 or 128).
+ * Tiling rule (Sec. IV-A "Pruning Order"): a column survives iff it keeps a weight; surviving
+ * columns, ascending, are swept left to right and a tile is closed when it has G columns or when
+ * the next column keeps a different set of rows.  TW_ERR_NOT_TILEWISE if that gives more than
+ * 2*ceil(N/G) tiles. */
+int tw_pack_size(const uint8_t* mask, int K, int N, int G, tw_dtype dt, size_t* blob_bytes);
+
+/* Build the blob: per-tile kept-row lists, compacted 16-bit tiles (bit-exact copies of the kept
+ * weights, laid out for the MFMA operand loads), gather tables and the kept-K-sorted schedule.
+ * B: host, K x N elements of type dt, row-major, ldb >= N.  blob: host buffer of blob_bytes
+ * (>= tw_pack_size), 16-byte aligned, owned by the caller. */
+int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N, int G, tw_dtype dt,
+            void* blob, size_t blob_bytes);
+
+/* Inverse of tw_pack, bit-exact: B_out (host, K x N, ldb) receives the kept weights and +0 at
+ * pruned positions; mask_out (host, K x N bytes) receives 1/0.  Either output may be NULL. */
+int tw_unpack(const void* blob, void* B_out, int ldb, uint8_t* mask_out);
+
+/* Fill *out from a host blob. */
+int tw_info(const void* blob, tw_info_t* out);
+
+/* ---- device side ---- */
+
+/* Bytes of device workspace tw_gemm needs for M rows (scheduler counters).  The workspace must be
+ * zero before its first use; tw_gemm leaves it zero when the enqueued work has finished, so one
+ * zeroed buffer serves any number of calls that do not overlap in time. */
+int tw_gemm_workspace(const void* blob_host, int M, size_t* ws_bytes);
+
+/* C = A . (B * mask) (Sec. VI, Listing 1's role).  Enqueues on `hip_stream` (a hipStream_t, may be
+ * NULL for the default stream) and returns.
+ *   blob_host  host copy of the blob (read during the call only)
+ *   blob_dev   device copy of the same bytes, 256-byte aligned
+ *   A          device, M x K, lda >= K, lda % 8 == 0, 16-byte aligned base
+ *   C          device, M x N, ldc >= N; EVERY element of C[0:M, 0:N] is written (zeros in pruned
+ *              columns); 2-byte aligned rows suffice
+ *   workspace  device, >= tw_gemm_workspace bytes, 256-byte aligned, zeroed as described above
+ * M >= 0 (M = 0 enqueues nothing). */
+int tw_gemm(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
+            void* C, int ldc, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* Dense reference C = A . B on the same MFMA pipeline (the paper's dense baseline, Sec. VI
+ * "Tiling" / Sec. VII-A).  A: device M x K (lda % 8 == 0), B: device K x N row-major
+ * (ldb % 8 == 0), C: device M x N (ldc % 8 == 0); bases 16-byte aligned. */
+int tw_dense_gemm(const void* A, int lda, const void* B, int ldb, void* C, int ldc,
+                  int M, int N, int K, tw_dtype dt, void* hip_stream);
+
+const char* tw_strerror(int status);
+int tw_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TW_H_ */

@@ -1,0 +1,229 @@
+"""ctypes binding of the C-ABI library ``libtw.so`` (see ``include/tw.h``).
+
+Argument marshalling only: every step of the path (tiling analysis, compaction, schedule,
+the GEMMs) runs inside the library.  PyTorch appears here solely as the owner of device
+memory and streams.  Importing this module without a built library raises; there is no
+fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtw.so")
+
+TW_F16, TW_BF16 = 0, 1
+_DT = {"f16": TW_F16, "bf16": TW_BF16}
+
+SYMBOLS = ["tw_pack_size", "tw_pack", "tw_unpack", "tw_info", "tw_gemm_workspace", "tw_gemm",
+           "tw_dense_gemm", "tw_strerror", "tw_version"]
+
+
+class TwError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {_strerror(status)} ({status})")
+
+
+class TwInfo(ctypes.Structure):
+    _fields_ = [("version", ctypes.c_int32), ("dtype", ctypes.c_int32), ("K", ctypes.c_int32),
+                ("N", ctypes.c_int32), ("G", ctypes.c_int32), ("T", ctypes.c_int32),
+                ("n_kept_cols", ctypes.c_int32), ("k_chunk", ctypes.c_int32),
+                ("nnz", ctypes.c_int64), ("padded_macs_per_row", ctypes.c_int64),
+                ("blob_bytes", ctypes.c_uint64),
+                ("off_col_idx", ctypes.c_uint64), ("off_tile_col_ptr", ctypes.c_uint64),
+                ("off_tile_row_ptr", ctypes.c_uint64), ("off_row_idx", ctypes.c_uint64),
+                ("off_tile_span", ctypes.c_uint64), ("off_sched_order", ctypes.c_uint64)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(hipcc, gfx950) first; there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    lib.tw_pack_size.argtypes = [vp, i, i, i, i, ctypes.POINTER(sz)]
+    lib.tw_pack.argtypes = [vp, i, vp, i, i, i, i, vp, sz]
+    lib.tw_unpack.argtypes = [vp, vp, i, vp]
+    lib.tw_info.argtypes = [vp, ctypes.POINTER(TwInfo)]
+    lib.tw_gemm_workspace.argtypes = [vp, i, ctypes.POINTER(sz)]
+    lib.tw_gemm.argtypes = [vp, vp, vp, i, i, vp, i, vp, sz, vp]
+    lib.tw_dense_gemm.argtypes = [vp, i, vp, i, vp, i, i, i, i, i, vp]
+    lib.tw_strerror.argtypes = [i]
+    lib.tw_strerror.restype = ctypes.c_char_p
+    for name in SYMBOLS:
+        if name != "tw_strerror":
+            getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def _strerror(status: int) -> str:
+    return _lib.tw_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise TwError(status, where)
+
+
+def _np_ptr(a: np.ndarray) -> ctypes.c_void_p:
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def tw_version() -> int:
+    return int(_lib.tw_version())
+
+
+# --------------------------------------------------------------------------- host side
+def tw_pack_size(mask: np.ndarray, G: int, dtype: str) -> int:
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    K, N = mask.shape
+    n = ctypes.c_size_t(0)
+    _check(_lib.tw_pack_size(_np_ptr(mask), K, N, int(G), _DT[dtype], ctypes.byref(n)), "tw_pack_size")
+    return int(n.value)
+
+
+def tw_pack(B_bits: np.ndarray, mask: np.ndarray, G: int, dtype: str) -> np.ndarray:
+    """B_bits: uint16 [K, N] (row stride may exceed N), mask: uint8 [K, N].  Returns the blob (uint8)."""
+    assert B_bits.dtype == np.uint16 and B_bits.ndim == 2 and B_bits.strides[1] == 2
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    K, N = mask.shape
+    assert B_bits.shape == (K, N)
+    ldb = B_bits.strides[0] // 2 if K > 1 else N
+    nbytes = tw_pack_size(mask, G, dtype)
+    blob = _aligned_bytes(nbytes, 256)
+    _check(_lib.tw_pack(_np_ptr(B_bits), ldb, _np_ptr(mask), K, N, int(G), _DT[dtype], _np_ptr(blob), nbytes),
+           "tw_pack")
+    return blob
+
+
+def _aligned_bytes(n: int, align: int) -> np.ndarray:
+    raw = np.zeros(n + align, dtype=np.uint8)
+    off = (-raw.ctypes.data) % align
+    return raw[off:off + n]
+
+
+def tw_unpack(blob: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    inf = tw_info(blob)
+    K, N = inf["K"], inf["N"]
+    B = np.empty((K, N), dtype=np.uint16)
+    mask = np.empty((K, N), dtype=np.uint8)
+    _check(_lib.tw_unpack(_np_ptr(blob), _np_ptr(B), N, _np_ptr(mask)), "tw_unpack")
+    return B, mask
+
+
+def tw_info(blob: np.ndarray) -> Dict:
+    """Header fields plus views of the canonical int32 index arrays inside the blob."""
+    assert blob.dtype == np.uint8 and blob.flags["C_CONTIGUOUS"]
+    ti = TwInfo()
+    _check(_lib.tw_info(_np_ptr(blob), ctypes.byref(ti)), "tw_info")
+    out = {f: getattr(ti, f) for f, _ in TwInfo._fields_}
+    T, nk = ti.T, ti.n_kept_cols
+
+    def arr(off, n):
+        return blob[off:off + 4 * n].view(np.int32)
+
+    out["tile_row_ptr"] = arr(ti.off_tile_row_ptr, T + 1)
+    out["tile_col_ptr"] = arr(ti.off_tile_col_ptr, T + 1)
+    out["col_idx"] = arr(ti.off_col_idx, nk)
+    out["row_idx"] = arr(ti.off_row_idx, int(out["tile_row_ptr"][T]) if T > 0 else 0)
+    out["tile_span"] = arr(ti.off_tile_span, T + 1)
+    out["sched_order"] = arr(ti.off_sched_order, T)
+    return out
+
+
+# --------------------------------------------------------------------------- device side
+def _torch():
+    import torch
+    return torch
+
+
+def _tdtype(dtype: str):
+    torch = _torch()
+    return torch.float16 if dtype == "f16" else torch.bfloat16
+
+
+def _stream_ptr(stream=None) -> ctypes.c_void_p:
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def tw_gemm_workspace(blob: np.ndarray, M: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.tw_gemm_workspace(_np_ptr(blob), int(M), ctypes.byref(n)), "tw_gemm_workspace")
+    return int(n.value)
+
+
+class TwWeight:
+    """A packed weight resident on one GPU: host blob, device copy and a zeroed workspace."""
+
+    def __init__(self, blob: np.ndarray, device="cuda:0"):
+        torch = _torch()
+        self.blob = blob
+        self.info = tw_info(blob)
+        self.dtype = "f16" if self.info["dtype"] == TW_F16 else "bf16"
+        self.blob_dev = torch.from_numpy(blob).to(device)
+        assert self.blob_dev.data_ptr() % 256 == 0
+        self.workspace = torch.zeros(max(256, tw_gemm_workspace(blob, 1)), dtype=torch.uint8, device=device)
+
+    @classmethod
+    def from_dense(cls, B_bits: np.ndarray, mask: np.ndarray, G: int, dtype: str, device="cuda:0"):
+        return cls(tw_pack(B_bits, mask, G, dtype), device)
+
+
+def tw_gemm(w: TwWeight, A, C=None, stream=None):
+    """C = A . (B * mask).  A: torch tensor [M, K] (f16/bf16, cuda, unit column stride)."""
+    torch = _torch()
+    assert A.is_cuda and A.dtype == _tdtype(w.dtype) and A.dim() == 2 and A.stride(1) == 1
+    M, K = A.shape
+    assert K == w.info["K"]
+    N = w.info["N"]
+    if C is None:
+        C = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    assert C.is_cuda and C.dtype == A.dtype and C.shape == (M, N) and C.stride(1) == 1
+    lda = A.stride(0) if M > 1 else max(K, A.stride(0))
+    ldc = C.stride(0) if M > 1 else max(N, C.stride(0))
+    _check(_lib.tw_gemm(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()), ctypes.c_void_p(A.data_ptr()),
+                        M, lda, ctypes.c_void_p(C.data_ptr()), ldc, ctypes.c_void_p(w.workspace.data_ptr()),
+                        w.workspace.numel(), _stream_ptr(stream)), "tw_gemm")
+    return C
+
+
+def tw_dense_gemm(A, B, C=None, stream=None):
+    """C = A . B, both row-major torch tensors on the GPU."""
+    torch = _torch()
+    assert A.is_cuda and B.is_cuda and A.dtype == B.dtype and A.dtype in (torch.float16, torch.bfloat16)
+    assert A.dim() == 2 and B.dim() == 2 and A.stride(1) == 1 and B.stride(1) == 1
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2
+    if C is None:
+        C = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    assert C.shape == (M, N) and C.dtype == A.dtype and C.stride(1) == 1
+    dt = TW_F16 if A.dtype == torch.float16 else TW_BF16
+    lda = A.stride(0) if M > 1 else max(K, A.stride(0))
+    ldb = B.stride(0) if K > 1 else max(N, B.stride(0))
+    ldc = C.stride(0) if M > 1 else max(N, C.stride(0))
+    _check(_lib.tw_dense_gemm(ctypes.c_void_p(A.data_ptr()), lda, ctypes.c_void_p(B.data_ptr()), ldb,
+                              ctypes.c_void_p(C.data_ptr()), ldc, M, N, K, dt, _stream_ptr(stream)), "tw_dense_gemm")
+    return C
+
+
+def bits_to_tensor(bits: np.ndarray, dtype: str, device="cuda:0"):
+    """uint16 bit patterns -> torch tensor of the 16-bit float type on `device` (a pure reinterpretation)."""
+    torch = _torch()
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device)
+    return t.view(_tdtype(dtype))
+
+
+def tensor_to_bits(t) -> np.ndarray:
+    torch = _torch()
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)

@@ -1,0 +1,181 @@
+// tw_dense_gemm: C = A . B, the dense yardstick of the TW kernel (the paper's baseline is a tiled
+// dense GEMM on the matrix unit, Sec. IV-A Fig. 4 step 1 and Sec. VI "Tiling").  Same MFMA
+// instruction, same operand roles, same epilogue as tw_gemm; B is ordinary row-major K x N.
+//
+// Workgroup: 256 x 256 block of C, 8 waves as 2 (rows) x 4 (columns), wave tile 128 x 64.
+// K advances 64 at a time through two LDS buffers; global loads of step i+1 are in flight
+// while step i is multiplied.
+#include <hip/hip_runtime.h>
+
+#include "../../include/tw.h"
+#include "tw_device.hpp"
+
+namespace {
+
+constexpr int kThreads = 512;
+constexpr int BM = 256, BN = 256, KB = 64;
+constexpr int A_PITCH = KB * 2 + 16;   // 144 B: 16-byte reads of 16 consecutive rows hit distinct banks
+constexpr int B_PITCH = BN * 2 + 8;    // 520 B
+constexpr int A_BYTES = BM * A_PITCH;  // 36864
+constexpr int B_BYTES = KB * B_PITCH;  // 33280
+constexpr int BUF_BYTES = A_BYTES + B_BYTES;
+constexpr int LDS_BYTES = 2 * BUF_BYTES;  // 140288
+
+struct DenseParams {
+    const unsigned short* A;
+    const unsigned short* B;
+    unsigned short* C;
+    long lda, ldb, ldc;
+    int M, N, K;
+    int nbm, nbn;
+};
+
+struct Staged {
+    tw_u32x4 a[4];
+    tw_u32x4 b[4];
+};
+
+__device__ __forceinline__ tw_u32x4 load8_guard(const unsigned short* p, int valid) {
+    // valid >= 8: one 16-byte load; 0 < valid < 8: element-wise, zero filled; <= 0: zeros
+    if (valid >= 8) return *(const tw_u32x4*)p;
+    unsigned short e[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) e[i] = i < valid ? p[i] : (unsigned short)0;
+    return tw_u32x4{e[0] | ((unsigned)e[1] << 16), e[2] | ((unsigned)e[3] << 16), e[4] | ((unsigned)e[5] << 16),
+                    e[6] | ((unsigned)e[7] << 16)};
+}
+
+__device__ __forceinline__ void global_fetch(const DenseParams& p, int m0, int n0, int k0, int tid, Staged& st) {
+    // A tile: 256 rows x 8 pieces of 16 B; thread handles pieces id = tid + 512*i
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = tid + kThreads * i;
+        const int r = id >> 3, u = id & 7;
+        int gm = m0 + r;
+        gm = gm < p.M ? gm : p.M - 1;
+        const int k = k0 + u * 8;
+        st.a[i] = load8_guard(p.A + (long)gm * p.lda + k, p.K - k);
+    }
+    // B tile: 64 rows x 32 pieces
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = tid + kThreads * i;
+        const int r = id >> 5, u = id & 31;
+        const int k = k0 + r, n = n0 + u * 8;
+        if (k < p.K)
+            st.b[i] = load8_guard(p.B + (long)k * p.ldb + n, p.N - n);
+        else
+            st.b[i] = tw_u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
+__device__ __forceinline__ void lds_commit(unsigned char* buf, int tid, const Staged& st) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = tid + kThreads * i;
+        const int r = id >> 3, u = id & 7;
+        *(tw_u32x4*)(buf + r * A_PITCH + u * 16) = st.a[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = tid + kThreads * i;
+        const int r = id >> 5, u = id & 31;
+        unsigned char* d = buf + A_BYTES + r * B_PITCH + u * 16;
+        *(tw_u32x2*)d = tw_u32x2{st.b[i].x, st.b[i].y};
+        *(tw_u32x2*)(d + 8) = tw_u32x2{st.b[i].z, st.b[i].w};
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int h = lane >> 5, l32 = lane & 31;
+
+    // workgroups that land on the same XCD (ids equal modulo 8) get neighbouring blocks of C,
+    // so they share rows of A and columns of B in that XCD's L2
+    int bid = blockIdx.x;
+    const int total = p.nbm * p.nbn;
+    if ((total & 7) == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);
+    const int mb = bid / p.nbn, nb = bid - mb * p.nbn;
+    const int m0 = mb * BM, n0 = nb * BN;
+
+    tw_f32x16 acc[4][2];
+#pragma unroll
+    for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[ms][cb][r] = 0.f;
+
+    const int nk = (p.K + KB - 1) / KB;
+    Staged st;
+    global_fetch(p, m0, n0, 0, tid, st);
+    lds_commit(smem, tid, st);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        unsigned char* cur = smem + (kt & 1) * BUF_BYTES;
+        unsigned char* nxt = smem + ((kt + 1) & 1) * BUF_BYTES;
+        const bool more = kt + 1 < nk;
+        if (more) global_fetch(p, m0, n0, (kt + 1) * KB, tid, st);
+
+        const unsigned char* la = cur + (wm * 128 + l32) * A_PITCH + h * 16;
+        const unsigned char* lb = cur + A_BYTES + (8 * h) * B_PITCH + (wn * 64 + l32) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KB / 16; ++ks) {
+            tw_u16x8 w[2], a[4];
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    w[cb][e] = *(const unsigned short*)(lb + (ks * 16 + e) * B_PITCH + cb * 64);
+#pragma unroll
+            for (int ms = 0; ms < 4; ++ms) a[ms] = *(const tw_u16x8*)(la + ms * 32 * A_PITCH + ks * 32);
+#pragma unroll
+            for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) acc[ms][cb] = tw_mfma<DT>(w[cb], a[ms], acc[ms][cb]);
+        }
+        if (more) lds_commit(nxt, tid, st);
+        __syncthreads();
+    }
+
+    // epilogue through per-wave staging areas laid over the (now idle) operand buffers
+    unsigned char* stage = smem + wave * TW_STAGE_BYTES;
+    const int col0 = n0 + wn * 64;
+    const int width = (p.N - col0) < 64 ? (p.N - col0) : 64;
+    if (width > 0) {
+        auto dst = [](int, int, int) -> unsigned { return 0u; };
+#pragma unroll
+        for (int ms = 0; ms < 4; ++ms)
+            tw_store_block<DT, 2>(acc[ms], dst, true, stage, p.C, p.ldc, m0 + wm * 128 + ms * 32, p.M, col0, width,
+                                  lane);
+    }
+}
+
+}  // namespace
+
+extern "C" int tw_dense_gemm(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+                             tw_dtype dt, void* hip_stream) {
+    if (!A || !B || !C || M < 0 || N <= 0 || K <= 0) return TW_ERR_ARG;
+    if (dt != TW_F16 && dt != TW_BF16) return TW_ERR_ARG;
+    if (lda < K || ldb < N || ldc < N) return TW_ERR_ARG;
+    if ((lda & 7) || (ldb & 7) || (ldc & 7)) return TW_ERR_ALIGN;
+    if (((uintptr_t)A & 15) || ((uintptr_t)B & 15) || ((uintptr_t)C & 15)) return TW_ERR_ALIGN;
+    if (M == 0) return TW_OK;
+    DenseParams p;
+    p.A = (const unsigned short*)A; p.B = (const unsigned short*)B; p.C = (unsigned short*)C;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.M = M; p.N = N; p.K = K;
+    p.nbm = (M + BM - 1) / BM; p.nbn = (N + BN - 1) / BN;
+    const long blocks = (long)p.nbm * p.nbn;
+    if (blocks > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
+    auto fn = dt == TW_F16 ? tw_dense_kernel<TW_F16> : tw_dense_kernel<TW_BF16>;
+    if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+        return TW_ERR_HIP;
+    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(kThreads), LDS_BYTES, (hipStream_t)hip_stream, p);
+    return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
+}

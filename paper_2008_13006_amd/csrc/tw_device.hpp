@@ -1,0 +1,126 @@
+// Device-side building blocks shared by the TW and the dense kernels (gfx950 only).
+//
+// MFMA used: v_mfma_f32_32x32x16_{f16,bf16}.  Operand layout (64-lane wave, lane l):
+//   first operand  (32 x 16): row  i = l % 32, contraction slots 8*(l/32) .. 8*(l/32)+7
+//   second operand (16 x 32): col  j = l % 32, contraction slots 8*(l/32) .. 8*(l/32)+7
+//   result 32 x 32, 16 floats per lane: register r holds row i = 8*(r/4) + 4*(l/32) + r%4, col j = l%32
+// The kernels put the WEIGHT tile in the first operand (i = output column n) and the ACTIVATIONS
+// in the second (j = output row m), so a lane owns one row m of C and, per group of four
+// registers, four consecutive columns: stores to row-major C need no cross-lane transpose.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tw.h"
+
+typedef _Float16 tw_f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 tw_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float tw_f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned short tw_u16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short tw_u16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int tw_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int tw_u32x2 __attribute__((ext_vector_type(2)));
+
+template <int DT>
+__device__ __forceinline__ tw_f32x16 tw_mfma(tw_u16x8 w, tw_u16x8 a, tw_f32x16 c) {
+    if constexpr (DT == TW_F16) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(tw_f16x8, w),
+                                                      __builtin_bit_cast(tw_f16x8, a), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(tw_bf16x8, w),
+                                                       __builtin_bit_cast(tw_bf16x8, a), c, 0, 0, 0);
+    }
+}
+
+// fp32 -> 16-bit storage type, round to nearest even.
+template <int DT>
+__device__ __forceinline__ unsigned short tw_cvt(float x) {
+    if constexpr (DT == TW_F16) {
+        _Float16 h = (_Float16)x;
+        return __builtin_bit_cast(unsigned short, h);
+    } else {
+        __bf16 b = (__bf16)x;
+        return __builtin_bit_cast(unsigned short, b);
+    }
+}
+
+// Orders this wave's LDS traffic: everything issued before is complete and visible to the
+// wave's other lanes afterwards.  Not a workgroup barrier.
+__device__ __forceinline__ void tw_wave_lds_sync() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Staging area of one wave in the epilogue: 32 rows x 64 columns of 16-bit values, rows 136 bytes
+// apart (the 8 extra bytes spread rows over the LDS banks).
+#define TW_STAGE_PITCH 136
+#define TW_STAGE_BYTES (32 * TW_STAGE_PITCH)
+#define TW_STAGE_COLS 64
+
+typedef tw_u32x4 __attribute__((aligned(2))) tw_u32x4_a2;
+
+// Writes one 32-row block of a wave's results to C through the wave's LDS staging area.
+//   acc[cb][r]     fp32 results of the block: lane l owns row (l%32), column c = 32*cb + 8*(r/4) + 4*(l/32) + r%4
+//   dst(cb, q, e)  destination column of c = 32*cb+8*q+4*(l/32)+e relative to `col0`, or >= 0xFFFF: none
+//   width          columns [col0, col0+width) of C are written, positions nobody fills get zeros
+template <int DT, int NCB, typename DstFn>
+__device__ __forceinline__ void tw_store_block(const tw_f32x16 (&acc)[NCB], DstFn dst, bool contiguous,
+                                               unsigned char* stage, unsigned short* C, long ldc,
+                                               int row0, int M, int col0, int width, int lane) {
+    const int mrow = lane & 31, h = lane >> 5;
+    for (int w0 = 0; w0 < width; w0 += TW_STAGE_COLS) {
+        // clear the window
+#pragma unroll
+        for (int i = 0; i < (TW_STAGE_BYTES + 1023) / 1024; ++i) {
+            const int off = i * 1024 + lane * 16;
+            if (off < TW_STAGE_BYTES) *(tw_u32x4*)(stage + off) = tw_u32x4{0u, 0u, 0u, 0u};
+        }
+        tw_wave_lds_sync();
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (contiguous) {
+                    const int d0 = 32 * cb + 8 * q + 4 * h - w0;   // multiple of 4
+                    if (d0 >= 0 && d0 < TW_STAGE_COLS) {
+                        tw_u32x2 v;
+                        v.x = (unsigned)tw_cvt<DT>(acc[cb][4 * q + 0]) | ((unsigned)tw_cvt<DT>(acc[cb][4 * q + 1]) << 16);
+                        v.y = (unsigned)tw_cvt<DT>(acc[cb][4 * q + 2]) | ((unsigned)tw_cvt<DT>(acc[cb][4 * q + 3]) << 16);
+                        *(tw_u32x2*)(stage + mrow * TW_STAGE_PITCH + d0 * 2) = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int d = (int)dst(cb, q, e) - w0;
+                        if (d >= 0 && d < TW_STAGE_COLS)
+                            *(unsigned short*)(stage + mrow * TW_STAGE_PITCH + d * 2) = tw_cvt<DT>(acc[cb][4 * q + e]);
+                    }
+                }
+            }
+        }
+        tw_wave_lds_sync();
+        // 8 lanes cover the 64 columns of a row with 16-byte pieces, 8 rows per pass
+        const int j = lane & 7;
+        const int cw = w0 + 8 * j;              // column inside [0, width)
+        const int nvalid = width - cw;          // > 0: something to store
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = (lane >> 3) + 8 * p;
+            const int grow = row0 + r;
+            const tw_u32x2 lo = *(const tw_u32x2*)(stage + r * TW_STAGE_PITCH + j * 16);
+            const tw_u32x2 hi = *(const tw_u32x2*)(stage + r * TW_STAGE_PITCH + j * 16 + 8);
+            if (grow < M && nvalid > 0) {
+                unsigned short* dstp = C + (long)grow * ldc + col0 + cw;
+                if (nvalid >= 8) {
+                    *(tw_u32x4_a2*)dstp = tw_u32x4{lo.x, lo.y, hi.x, hi.y};
+                } else {
+                    const unsigned v[4] = {lo.x, lo.y, hi.x, hi.y};
+#pragma unroll
+                    for (int e = 0; e < 7; ++e)
+                        if (e < nvalid) dstp[e] = (unsigned short)(v[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        tw_wave_lds_sync();
+    }
+}

@@ -1,0 +1,345 @@
+// Host-side packer for the tile-wise (TW) format: tiling analysis, compaction, schedule.
+// Paper: Sec. IV-A (pattern, column pruning first, re-grouping), Sec. VI "Tiling" (pruned rows and
+// columns of B are removed offline; per-tile mask vectors tell the kernel what to skip) and
+// "Load Imbalance Mitigation" (tiles differ in work; here they are ordered by kept rows).
+#include "../../include/tw.h"
+#include "tw_format.h"
+
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+namespace {
+
+struct Tiling {
+    std::vector<int32_t> col_idx;
+    std::vector<int32_t> tile_col_ptr;  // T+1
+    std::vector<int32_t> tile_row_ptr;  // T+1
+    std::vector<int32_t> row_idx;
+    std::vector<int32_t> tile_span;     // T+1
+    int T = 0;
+    int64_t nnz = 0;
+};
+
+struct Layout {
+    int k_chunk = 0, n_chunks = 0, ncb = 0;
+    std::vector<int32_t> step_ptr;    // [T][n_chunks+1], tile-local step numbers
+    std::vector<int32_t> first_step;  // [T] global step index
+    int64_t total_steps = 0;
+    uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
+        off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dcol, off_bvals, bytes;
+};
+
+inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+bool supported_g(int G) { return G == 32 || G == 64 || G == 128; }
+
+// Sweep of the surviving columns (see tw.h, tw_pack_size).
+int analyse(const uint8_t* mask, int K, int N, int G, Tiling& tl) {
+    std::vector<uint8_t> alive(N, 0);
+    for (int k = 0; k < K; ++k) {
+        const uint8_t* r = mask + (size_t)k * N;
+        for (int n = 0; n < N; ++n) alive[n] |= (r[n] != 0);
+    }
+    for (int n = 0; n < N; ++n)
+        if (alive[n]) tl.col_idx.push_back(n);
+    const int nk = (int)tl.col_idx.size();
+    const int max_tiles = 2 * ((N + G - 1) / G);
+    std::vector<uint8_t> pat(K), cur(K);
+    tl.tile_col_ptr.push_back(0);
+    tl.tile_row_ptr.push_back(0);
+    int i = 0;
+    while (i < nk) {
+        const int c0 = tl.col_idx[i];
+        for (int k = 0; k < K; ++k) pat[k] = mask[(size_t)k * N + c0] != 0;
+        int j = i + 1;
+        while (j < nk && j - i < G) {
+            const int c = tl.col_idx[j];
+            bool same = true;
+            for (int k = 0; k < K; ++k)
+                if ((mask[(size_t)k * N + c] != 0) != (pat[k] != 0)) { same = false; break; }
+            if (!same) break;
+            ++j;
+        }
+        for (int k = 0; k < K; ++k)
+            if (pat[k]) tl.row_idx.push_back(k);
+        tl.tile_col_ptr.push_back(j);
+        tl.tile_row_ptr.push_back((int32_t)tl.row_idx.size());
+        if ((int)tl.tile_col_ptr.size() - 1 > max_tiles) return TW_ERR_NOT_TILEWISE;
+        i = j;
+    }
+    tl.T = (int)tl.tile_col_ptr.size() - 1;
+    tl.tile_span.assign(tl.T + 1, 0);
+    for (int t = 1; t < tl.T; ++t) tl.tile_span[t] = tl.col_idx[tl.tile_col_ptr[t]];
+    tl.tile_span[tl.T] = tl.T > 0 ? N : 0;
+    tl.nnz = 0;
+    for (int t = 0; t < tl.T; ++t)
+        tl.nnz += (int64_t)(tl.tile_col_ptr[t + 1] - tl.tile_col_ptr[t]) *
+                  (tl.tile_row_ptr[t + 1] - tl.tile_row_ptr[t]);
+    return TW_OK;
+}
+
+void plan(const Tiling& tl, int K, int G, Layout& lo) {
+    const int T = tl.T;
+    if (K <= TW_K_RESIDENT_MAX) {
+        lo.k_chunk = (K + 7) / 8 * 8;
+        lo.n_chunks = 1;
+    } else {
+        lo.k_chunk = TW_K_STREAM_CHUNK;
+        lo.n_chunks = (K + lo.k_chunk - 1) / lo.k_chunk;
+    }
+    lo.ncb = G / TW_COLBLK;
+    lo.step_ptr.assign((size_t)T * (lo.n_chunks + 1), 0);
+    lo.first_step.assign(T, 0);
+    int64_t total = 0;
+    for (int t = 0; t < T; ++t) {
+        lo.first_step[t] = (int32_t)total;
+        int32_t* sp = &lo.step_ptr[(size_t)t * (lo.n_chunks + 1)];
+        const int32_t* r = tl.row_idx.data() + tl.tile_row_ptr[t];
+        const int kt = tl.tile_row_ptr[t + 1] - tl.tile_row_ptr[t];
+        int p = 0, steps = 0;
+        for (int c = 0; c < lo.n_chunks; ++c) {
+            sp[c] = steps;
+            int cnt = 0;
+            const int hi = (c + 1) * lo.k_chunk;
+            while (p < kt && r[p] < hi) { ++p; ++cnt; }
+            steps += (cnt + TW_KSTEP - 1) / TW_KSTEP;
+        }
+        sp[lo.n_chunks] = steps;
+        total += steps;
+    }
+    lo.total_steps = total;
+    uint64_t o = sizeof(TwHeader);
+    auto take = [&](uint64_t bytes, uint64_t al) { o = align_up(o, al); uint64_t r = o; o += bytes; return r; };
+    const size_t nk = tl.col_idx.size();
+    lo.off_col_idx = take(4 * nk, 16);
+    lo.off_tile_col_ptr = take(4 * (size_t)(T + 1), 16);
+    lo.off_tile_row_ptr = take(4 * (size_t)(T + 1), 16);
+    lo.off_row_idx = take(4 * tl.row_idx.size(), 16);
+    lo.off_tile_span = take(4 * (size_t)(T + 1), 16);
+    lo.off_sched_order = take(4 * (size_t)T, 16);
+    lo.off_tile_desc = take(sizeof(TwTileDesc) * (size_t)T, 64);
+    lo.off_step_ptr = take(4 * lo.step_ptr.size(), 16);
+    lo.off_goff = take(2 * 16 * (uint64_t)total, 256);
+    lo.off_dcol = take(2 * (uint64_t)T * G, 256);
+    lo.off_bvals = take(2 * (uint64_t)total * lo.ncb * 64 * 8, 256);
+    lo.bytes = align_up(o, 256);
+}
+
+int check_common(const uint8_t* mask, int K, int N, int G, int dt) {
+    if (!mask || K <= 0 || N <= 0) return TW_ERR_ARG;
+    if (dt != TW_F16 && dt != TW_BF16) return TW_ERR_ARG;
+    if (G <= 0) return TW_ERR_ARG;
+    if (!supported_g(G)) return TW_ERR_UNSUPPORTED;
+    if ((int64_t)K * 2 + 8 > 65535 && K <= TW_K_RESIDENT_MAX) return TW_ERR_UNSUPPORTED;
+    return TW_OK;
+}
+
+const TwHeader* header_of(const void* blob) {
+    if (!blob) return nullptr;
+    const TwHeader* h = (const TwHeader*)blob;
+    if (h->magic != TW_MAGIC || h->version != TW_FORMAT_VERSION) return nullptr;
+    return h;
+}
+
+}  // namespace
+
+extern "C" int tw_pack_size(const uint8_t* mask, int K, int N, int G, tw_dtype dt, size_t* blob_bytes) {
+    if (!blob_bytes) return TW_ERR_ARG;
+    int rc = check_common(mask, K, N, G, (int)dt);
+    if (rc) return rc;
+    Tiling tl;
+    rc = analyse(mask, K, N, G, tl);
+    if (rc) return rc;
+    Layout lo;
+    plan(tl, K, G, lo);
+    *blob_bytes = (size_t)lo.bytes;
+    return TW_OK;
+}
+
+extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N, int G, tw_dtype dt,
+                       void* blob, size_t blob_bytes) {
+    if (!B || !blob) return TW_ERR_ARG;
+    int rc = check_common(mask, K, N, G, (int)dt);
+    if (rc) return rc;
+    if (ldb < N) return TW_ERR_ARG;
+    if (((uintptr_t)blob & 15) != 0) return TW_ERR_ALIGN;
+    Tiling tl;
+    rc = analyse(mask, K, N, G, tl);
+    if (rc) return rc;
+    Layout lo;
+    plan(tl, K, G, lo);
+    if (blob_bytes < lo.bytes) return TW_ERR_BUF;
+
+    uint8_t* base = (uint8_t*)blob;
+    std::memset(base, 0, (size_t)lo.bytes);
+    TwHeader* h = (TwHeader*)base;
+    h->magic = TW_MAGIC;
+    h->version = TW_FORMAT_VERSION;
+    h->dtype = (int)dt; h->K = K; h->N = N; h->G = G; h->T = tl.T;
+    h->n_kept_cols = (int32_t)tl.col_idx.size();
+    h->nnz = tl.nnz;
+    h->blob_bytes = lo.bytes;
+    h->k_chunk = lo.k_chunk; h->n_chunks = lo.n_chunks; h->ncb = lo.ncb;
+    h->total_steps = lo.total_steps;
+    h->off_col_idx = lo.off_col_idx; h->off_tile_col_ptr = lo.off_tile_col_ptr;
+    h->off_tile_row_ptr = lo.off_tile_row_ptr; h->off_row_idx = lo.off_row_idx;
+    h->off_tile_span = lo.off_tile_span; h->off_sched_order = lo.off_sched_order;
+    h->off_tile_desc = lo.off_tile_desc; h->off_step_ptr = lo.off_step_ptr;
+    h->off_goff = lo.off_goff; h->off_dcol = lo.off_dcol; h->off_bvals = lo.off_bvals;
+
+    auto put = [&](uint64_t off, const std::vector<int32_t>& v) {
+        if (!v.empty()) std::memcpy(base + off, v.data(), 4 * v.size());
+    };
+    put(lo.off_col_idx, tl.col_idx);
+    put(lo.off_tile_col_ptr, tl.tile_col_ptr);
+    put(lo.off_tile_row_ptr, tl.tile_row_ptr);
+    put(lo.off_row_idx, tl.row_idx);
+    put(lo.off_tile_span, tl.tile_span);
+    put(lo.off_step_ptr, lo.step_ptr);
+
+    // schedule: heaviest tile (most kept rows) first, ties keep tile order
+    std::vector<int32_t> order(tl.T);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+        return (tl.tile_row_ptr[a + 1] - tl.tile_row_ptr[a]) > (tl.tile_row_ptr[b + 1] - tl.tile_row_ptr[b]);
+    });
+    put(lo.off_sched_order, order);
+
+    const uint16_t* Bv = (const uint16_t*)B;
+    const uint16_t pad_off = (uint16_t)(2 * lo.k_chunk);
+    TwTileDesc* desc = (TwTileDesc*)(base + lo.off_tile_desc);
+    uint16_t* goff = (uint16_t*)(base + lo.off_goff);
+    uint16_t* dcol_all = (uint16_t*)(base + lo.off_dcol);
+    uint16_t* bvals = (uint16_t*)(base + lo.off_bvals);
+    const int ncb = lo.ncb;
+
+    for (int t = 0; t < tl.T; ++t) {
+        const int c0 = tl.tile_col_ptr[t], w = tl.tile_col_ptr[t + 1] - c0;
+        const int r0 = tl.tile_row_ptr[t], kt = tl.tile_row_ptr[t + 1] - r0;
+        const int32_t* sp = &lo.step_ptr[(size_t)t * (lo.n_chunks + 1)];
+        const int nsteps = sp[lo.n_chunks];
+        TwTileDesc& d = desc[t];
+        d.w = w; d.k = kt;
+        d.span_start = tl.tile_span[t];
+        d.span_w = tl.tile_span[t + 1] - tl.tile_span[t];
+        d.nsteps = nsteps;
+        d.step_ptr = t * (lo.n_chunks + 1);
+        d.first_step = lo.first_step[t];
+        d.bvals_off = lo.off_bvals + 2 * (uint64_t)lo.first_step[t] * ncb * 64 * 8;
+        d.dcol_off = (uint32_t)(lo.off_dcol + 2 * (uint64_t)t * G);
+        bool nogap = true;
+        for (int c = 0; c < w; ++c)
+            if (tl.col_idx[c0 + c] != d.span_start + c) { nogap = false; break; }
+        d.flags = nogap ? TW_TILE_NOGAP : 0;
+
+        // destination columns, stored in the order the epilogue's lanes consume them
+        uint16_t* dc = dcol_all + (size_t)t * G;
+        for (int hh = 0; hh < 2; ++hh)
+            for (int cb = 0; cb < ncb; ++cb)
+                for (int q = 0; q < 4; ++q)
+                    for (int e = 0; e < 4; ++e) {
+                        const int c = 32 * cb + 8 * q + 4 * hh + e;
+                        dc[((hh * ncb + cb) * 4 + q) * 4 + e] =
+                            c < w ? (uint16_t)(tl.col_idx[c0 + c] - d.span_start) : (uint16_t)0xFFFF;
+                    }
+
+        // gather offsets and packed values, chunk by chunk
+        uint16_t* tg = goff + (size_t)lo.first_step[t] * 16;
+        for (int s = 0; s < nsteps * 16; ++s) tg[s] = pad_off;
+        uint16_t* tb = bvals + (size_t)lo.first_step[t] * ncb * 64 * 8;
+        int p = 0;
+        for (int c = 0; c < lo.n_chunks; ++c) {
+            const int hi = (c + 1) * lo.k_chunk, kbase = c * lo.k_chunk;
+            int slot = sp[c] * 16;
+            while (p < kt && tl.row_idx[r0 + p] < hi) {
+                const int k = tl.row_idx[r0 + p];
+                tg[slot] = (uint16_t)(2 * (k - kbase));
+                const int s = slot / 16, kl = slot % 16;       // step, contraction slot in the step
+                const int half = kl / 8, e = kl % 8;
+                for (int cc = 0; cc < w; ++cc) {
+                    const int cb = cc / 32, lane = 32 * half + cc % 32;
+                    tb[(((size_t)s * ncb + cb) * 64 + lane) * 8 + e] =
+                        Bv[(size_t)k * ldb + tl.col_idx[c0 + cc]];
+                }
+                ++slot; ++p;
+            }
+        }
+    }
+    return TW_OK;
+}
+
+extern "C" int tw_info(const void* blob, tw_info_t* out) {
+    const TwHeader* h = header_of(blob);
+    if (!out) return TW_ERR_ARG;
+    if (!h) return TW_ERR_BUF;
+    out->version = (int32_t)h->version;
+    out->dtype = h->dtype; out->K = h->K; out->N = h->N; out->G = h->G; out->T = h->T;
+    out->n_kept_cols = h->n_kept_cols;
+    out->k_chunk = h->k_chunk;
+    out->nnz = h->nnz;
+    out->padded_macs_per_row = h->total_steps * TW_KSTEP * (int64_t)h->G;
+    out->blob_bytes = h->blob_bytes;
+    out->off_col_idx = h->off_col_idx; out->off_tile_col_ptr = h->off_tile_col_ptr;
+    out->off_tile_row_ptr = h->off_tile_row_ptr; out->off_row_idx = h->off_row_idx;
+    out->off_tile_span = h->off_tile_span; out->off_sched_order = h->off_sched_order;
+    return TW_OK;
+}
+
+extern "C" int tw_unpack(const void* blob, void* B_out, int ldb, uint8_t* mask_out) {
+    const TwHeader* h = header_of(blob);
+    if (!h) return TW_ERR_BUF;
+    if (B_out && ldb < h->N) return TW_ERR_ARG;
+    const uint8_t* base = (const uint8_t*)blob;
+    const int K = h->K, N = h->N, T = h->T, ncb = h->ncb;
+    const int32_t* col_idx = (const int32_t*)(base + h->off_col_idx);
+    const int32_t* tcp = (const int32_t*)(base + h->off_tile_col_ptr);
+    const int32_t* trp = (const int32_t*)(base + h->off_tile_row_ptr);
+    const int32_t* row_idx = (const int32_t*)(base + h->off_row_idx);
+    const int32_t* step_ptr = (const int32_t*)(base + h->off_step_ptr);
+    const TwTileDesc* desc = (const TwTileDesc*)(base + h->off_tile_desc);
+    uint16_t* Bo = (uint16_t*)B_out;
+    if (Bo)
+        for (int k = 0; k < K; ++k) std::memset(Bo + (size_t)k * ldb, 0, 2 * (size_t)N);
+    if (mask_out) std::memset(mask_out, 0, (size_t)K * N);
+    for (int t = 0; t < T; ++t) {
+        const int c0 = tcp[t], w = tcp[t + 1] - c0, r0 = trp[t], kt = trp[t + 1] - r0;
+        const int32_t* sp = step_ptr + desc[t].step_ptr;
+        const uint16_t* tb = (const uint16_t*)(base + desc[t].bvals_off);
+        int p = 0;
+        for (int c = 0; c < h->n_chunks; ++c) {
+            const int hi = (c + 1) * h->k_chunk;
+            int slot = sp[c] * 16;
+            while (p < kt && row_idx[r0 + p] < hi) {
+                const int k = row_idx[r0 + p];
+                const int s = slot / 16, kl = slot % 16, half = kl / 8, e = kl % 8;
+                for (int cc = 0; cc < w; ++cc) {
+                    const int n = col_idx[c0 + cc];
+                    if (mask_out) mask_out[(size_t)k * N + n] = 1;
+                    if (Bo) {
+                        const int cb = cc / 32, lane = 32 * half + cc % 32;
+                        Bo[(size_t)k * ldb + n] = tb[(((size_t)s * ncb + cb) * 64 + lane) * 8 + e];
+                    }
+                }
+                ++slot; ++p;
+            }
+        }
+    }
+    return TW_OK;
+}
+
+extern "C" const char* tw_strerror(int status) {
+    switch (status) {
+        case TW_OK: return "ok";
+        case TW_ERR_ARG: return "bad argument";
+        case TW_ERR_NOT_TILEWISE: return "mask is not tile-wise for this granularity";
+        case TW_ERR_BUF: return "buffer too small or not a packed blob";
+        case TW_ERR_ALIGN: return "pointer or leading dimension not aligned";
+        case TW_ERR_HIP: return "HIP runtime error";
+        case TW_ERR_UNSUPPORTED: return "unsupported granularity or shape";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int tw_version(void) { return TW_FORMAT_VERSION; }

@@ -1,0 +1,235 @@
+"""GPU parity: tw_gemm and tw_dense_gemm, called through the C-ABI, against the fp64 CPU oracle on
+the same seeded inputs.  Tolerance (max|err| / max|ref|): 2e-3 for fp16, 1e-2 for bf16 - the output
+rounding (2^-11, 2^-8) dominates, fp32 accumulation adds ~1e-6.  Integer-valued inputs make every
+product and sum exact, so those cases are compared bit for bit."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import tw_ref
+from paper_2008_13006_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+TOL = {"f16": 2e-3, "bf16": 1e-2}
+
+
+@pytest.fixture(scope="module")
+def tw():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2008_13006_amd import binding
+    return binding
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def _to_f64(t):
+    return t.to(torch.float64).cpu().numpy()
+
+
+def _rel_err(got64, ref):
+    scale = np.max(np.abs(ref))
+    return float(np.max(np.abs(got64 - ref)) / scale) if scale > 0 else float(np.max(np.abs(got64)))
+
+
+def _device_A(tw, A_bits, dtype, pad_to=8):
+    """A on the GPU with a row stride that is a multiple of 8 elements."""
+    M, K = A_bits.shape
+    lda = (K + pad_to - 1) // pad_to * pad_to
+    buf = torch.zeros((M, lda), dtype=torch.float16 if dtype == "f16" else torch.bfloat16, device="cuda:0")
+    buf[:, :K] = tw.bits_to_tensor(A_bits, dtype)
+    return buf[:, :K]
+
+
+def _run_tw(tw, w, rows=None, poison=True):
+    spec = w.spec
+    wt = tw.TwWeight.from_dense(w.B, w.mask, spec.G, spec.dtype)
+    A = _device_A(tw, w.A, spec.dtype)
+    M = A.shape[0]
+    C = torch.full((M, spec.N), float("nan"), dtype=A.dtype, device="cuda:0") if poison else None
+    C = tw.tw_gemm(wt, A, C)
+    torch.cuda.synchronize()
+    assert int(wt.workspace.view(torch.int32)[:2].abs().sum().item()) == 0, "scheduler counters not reset"
+    return wt, A, C
+
+
+def _check_tw(tw, w, rows=None):
+    spec = w.spec
+    wt, A, C = _run_tw(tw, w)
+    if rows is None:
+        ref = tw_ref.masked_gemm(w.A, w.B, w.mask, spec.dtype)
+        got = _to_f64(C)
+    else:
+        ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, w.mask, spec.dtype)
+        got = _to_f64(C[torch.as_tensor(rows, device="cuda:0")])
+    assert np.isfinite(got).all(), "some element of C was not written"
+    err = _rel_err(got, ref)
+    _say(f"{spec.name}: rel err {err:.3e}")
+    assert err <= TOL[spec.dtype]
+    # properties that hold for the whole C at any size: pruned columns are exact zeros
+    pruned = np.flatnonzero(~w.mask.any(axis=0))
+    if len(pruned):
+        assert float(C[:, torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
+    assert bool(torch.isfinite(C.float()).all().item())
+    return wt, A, C
+
+
+# ------------------------------------------------------------------ small, element by element
+SMALL = [
+    # name, M, K, N, G, dtype, col_prune, keep
+    ("tiny_one_tile", 5, 24, 32, 32, "f16", 0.0, ("const", 0.5)),
+    ("ragged_rows_gaps", 77, 200, 300, 128, "f16", 0.07, ("upow", 0.05, 0.7)),
+    ("k_not_mult_of_8", 33, 203, 190, 64, "f16", 0.1, ("upow", 0.1, 0.9)),
+    ("bf16_g64", 130, 320, 256, 64, "bf16", 0.05, ("upow", 0.1, 0.6)),
+    ("g32_many_tiles", 65, 96, 320, 32, "f16", 0.2, ("upow", 0.02, 1.0)),
+    ("one_row", 1, 128, 256, 128, "bf16", 0.0, ("upow", 0.1, 0.5)),
+    ("several_row_blocks", 300, 512, 640, 128, "f16", 0.05, ("upow", 0.1, 0.5)),
+    ("kept_one_row_each", 40, 64, 256, 128, "f16", 0.0, ("const", 0.0)),
+    ("streamed_k", 100, 2304, 200, 64, "f16", 0.1, ("upow", 0.05, 0.5)),
+    ("streamed_k_bf16_ragged", 67, 2100, 300, 128, "bf16", 0.05, ("upow", 0.02, 0.6)),
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_tw_gemm_small_cases(tw, case):
+    name, M, K, N, G, dtype, cp, keep = case
+    _say(f"tw_gemm small {name} M={M} K={K} N={N} G={G} {dtype}")
+    spec = W.small_spec(name, M=M, K=K, N=N, G=G, dtype=dtype, col_prune=cp, keep=keep,
+                        seed_offset=9500 + len(name))
+    _check_tw(tw, W.generate(spec))
+
+
+def test_tw_gemm_integer_inputs_bit_exact(tw):
+    """Small integers: every product and partial sum is exact in fp32 and the result is exact in fp16."""
+    _say("tw_gemm integer inputs, bit exact")
+    spec = W.small_spec("ints", M=150, K=256, N=384, G=128, dtype="f16", col_prune=0.05,
+                        keep=("upow", 0.1, 0.6), a_dist="smallint", seed_offset=9600)
+    w = W.generate(spec)
+    _, _, C = _run_tw(tw, w)
+    ref = tw_ref.masked_gemm(w.A, w.B, w.mask, "f16")
+    assert np.max(np.abs(ref)) < 2048                    # integers below 2^11 are exact in fp16
+    assert np.array_equal(_to_f64(C), ref)
+
+
+def test_tw_gemm_zero_sparsity_equals_dense(tw):
+    """0 % sparsity: TW result, dense kernel result and the oracle agree (spec invariant)."""
+    _say("tw_gemm at 0 % sparsity vs tw_dense_gemm")
+    spec = W.small_spec("dense0", M=200, K=256, N=384, G=128, dtype="f16", keep=("const", 1.0), seed_offset=9700)
+    w = W.generate(spec)
+    assert w.mask.all()
+    wt, A, C = _check_tw(tw, w)
+    B = tw.bits_to_tensor(w.B, "f16")
+    Cd = tw.tw_dense_gemm(A.contiguous(), B)
+    torch.cuda.synchronize()
+    ref = tw_ref.masked_gemm(w.A, w.B, w.mask, "f16")
+    assert _rel_err(_to_f64(Cd), ref) <= TOL["f16"]
+    assert _rel_err(_to_f64(C), _to_f64(Cd)) <= TOL["f16"]
+
+
+def test_tw_gemm_all_pruned_tile_and_empty_weight(tw):
+    _say("tw_gemm all-pruned tile / empty weight")
+    spec = W.small_spec("holes", M=70, K=64, N=384, G=128, dtype="f16", keep=("const", 0.5), seed_offset=9800)
+    w = W.generate(spec)
+    w.mask[:, 128:256] = 0                               # the middle tile disappears entirely
+    _, _, C = _check_tw(tw, w)
+    assert float(C[:, 128:256].float().abs().max().item()) == 0.0
+    w.mask[:] = 0
+    _, _, C = _run_tw(tw, w)
+    assert float(C.float().abs().max().item()) == 0.0
+
+
+def test_tw_gemm_is_deterministic_and_workspace_reusable(tw):
+    _say("tw_gemm twice on one workspace, bit-identical")
+    w = W.generate(W.CONFIGS["c1_single"][0])
+    wt, A, C1 = _run_tw(tw, w)
+    C2 = tw.tw_gemm(wt, A)
+    C3 = tw.tw_gemm(wt, A)
+    torch.cuda.synchronize()
+    assert torch.equal(C1, C2) and torch.equal(C1, C3)
+
+
+def test_tw_gemm_strided_output(tw):
+    _say("tw_gemm into a strided C")
+    spec = W.small_spec("ldc", M=50, K=128, N=200, G=64, dtype="f16", col_prune=0.1, seed_offset=9900)
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, 64, "f16")
+    A = _device_A(tw, w.A, "f16")
+    big = torch.full((50, 333), 7.0, dtype=torch.float16, device="cuda:0")
+    tw.tw_gemm(wt, A, big[:, 11:211])
+    torch.cuda.synchronize()
+    ref = tw_ref.masked_gemm(w.A, w.B, w.mask, "f16")
+    assert _rel_err(_to_f64(big[:, 11:211]), ref) <= TOL["f16"]
+    assert bool((big[:, :11] == 7.0).all()) and bool((big[:, 211:] == 7.0).all())
+
+
+def test_bad_device_arguments_are_refused(tw):
+    spec = W.small_spec("args", M=8, K=64, N=128, G=64, seed_offset=9950)
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, 64, "f16")
+    A = torch.zeros((8, 65), dtype=torch.float16, device="cuda:0")[:, :64]   # row stride 65: not a multiple of 8
+    with pytest.raises(tw.TwError) as e:
+        tw.tw_gemm(wt, A)
+    assert e.value.status == -4
+
+
+# ------------------------------------------------------------------ dense kernel
+DENSE = [("d_small", 70, 96, 130, "f16"), ("d_ragged", 300, 200, 520, "bf16"), ("d_blocks", 512, 256, 512, "f16"),
+         ("d_k_tail", 257, 1000, 264, "f16")]
+
+
+@pytest.mark.parametrize("case", DENSE, ids=[c[0] for c in DENSE])
+def test_dense_gemm_small_cases(tw, case):
+    name, M, K, N, dtype = case
+    _say(f"tw_dense_gemm {name} M={M} K={K} N={N} {dtype}")
+    rng = np.random.default_rng(sum(map(ord, name)))
+    A_bits = W.f32_to_bits(rng.standard_normal((M, K), dtype=np.float32), dtype)
+    B_bits = W.f32_to_bits(rng.standard_normal((K, N), dtype=np.float32) * np.float32(0.05), dtype)
+    lda, ldb, ldc = (K + 7) // 8 * 8, (N + 7) // 8 * 8, (N + 7) // 8 * 8 + 8
+    td = torch.float16 if dtype == "f16" else torch.bfloat16
+    A = torch.zeros((M, lda), dtype=td, device="cuda:0"); A[:, :K] = tw.bits_to_tensor(A_bits, dtype)
+    B = torch.zeros((K, ldb), dtype=td, device="cuda:0"); B[:, :N] = tw.bits_to_tensor(B_bits, dtype)
+    Cbuf = torch.full((M, ldc), float("nan"), dtype=td, device="cuda:0")
+    tw.tw_dense_gemm(A[:, :K], B[:, :N], Cbuf[:, :N])
+    torch.cuda.synchronize()
+    ref = tw_ref.masked_gemm(A_bits, B_bits, np.ones((K, N), np.uint8), dtype)
+    got = _to_f64(Cbuf[:, :N])
+    assert np.isfinite(got).all()
+    assert _rel_err(got, ref) <= TOL[dtype]
+    assert bool(torch.isnan(Cbuf[:, N:].float()).all().item()), "wrote outside C"
+
+
+# ------------------------------------------------------------------ the five workloads, full size
+def test_config1_full(tw):
+    _say("config 1, every element")
+    _check_tw(tw, W.generate(W.CONFIGS["c1_single"][0]))
+
+
+def _sample_rows(M, n=192, seed=0):
+    rng = np.random.default_rng(seed)
+    fixed = np.array([0, 1, 31, 32, 63, 64, M - 65, M - 64, M - 33, M - 2, M - 1])
+    rows = np.unique(np.concatenate([fixed, rng.choice(M, size=n, replace=False)]))
+    return rows[(rows >= 0) & (rows < M)]
+
+
+@pytest.mark.parametrize("cfg", ["c2_bert_base_ffn_up", "c3_bert_base_layer", "c4_bert_large_skewed", "c5_conv_im2col"])
+def test_full_size_workloads_on_sampled_rows(tw, cfg):
+    """Full-size launch (the configuration bench.py times), checked on ~200 sampled rows of C that the
+    oracle computes one by one, plus whole-matrix properties (finite, exact zeros in pruned columns)."""
+    for spec in W.CONFIGS[cfg]:
+        _say(f"{cfg} / {spec.name} M={spec.M} K={spec.K} N={spec.N}")
+        w = W.generate(spec)
+        wt, A, C = _check_tw(tw, w, rows=_sample_rows(spec.M))
+        if cfg == "c2_bert_base_ffn_up":
+            # the dense yardstick at the same shape, same sampled rows
+            B = tw.bits_to_tensor(w.B, spec.dtype)
+            Cd = tw.tw_dense_gemm(A.contiguous(), B)
+            torch.cuda.synchronize()
+            rows = _sample_rows(spec.M, n=64, seed=1)
+            ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, np.ones_like(w.mask), spec.dtype)
+            assert _rel_err(_to_f64(Cd[torch.as_tensor(rows, device="cuda:0")]), ref) <= TOL[spec.dtype]
+        del wt, A, C
+        torch.cuda.empty_cache()

@@ -1,0 +1,157 @@
+"""Host side of the C-ABI library (no GPU needed): the library loads and exports what include/tw.h
+declares, tw_pack's integer arrays equal the oracle's tile structure bit for bit, pack -> unpack
+gives back B*mask and the mask bit for bit, and bad input is refused with the documented codes."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from oracle import tw_ref
+from paper_2008_13006_amd import binding as tw
+from paper_2008_13006_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "tw.h")).read()
+    declared = set(re.findall(r"\b(tw_[a-z_]+)\s*\(", text))
+    declared -= {"tw_info_t"}
+    assert declared == set(tw.SYMBOLS)
+    lib = ctypes.CDLL(tw.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert tw.tw_version() == 1
+
+
+def _check_against_oracle(mask, B, G, dtype):
+    blob = tw.tw_pack(B, mask, G, dtype)
+    inf = tw.tw_info(blob)
+    s = tw_ref.tile_structure(mask, G)
+    assert inf["T"] == s["T"] and inf["K"] == s["K"] and inf["N"] == s["N"] and inf["G"] == G
+    assert inf["nnz"] == s["nnz"] and inf["n_kept_cols"] == len(s["col_idx"])
+    for key in ("col_idx", "tile_col_ptr", "tile_row_ptr", "row_idx", "tile_span"):
+        assert np.array_equal(inf[key], s[key]), key
+    k_t = np.diff(s["tile_row_ptr"])
+    assert np.array_equal(inf["sched_order"], np.argsort(-k_t, kind="stable").astype(np.int32))
+    Bu, mu = tw.tw_unpack(blob)
+    assert np.array_equal(mu, (mask != 0).astype(np.uint8))
+    assert np.array_equal(Bu, tw_ref.masked_weight_bits(B, mask))
+    assert inf["padded_macs_per_row"] >= inf["nnz"]
+    return inf
+
+
+@pytest.mark.parametrize("cfg", ["c1_single", "c2_bert_base_ffn_up", "c4_bert_large_skewed", "c5_conv_im2col"])
+def test_pack_matches_oracle_on_the_paper_shaped_workloads(cfg):
+    for spec in W.CONFIGS[cfg]:
+        w = W.generate(spec, with_A=False)
+        inf = _check_against_oracle(w.mask, w.B, spec.G, spec.dtype)
+        assert inf["T"] == w.info["T"]
+
+
+def test_pack_matches_oracle_bert_base_layer():
+    for spec in W.CONFIGS["c3_bert_base_layer"]:
+        w = W.generate(spec, with_A=False)
+        _check_against_oracle(w.mask, w.B, spec.G, spec.dtype)
+
+
+def test_fig4_worked_example_through_the_library():
+    from tests.test_tile_structure_pins import fig4_mask
+    G, K = 32, 64
+    mask, g = fig4_mask(G, K)
+    B = np.arange(K * 4 * G, dtype=np.uint32).astype(np.uint16).reshape(K, 4 * G)
+    inf = _check_against_oracle(mask, B, G, "f16")
+    assert (np.diff(inf["tile_col_ptr"]) - G).tolist() == g["width_minus_G"]
+    assert (np.diff(inf["tile_span"]) - G).tolist() == g["span_minus_G"]
+    assert (np.diff(inf["tile_row_ptr"]) - K).tolist() == g["height_minus_K"]
+
+
+def test_negative_zero_and_odd_strides_round_trip():
+    K, N, G = 40, 70, 32
+    rng = np.random.default_rng(0)
+    Bbig = rng.integers(0, 65536, size=(K, N + 9)).astype(np.uint16)
+    Bbig[3, 5] = 0x8000                                   # -0.0 at a kept position must survive
+    mask = np.zeros((K, N), np.uint8)
+    mask[np.ix_([1, 3, 8, 39], np.arange(0, 32))] = 1
+    mask[np.ix_([0, 3], np.arange(33, 70))] = 1
+    blob = tw.tw_pack(Bbig[:, :N], mask, G, "bf16")
+    Bu, mu = tw.tw_unpack(blob)
+    assert np.array_equal(mu, mask)
+    assert np.array_equal(Bu, tw_ref.masked_weight_bits(Bbig[:, :N], mask))
+    assert Bu[3, 5] == 0x8000
+
+
+def test_streamed_k_layout_round_trips():
+    """K above the LDS-resident limit switches the blob to chunked K; the integer arrays do not change."""
+    spec = W.small_spec("bigk", M=1, K=2304, N=200, G=64, col_prune=0.1, keep=("upow", 0.05, 0.5), seed_offset=9100)
+    w = W.generate(spec, with_A=False)
+    inf = _check_against_oracle(w.mask, w.B, 64, "f16")
+    assert inf["k_chunk"] < 2304
+
+
+def test_empty_and_full_masks():
+    K, N, G = 24, 64, 32
+    B = np.full((K, N), 0x3C00, np.uint16)
+    inf = _check_against_oracle(np.zeros((K, N), np.uint8), B, G, "f16")
+    assert inf["T"] == 0 and inf["nnz"] == 0
+    inf = _check_against_oracle(np.ones((K, N), np.uint8), B, G, "f16")
+    assert inf["T"] == 2 and inf["nnz"] == K * N and inf["row_idx"].tolist() == list(range(K)) * 2
+
+
+def test_error_codes():
+    K, N = 16, 64
+    B = np.zeros((K, N), np.uint16)
+    rng = np.random.default_rng(3)
+    unstructured = (rng.random((K, N)) < 0.5).astype(np.uint8)
+    with pytest.raises(tw.TwError) as e:
+        tw.tw_pack(B, unstructured, 32, "f16")
+    assert e.value.status == -2                            # TW_ERR_NOT_TILEWISE
+    with pytest.raises(tw.TwError) as e:
+        tw.tw_pack(B, np.ones((K, N), np.uint8), 48, "f16")
+    assert e.value.status == -6                            # TW_ERR_UNSUPPORTED granularity
+    with pytest.raises(tw.TwError) as e:
+        tw.tw_info(np.zeros(512, np.uint8))
+    assert e.value.status == -3                            # TW_ERR_BUF: not a blob
+    lib = ctypes.CDLL(tw.LIB_PATH)
+    n = ctypes.c_size_t(0)
+    assert lib.tw_pack_size(None, 4, 4, 32, 0, ctypes.byref(n)) == -1
+    m = np.ones((K, N), np.uint8)
+    assert lib.tw_pack_size(ctypes.c_void_p(m.ctypes.data), K, N, 32, 7, ctypes.byref(n)) == -1
+    blob = tw.tw_pack(B, m, 32, "f16")
+    small = np.zeros(64, np.uint8)
+    assert lib.tw_pack(ctypes.c_void_p(B.ctypes.data), N, ctypes.c_void_p(m.ctypes.data), K, N, 32, 0,
+                       ctypes.c_void_p(blob.ctypes.data), ctypes.c_size_t(64)) == -3
+    assert small.sum() == 0
+    assert tw._strerror(-2).startswith("mask is not tile-wise")
+
+
+@st.composite
+def tw_masks(draw):
+    G = draw(st.sampled_from([32, 64, 128]))
+    K = draw(st.integers(1, 70))
+    T = draw(st.integers(1, 4))
+    N = draw(st.integers(max(1, (T - 1) * G + 1), T * G + 20))
+    seed = draw(st.integers(0, 2 ** 31 - 1))
+    rng = np.random.default_rng(seed)
+    n_prune = draw(st.integers(0, min(N - 1, 25)))
+    pruned = rng.choice(N, size=n_prune, replace=False)
+    kept = np.setdiff1d(np.arange(N), pruned)
+    mask = np.zeros((K, N), np.uint8)
+    for t in range(0, len(kept), G):
+        cols = kept[t:t + G]
+        kt = int(rng.integers(1, K + 1))
+        rows = rng.choice(K, size=kt, replace=False)
+        mask[np.ix_(rows, cols)] = 1
+    return G, mask, seed
+
+
+@settings(max_examples=60, deadline=None)
+@given(tw_masks())
+def test_random_tile_wise_masks_round_trip(arg):
+    G, mask, seed = arg
+    rng = np.random.default_rng(seed + 1)
+    B = rng.integers(0, 65536, size=mask.shape).astype(np.uint16)
+    _check_against_oracle(mask, B, G, "f16" if seed % 2 else "bf16")
