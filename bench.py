@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the TW-sparse GEMM hot path on one MI355X.
+
+A "step" is one tw_gemm launch on the BERT-base FFN-up workload (M=16384 tokens, K=768, N=3072,
+fp16, G=128, 75 % tile-wise sparsity, 5 % of columns pruned), inputs resident in HBM.  The packer
+runs once before the timed region (the paper packs offline, Sec. VI "Tiling"); its time is reported
+separately.  The timed launches rotate over several (A, C) buffer sets that together exceed the
+256 MB last-level cache, so `value` is the cold-cache time; the warm time is reported next to it.
+
+Prints ONE JSON line on stdout.  `--report FILE` additionally writes a per-GEMM table for all five
+workloads (time, nonzero TFLOP/s, bytes/s, dense time, speedup) to FILE.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+MFMA_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA
+PAPER_CONTEXT = {"tw128_speedup_vs_dense_75pct": 2.26, "hardware": "NVIDIA V100 tensor cores, FP16",
+                 "where": "Sec. VII-B, Fig. 8b"}
+
+
+def algorithmic_bytes(info: dict, M: int) -> int:
+    """Bytes the method itself must move per launch: A once, the compacted tiles and their kept-row
+    lists once, C once (16-bit elements, 4-byte indices)."""
+    sum_kt = int(info["tile_row_ptr"][-1]) if info["T"] > 0 else 0
+    return 2 * M * info["K"] + 2 * int(info["nnz"]) + 4 * sum_kt + 2 * M * info["N"]
+
+
+def time_launches(torch, fn, n_sets: int, steps: int, warmup: int):
+    """Average duration of `steps` back-to-back launches, by HIP events on the launch stream."""
+    for i in range(warmup):
+        fn(i % n_sets)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        fn(i % n_sets)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def per_launch_stats(torch, fn, n_sets: int, steps: int):
+    """Individually bracketed launches: median / min in ms."""
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for i, (a, b) in enumerate(evs):
+        a.record()
+        fn(i % n_sets)
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return ts[len(ts) // 2], ts[0]
+
+
+def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = True, n_sets=None):
+    w = W.generate(spec)
+    t0 = time.perf_counter()
+    blob = tw.tw_pack(w.B, w.mask, spec.G, spec.dtype)
+    pack_ms = (time.perf_counter() - t0) * 1e3
+    wt = tw.TwWeight(blob)
+    info = wt.info
+    M = spec.M
+    td = torch.float16 if spec.dtype == "f16" else torch.bfloat16
+    set_bytes = 2 * M * (spec.K + spec.N)
+    if n_sets is None:
+        n_sets = max(3, -(-320 * 2 ** 20 // set_bytes))       # > 256 MB in rotation
+    A0 = tw.bits_to_tensor(w.A, spec.dtype)
+    As = [A0] + [A0.clone() for _ in range(n_sets - 1)]
+    Cs = [torch.empty((M, spec.N), dtype=td, device="cuda:0") for _ in range(n_sets)]
+    Bd = tw.bits_to_tensor(w.B, spec.dtype)
+
+    cold_ms, cold_wall = time_launches(torch, lambda i: tw.tw_gemm(wt, As[i], Cs[i]), n_sets, steps, warmup)
+    warm_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wt, As[0], Cs[0]), 1, steps, warmup)
+    med_ms, min_ms = per_launch_stats(torch, lambda i: tw.tw_gemm(wt, As[i], Cs[i]), n_sets, min(steps, 50))
+    out = dict(name=spec.name, M=M, K=spec.K, N=spec.N, G=spec.G, dtype=spec.dtype, T=int(info["T"]),
+               sparsity=w.info["sparsity"], tw_ms=cold_ms, tw_ms_warm=warm_ms, tw_ms_median=med_ms,
+               tw_ms_min=min_ms, tw_wall_ms=cold_wall, pack_ms=pack_ms, n_buffer_sets=n_sets)
+    nz_flops = W.nonzero_flops(w.mask, M)
+    dense_flops = 2.0 * M * spec.K * spec.N
+    abytes = algorithmic_bytes(info, M)
+    out.update(nonzero_gflop=nz_flops / 1e9, tw_tflops_nonzero=nz_flops / (cold_ms * 1e-3) / 1e12,
+               tw_mfma_frac_nonzero=nz_flops / (cold_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+               padded_mfma_frac=2.0 * M * int(info["padded_macs_per_row"]) / (cold_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+               algorithmic_bytes=abytes, tw_gbs=abytes / (cold_ms * 1e-3) / 1e9,
+               tw_hbm_frac=abytes / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS)
+    if with_dense:
+        d_ms, _ = time_launches(torch, lambda i: tw.tw_dense_gemm(As[i], Bd, Cs[i]), n_sets, steps, warmup)
+        out.update(dense_ms=d_ms, dense_tflops=dense_flops / (d_ms * 1e-3) / 1e12,
+                   dense_mfma_frac=dense_flops / (d_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                   speedup_vs_dense=d_ms / cold_ms)
+        # context only: the vendor library's dense GEMM through torch
+        t_ms, _ = time_launches(torch, lambda i: torch.matmul(As[i], Bd, out=Cs[i]), n_sets, steps, warmup)
+        out.update(torch_matmul_ms=t_ms)
+    return out, w, info
+
+
+def cpu_baseline(W, w, spec, budget_s: float = 15.0):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import tw_ref
+    cal_rows = min(128, spec.M)
+    t0 = time.perf_counter()
+    tw_ref.masked_gemm(np.ascontiguousarray(w.A[:cal_rows]), w.B, w.mask, spec.dtype)
+    cal = time.perf_counter() - t0
+    rows = int(min(spec.M, max(cal_rows, budget_s / max(cal, 1e-6) * cal_rows)))
+    rows = max(8, rows // 8 * 8)
+    t0 = time.perf_counter()
+    tw_ref.masked_gemm(np.ascontiguousarray(w.A[:rows]), w.B, w.mask, spec.dtype)
+    dt = time.perf_counter() - t0
+    full_ms = dt / rows * spec.M * 1e3
+    return {"value": full_ms, "unit": "ms", "cores": tw_ref.num_threads(), "kind": "oracle",
+            "sample": f"first {rows} of {spec.M} rows of A in {dt:.2f} s (fp64 masked triple loop, OpenMP), "
+                      f"scaled to all rows"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--report", type=str, default=None, help="also time all five workloads, write a table here")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the path needs no collective; see DESIGN.md for how "
+              "it would shard); re-run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2008_13006_amd import binding as tw
+    from paper_2008_13006_amd import workloads as W
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+
+    spec = W.CONFIGS["c2_bert_base_ffn_up"][0]
+    res, w, info = bench_gemm(torch, tw, W, spec, args.steps, args.warmup)
+    line = {
+        "metric": "tw_gemm_ms (TW-sparse GEMM time, BERT-base FFN-up, 75% tile-wise sparsity)",
+        "value": res["tw_ms"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["tw_ms"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "c2_bert_base_ffn_up: M=16384 K=768 N=3072 fp16 G=128, 75% TW sparsity, "
+                               "5% columns pruned, tiles 10-50% kept", "T": res["T"],
+                   "sparsity": round(res["sparsity"], 4), "cache": f"cold: {res['n_buffer_sets']} rotating (A,C) sets"},
+        "speedup_vs_dense": res["speedup_vs_dense"], "dense_ms": res["dense_ms"],
+        "dense_tflops": res["dense_tflops"], "dense_mfma_frac": res["dense_mfma_frac"],
+        "tw_tflops_nonzero": res["tw_tflops_nonzero"], "mfma_util_nonzero": res["tw_mfma_frac_nonzero"],
+        "mfma_util_issued": res["padded_mfma_frac"],
+        "tw_ms_warm": res["tw_ms_warm"], "tw_ms_median": res["tw_ms_median"], "tw_ms_min": res["tw_ms_min"],
+        "torch_matmul_dense_ms_context": res["torch_matmul_ms"], "pack_ms_offline": res["pack_ms"],
+        "roofline": {"bound": "hbm", "achieved": res["tw_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": res["tw_hbm_frac"], "traffic": None,
+                     "kernel": "tw_gemm_kernel<f16, 64 rows, G=128, K resident>",
+                     "algorithmic_bytes_per_launch": res["algorithmic_bytes"]},
+        "paper_context": PAPER_CONTEXT,
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "tw_gemm_c2_traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            line["roofline"]["traffic"] = json.load(open(traffic_file)).get("hbm_bytes_per_launch")
+        except Exception:
+            pass
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(W, w, spec)
+    if args.report:
+        rows = []
+        for cfg, specs in W.CONFIGS.items():
+            for s in specs:
+                r, _, _ = bench_gemm(torch, tw, W, s, max(20, args.steps // 4), 5)
+                r["config"] = cfg
+                rows.append(r)
+                print(f"[report] {cfg}/{s.name}: tw {r['tw_ms']*1e3:.1f} us  dense {r['dense_ms']*1e3:.1f} us  "
+                      f"x{r['speedup_vs_dense']:.2f}  nz {r['tw_tflops_nonzero']:.0f} TF  {r['tw_gbs']:.0f} GB/s",
+                      file=sys.stderr, flush=True)
+                torch.cuda.empty_cache()
+        with open(args.report, "w") as f:
+            json.dump(rows, f, indent=1)
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -35,7 +35,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
         obj = os.path.join(CSRC, src + ".o")
         cmd = [hipcc(), "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wno-unused-command-line-argument", "-c", os.path.join(CSRC, src), "-o", obj]
+               "-Wno-unused-command-line-argument"] + os.environ.get("TW_BUILD_FLAGS", "").split() + [
+               "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)

@@ -7,6 +7,8 @@
 // while step i is multiplied.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "../../include/tw.h"
 #include "tw_device.hpp"
 
@@ -148,11 +150,9 @@ __global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p)
     const int col0 = n0 + wn * 64;
     const int width = (p.N - col0) < 64 ? (p.N - col0) : 64;
     if (width > 0) {
-        auto dst = [](int, int, int) -> unsigned { return 0u; };
 #pragma unroll
         for (int ms = 0; ms < 4; ++ms)
-            tw_store_block<DT, 2>(acc[ms], dst, true, stage, p.C, p.ldc, m0 + wm * 128 + ms * 32, p.M, col0, width,
-                                  lane);
+            tw_store_block<DT, 2>(acc[ms], stage, p.C, p.ldc, m0 + wm * 128 + ms * 32, p.M, col0, width, lane);
     }
 }
 
@@ -174,8 +174,14 @@ extern "C" int tw_dense_gemm(const void* A, int lda, const void* B, int ldb, voi
     const long blocks = (long)p.nbm * p.nbn;
     if (blocks > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
     auto fn = dt == TW_F16 ? tw_dense_kernel<TW_F16> : tw_dense_kernel<TW_BF16>;
-    if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
-        return TW_ERR_HIP;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return TW_ERR_HIP;
+    static std::atomic<unsigned char> lds_set[64][2];
+    if (!lds_set[dev][dt].load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+            return TW_ERR_HIP;
+        lds_set[dev][dt].store(1, std::memory_order_release);
+    }
     hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(kThreads), LDS_BYTES, (hipStream_t)hip_stream, p);
     return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
 }

@@ -51,74 +51,73 @@ __device__ __forceinline__ void tw_wave_lds_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
-// Staging area of one wave in the epilogue: 32 rows x 64 columns of 16-bit values, rows 136 bytes
-// apart (the 8 extra bytes spread rows over the LDS banks).
+// Staging area of one wave in the epilogue.  The dense kernel uses it as 32 rows x 64 columns of
+// 16-bit values, rows 136 bytes apart (the 8 extra bytes spread rows over the LDS banks); the TW
+// kernel as 16 rows x 144 columns, rows 304 bytes apart.
 #define TW_STAGE_PITCH 136
-#define TW_STAGE_BYTES (32 * TW_STAGE_PITCH)
+#define TW_STAGE_BYTES 4864
 #define TW_STAGE_COLS 64
 
 typedef tw_u32x4 __attribute__((aligned(2))) tw_u32x4_a2;
+typedef tw_u32x2 __attribute__((aligned(2))) tw_u32x2_a2;
+typedef unsigned int __attribute__((aligned(2))) tw_u32_a2;
 
-// Writes one 32-row block of a wave's results to C through the wave's LDS staging area.
-//   acc[cb][r]     fp32 results of the block: lane l owns row (l%32), column c = 32*cb + 8*(r/4) + 4*(l/32) + r%4
-//   dst(cb, q, e)  destination column of c = 32*cb+8*q+4*(l/32)+e relative to `col0`, or >= 0xFFFF: none
-//   width          columns [col0, col0+width) of C are written, positions nobody fills get zeros
-template <int DT, int NCB, typename DstFn>
-__device__ __forceinline__ void tw_store_block(const tw_f32x16 (&acc)[NCB], DstFn dst, bool contiguous,
-                                               unsigned char* stage, unsigned short* C, long ldc,
-                                               int row0, int M, int col0, int width, int lane) {
+#ifdef TW_EXPERIMENT
+// per-wave event trace: (tag, clock) pairs
+struct TwTrace {
+    long long* buf;
+    int n;
+    __device__ __forceinline__ void mark(int tag, int lane) {
+        if (buf && lane == 0 && n < 64) { buf[2 * n] = tag; buf[2 * n + 1] = (long long)__builtin_readcyclecounter(); ++n; }
+    }
+};
+#define TW_MARK(tr, tag, lane) (tr).mark((tag), (lane))
+#else
+struct TwTrace {};
+#define TW_MARK(tr, tag, lane) ((void)0)
+#endif
+
+// Writes one 32-row block of a wave's results to C[row0.., col0 .. col0+width) through the wave's
+// LDS staging area, 64 columns at a time (used where result column c goes to column col0 + c).
+//   acc[cb][r]   fp32 results: lane l owns row (l%32) and column c = 32*cb + 8*(r/4) + 4*(l/32) + r%4
+template <int DT, int NCB>
+__device__ __forceinline__ void tw_store_block(const tw_f32x16 (&acc)[NCB], unsigned char* stage, unsigned short* C,
+                                               long ldc, int row0, int M, int col0, int width, int lane) {
     const int mrow = lane & 31, h = lane >> 5;
+    unsigned char* myrow = stage + mrow * TW_STAGE_PITCH;
     for (int w0 = 0; w0 < width; w0 += TW_STAGE_COLS) {
-        // clear the window
-#pragma unroll
-        for (int i = 0; i < (TW_STAGE_BYTES + 1023) / 1024; ++i) {
-            const int off = i * 1024 + lane * 16;
-            if (off < TW_STAGE_BYTES) *(tw_u32x4*)(stage + off) = tw_u32x4{0u, 0u, 0u, 0u};
-        }
-        tw_wave_lds_sync();
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                if (contiguous) {
-                    const int d0 = 32 * cb + 8 * q + 4 * h - w0;   // multiple of 4
-                    if (d0 >= 0 && d0 < TW_STAGE_COLS) {
-                        tw_u32x2 v;
-                        v.x = (unsigned)tw_cvt<DT>(acc[cb][4 * q + 0]) | ((unsigned)tw_cvt<DT>(acc[cb][4 * q + 1]) << 16);
-                        v.y = (unsigned)tw_cvt<DT>(acc[cb][4 * q + 2]) | ((unsigned)tw_cvt<DT>(acc[cb][4 * q + 3]) << 16);
-                        *(tw_u32x2*)(stage + mrow * TW_STAGE_PITCH + d0 * 2) = v;
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int d = (int)dst(cb, q, e) - w0;
-                        if (d >= 0 && d < TW_STAGE_COLS)
-                            *(unsigned short*)(stage + mrow * TW_STAGE_PITCH + d * 2) = tw_cvt<DT>(acc[cb][4 * q + e]);
-                    }
-                }
+                const int c_lo = 32 * cb + 8 * q;          // wave-uniform: columns c_lo .. c_lo+7
+                if (c_lo < w0 || c_lo >= w0 + TW_STAGE_COLS) continue;
+                tw_u32x2 v;
+                v.x = (unsigned)tw_cvt<DT>(acc[cb][4 * q + 0]) | ((unsigned)tw_cvt<DT>(acc[cb][4 * q + 1]) << 16);
+                v.y = (unsigned)tw_cvt<DT>(acc[cb][4 * q + 2]) | ((unsigned)tw_cvt<DT>(acc[cb][4 * q + 3]) << 16);
+                *(tw_u32x2*)(myrow + (c_lo + 4 * h - w0) * 2) = v;
             }
         }
         tw_wave_lds_sync();
         // 8 lanes cover the 64 columns of a row with 16-byte pieces, 8 rows per pass
         const int j = lane & 7;
-        const int cw = w0 + 8 * j;              // column inside [0, width)
-        const int nvalid = width - cw;          // > 0: something to store
+        const int left = width - w0;                 // columns of this window that exist (may exceed 64)
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int r = (lane >> 3) + 8 * p;
             const int grow = row0 + r;
             const tw_u32x2 lo = *(const tw_u32x2*)(stage + r * TW_STAGE_PITCH + j * 16);
             const tw_u32x2 hi = *(const tw_u32x2*)(stage + r * TW_STAGE_PITCH + j * 16 + 8);
-            if (grow < M && nvalid > 0) {
-                unsigned short* dstp = C + (long)grow * ldc + col0 + cw;
-                if (nvalid >= 8) {
-                    *(tw_u32x4_a2*)dstp = tw_u32x4{lo.x, lo.y, hi.x, hi.y};
-                } else {
-                    const unsigned v[4] = {lo.x, lo.y, hi.x, hi.y};
-#pragma unroll
-                    for (int e = 0; e < 7; ++e)
-                        if (e < nvalid) dstp[e] = (unsigned short)(v[e >> 1] >> (16 * (e & 1)));
-                }
+            if (grow < M && 8 * j + 8 <= left)
+                *(tw_u32x4_a2*)(C + (long)grow * ldc + col0 + w0 + 8 * j) = tw_u32x4{lo.x, lo.y, hi.x, hi.y};
+        }
+        // ragged end of the row: fewer than 8 columns left in the last group, one row per lane
+        if (left < TW_STAGE_COLS && (left & 7) != 0) {
+            const int rem = left & 7, cbeg = left & ~7;
+            const int grow = row0 + mrow;
+            if (h == 0 && grow < M) {
+                unsigned short* dstp = C + (long)grow * ldc + col0 + w0 + cbeg;
+                for (int e = 0; e < rem; ++e) dstp[e] = *(const unsigned short*)(myrow + (cbeg + e) * 2);
             }
         }
         tw_wave_lds_sync();

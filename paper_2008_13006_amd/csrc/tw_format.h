@@ -4,14 +4,13 @@
 #include <stdint.h>
 
 #define TW_MAGIC 0x31425754u /* "TWB1" */
-#define TW_FORMAT_VERSION 1
+#define TW_FORMAT_VERSION 5
 
 // MFMA step geometry the packed values are laid out for: one step contracts 16 kept rows
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
 #define TW_KSTEP 16
 #define TW_COLBLK 32
-// Byte offset (inside an LDS row of A) that padded contraction slots gather from: the row's
-// zeroed pad, directly behind the k_chunk staged elements.  Stored as k_chunk*2 in the tables.
+// Padded contraction slots gather row `k_chunk` of the LDS copy of A, which the kernel keeps zero.
 
 struct TwHeader {
     uint32_t magic;
@@ -28,12 +27,15 @@ struct TwHeader {
         off_sched_order;
     uint64_t off_tile_desc;  // TwTileDesc[T], canonical tile order
     uint64_t off_step_ptr;   // int32 [T][n_chunks+1]: first step of every chunk, per tile
-    uint64_t off_goff;       // uint16 [total_steps][16]: LDS byte offsets of the gathered rows
-    uint64_t off_dcol;       // uint16 [T][2][ncb][4][4]: destination column (relative to the span
-                             //   start) of packed column c = 32*cb + 8*q + 4*h + e, stored at
-                             //   [h][cb][q][e]; 0xFFFF for c >= w
+    uint64_t off_goff;       // uint16 [total_steps][16]: chunk-local K index of every contraction slot,
+                             //   slot s = 8*h + 4*r + q stored at [h][q][r] (the order the lanes of a
+                             //   transposing LDS read consume them); k_chunk for padded slots
+    uint64_t off_dpos;       // uint32 [T][32][ncb]: destination column of packed column c = 32*cb + n, stored
+                             //   at [n][cb], counted from the 8-aligned column at or below the tile's
+                             //   span start; 0xFFFFFFFF for c >= w
     uint64_t off_bvals;      // 16-bit weights: per tile, per step, per column block, per lane 8 values
-    uint8_t pad[256 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 5];
+    uint64_t off_sched_desc; // TwSchedDesc[T], kept-K-descending order (what the kernel walks)
+    uint8_t pad[256 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 6];
 };
 static_assert(sizeof(TwHeader) == 256, "header is 256 bytes");
 
@@ -47,15 +49,27 @@ struct TwTileDesc {
     int32_t step_ptr;    // index of this tile's row in the step_ptr table (int32 units)
     int32_t first_step;  // index of this tile's first step in the goff table
     uint64_t bvals_off;  // byte offset from blob start of this tile's packed values
-    uint32_t dcol_off;   // byte offset from blob start of this tile's dcol table
-    uint32_t reserved;
+    uint32_t reserved1;
+    uint32_t reserved2;
     uint8_t pad[64 - 4 * 8 - 8 - 4 * 2];
 };
 static_assert(sizeof(TwTileDesc) == 64, "tile descriptor is 64 bytes");
 
 #define TW_TILE_NOGAP 1
 
-// Chunking policy: the whole K extent stays resident when it fits next to the epilogue staging
-// area with 32-row blocks; otherwise A is streamed in double-buffered chunks.
-#define TW_K_RESIDENT_MAX 1984
+// What the kernel needs of a tile, 32 bytes, in schedule order.
+struct TwSchedDesc {
+    int32_t w;           // kept columns
+    int32_t span_start;  // first original column owned
+    int32_t span_w;      // original columns owned
+    int32_t nsteps;      // 16-row steps, all chunks
+    int32_t tile;        // canonical tile number (selects the dpos table)
+    int32_t step_ptr;    // row of the step_ptr table (int32 units)
+    int32_t first_step;  // first step in the goff / bvals tables
+    int32_t reserved;
+};
+
+// Chunking policy: the whole K extent of a 32-row block stays resident in LDS when it fits next to
+// the epilogue staging area; otherwise A is streamed in chunks.
+#define TW_K_RESIDENT_MAX 1536
 #define TW_K_STREAM_CHUNK 384

@@ -28,7 +28,7 @@ struct Layout {
     std::vector<int32_t> first_step;  // [T] global step index
     int64_t total_steps = 0;
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
-        off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dcol, off_bvals, bytes;
+        off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, bytes;
 };
 
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -120,9 +120,10 @@ void plan(const Tiling& tl, int K, int G, Layout& lo) {
     lo.off_tile_span = take(4 * (size_t)(T + 1), 16);
     lo.off_sched_order = take(4 * (size_t)T, 16);
     lo.off_tile_desc = take(sizeof(TwTileDesc) * (size_t)T, 64);
+    lo.off_sched_desc = take(sizeof(TwSchedDesc) * (size_t)T, 64);
     lo.off_step_ptr = take(4 * lo.step_ptr.size(), 16);
     lo.off_goff = take(2 * 16 * (uint64_t)total, 256);
-    lo.off_dcol = take(2 * (uint64_t)T * G, 256);
+    lo.off_dpos = take(4 * (uint64_t)T * 32 * lo.ncb, 256);
     lo.off_bvals = take(2 * (uint64_t)total * lo.ncb * 64 * 8, 256);
     lo.bytes = align_up(o, 256);
 }
@@ -132,7 +133,6 @@ int check_common(const uint8_t* mask, int K, int N, int G, int dt) {
     if (dt != TW_F16 && dt != TW_BF16) return TW_ERR_ARG;
     if (G <= 0) return TW_ERR_ARG;
     if (!supported_g(G)) return TW_ERR_UNSUPPORTED;
-    if ((int64_t)K * 2 + 8 > 65535 && K <= TW_K_RESIDENT_MAX) return TW_ERR_UNSUPPORTED;
     return TW_OK;
 }
 
@@ -187,7 +187,8 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
     h->off_tile_row_ptr = lo.off_tile_row_ptr; h->off_row_idx = lo.off_row_idx;
     h->off_tile_span = lo.off_tile_span; h->off_sched_order = lo.off_sched_order;
     h->off_tile_desc = lo.off_tile_desc; h->off_step_ptr = lo.off_step_ptr;
-    h->off_goff = lo.off_goff; h->off_dcol = lo.off_dcol; h->off_bvals = lo.off_bvals;
+    h->off_goff = lo.off_goff; h->off_dpos = lo.off_dpos; h->off_bvals = lo.off_bvals;
+    h->off_sched_desc = lo.off_sched_desc;
 
     auto put = [&](uint64_t off, const std::vector<int32_t>& v) {
         if (!v.empty()) std::memcpy(base + off, v.data(), 4 * v.size());
@@ -208,10 +209,10 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
     put(lo.off_sched_order, order);
 
     const uint16_t* Bv = (const uint16_t*)B;
-    const uint16_t pad_off = (uint16_t)(2 * lo.k_chunk);
+    const uint16_t pad_k = (uint16_t)lo.k_chunk;
     TwTileDesc* desc = (TwTileDesc*)(base + lo.off_tile_desc);
     uint16_t* goff = (uint16_t*)(base + lo.off_goff);
-    uint16_t* dcol_all = (uint16_t*)(base + lo.off_dcol);
+    uint32_t* dpos_all = (uint32_t*)(base + lo.off_dpos);
     uint16_t* bvals = (uint16_t*)(base + lo.off_bvals);
     const int ncb = lo.ncb;
 
@@ -228,26 +229,25 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
         d.step_ptr = t * (lo.n_chunks + 1);
         d.first_step = lo.first_step[t];
         d.bvals_off = lo.off_bvals + 2 * (uint64_t)lo.first_step[t] * ncb * 64 * 8;
-        d.dcol_off = (uint32_t)(lo.off_dcol + 2 * (uint64_t)t * G);
         bool nogap = true;
         for (int c = 0; c < w; ++c)
             if (tl.col_idx[c0 + c] != d.span_start + c) { nogap = false; break; }
         d.flags = nogap ? TW_TILE_NOGAP : 0;
 
-        // destination columns, stored in the order the epilogue's lanes consume them
-        uint16_t* dc = dcol_all + (size_t)t * G;
-        for (int hh = 0; hh < 2; ++hh)
-            for (int cb = 0; cb < ncb; ++cb)
-                for (int q = 0; q < 4; ++q)
-                    for (int e = 0; e < 4; ++e) {
-                        const int c = 32 * cb + 8 * q + 4 * hh + e;
-                        dc[((hh * ncb + cb) * 4 + q) * 4 + e] =
-                            c < w ? (uint16_t)(tl.col_idx[c0 + c] - d.span_start) : (uint16_t)0xFFFF;
-                    }
+        // destination columns, counted from the aligned column at or below the span start
+        {
+            uint32_t* dp = dpos_all + (size_t)t * 32 * ncb;
+            const int origin = d.span_start / 8 * 8;
+            for (int n = 0; n < 32; ++n)
+                for (int cb = 0; cb < ncb; ++cb) {
+                    const int c = 32 * cb + n;
+                    dp[n * ncb + cb] = c < w ? (uint32_t)(tl.col_idx[c0 + c] - origin) : 0xFFFFFFFFu;
+                }
+        }
 
         // gather offsets and packed values, chunk by chunk
         uint16_t* tg = goff + (size_t)lo.first_step[t] * 16;
-        for (int s = 0; s < nsteps * 16; ++s) tg[s] = pad_off;
+        for (int s = 0; s < nsteps * 16; ++s) tg[s] = pad_k;
         uint16_t* tb = bvals + (size_t)lo.first_step[t] * ncb * 64 * 8;
         int p = 0;
         for (int c = 0; c < lo.n_chunks; ++c) {
@@ -255,9 +255,9 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
             int slot = sp[c] * 16;
             while (p < kt && tl.row_idx[r0 + p] < hi) {
                 const int k = tl.row_idx[r0 + p];
-                tg[slot] = (uint16_t)(2 * (k - kbase));
                 const int s = slot / 16, kl = slot % 16;       // step, contraction slot in the step
                 const int half = kl / 8, e = kl % 8;
+                tg[s * 16 + (half * 4 + (e & 3)) * 2 + (e >> 2)] = (uint16_t)(k - kbase);
                 for (int cc = 0; cc < w; ++cc) {
                     const int cb = cc / 32, lane = 32 * half + cc % 32;
                     tb[(((size_t)s * ncb + cb) * 64 + lane) * 8 + e] =
@@ -266,6 +266,13 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
                 ++slot; ++p;
             }
         }
+    }
+    TwSchedDesc* sd = (TwSchedDesc*)(base + lo.off_sched_desc);
+    for (int i = 0; i < tl.T; ++i) {
+        const TwTileDesc& d = desc[order[i]];
+        sd[i].w = d.w; sd[i].span_start = d.span_start; sd[i].span_w = d.span_w; sd[i].nsteps = d.nsteps;
+        sd[i].tile = order[i]; sd[i].step_ptr = d.step_ptr; sd[i].first_step = d.first_step;
+        sd[i].reserved = 0;
     }
     return TW_OK;
 }
