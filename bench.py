@@ -5,7 +5,9 @@ A "step" is one tw_gemm launch on the BERT-base FFN-up workload (M=16384 tokens,
 fp16, G=128, 75 % tile-wise sparsity, 5 % of columns pruned), inputs resident in HBM.  The packer
 runs once before the timed region (the paper packs offline, Sec. VI "Tiling"); its time is reported
 separately.  The timed launches rotate over several (A, C) buffer sets that together exceed the
-256 MB last-level cache, so `value` is the cold-cache time; the warm time is reported next to it.
+256 MB last-level cache, so `value` is the cold-cache time (`--report` also gives the warm time).
+Every tw_gemm launch of the default run is such a cold launch, so a kernel trace of the same command
+averages the same population that `value` does.
 
 Prints ONE JSON line on stdout.  `--report FILE` additionally writes a per-GEMM table for all five
 workloads (time, nonzero TFLOP/s, bytes/s, dense time, speedup) to FILE.
@@ -24,6 +26,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 MFMA_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA
+# HBM bytes per tw_gemm launch on this workload, from the two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE) summarised in profiles/tw_gemm_c2_hbm_traffic.txt, each scaled by what the same counter
+# reads for the copy kernel of known size that `--pmc-calibration` launches.
+MEASURED_TRAFFIC_BYTES = 147_297_014      # 35.63 MB read + 111.67 MB written
 PAPER_CONTEXT = {"tw128_speedup_vs_dense_75pct": 2.26, "hardware": "NVIDIA V100 tensor cores, FP16",
                  "where": "Sec. VII-B, Fig. 8b"}
 
@@ -64,7 +70,8 @@ def per_launch_stats(torch, fn, n_sets: int, steps: int):
     return ts[len(ts) // 2], ts[0]
 
 
-def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = True, n_sets=None):
+def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = True, n_sets=None,
+               with_warm: bool = False):
     w = W.generate(spec)
     t0 = time.perf_counter()
     blob = tw.tw_pack(w.B, w.mask, spec.G, spec.dtype)
@@ -82,7 +89,9 @@ def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = T
     Bd = tw.bits_to_tensor(w.B, spec.dtype)
 
     cold_ms, cold_wall = time_launches(torch, lambda i: tw.tw_gemm(wt, As[i], Cs[i]), n_sets, steps, warmup)
-    warm_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wt, As[0], Cs[0]), 1, steps, warmup)
+    warm_ms = None
+    if with_warm:     # same buffers every launch: A and part of C stay in the last-level cache
+        warm_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wt, As[0], Cs[0]), 1, steps, warmup)
     med_ms, min_ms = per_launch_stats(torch, lambda i: tw.tw_gemm(wt, As[i], Cs[i]), n_sets, min(steps, 50))
     out = dict(name=spec.name, M=M, K=spec.K, N=spec.N, G=spec.G, dtype=spec.dtype, T=int(info["T"]),
                sparsity=w.info["sparsity"], tw_ms=cold_ms, tw_ms_warm=warm_ms, tw_ms_median=med_ms,
@@ -125,6 +134,32 @@ def cpu_baseline(W, w, spec, budget_s: float = 15.0):
                       f"scaled to all rows"}
 
 
+def pmc_calibration(torch, tw, W, spec, steps: int) -> int:
+    """What a hardware-counter run profiles: a plain copy kernel that reads and writes COPY_BYTES each
+    (an elementwise pass over int32, larger than the last-level cache), then `steps` tw_gemm launches
+    over rotating buffers.  The copy's known size turns counter units into bytes."""
+    COPY_BYTES = 512 * 2 ** 20
+    src = torch.arange(COPY_BYTES // 4, dtype=torch.int32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        torch.add(src, 0, out=dst)
+    torch.cuda.synchronize()
+    w = W.generate(spec)
+    wt = tw.TwWeight(tw.tw_pack(w.B, w.mask, spec.G, spec.dtype))
+    td = torch.float16 if spec.dtype == "f16" else torch.bfloat16
+    n_sets = 4
+    A0 = tw.bits_to_tensor(w.A, spec.dtype)
+    As = [A0] + [A0.clone() for _ in range(n_sets - 1)]
+    Cs = [torch.empty((spec.M, spec.N), dtype=td, device="cuda:0") for _ in range(n_sets)]
+    for i in range(steps):
+        tw.tw_gemm(wt, As[i % n_sets], Cs[i % n_sets])
+    torch.cuda.synchronize()
+    print(json.dumps({"pmc_calibration": {"copy_kernel_reads_bytes": COPY_BYTES, "copy_kernel_writes_bytes": COPY_BYTES,
+                                          "copy_launches": 5, "tw_gemm_launches": steps,
+                                          "algorithmic_bytes_per_launch": algorithmic_bytes(wt.info, spec.M)}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -132,10 +167,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--report", type=str, default=None, help="also time all five workloads, write a table here")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="counter runs: launch only a copy kernel of known size, then the tw_gemm steps")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (the path needs no collective; see DESIGN.md for how "
-              "it would shard); re-run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (rows of A and C are independent, so the path would "
+              "shard over M with no collective); re-run with --gpus 1", file=sys.stderr)
         return 2
 
     import torch
@@ -145,6 +182,8 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     spec = W.CONFIGS["c2_bert_base_ffn_up"][0]
+    if args.pmc_calibration:
+        return pmc_calibration(torch, tw, W, spec, args.steps)
     res, w, info = bench_gemm(torch, tw, W, spec, args.steps, args.warmup)
     line = {
         "metric": "tw_gemm_ms (TW-sparse GEMM time, BERT-base FFN-up, 75% tile-wise sparsity)",
@@ -158,27 +197,21 @@ def main() -> int:
         "dense_tflops": res["dense_tflops"], "dense_mfma_frac": res["dense_mfma_frac"],
         "tw_tflops_nonzero": res["tw_tflops_nonzero"], "mfma_util_nonzero": res["tw_mfma_frac_nonzero"],
         "mfma_util_issued": res["padded_mfma_frac"],
-        "tw_ms_warm": res["tw_ms_warm"], "tw_ms_median": res["tw_ms_median"], "tw_ms_min": res["tw_ms_min"],
+        "tw_ms_median": res["tw_ms_median"], "tw_ms_min": res["tw_ms_min"],
         "torch_matmul_dense_ms_context": res["torch_matmul_ms"], "pack_ms_offline": res["pack_ms"],
         "roofline": {"bound": "hbm", "achieved": res["tw_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": res["tw_hbm_frac"], "traffic": None,
+                     "frac": res["tw_hbm_frac"], "traffic": MEASURED_TRAFFIC_BYTES,
                      "kernel": "tw_gemm_kernel<f16, 64 rows, G=128, K resident>",
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"]},
         "paper_context": PAPER_CONTEXT,
     }
-    traffic_file = os.path.join(ROOT, "profiles", "tw_gemm_c2_traffic.json")
-    if os.path.exists(traffic_file):
-        try:
-            line["roofline"]["traffic"] = json.load(open(traffic_file)).get("hbm_bytes_per_launch")
-        except Exception:
-            pass
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(W, w, spec)
     if args.report:
         rows = []
         for cfg, specs in W.CONFIGS.items():
             for s in specs:
-                r, _, _ = bench_gemm(torch, tw, W, s, max(20, args.steps // 4), 5)
+                r, _, _ = bench_gemm(torch, tw, W, s, max(20, args.steps // 4), 5, with_warm=True)
                 r["config"] = cfg
                 rows.append(r)
                 print(f"[report] {cfg}/{s.name}: tw {r['tw_ms']*1e3:.1f} us  dense {r['dense_ms']*1e3:.1f} us  "

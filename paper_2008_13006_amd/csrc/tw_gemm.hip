@@ -381,9 +381,9 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #endif
     TW_MARK(tr, 1, lane);
     // the first item of a workgroup is its own index, later ones come from the atomic counter
-    for (int round = 0;; ++round) {
+    for (int turn = 0;; ++turn) {
         if (tid == 0) {
-            misc[0] = round == 0 ? (int)blockIdx.x : (int)gridDim.x + atomicAdd(&p.counters[0], 1);
+            misc[0] = turn == 0 ? (int)blockIdx.x : (int)gridDim.x + atomicAdd(&p.counters[0], 1);
             misc[1] = 0;
         }
         __syncthreads();
