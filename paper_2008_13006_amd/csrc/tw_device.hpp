@@ -53,7 +53,7 @@ __device__ __forceinline__ void tw_wave_lds_sync() {
 
 // Staging area of one wave in the epilogue.  The dense kernel uses it as 32 rows x 64 columns of
 // 16-bit values, rows 136 bytes apart (the 8 extra bytes spread rows over the LDS banks); the TW
-// kernel as 16 rows x 144 columns, rows 304 bytes apart.
+// kernel as 8 rows x 256 columns, rows 528 bytes apart.
 #define TW_STAGE_PITCH 136
 #define TW_STAGE_BYTES 4864
 #define TW_STAGE_COLS 64
@@ -61,21 +61,6 @@ __device__ __forceinline__ void tw_wave_lds_sync() {
 typedef tw_u32x4 __attribute__((aligned(2))) tw_u32x4_a2;
 typedef tw_u32x2 __attribute__((aligned(2))) tw_u32x2_a2;
 typedef unsigned int __attribute__((aligned(2))) tw_u32_a2;
-
-#ifdef TW_EXPERIMENT
-// per-wave event trace: (tag, clock) pairs
-struct TwTrace {
-    long long* buf;
-    int n;
-    __device__ __forceinline__ void mark(int tag, int lane) {
-        if (buf && lane == 0 && n < 64) { buf[2 * n] = tag; buf[2 * n + 1] = (long long)__builtin_readcyclecounter(); ++n; }
-    }
-};
-#define TW_MARK(tr, tag, lane) (tr).mark((tag), (lane))
-#else
-struct TwTrace {};
-#define TW_MARK(tr, tag, lane) ((void)0)
-#endif
 
 // Writes one 32-row block of a wave's results to C[row0.., col0 .. col0+width) through the wave's
 // LDS staging area, 64 columns at a time (used where result column c goes to column col0 + c).

@@ -4,11 +4,13 @@
 #include <stdint.h>
 
 #define TW_MAGIC 0x31425754u /* "TWB1" */
-#define TW_FORMAT_VERSION 5
+#define TW_FORMAT_VERSION 6
 
 // MFMA step geometry the packed values are laid out for: one step contracts 16 kept rows
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
 #define TW_KSTEP 16
+// Waves per workgroup of the TW kernel (the packer shapes the dispatch order for it).
+#define TW_WAVES_PER_WG 8
 #define TW_COLBLK 32
 // Padded contraction slots gather row `k_chunk` of the LDS copy of A, which the kernel keeps zero.
 
@@ -34,7 +36,7 @@ struct TwHeader {
                              //   at [n][cb], counted from the 8-aligned column at or below the tile's
                              //   span start; 0xFFFFFFFF for c >= w
     uint64_t off_bvals;      // 16-bit weights: per tile, per step, per column block, per lane 8 values
-    uint64_t off_sched_desc; // TwSchedDesc[T], kept-K-descending order (what the kernel walks)
+    uint64_t off_sched_desc; // TwSchedDesc[T], dispatch order (what the kernel walks)
     uint8_t pad[256 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 6];
 };
 static_assert(sizeof(TwHeader) == 256, "header is 256 bytes");
@@ -57,7 +59,7 @@ static_assert(sizeof(TwTileDesc) == 64, "tile descriptor is 64 bytes");
 
 #define TW_TILE_NOGAP 1
 
-// What the kernel needs of a tile, 32 bytes, in schedule order.
+// What the kernel needs of a tile, 32 bytes, in dispatch order.
 struct TwSchedDesc {
     int32_t w;           // kept columns
     int32_t span_start;  // first original column owned

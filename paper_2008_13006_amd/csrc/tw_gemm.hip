@@ -26,11 +26,23 @@
 #include "tw_device.hpp"
 #include "tw_format.h"
 
+#if defined(TW_EXPERIMENT) && defined(TW_TRACE)
+#define TW_MARK() do { if (p.trace && nmark < 16) { unsigned long long t_ = __builtin_readcyclecounter(); \
+    if (lane == 0) p.trace[((long)blockIdx.x * kWaves + wave) * 16 + nmark] = (unsigned)t_; ++nmark; } } while (0)
+#else
+#define TW_MARK() do {} while (0)
+#endif
+#if defined(TW_EXPERIMENT) && defined(TW_DBG_CONST)
+#define TWD(x) (TW_DBG_CONST)
+#else
+#define TWD(x) (x)
+#endif
+
 namespace {
 
-constexpr int kWaves = 8;
+constexpr int kWaves = TW_WAVES_PER_WG;
 constexpr int kThreads = kWaves * 64;
-constexpr int kPrefetch = 3;  // B-operand steps in flight per wave
+constexpr int kPrefetch = 2;  // B-operand steps in flight per wave
 
 typedef short tw_i16x4 __attribute__((ext_vector_type(4)));
 
@@ -49,7 +61,7 @@ struct TwGemmParams {
     uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals;
 #ifdef TW_EXPERIMENT
     int dbg;  // bit0: no A load, bit1: no main loop, bit2: no epilogue
-    long long* trace;
+    unsigned* trace;  // per wave 16 clock samples
 #endif
 };
 
@@ -84,8 +96,9 @@ __device__ __forceinline__ TileU fetch_tile(const TwGemmParams& p, int ti) {
 // Cooperative load of A[row0 .. row0+32*MS) x [k0, k0+kw) into LDS, transposed: LDS row k (pitch
 // at_pitch bytes) holds the 32*MS values A[row0 .. , k0+k].  A wave instruction reads 8 rows x 128
 // contiguous bytes of A (8 lanes x 16 B per row) and scatters them with eight 2-byte LDS writes per
-// lane.  Row k_chunk of the LDS copy is kept zero for padded contraction slots.
-template <int MS>
+// lane.  Row k_chunk of the LDS copy is kept zero for padded contraction slots; rows k_chunk+1 ..
+// k_chunk+8 take the writes of absent pieces.
+template <int MS, int BATCH>
 __device__ __forceinline__ void load_a_block(const TwGemmParams& p, unsigned char* at, int row0, int k0, int kw,
                                              int wave, int lane_in, int tid_in) {
     const int lane = fresh(lane_in), tid = fresh(tid_in);
@@ -95,59 +108,91 @@ __device__ __forceinline__ void load_a_block(const TwGemmParams& p, unsigned cha
     const int og_n = (octets + 7) >> 3;        // groups of 8 pieces
     const int tasks = RG * og_n;
     const int lr = lane >> 3, lo = lane & 7;
-    constexpr int BATCH = 4;
+    // BATCH requests per wave are in flight before the first LDS write; with 12 a block of 64 rows x 768
+    // columns takes one round trip to memory
+    // Neither the loads nor the LDS writes carry branches: a request for an absent piece re-reads a valid
+    // one and its values go to eight spare LDS rows behind the zero row.  So all BATCH requests are
+    // outstanding together.  A piece is always read as 16 bytes: lda is a multiple of 8 elements, so the
+    // bytes past column K-1 of a row still belong to that row's pitch; they are dropped at the LDS
+    // write (only a width that is not a multiple of 8 needs that test).
+    const int dump = p.k_chunk + 1;
+    const bool tail = (kw & 7) != 0;                  // wave-uniform
     for (int t0 = wave; t0 < tasks; t0 += kWaves * BATCH) {
         tw_u32x4 v[BATCH];
-        int oct[BATCH], row[BATCH];
+        int kcol[BATCH], row[BATCH];
 #pragma unroll
         for (int b = 0; b < BATCH; ++b) {
             const int t = t0 + b * kWaves;
-            const int rg = t % RG, og = t / RG;
+            const int tc = t < tasks ? t : tasks - 1;
+            const int rg = tc % RG, og = tc / RG;
             row[b] = rg * 8 + lr;
-            oct[b] = og * 8 + lo;
-            v[b] = tw_u32x4{0u, 0u, 0u, 0u};
-            if (t < tasks && oct[b] < octets) {
-                int grow = row0 + row[b];
-                grow = grow < p.M ? grow : p.M - 1;   // rows past M: any valid row, never stored
-                const int k = k0 + oct[b] * 8;
-                const unsigned short* src = p.A + (long)grow * p.lda + k;
-                if (k + 8 <= p.K) {
-                    v[b] = *(const tw_u32x4*)src;
-                } else {
-                    unsigned short e[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) e[i] = (k + i < p.K) ? src[i] : (unsigned short)0;
-                    v[b] = tw_u32x4{e[0] | ((unsigned)e[1] << 16), e[2] | ((unsigned)e[3] << 16),
-                                    e[4] | ((unsigned)e[5] << 16), e[6] | ((unsigned)e[7] << 16)};
-                }
-            } else {
-                oct[b] = -1;
-            }
+            int oc = og * 8 + lo;
+            const bool have = t < tasks && oc < octets;
+            oc = oc < octets ? oc : octets - 1;
+            int grow = row0 + row[b];
+            grow = grow < p.M ? grow : p.M - 1;       // rows past M: any valid row, never stored
+            v[b] = *(const tw_u32x4*)(p.A + (long)grow * p.lda + (k0 + oc * 8));
+            kcol[b] = have ? oc * 8 : dump;
         }
 #pragma unroll
         for (int b = 0; b < BATCH; ++b) {
-            if (oct[b] >= 0) {
-                unsigned char* dst = at + (unsigned)(oct[b] * 8) * p.at_pitch + row[b] * 2;
-                const unsigned w[4] = {v[b].x, v[b].y, v[b].z, v[b].w};
+            unsigned char* dst = at + (unsigned)kcol[b] * p.at_pitch + row[b] * 2;
+            const unsigned w[4] = {v[b].x, v[b].y, v[b].z, v[b].w};
+            if (!tail) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
                     *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (kcol[b] + i < kw || kcol[b] == dump)
+                        *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
             }
         }
     }
     if (tid < BM / 2) *(unsigned*)(at + (unsigned)p.k_chunk * p.at_pitch + tid * 4) = 0u;
 }
 
-// Steps [s0, s1) of one tile for this wave: gather A from LDS, stream packed B from global, MFMA.
-// The packed B and the K indices of step s+kPrefetch are requested while step s is multiplied, and the
-// LDS gather of step s+1 is issued before the MFMAs of step s, so both latencies hide behind MFMAs.
-// The loop body has no branches except its exits (requests past the last step are clamped to the last
-// step and never used), which keeps the compiler's wait counts exact.
+// Operand registers of the main loop that live across tiles: packed B and K indices of the next
+// kPrefetch steps.
+template <int NCB>
+struct StepRegs {
+    tw_u16x8 bq[kPrefetch][NCB];
+    unsigned kk[kPrefetch];
+};
+
+// Requests the packed B and the K indices of step s (clamped to `last`) of a tile into slot `slot`.
+template <int NCB>
+__device__ __forceinline__ void issue_step(StepRegs<NCB>& rg, int slot, const unsigned char* gk, const unsigned char* bl,
+                                           int s, int last) {
+    s = s < last ? s : last;
+    rg.kk[slot] = *(const unsigned*)(gk + (long)s * 32);
+    const unsigned char* b = bl + ((long)s * NCB) * 1024;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) rg.bq[slot][cb] = *(const tw_u16x8*)(b + cb * 1024);
+}
+
+// Requests steps s0 .. s0+kPrefetch-1 of a tile; the range [s0, s1) must not be empty.
+template <int NCB>
+__device__ __forceinline__ void prefetch_first_steps(StepRegs<NCB>& rg, const unsigned char* goff_tile,
+                                                     const unsigned char* bvals_tile, int s0, int s1, int lane_in) {
+    const int lane = fresh(lane_in);
+    const unsigned char* gk = goff_tile + ((lane >> 5) * 4 + ((lane & 15) >> 2)) * 4;
+    const unsigned char* bl = bvals_tile + lane * 16;
+#pragma unroll
+    for (int i = 0; i < kPrefetch; ++i) issue_step<NCB>(rg, i, gk, bl, s0 + i, s1 - 1);
+}
+
+// Steps [s0, s1) (not empty) of one tile for this wave: gather A from LDS, stream packed B from global, MFMA.
+// Expects the first kPrefetch steps in `rg` (prefetch_first_steps).  The packed B and the K indices of
+// step s+kPrefetch are requested while step s is multiplied, and the LDS gather of step s+1 is issued
+// before the MFMAs of step s, so both latencies hide behind MFMAs.  The loop body has no branches
+// except its exits (requests past the last step are clamped to the last step and never used), which
+// keeps the compiler's wait counts exact.
 template <int DT, int MS, int NCB>
-__device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], const unsigned char* at, unsigned at_pitch,
-                                          const unsigned char* goff_tile, const unsigned char* bvals_tile,
-                                          int s0, int s1, int lane_in, int dbg = 0) {
-    if (s0 >= s1) return;
+__device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], StepRegs<NCB>& rg, const unsigned char* at,
+                                          unsigned at_pitch, const unsigned char* goff_tile,
+                                          const unsigned char* bvals_tile, int s0, int s1, int lane_in, int dbg = 0) {
     const int lane = fresh(lane_in);
     // lane l: 16-lane block b = l/16 covers rows 16*(b%2).. of the 32-row block, contraction half h = l/32;
     // inside the block, lane j addresses the K row of slot 8h + 4r + j/4 at row quad j%4
@@ -157,15 +202,6 @@ __device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], const unsig
     const unsigned char* bl = bvals_tile + lane * 16;
     const int last = s1 - 1;
 
-    tw_u16x8 bq[kPrefetch][NCB];
-    unsigned kk[kPrefetch];
-    auto issue = [&](int slot, int s) {
-        s = s < last ? s : last;
-        kk[slot] = *(const unsigned*)(gk + (long)s * 32);
-        const unsigned char* b = bl + ((long)s * NCB) * 1024;
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) bq[slot][cb] = *(const tw_u16x8*)(b + cb * 1024);
-    };
     auto gather = [&](tw_u16x8 (&a)[MS], unsigned k2) {
         const unsigned a0 = (k2 & 0xFFFFu) * at_pitch + lanebase;
         const unsigned a1 = (k2 >> 16) * at_pitch + lanebase;
@@ -180,24 +216,32 @@ __device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], const unsig
                              (unsigned short)hi4[2], (unsigned short)hi4[3]};
         }
     };
-#pragma unroll
-    for (int i = 0; i < kPrefetch; ++i) issue(i, s0 + i);
-
     // two gather buffers used alternately (the unrolled body covers an even number of steps)
+    // (both start defined: an undefined second buffer would be carried around the tile loop as a live value)
     tw_u16x8 a[2][MS];
-    gather(a[0], kk[0]);
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms) a[1][ms] = tw_u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    gather(a[0], rg.kk[0]);
     constexpr int kUnroll = (kPrefetch % 2 == 0) ? kPrefetch : 2 * kPrefetch;
     auto step = [&](int i, int s) {
         const int slot = i % kPrefetch;
-        gather(a[(i + 1) & 1], kk[(i + 1) % kPrefetch]);
+        // the three stages keep this order: left alone, the instruction scheduler sinks the loads of
+        // step s+kPrefetch next to their first use and the prefetch distance is lost
+#ifdef TW_EXPERIMENT
+        if (!(TWD(dbg) & 128))
+#endif
+        gather(a[(i + 1) & 1], rg.kk[(i + 1) % kPrefetch]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
-            for (int ms = 0; ms < MS; ++ms) acc[ms][cb] = tw_mfma<DT>(a[i & 1][ms], bq[slot][cb], acc[ms][cb]);
+            for (int ms = 0; ms < MS; ++ms) acc[ms][cb] = tw_mfma<DT>(a[i & 1][ms], rg.bq[slot][cb], acc[ms][cb]);
+        __builtin_amdgcn_sched_barrier(0);
 #ifdef TW_EXPERIMENT
-        if (!(dbg & 64))
+        if (!(TWD(dbg) & 64))
 #endif
-        issue(slot, s + kPrefetch);
+        issue_step<NCB>(rg, slot, gk, bl, s + kPrefetch, last);
+        __builtin_amdgcn_sched_barrier(0);
     };
     int s = s0;
     for (; s + kUnroll <= s1; s += kUnroll) {      // whole groups: no branch inside
@@ -212,144 +256,157 @@ __device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], const unsig
 
 // Epilogue of one tile for this wave.  In this kernel the activations are the FIRST MFMA operand, so a
 // lane owns one packed column of the tile (n = lane % 32 of every 32-column block) and its registers
-// are rows: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4.  16 rows at a time, every
-// lane writes its values into the wave's LDS staging area at the DESTINATION column of its packed
-// column (2-byte writes; the staging area was cleared first, so pruned columns inside the span read
-// back as zeros).  The staged rows are then read back 16 bytes at a time and stored to C as aligned
-// 8-column groups; the two groups at the ragged ends of the span go out as aligned 8/4/2-byte pieces.
+// are rows: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4.
+//
+// What the stores cost is the number of (128-byte line of C, store instruction) pairs, so every store
+// instruction should cover whole lines.  The wave's LDS staging window therefore starts at the
+// 64-column (128-byte) boundary at or below the tile's span and is up to four lines wide.  Eight rows
+// at a time, every lane writes its rounded values at the DESTINATION column of its packed column
+// (2-byte LDS writes).  The window is cleared once per tile: every pass writes the same columns, so
+// the pruned columns inside the span keep reading back as zeros.  Each staged row is read back as 16-byte
+// groups, eight lanes per line, and a store instruction writes one line of eight rows; groups that
+// straddle the ends of the span go out as 8/4/2-byte pieces.
 // LDS instructions of one wave execute in order, so the wave needs no waits between its own writes
 // and reads of the staging area, only compiler barriers.
-constexpr int kWinGroups = 18;                    // 8-column groups per staging window (144 columns)
-constexpr int kStagePitch = kWinGroups * 16 + 16; // 304 bytes (16-byte aligned rows); the tail takes writes of absent columns
-constexpr int kDummyOff = kWinGroups * 16;
-constexpr int kReadIters = (kWinGroups + 3) / 4;  // wave instructions that read a window of 16 rows back
-static_assert(16 * kStagePitch <= TW_STAGE_BYTES, "staging area too small");
+constexpr int kLineCols = 64;                       // columns in a 128-byte line of C
+constexpr int kWinLines = 4;                        // lines per staging window
+constexpr int kWinCols = kWinLines * kLineCols;     // 256
+constexpr int kStagePitch = kWinLines * 128 + 16;   // 528 bytes; the tail takes writes of absent columns
+constexpr int kDummyOff = kWinLines * 128;
+constexpr int kStageRows = 8;
+static_assert(kStageRows * kStagePitch <= TW_STAGE_BYTES, "staging area too small");
 
 __device__ __forceinline__ void tw_compiler_fence() { asm volatile("" ::: "memory"); }
 
-// rows [16*HP, 16*HP+16) of one 32-row block -> staging rows 0..15
-template <int DT, int NCB, int HP>
-__device__ __forceinline__ void stage_cols(const tw_f32x16 (&acc)[NCB], unsigned char* wbase, const unsigned (&pos)[NCB]) {
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-        for (int rq = 0; rq < 2; ++rq)
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-                // one conversion per value: a packed conversion of two values followed by 2-byte stores
-                // of the two halves was miscompiled by hipcc 7.2 (the low half was stored twice)
-                const int r = 8 * HP + 4 * rq + rr;
-                *(unsigned short*)(wbase + pos[cb] + (8 * rq + rr) * kStagePitch) = tw_cvt<DT>(acc[cb][r]);
-            }
-}
-
-// columns [lo, hi) of an aligned group of 8 (16 bytes in v) -> aligned 8/4/2-byte stores
-__device__ __forceinline__ void store_ragged(unsigned short* dst, const tw_u32x4& v, int lo, int hi) {
-    const unsigned w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const int b = 4 * half;
-        if (lo <= b && b + 4 <= hi) {
-            *(tw_u32x2_a2*)(dst + b) = tw_u32x2{w[2 * half], w[2 * half + 1]};
-        } else {
-#pragma unroll
-            for (int pr = 0; pr < 2; ++pr) {
-                const int e = b + 2 * pr;
-                const unsigned x = w[2 * half + pr];
-                if (lo <= e && e + 2 <= hi) {
-                    *(tw_u32_a2*)(dst + e) = x;
-                } else {
-                    if (lo <= e && e < hi) dst[e] = (unsigned short)x;
-                    if (lo <= e + 1 && e + 1 < hi) dst[e + 1] = (unsigned short)(x >> 16);
-                }
-            }
-        }
-    }
-}
-
-template <int DT, int NCB, int MSI, int HP>
-__device__ __forceinline__ void store_pass(const TwGemmParams& p, const tw_f32x16 (&acc)[NCB], unsigned char* stage,
-                                           const unsigned (&pos)[NCB], int row0, int S, int E, int g_first, int ng,
-                                           int lane_in, TwTrace& tr) {
-    const int lane = fresh(lane_in);
-    const int h = lane >> 5, trow = lane & 15, tg = lane >> 4;
-    TW_MARK(tr, 100 + 2 * MSI + HP, lane);
-    tw_compiler_fence();
-    // clear the window, then write this pass's 16 rows
-#pragma unroll
-    for (int i = 0; i < (16 * kStagePitch + 1023) / 1024; ++i) {
-        const int off = i * 1024 + lane * 16;
-        if (off < 16 * kStagePitch) *(tw_u32x4*)(stage + off) = tw_u32x4{0u, 0u, 0u, 0u};
-    }
-    tw_compiler_fence();
-    stage_cols<DT, NCB, HP>(acc, stage + 4 * h * kStagePitch, pos);
-    tw_compiler_fence();
-    TW_MARK(tr, 110, lane);
-    const int grow = row0 + 32 * MSI + 16 * HP + trow;
-    const unsigned char* rrow = stage + trow * kStagePitch + tg * 16;
-    unsigned short* crow = p.C + (long)grow * p.ldc;
-    tw_u32x4 v[kReadIters];
-#pragma unroll
-    for (int it = 0; it < kReadIters; ++it)
-        if (4 * it < ng) v[it] = *(const tw_u32x4*)(rrow + it * 64);
-#pragma unroll
-    for (int it = 0; it < kReadIters; ++it) {
-        if (4 * it < ng) {                                   // wave-uniform
-            const int g = 4 * it + tg;
-            const int col = (g_first + g) * 8;
-#ifdef TW_EXPERIMENT
-            if (!(p.dbg & 512))
-#endif
-            if (g < ng && grow < p.M && col >= S && col + 8 <= E) {
-#ifdef TW_NT_STORE
-                __builtin_nontemporal_store(v[it], (tw_u32x4_a2*)(crow + col));
-#else
-                *(tw_u32x4_a2*)(crow + col) = v[it];
-#endif
-            }
-        }
-    }
-    // the ragged ends of the span: only the first and the last group of the whole span can be partial
-    {
-        const int g = tg == 0 ? 0 : ng - 1;                  // lanes 0-15: first group, 16-31: last group of the window
-        const int col = (g_first + g) * 8;
-        const bool ragged = (tg == 0 || (tg == 1 && ng > 1)) && (col < S || col + 8 > E);
-#ifdef TW_EXPERIMENT
-        if (!(p.dbg & 8))
-#endif
-        if (__builtin_amdgcn_ballot_w64(ragged) != 0ull) {
-            if (ragged && grow < p.M) {
-                const tw_u32x4 vr = *(const tw_u32x4*)(stage + trow * kStagePitch + g * 16);
-                const int lo = S > col ? S - col : 0, hi = (E - col) < 8 ? (E - col) : 8;
-                store_ragged(crow + col, vr, lo, hi);
-            }
-        }
-    }
-    tw_compiler_fence();
-}
-
 // dpos: destination columns of this lane's packed columns (one per 32-column block), counted from the
-// aligned column at or below the span start
+// 8-aligned column at or below the span start.
+// The eight (MS = 1: four) passes of 8 rows run as a real loop: only the choice of the pass's 4 x NCB
+// accumulator registers is unrolled, the staging, read-back and store code exists once.  The loop is
+// software-pipelined: the LDS writes of pass P+1 are issued behind the read-back of pass P and ahead
+// of the wait for it (the LDS executes a wave's instructions in order, so the reads still see pass P).
+// The groups that straddle the ends of the span are stored element-wise, one 2-byte store
+// instruction per end and pass: lane (row, element) of 8 x 8.
 template <int DT, int MS, int NCB>
 __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
-                                           unsigned char* stage, const unsigned (&dpos)[NCB], int row0, int lane,
-                                           TwTrace& tr) {
+                                           unsigned char* stage, const unsigned (&dpos)[NCB], int row0, int lane_in) {
+    const int lane = fresh(lane_in);
+    const int h = lane >> 5, trow = lane >> 3, tg = lane & 7;
     const int S = d.span_start, E = d.span_start + d.span_w;
-    const int G0 = S >> 3, G8 = ((E + 7) >> 3) - G0;
-    for (int gw = 0; gw < G8; gw += kWinGroups) {            // one window unless the span is very wide
-        const int ng = (G8 - gw) < kWinGroups ? (G8 - gw) : kWinGroups;
+    const int W0 = S & ~(kLineCols - 1);
+    const unsigned shift = (unsigned)((S & ~7) - W0);       // dpos counts from S & ~7
+    constexpr int NP = 4 * MS;
+    for (int win0 = W0; win0 < E; win0 += kWinCols) {       // one window unless the span is very wide
+        const int left = E - win0;
+        const int nl = left >= kWinCols ? kWinLines : (left + kLineCols - 1) / kLineCols;
         unsigned pos[NCB];
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
-            const unsigned rel = dpos[cb] - (unsigned)(gw * 8);
-            pos[cb] = rel < (unsigned)(ng * 8) ? rel * 2u : (unsigned)kDummyOff;
+            const unsigned rel = dpos[cb] + shift - (unsigned)(win0 - W0);   // wraps for columns left of the window
+            pos[cb] = rel < (unsigned)kWinCols ? rel * 2u : (unsigned)kDummyOff;
         }
-        store_pass<DT, NCB, 0, 0>(p, acc[0], stage, pos, row0, S, E, G0 + gw, ng, lane, tr);
-        store_pass<DT, NCB, 0, 1>(p, acc[0], stage, pos, row0, S, E, G0 + gw, ng, lane, tr);
-        if constexpr (MS == 2) {
-            store_pass<DT, NCB, 1, 0>(p, acc[1], stage, pos, row0, S, E, G0 + gw, ng, lane, tr);
-            store_pass<DT, NCB, 1, 1>(p, acc[1], stage, pos, row0, S, E, G0 + gw, ng, lane, tr);
+        // partial groups at the two ends of the span, if they lie in this window (window-relative index)
+        int g_first = -1, g_last = -1;
+        if ((S & 7) != 0 && win0 == W0) g_first = (S - win0) >> 3;
+        if ((E & 7) != 0 && left <= kWinCols) g_last = (E - 1 - win0) >> 3;
+        const int colF = win0 + g_first * 8 + tg, colL = win0 + g_last * 8 + tg;   // this lane's element
+        const bool inF = g_first >= 0 && colF >= S && colF < E;
+        const bool inL = g_last >= 0 && colL >= S && colL < E;
+        const unsigned char* ragF = stage + trow * kStagePitch + ((g_first < 0 ? 0 : g_first) * 8 + tg) * 2;
+        const unsigned char* ragL = stage + trow * kStagePitch + ((g_last < 0 ? 0 : g_last) * 8 + tg) * 2;
+        unsigned char* wrow = stage + 4 * h * kStagePitch;
+        const unsigned char* rrow = stage + trow * kStagePitch + tg * 16;
+
+        auto extract = [&](int P, float (&t)[NCB][4]) {
+            // pass 0 is the default so that t is defined on every path (an undefined t would be carried
+            // around the tile loop as a live value)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) t[cb][rr] = acc[0][cb][rr];
+#pragma unroll
+            for (int q = 1; q < NP; ++q)
+                if (P == q) {
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) t[cb][rr] = acc[q >> 2][cb][4 * (q & 3) + rr];
+                }
+        };
+        auto write_pass = [&](const float (&t)[NCB][4]) {
+#ifdef TW_EXPERIMENT
+            if (!(TWD(p.dbg) & 1024))
+#endif
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    // one conversion per value: a packed conversion of two values followed by 2-byte stores
+                    // of the two halves was miscompiled by hipcc 7.2 (the low half was stored twice)
+                    *(unsigned short*)(wrow + pos[cb] + rr * kStagePitch) = tw_cvt<DT>(t[cb][rr]);
+                }
+        };
+        auto read_pass = [&](tw_u32x4 (&v)[kWinLines], unsigned short& eF, unsigned short& eL) {
+            // all four lines of the window (lines past the span are read, not stored) and this lane's
+            // elements of the two partial groups
+#pragma unroll
+            for (int l = 0; l < kWinLines; ++l) v[l] = *(const tw_u32x4*)(rrow + l * 128);
+            eF = *(const unsigned short*)ragF;
+            eL = *(const unsigned short*)ragL;
+        };
+        auto store_pass = [&](int P, const tw_u32x4 (&v)[kWinLines], unsigned short eF, unsigned short eL) {
+            const int grow = row0 + 8 * P + trow;
+            unsigned short* crow = p.C + (long)grow * p.ldc;
+#pragma unroll
+            for (int l = 0; l < kWinLines; ++l) {
+                const int col = win0 + l * kLineCols + tg * 8;
+#ifdef TW_EXPERIMENT
+                if (!(TWD(p.dbg) & 512))
+#endif
+                if (l < nl && grow < p.M && col >= S && col + 8 <= E) *(tw_u32x4_a2*)(crow + col) = v[l];
+            }
+#ifdef TW_EXPERIMENT
+            if (!(TWD(p.dbg) & 8))
+#endif
+            {
+                if (g_first >= 0) {                          // wave-uniform
+                    if (inF && grow < p.M) crow[colF] = eF;
+                }
+                if (g_last >= 0) {
+                    if (inL && grow < p.M) crow[colL] = eL;
+                }
+            }
+        };
+
+        // clear the window once: the passes all write the same columns
+        tw_compiler_fence();
+#ifdef TW_EXPERIMENT
+        if (!(TWD(p.dbg) & 2048))
+#endif
+#pragma unroll
+        for (int i = 0; i < (kStageRows * kStagePitch + 1023) / 1024; ++i) {
+            const int off = i * 1024 + lane * 16;
+            if (off < kStageRows * kStagePitch) *(tw_u32x4*)(stage + off) = tw_u32x4{0u, 0u, 0u, 0u};
         }
+        tw_compiler_fence();
+        float t[NCB][4];
+        tw_u32x4 v[kWinLines];
+        unsigned short eF, eL;
+        extract(0, t);
+        write_pass(t);
+        tw_compiler_fence();
+#pragma clang loop unroll(disable)
+        for (int P = 0; P < NP - 1; ++P) {
+            read_pass(v, eF, eL);
+            tw_compiler_fence();
+            extract(P + 1, t);
+            write_pass(t);
+            tw_compiler_fence();
+            store_pass(P, v, eF, eL);
+        }
+        read_pass(v, eF, eL);
+        tw_compiler_fence();
+        store_pass(NP - 1, v, eF, eL);
+        tw_compiler_fence();
     }
 }
 
@@ -374,45 +431,43 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
     const int* step_ptr = (const int*)(p.blob + p.off_step_ptr);
 
 #ifdef TW_EXPERIMENT
-    if (p.dbg & 16) return;
-    TwTrace tr{p.trace ? p.trace + ((long)blockIdx.x * kWaves + wave) * 128 : nullptr, 0};
-#else
-    TwTrace tr{};
+    if (TWD(p.dbg) & 16) return;
+    int nmark = 0;
 #endif
-    TW_MARK(tr, 1, lane);
+    TW_MARK();
     // the first item of a workgroup is its own index, later ones come from the atomic counter
     for (int turn = 0;; ++turn) {
         if (tid == 0) {
-            misc[0] = turn == 0 ? (int)blockIdx.x : (int)gridDim.x + atomicAdd(&p.counters[0], 1);
+            // the counter is touched only when there are more items than workgroups
+            misc[0] = turn == 0 ? (int)blockIdx.x
+                                : (p.n_items > (int)gridDim.x ? (int)gridDim.x + atomicAdd(&p.counters[0], 1) : p.n_items);
             misc[1] = 0;
         }
         __syncthreads();
         const int item = misc[0];
         if (item >= p.n_items) break;
-        TW_MARK(tr, 2, lane);
 
         if constexpr (RESIDENT) {
             // the whole K extent of the row block stays in LDS; waves pull tiles of this item's set
             const int mb = item / p.n_seg, seg = item - mb * p.n_seg;
             const int row0 = mb * BM;
-            // first tile of this wave: fetch its descriptor while A is being staged
+            // first tile of this wave: its descriptor is requested before A is staged
             int i = 0;
             if (lane == 0) i = atomicAdd((int*)&misc[1], 1);
             int ti = seg + uni(i) * p.n_seg;
             TileU next = fetch_tile(p, ti < p.T ? ti : 0);
 #ifdef TW_EXPERIMENT
-            if (!(p.dbg & 1))
+            if (!(TWD(p.dbg) & 1))
 #endif
-            load_a_block<MS>(p, smem, row0, 0, p.K, wave, lane, tid);
-            TW_MARK(tr, 3, lane);
+            load_a_block<MS, 12>(p, smem, row0, 0, p.K, wave, lane, tid);
+            TW_MARK();
             __syncthreads();
-            TW_MARK(tr, 4, lane);
+            TW_MARK();
 #ifdef TW_EXPERIMENT
-            if (p.dbg & 32) ti = p.T;
+            if (TWD(p.dbg) & 32) ti = p.T;
 #endif
             while (ti < p.T) {
                 const TileU d = next;
-                TW_MARK(tr, 10, lane);
                 // claim the next tile now so that its descriptor arrives during this tile's work
                 if (lane == 0) i = atomicAdd((int*)&misc[1], 1);
                 ti = seg + uni(i) * p.n_seg;
@@ -425,27 +480,40 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #pragma unroll
                     for (int cb = 0; cb < NCB; ++cb) dpos[cb] = dp[cb];
                 }
+                StepRegs<NCB> rg;
+                prefetch_first_steps<NCB>(rg, p.blob + p.off_goff + (long)d.first_step * 32,
+                                          p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
                 tw_f32x16 acc[MS][NCB];
                 zero_acc<MS, NCB>(acc);
 #ifdef TW_EXPERIMENT
-                if (!(p.dbg & 2))
+                if (!(TWD(p.dbg) & 2))
 #endif
-                run_steps<DT, MS, NCB>(acc, smem, p.at_pitch, p.blob + p.off_goff + (long)d.first_step * 32,
+                run_steps<DT, MS, NCB>(acc, rg, smem, p.at_pitch, p.blob + p.off_goff + (long)d.first_step * 32,
                                        p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane
 #ifdef TW_EXPERIMENT
                                        , p.dbg
 #endif
                                        );
-                TW_MARK(tr, 20, lane);
-#ifdef TW_EXPERIMENT
-                if (!(p.dbg & 4))
+#if defined(TW_EXPERIMENT) && defined(TW_DBG_CONST)
+                if (TW_DBG_CONST & 4) {   // keep the products alive when the epilogue is compiled out
+                    float sink = 0.f;
+#pragma unroll
+                    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) sink += acc[ms][cb][r];
+                    if (sink == 1.2345e-30f) p.C[lane] = 1;
+                }
 #endif
-                store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane, tr);
-                TW_MARK(tr, 30, lane);
+                TW_MARK();
+#ifdef TW_EXPERIMENT
+                if (!(TWD(p.dbg) & 4))
+#endif
+                store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+                TW_MARK();
             }
-            TW_MARK(tr, 40, lane);
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
-            TW_MARK(tr, 41, lane);
         } else {
             // K is streamed in chunks; wave w owns tile (8*set + w) of the kept-K ordering
             const int set = item / p.n_mblocks, mb = item - set * p.n_mblocks;
@@ -465,19 +533,23 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             for (int c = 0; c < p.n_chunks; ++c) {
                 const int k0 = c * p.k_chunk;
                 const int kw = (p.K - k0) < p.k_chunk ? (p.K - k0) : p.k_chunk;
-                load_a_block<MS>(p, smem, row0, k0, kw, wave, lane, tid);
+                load_a_block<MS, 4>(p, smem, row0, k0, kw, wave, lane, tid);
                 __syncthreads();
-                if (active)
-                    run_steps<DT, MS, NCB>(acc, smem, p.at_pitch, p.blob + p.off_goff + (long)d.first_step * 32,
-                                           p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, uni(sp[c]),
-                                           uni(sp[c + 1]), lane);
+                const int c0 = uni(sp[c]), c1 = uni(sp[c + 1]);
+                if (active && c0 < c1) {
+                    const unsigned char* gt = p.blob + p.off_goff + (long)d.first_step * 32;
+                    const unsigned char* bt = p.blob + p.off_bvals + (long)d.first_step * NCB * 1024;
+                    StepRegs<NCB> rg;
+                    prefetch_first_steps<NCB>(rg, gt, bt, c0, c1, lane);
+                    run_steps<DT, MS, NCB>(acc, rg, smem, p.at_pitch, gt, bt, c0, c1, lane);
+                }
                 __syncthreads();
             }
-            if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane, tr);
+            if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
         }
     }
     // the last workgroup to leave puts the counters back to zero for the next call
-    if (tid == 0) {
+    if (tid == 0 && p.n_items > (int)gridDim.x) {
         __threadfence();
         const int done = atomicAdd(&p.counters[1], 1);
         if (done == (int)gridDim.x - 1) {
@@ -504,7 +576,7 @@ constexpr unsigned kLdsLimit = 160 * 1024;
 
 unsigned at_bytes(int ms, int k_chunk) {
     const unsigned pitch = 64u * ms + 8u;
-    return ((unsigned)(k_chunk + 1) * pitch + 15u) & ~15u;
+    return ((unsigned)(k_chunk + 9) * pitch + 15u) & ~15u;
 }
 unsigned lds_need(int ms, int k_chunk) { return at_bytes(ms, k_chunk) + kWaves * TW_STAGE_BYTES + 16u; }
 
@@ -654,7 +726,7 @@ extern "C" int tw_gemm(const void* blob_host, const void* blob_dev, const void* 
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
 #ifdef TW_EXPERIMENT
     p.dbg = getenv("TW_DBG") ? atoi(getenv("TW_DBG")) : 0;
-    p.trace = getenv("TW_TRACE_PTR") ? (long long*)strtoull(getenv("TW_TRACE_PTR"), nullptr, 16) : nullptr;
+    p.trace = getenv("TW_TRACE_PTR") ? (unsigned*)strtoull(getenv("TW_TRACE_PTR"), nullptr, 16) : nullptr;
 #endif
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), pl.lds_bytes, stream, p);

@@ -267,11 +267,26 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
             }
         }
     }
+    // Dispatch order of the kernel.  With K resident the waves of a workgroup pull tiles one after the
+    // other: the first TW_WAVES_PER_WG pulls alternate between the heaviest and the lightest tiles, so
+    // the waves leave their first tile at different times and their store phases do not coincide;
+    // the remaining tiles follow heaviest first.  With K streamed the waves of a set advance in
+    // lock step, so sets hold tiles of similar weight (plain heaviest-first order).
+    std::vector<int32_t> dispatch(order);
+    if (lo.n_chunks == 1 && tl.T >= TW_WAVES_PER_WG) {
+        const int half = TW_WAVES_PER_WG / 2;
+        int n = 0;
+        for (int i = 0; i < half; ++i) {
+            dispatch[n++] = order[i];
+            dispatch[n++] = order[tl.T - 1 - i];
+        }
+        for (int i = half; i < tl.T - half; ++i) dispatch[n++] = order[i];
+    }
     TwSchedDesc* sd = (TwSchedDesc*)(base + lo.off_sched_desc);
     for (int i = 0; i < tl.T; ++i) {
-        const TwTileDesc& d = desc[order[i]];
+        const TwTileDesc& d = desc[dispatch[i]];
         sd[i].w = d.w; sd[i].span_start = d.span_start; sd[i].span_w = d.span_w; sd[i].nsteps = d.nsteps;
-        sd[i].tile = order[i]; sd[i].step_ptr = d.step_ptr; sd[i].first_step = d.first_step;
+        sd[i].tile = dispatch[i]; sd[i].step_ptr = d.step_ptr; sd[i].first_step = d.first_step;
         sd[i].reserved = 0;
     }
     return TW_OK;
