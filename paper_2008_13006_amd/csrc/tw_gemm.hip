@@ -56,6 +56,7 @@ struct TwGemmParams {
     int k_chunk, n_chunks, G;
     int n_mblocks, n_seg, n_items;
     unsigned at_pitch;          // bytes between K rows of the LDS copy of A (32*MS rows of A wide, padded)
+    unsigned abuf_bytes;        // size of one LDS copy of A (streamed K uses two)
     unsigned stage_off;         // LDS offset of the per-wave staging areas
     unsigned misc_off;          // LDS offset of two ints (item, tile counter)
     uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals;
@@ -98,59 +99,89 @@ __device__ __forceinline__ TileU fetch_tile(const TwGemmParams& p, int ti) {
 // contiguous bytes of A (8 lanes x 16 B per row) and scatters them with eight 2-byte LDS writes per
 // lane.  Row k_chunk of the LDS copy is kept zero for padded contraction slots; rows k_chunk+1 ..
 // k_chunk+8 take the writes of absent pieces.
+//
+// Work is cut into tasks of 8 rows x 8 pieces; wave w takes tasks w, w+8, ...  Neither the loads nor
+// the LDS writes carry branches: a request for an absent piece re-reads a valid one and its values go
+// to the spare rows, so all requests of a batch are outstanding together.  A piece is always read as
+// 16 bytes: lda is a multiple of 8 elements, so the bytes past column K-1 of a row still belong to
+// that row's pitch; they are dropped at the LDS write (only a width that is not a multiple of 8 needs
+// that test).
+template <int BATCH>
+struct ARegs {
+    tw_u32x4 v[BATCH];
+};
+
+template <int MS>
+struct ATask {
+    int row, oc;
+    bool have;
+    __device__ __forceinline__ ATask(int t, int kw, int lane) {
+        constexpr int RG = 4 * MS;                  // groups of 8 rows
+        const int octets = (kw + 7) >> 3;           // 16-byte pieces per row
+        const int tasks = RG * ((octets + 7) >> 3);
+        const int tc = t < tasks ? t : tasks - 1;
+        row = (tc % RG) * 8 + (lane >> 3);
+        const int o = (tc / RG) * 8 + (lane & 7);
+        have = t < tasks && o < octets;
+        oc = o < octets ? o : octets - 1;
+    }
+};
+
+// requests tasks t0, t0+8, ... (BATCH of them) of the block
 template <int MS, int BATCH>
-__device__ __forceinline__ void load_a_block(const TwGemmParams& p, unsigned char* at, int row0, int k0, int kw,
-                                             int wave, int lane_in, int tid_in) {
-    const int lane = fresh(lane_in), tid = fresh(tid_in);
-    constexpr int BM = 32 * MS;
-    constexpr int RG = BM / 8;                 // groups of 8 rows
-    const int octets = (kw + 7) >> 3;          // 16-byte pieces per row
-    const int og_n = (octets + 7) >> 3;        // groups of 8 pieces
-    const int tasks = RG * og_n;
-    const int lr = lane >> 3, lo = lane & 7;
-    // BATCH requests per wave are in flight before the first LDS write; with 12 a block of 64 rows x 768
-    // columns takes one round trip to memory
-    // Neither the loads nor the LDS writes carry branches: a request for an absent piece re-reads a valid
-    // one and its values go to eight spare LDS rows behind the zero row.  So all BATCH requests are
-    // outstanding together.  A piece is always read as 16 bytes: lda is a multiple of 8 elements, so the
-    // bytes past column K-1 of a row still belong to that row's pitch; they are dropped at the LDS
-    // write (only a width that is not a multiple of 8 needs that test).
+__device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int row0, int k0, int kw, int t0,
+                                        int lane_in) {
+    const int lane = fresh(lane_in);
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+        const ATask<MS> t(t0 + b * kWaves, kw, lane);
+        int grow = row0 + t.row;
+        grow = grow < p.M ? grow : p.M - 1;           // rows past M: any valid row, never stored
+        ar.v[b] = *(const tw_u32x4*)(p.A + (long)grow * p.lda + (k0 + t.oc * 8));
+    }
+}
+
+// writes what a_issue requested into the LDS copy `at`
+template <int MS, int BATCH>
+__device__ __forceinline__ void a_commit(const TwGemmParams& p, const ARegs<BATCH>& ar, unsigned char* at, int kw, int t0,
+                                         int lane_in) {
+    const int lane = fresh(lane_in);
     const int dump = p.k_chunk + 1;
     const bool tail = (kw & 7) != 0;                  // wave-uniform
-    for (int t0 = wave; t0 < tasks; t0 += kWaves * BATCH) {
-        tw_u32x4 v[BATCH];
-        int kcol[BATCH], row[BATCH];
 #pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            const int t = t0 + b * kWaves;
-            const int tc = t < tasks ? t : tasks - 1;
-            const int rg = tc % RG, og = tc / RG;
-            row[b] = rg * 8 + lr;
-            int oc = og * 8 + lo;
-            const bool have = t < tasks && oc < octets;
-            oc = oc < octets ? oc : octets - 1;
-            int grow = row0 + row[b];
-            grow = grow < p.M ? grow : p.M - 1;       // rows past M: any valid row, never stored
-            v[b] = *(const tw_u32x4*)(p.A + (long)grow * p.lda + (k0 + oc * 8));
-            kcol[b] = have ? oc * 8 : dump;
-        }
+    for (int b = 0; b < BATCH; ++b) {
+        const ATask<MS> t(t0 + b * kWaves, kw, lane);
+        const int kcol = t.have ? t.oc * 8 : dump;
+        unsigned char* dst = at + (unsigned)kcol * p.at_pitch + t.row * 2;
+        const unsigned w[4] = {ar.v[b].x, ar.v[b].y, ar.v[b].z, ar.v[b].w};
+        if (!tail) {
 #pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            unsigned char* dst = at + (unsigned)kcol[b] * p.at_pitch + row[b] * 2;
-            const unsigned w[4] = {v[b].x, v[b].y, v[b].z, v[b].w};
-            if (!tail) {
+            for (int i = 0; i < 8; ++i)
+                *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
+        } else {
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < 8; ++i)
+                if (kcol + i < kw || kcol == dump)
                     *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (kcol[b] + i < kw || kcol[b] == dump)
-                        *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
-            }
         }
     }
-    if (tid < BM / 2) *(unsigned*)(at + (unsigned)p.k_chunk * p.at_pitch + tid * 4) = 0u;
+}
+
+__device__ __forceinline__ void a_zero_row(const TwGemmParams& p, unsigned char* at, int bm, int tid) {
+    if (tid < bm / 2) *(unsigned*)(at + (unsigned)p.k_chunk * p.at_pitch + tid * 4) = 0u;
+}
+
+// whole block, BATCH requests per wave in flight at a time (12 cover 64 rows x 768 columns)
+template <int MS, int BATCH>
+__device__ __forceinline__ void load_a_block(const TwGemmParams& p, unsigned char* at, int row0, int k0, int kw,
+                                             int wave, int lane, int tid) {
+    const int tasks = 4 * MS * ((((kw + 7) >> 3) + 7) >> 3);
+    for (int t0 = wave; t0 < tasks; t0 += kWaves * BATCH) {
+        ARegs<BATCH> ar;
+        a_issue<MS, BATCH>(p, ar, row0, k0, kw, t0, lane);
+        a_commit<MS, BATCH>(p, ar, at, kw, t0, lane);
+    }
+    a_zero_row(p, at, 32 * MS, tid);
 }
 
 // Operand registers of the main loop that live across tiles: packed B and K indices of the next
@@ -420,10 +451,15 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
             for (int r = 0; r < 16; ++r) acc[ms][cb][r] = 0.f;
 }
 
-template <int DT, int MS, int NCB, bool RESIDENT>
+// MODE 0: the K extent of a row block of 32*MS rows is resident in LDS, waves pull whole tiles.
+// MODE 1: K streamed through two LDS buffers, row block of 32*MS rows, wave w owns tile 8*set + w.
+// MODE 2: K streamed, row block of 64 rows, for weights with at most four tiles: wave w owns the
+//         32-row half w%2 of tile 4*set + w/2 (MS = 1 is the wave's height).
+template <int DT, int MS, int NCB, int MODE>
 __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int BM = 32 * MS;
+    constexpr int MSB = MODE == 2 ? 2 : MS;      // 32-row blocks in the workgroup's row block
+    constexpr int BM = 32 * MSB;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = uni(tid >> 6);
     unsigned char* stage = smem + p.stage_off + wave * TW_STAGE_BYTES;
@@ -447,7 +483,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
         const int item = misc[0];
         if (item >= p.n_items) break;
 
-        if constexpr (RESIDENT) {
+        if constexpr (MODE == 0) {
             // the whole K extent of the row block stays in LDS; waves pull tiles of this item's set
             const int mb = item / p.n_seg, seg = item - mb * p.n_seg;
             const int row0 = mb * BM;
@@ -515,10 +551,12 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
         } else {
-            // K is streamed in chunks; wave w owns tile (8*set + w) of the kept-K ordering
+            // K is streamed in chunks through two LDS buffers: the requests for chunk c+1 go out before
+            // the steps of chunk c and are written to the other buffer after them, one barrier per chunk
             const int set = item / p.n_mblocks, mb = item - set * p.n_mblocks;
             const int row0 = mb * BM;
-            const int ti = set * kWaves + wave;
+            const int ti = MODE == 2 ? set * (kWaves / 2) + (wave >> 1) : set * kWaves + wave;
+            const int half = MODE == 2 ? (wave & 1) : 0;
             const bool active = ti < p.T;
             const TileU d = fetch_tile(p, active ? ti : 0);
             unsigned dpos[NCB];
@@ -530,22 +568,38 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             tw_f32x16 acc[MS][NCB];
             zero_acc<MS, NCB>(acc);
             const int* sp = step_ptr + d.step_ptr;
+            const unsigned char* gt = p.blob + p.off_goff + (long)d.first_step * 32;
+            const unsigned char* bt = p.blob + p.off_bvals + (long)d.first_step * NCB * 1024;
+            constexpr int AB = 6;    // requests per wave and chunk: 64 rows x 384 columns in 8 waves
+            {
+                const int kw = p.K < p.k_chunk ? p.K : p.k_chunk;
+                load_a_block<MSB, AB>(p, smem, row0, 0, kw, wave, lane, tid);
+                a_zero_row(p, smem + p.abuf_bytes, BM, tid);
+            }
+            __syncthreads();
             for (int c = 0; c < p.n_chunks; ++c) {
-                const int k0 = c * p.k_chunk;
-                const int kw = (p.K - k0) < p.k_chunk ? (p.K - k0) : p.k_chunk;
-                load_a_block<MS, 4>(p, smem, row0, k0, kw, wave, lane, tid);
-                __syncthreads();
+                unsigned char* cur = smem + (c & 1) * p.abuf_bytes;
+                unsigned char* nxt = smem + ((c + 1) & 1) * p.abuf_bytes;
+                const bool more = c + 1 < p.n_chunks;
+                const int k0n = (c + 1) * p.k_chunk;
+                const int kwn = (p.K - k0n) < p.k_chunk ? (p.K - k0n) : p.k_chunk;
+                ARegs<AB> ar;
+                if (more) {
+                    a_issue<MSB, AB>(p, ar, row0, k0n, kwn, wave, lane);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < AB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
+                }
                 const int c0 = uni(sp[c]), c1 = uni(sp[c + 1]);
                 if (active && c0 < c1) {
-                    const unsigned char* gt = p.blob + p.off_goff + (long)d.first_step * 32;
-                    const unsigned char* bt = p.blob + p.off_bvals + (long)d.first_step * NCB * 1024;
                     StepRegs<NCB> rg;
                     prefetch_first_steps<NCB>(rg, gt, bt, c0, c1, lane);
-                    run_steps<DT, MS, NCB>(acc, rg, smem, p.at_pitch, gt, bt, c0, c1, lane);
+                    run_steps<DT, MS, NCB>(acc, rg, cur + half * 64, p.at_pitch, gt, bt, c0, c1, lane);
                 }
+                if (more) a_commit<MSB, AB>(p, ar, nxt, kwn, wave, lane);
                 __syncthreads();
             }
-            if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+            if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0 + 32 * half, lane);
         }
     }
     // the last workgroup to leave puts the counters back to zero for the next call
@@ -567,25 +621,31 @@ __global__ void tw_zero_kernel(unsigned short* C, long ldc, int M, int N) {
 }
 
 struct Plan {
-    int ms;         // 32-row blocks per workgroup row block (1 or 2)
+    int mode;       // kernel MODE
+    int ms;         // the kernel's MS
     int n_mblocks, n_seg, n_items;
-    unsigned at_pitch, stage_off, misc_off, lds_bytes;
+    unsigned at_pitch, abuf_bytes, stage_off, misc_off, lds_bytes;
 };
 
 constexpr unsigned kLdsLimit = 160 * 1024;
 
-unsigned at_bytes(int ms, int k_chunk) {
-    const unsigned pitch = 64u * ms + 8u;
+unsigned at_bytes(int msb, int k_chunk) {
+    const unsigned pitch = 64u * msb + 8u;
     return ((unsigned)(k_chunk + 9) * pitch + 15u) & ~15u;
 }
-unsigned lds_need(int ms, int k_chunk) { return at_bytes(ms, k_chunk) + kWaves * TW_STAGE_BYTES + 16u; }
+unsigned lds_need(int msb, int k_chunk, int buffers) {
+    return buffers * at_bytes(msb, k_chunk) + kWaves * TW_STAGE_BYTES + 16u;
+}
 
 int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
-    if (lds_need(1, h->k_chunk) > kLdsLimit) return TW_ERR_UNSUPPORTED;
+    const bool resident = h->n_chunks == 1;
+    const int buffers = resident ? 1 : 2;
+    if (lds_need(1, h->k_chunk, buffers) > kLdsLimit) return TW_ERR_UNSUPPORTED;
     const int T = h->T;
-    auto items_for = [&](int ms, int& n_mblocks, int& n_seg) {
-        n_mblocks = (M + 32 * ms - 1) / (32 * ms);
-        if (h->n_chunks == 1) {
+    // msb: 32-row blocks in a workgroup's row block; tpw: tiles a workgroup of the streamed kernel holds
+    auto items_for = [&](int msb, int tpw, int& n_mblocks, int& n_seg) {
+        n_mblocks = (M + 32 * msb - 1) / (32 * msb);
+        if (resident) {
             // split a row block's tiles over several workgroups only when there are too few row blocks
             n_seg = 1;
             if (n_mblocks < n_cu) n_seg = (n_cu + n_mblocks - 1) / n_mblocks;
@@ -593,22 +653,30 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
             if (n_seg < 1) n_seg = 1;
             return (long)n_mblocks * n_seg;
         }
-        n_seg = (T + kWaves - 1) / kWaves;
+        n_seg = (T + tpw - 1) / tpw;
         return (long)n_mblocks * n_seg;
     };
-    int ms = 2;
+    int msb = 2, tpw = kWaves;
     int nmb, nseg;
-    if (lds_need(2, h->k_chunk) > kLdsLimit) ms = 1;
-    if (ms == 2) {
+    if (lds_need(2, h->k_chunk, buffers) > kLdsLimit) msb = 1;
+    if (msb == 2) {
         // 64-row blocks halve the traffic of packed B, but only pay when they still fill the GPU
-        if (items_for(2, nmb, nseg) < n_cu) ms = 1;
+        if (items_for(2, tpw, nmb, nseg) < n_cu) msb = 1;
     }
-    const long items = items_for(ms, nmb, nseg);
+    pl.mode = resident ? 0 : 1;
+    pl.ms = msb;
+    if (!resident && msb == 2 && T <= kWaves / 2) {   // few tiles: two waves share a tile, 32 rows each
+        pl.mode = 2;
+        pl.ms = 1;
+        tpw = kWaves / 2;
+    }
+    const long items = items_for(msb, tpw, nmb, nseg);
     if (items > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
-    pl.ms = ms;
+    if (!resident && 4 * msb * ((((h->k_chunk + 7) >> 3) + 7) >> 3) > kWaves * 6) return TW_ERR_UNSUPPORTED;
     pl.n_mblocks = nmb; pl.n_seg = nseg; pl.n_items = (int)items;
-    pl.at_pitch = 64u * ms + 8u;
-    pl.stage_off = at_bytes(ms, h->k_chunk);
+    pl.at_pitch = 64u * msb + 8u;
+    pl.abuf_bytes = at_bytes(msb, h->k_chunk);
+    pl.stage_off = buffers * pl.abuf_bytes;
     pl.misc_off = pl.stage_off + kWaves * TW_STAGE_BYTES;
     pl.lds_bytes = pl.misc_off + 16u;
     return TW_OK;
@@ -616,24 +684,25 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
 
 typedef void (*KernelFn)(const TwGemmParams);
 
-template <int DT, int MS, bool RES>
+template <int DT, int MS, int MODE>
 KernelFn pick_ncb(int ncb) {
     switch (ncb) {
-        case 1: return tw_gemm_kernel<DT, MS, 1, RES>;
-        case 2: return tw_gemm_kernel<DT, MS, 2, RES>;
-        case 4: return tw_gemm_kernel<DT, MS, 4, RES>;
+        case 1: return tw_gemm_kernel<DT, MS, 1, MODE>;
+        case 2: return tw_gemm_kernel<DT, MS, 2, MODE>;
+        case 4: return tw_gemm_kernel<DT, MS, 4, MODE>;
         default: return nullptr;
     }
 }
 
 template <int DT>
-KernelFn pick_ms(int ms, bool res, int ncb) {
-    if (res) return ms == 2 ? pick_ncb<DT, 2, true>(ncb) : pick_ncb<DT, 1, true>(ncb);
-    return ms == 2 ? pick_ncb<DT, 2, false>(ncb) : pick_ncb<DT, 1, false>(ncb);
+KernelFn pick_mode(int mode, int ms, int ncb) {
+    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0>(ncb) : pick_ncb<DT, 1, 0>(ncb);
+    if (mode == 1) return ms == 2 ? pick_ncb<DT, 2, 1>(ncb) : pick_ncb<DT, 1, 1>(ncb);
+    return pick_ncb<DT, 1, 2>(ncb);
 }
 
-KernelFn pick_kernel(int dt, int ms, bool res, int ncb) {
-    return dt == TW_F16 ? pick_ms<TW_F16>(ms, res, ncb) : pick_ms<TW_BF16>(ms, res, ncb);
+KernelFn pick_kernel(int dt, int mode, int ms, int ncb) {
+    return dt == TW_F16 ? pick_mode<TW_F16>(mode, ms, ncb) : pick_mode<TW_BF16>(mode, ms, ncb);
 }
 
 // Per-device facts looked up once (the entries are written with the same value by every thread
@@ -656,7 +725,7 @@ int device_cus(int dev) {
 }
 
 // The dynamic-LDS limit of a kernel is raised to the hardware maximum once per (device, kernel).
-constexpr int kMaxKernels = 24;
+constexpr int kMaxKernels = 32;
 std::atomic<unsigned> g_lds_set[kMaxDevices][kMaxKernels];
 
 int ensure_lds(int dev, int kernel_id, const void* fn) {
@@ -704,10 +773,10 @@ extern "C" int tw_gemm(const void* blob_host, const void* blob_dev, const void* 
     Plan pl;
     int rc = make_plan(h, M, n_cu, pl);
     if (rc) return rc;
-    KernelFn fn = pick_kernel(h->dtype, pl.ms, h->n_chunks == 1, h->ncb);
+    KernelFn fn = pick_kernel(h->dtype, pl.mode, pl.ms, h->ncb);
     if (!fn) return TW_ERR_UNSUPPORTED;
-    const int kernel_id = (h->dtype == TW_F16 ? 0 : 12) + (pl.ms == 2 ? 0 : 6) + (h->n_chunks == 1 ? 0 : 3) +
-                          (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
+    const int variant = pl.mode == 2 ? 4 : 2 * pl.mode + (pl.ms == 2 ? 0 : 1);      // 0..4
+    const int kernel_id = (h->dtype == TW_F16 ? 0 : 15) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, (const void*)fn);
     if (rc) return rc;
 
@@ -720,7 +789,7 @@ extern "C" int tw_gemm(const void* blob_host, const void* blob_dev, const void* 
     p.M = M; p.K = h->K; p.N = h->N; p.T = h->T;
     p.k_chunk = h->k_chunk; p.n_chunks = h->n_chunks; p.G = h->G;
     p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items;
-    p.at_pitch = pl.at_pitch;
+    p.at_pitch = pl.at_pitch; p.abuf_bytes = pl.abuf_bytes;
     p.stage_off = pl.stage_off; p.misc_off = pl.misc_off;
     p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
