@@ -10,7 +10,9 @@
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
 #define TW_KSTEP 16
 // Waves per workgroup of the TW kernel (the packer shapes the dispatch order for it).
+#ifndef TW_WAVES_PER_WG
 #define TW_WAVES_PER_WG 8
+#endif
 #define TW_COLBLK 32
 // Padded contraction slots gather row `k_chunk` of the LDS copy of A, which the kernel keeps zero.
 

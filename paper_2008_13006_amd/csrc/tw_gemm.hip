@@ -42,7 +42,9 @@ namespace {
 
 constexpr int kWaves = TW_WAVES_PER_WG;
 constexpr int kThreads = kWaves * 64;
-constexpr int kPrefetch = 2;  // B-operand steps in flight per wave
+constexpr int kPrefetch = 3;  // B-operand steps in flight per wave
+constexpr int kIdxAhead = 6;  // steps the K indices are requested ahead (they feed the LDS gather, which itself
+                              // runs one step ahead of the MFMAs)
 
 typedef short tw_i16x4 __attribute__((ext_vector_type(4)));
 
@@ -184,26 +186,36 @@ __device__ __forceinline__ void load_a_block(const TwGemmParams& p, unsigned cha
     a_zero_row(p, at, 32 * MS, tid);
 }
 
-// Operand registers of the main loop that live across tiles: packed B and K indices of the next
-// kPrefetch steps.
+// Operand registers of the main loop: packed B of the next kPrefetch steps, K indices of the next
+// kIdxAhead steps.
 template <int NCB>
 struct StepRegs {
     tw_u16x8 bq[kPrefetch][NCB];
-    unsigned kk[kPrefetch];
+    unsigned kk[kIdxAhead];
 };
 
-// Requests the packed B and the K indices of step s (clamped to `last`) of a tile into slot `slot`.
+// Requests the packed B of step s (clamped to `last`) of a tile into slot `slot`.
 template <int NCB>
-__device__ __forceinline__ void issue_step(StepRegs<NCB>& rg, int slot, const unsigned char* gk, const unsigned char* bl,
-                                           int s, int last) {
+__device__ __forceinline__ void issue_b(StepRegs<NCB>& rg, int slot, const unsigned char* bl, int s, int last) {
     s = s < last ? s : last;
-    rg.kk[slot] = *(const unsigned*)(gk + (long)s * 32);
     const unsigned char* b = bl + ((long)s * NCB) * 1024;
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) rg.bq[slot][cb] = *(const tw_u16x8*)(b + cb * 1024);
+    for (int cb = 0; cb < NCB; ++cb) {
+#ifdef TW_NT_LOAD
+        rg.bq[slot][cb] = __builtin_nontemporal_load((const tw_u16x8*)(b + cb * 1024));
+#else
+        rg.bq[slot][cb] = *(const tw_u16x8*)(b + cb * 1024);
+#endif
+    }
+}
+// Requests this lane's two K indices of step s (clamped to `last`) into slot `slot`.
+template <int NCB>
+__device__ __forceinline__ void issue_k(StepRegs<NCB>& rg, int slot, const unsigned char* gk, int s, int last) {
+    s = s < last ? s : last;
+    rg.kk[slot] = *(const unsigned*)(gk + (long)s * 32);
 }
 
-// Requests steps s0 .. s0+kPrefetch-1 of a tile; the range [s0, s1) must not be empty.
+// Requests the first steps of a tile; the range [s0, s1) must not be empty.
 template <int NCB>
 __device__ __forceinline__ void prefetch_first_steps(StepRegs<NCB>& rg, const unsigned char* goff_tile,
                                                      const unsigned char* bvals_tile, int s0, int s1, int lane_in) {
@@ -211,13 +223,15 @@ __device__ __forceinline__ void prefetch_first_steps(StepRegs<NCB>& rg, const un
     const unsigned char* gk = goff_tile + ((lane >> 5) * 4 + ((lane & 15) >> 2)) * 4;
     const unsigned char* bl = bvals_tile + lane * 16;
 #pragma unroll
-    for (int i = 0; i < kPrefetch; ++i) issue_step<NCB>(rg, i, gk, bl, s0 + i, s1 - 1);
+    for (int i = 0; i < kIdxAhead; ++i) issue_k<NCB>(rg, i, gk, s0 + i, s1 - 1);
+#pragma unroll
+    for (int i = 0; i < kPrefetch; ++i) issue_b<NCB>(rg, i, bl, s0 + i, s1 - 1);
 }
 
 // Steps [s0, s1) (not empty) of one tile for this wave: gather A from LDS, stream packed B from global, MFMA.
-// Expects the first kPrefetch steps in `rg` (prefetch_first_steps).  The packed B and the K indices of
-// step s+kPrefetch are requested while step s is multiplied, and the LDS gather of step s+1 is issued
-// before the MFMAs of step s, so both latencies hide behind MFMAs.  The loop body has no branches
+// Expects the first steps in `rg` (prefetch_first_steps).  The packed B of step s+kPrefetch and the K
+// indices of step s+kIdxAhead are requested while step s is multiplied, and the LDS gather of step s+1
+// is issued before the MFMAs of step s, so both latencies hide behind MFMAs.  The loop body has no branches
 // except its exits (requests past the last step are clamped to the last step and never used), which
 // keeps the compiler's wait counts exact.
 template <int DT, int MS, int NCB>
@@ -253,25 +267,36 @@ __device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], StepRegs<NC
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms) a[1][ms] = tw_u16x8{0, 0, 0, 0, 0, 0, 0, 0};
     gather(a[0], rg.kk[0]);
-    constexpr int kUnroll = (kPrefetch % 2 == 0) ? kPrefetch : 2 * kPrefetch;
+    constexpr int kUnroll = 6;                      // a multiple of 2, kPrefetch and kIdxAhead
+    static_assert(kUnroll % 2 == 0 && kUnroll % kPrefetch == 0 && kUnroll % kIdxAhead == 0, "unroll factor");
     auto step = [&](int i, int s) {
-        const int slot = i % kPrefetch;
         // the three stages keep this order: left alone, the instruction scheduler sinks the loads of
-        // step s+kPrefetch next to their first use and the prefetch distance is lost
+        // later steps next to their first use and the prefetch distance is lost
 #ifdef TW_EXPERIMENT
         if (!(TWD(dbg) & 128))
 #endif
-        gather(a[(i + 1) & 1], rg.kk[(i + 1) % kPrefetch]);
+        gather(a[(i + 1) & 1], rg.kk[(i + 1) % kIdxAhead]);
         __builtin_amdgcn_sched_barrier(0);
+        // the request for a column block of step s+kPrefetch follows the MFMAs that read its registers:
+        // the requests reach the memory pipeline spread over the step instead of in a burst
+        const int sb = (s + kPrefetch) < last ? (s + kPrefetch) : last;
+        const unsigned char* bnext = bl + ((long)sb * NCB) * 1024;
 #pragma unroll
-        for (int cb = 0; cb < NCB; ++cb)
+        for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
-            for (int ms = 0; ms < MS; ++ms) acc[ms][cb] = tw_mfma<DT>(a[i & 1][ms], rg.bq[slot][cb], acc[ms][cb]);
-        __builtin_amdgcn_sched_barrier(0);
+            for (int ms = 0; ms < MS; ++ms)
+                acc[ms][cb] = tw_mfma<DT>(a[i & 1][ms], rg.bq[i % kPrefetch][cb], acc[ms][cb]);
+            __builtin_amdgcn_sched_barrier(0);
+#ifdef TW_EXPERIMENT
+            if (!(TWD(dbg) & 64))
+#endif
+            rg.bq[i % kPrefetch][cb] = *(const tw_u16x8*)(bnext + cb * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #ifdef TW_EXPERIMENT
         if (!(TWD(dbg) & 64))
 #endif
-        issue_step<NCB>(rg, slot, gk, bl, s + kPrefetch, last);
+        issue_k<NCB>(rg, i % kIdxAhead, gk, s + kIdxAhead, last);
         __builtin_amdgcn_sched_barrier(0);
     };
     int s = s0;
@@ -305,7 +330,7 @@ constexpr int kWinCols = kWinLines * kLineCols;     // 256
 constexpr int kStagePitch = kWinLines * 128 + 16;   // 528 bytes; the tail takes writes of absent columns
 constexpr int kDummyOff = kWinLines * 128;
 constexpr int kStageRows = 8;
-static_assert(kStageRows * kStagePitch <= TW_STAGE_BYTES, "staging area too small");
+constexpr unsigned kStageBytes = kStageRows * kStagePitch;   // per wave
 
 __device__ __forceinline__ void tw_compiler_fence() { asm volatile("" ::: "memory"); }
 
@@ -462,7 +487,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
     constexpr int BM = 32 * MSB;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = uni(tid >> 6);
-    unsigned char* stage = smem + p.stage_off + wave * TW_STAGE_BYTES;
+    unsigned char* stage = smem + p.stage_off + wave * kStageBytes;
     volatile int* misc = (volatile int*)(smem + p.misc_off);
     const int* step_ptr = (const int*)(p.blob + p.off_step_ptr);
 
@@ -634,7 +659,7 @@ unsigned at_bytes(int msb, int k_chunk) {
     return ((unsigned)(k_chunk + 9) * pitch + 15u) & ~15u;
 }
 unsigned lds_need(int msb, int k_chunk, int buffers) {
-    return buffers * at_bytes(msb, k_chunk) + kWaves * TW_STAGE_BYTES + 16u;
+    return buffers * at_bytes(msb, k_chunk) + kWaves * kStageBytes + 16u;
 }
 
 int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
@@ -677,7 +702,7 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
     pl.at_pitch = 64u * msb + 8u;
     pl.abuf_bytes = at_bytes(msb, h->k_chunk);
     pl.stage_off = buffers * pl.abuf_bytes;
-    pl.misc_off = pl.stage_off + kWaves * TW_STAGE_BYTES;
+    pl.misc_off = pl.stage_off + kWaves * kStageBytes;
     pl.lds_bytes = pl.misc_off + 16u;
     return TW_OK;
 }

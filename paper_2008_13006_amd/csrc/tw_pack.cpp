@@ -268,19 +268,16 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
         }
     }
     // Dispatch order of the kernel.  With K resident the waves of a workgroup pull tiles one after the
-    // other: the first TW_WAVES_PER_WG pulls alternate between the heaviest and the lightest tiles, so
-    // the waves leave their first tile at different times and their store phases do not coincide;
-    // the remaining tiles follow heaviest first.  With K streamed the waves of a set advance in
-    // lock step, so sets hold tiles of similar weight (plain heaviest-first order).
+    // other.  Nothing can be stored before the first tiles are finished, and while nothing is stored
+    // the memory system idles, so the first TW_WAVES_PER_WG pulls get the lightest tiles (lightest
+    // first); the remaining tiles follow heaviest first, which keeps the end of a workgroup balanced.
+    // With K streamed the waves of a set advance in lock step, so sets hold tiles of similar weight
+    // (plain heaviest-first order).
     std::vector<int32_t> dispatch(order);
-    if (lo.n_chunks == 1 && tl.T >= TW_WAVES_PER_WG) {
-        const int half = TW_WAVES_PER_WG / 2;
+    if (lo.n_chunks == 1 && tl.T > TW_WAVES_PER_WG) {
         int n = 0;
-        for (int i = 0; i < half; ++i) {
-            dispatch[n++] = order[i];
-            dispatch[n++] = order[tl.T - 1 - i];
-        }
-        for (int i = half; i < tl.T - half; ++i) dispatch[n++] = order[i];
+        for (int i = 0; i < TW_WAVES_PER_WG; ++i) dispatch[n++] = order[tl.T - 1 - i];
+        for (int i = 0; i < tl.T - TW_WAVES_PER_WG; ++i) dispatch[n++] = order[i];
     }
     TwSchedDesc* sd = (TwSchedDesc*)(base + lo.off_sched_desc);
     for (int i = 0; i < tl.T; ++i) {
