@@ -516,7 +516,13 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             int i = 0;
             if (lane == 0) i = atomicAdd((int*)&misc[1], 1);
             int ti = seg + uni(i) * p.n_seg;
-            TileU next = fetch_tile(p, ti < p.T ? ti : 0);
+#ifdef TW_ROTATE
+            const int rot = (int)((mb * 5u) % (unsigned)p.T);
+#define TW_ROT(t) (((t) + rot) % p.T)
+#else
+#define TW_ROT(t) (t)
+#endif
+            TileU next = fetch_tile(p, ti < p.T ? TW_ROT(ti) : 0);
 #ifdef TW_EXPERIMENT
             if (!(TWD(p.dbg) & 1))
 #endif
@@ -532,7 +538,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 // claim the next tile now so that its descriptor arrives during this tile's work
                 if (lane == 0) i = atomicAdd((int*)&misc[1], 1);
                 ti = seg + uni(i) * p.n_seg;
-                next = fetch_tile(p, ti < p.T ? ti : 0);
+                next = fetch_tile(p, ti < p.T ? TW_ROT(ti) : 0);
 
                 // destination columns of this lane's packed columns, needed only in the epilogue: request them now
                 unsigned dpos[NCB];

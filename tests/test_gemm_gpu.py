@@ -91,6 +91,13 @@ SMALL = [
     ("kept_one_row_each", 40, 64, 256, 128, "f16", 0.0, ("const", 0.0)),
     ("streamed_k", 100, 2304, 200, 64, "f16", 0.1, ("upow", 0.05, 0.5)),
     ("streamed_k_bf16_ragged", 67, 2100, 300, 128, "bf16", 0.05, ("upow", 0.02, 0.6)),
+    # 70 % of the columns pruned: a tile of 128 kept columns spans ~430 original columns, more than one
+    # staging window of the epilogue
+    ("wide_spans", 90, 256, 1400, 128, "f16", 0.7, ("upow", 0.1, 0.6)),
+    ("wide_spans_bf16_g64", 45, 160, 900, 64, "bf16", 0.8, ("upow", 0.1, 0.9)),
+    # few kept columns: spans narrower than a 16-byte group
+    ("thin_tiles", 37, 64, 24, 32, "f16", 0.75, ("const", 0.5)),
+    ("odd_everything", 71, 333, 1001, 128, "f16", 0.33, ("upow", 0.05, 0.8)),
 ]
 
 
