@@ -167,6 +167,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--report", type=str, default=None, help="also time all five workloads, write a table here")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", type=str, default=None,
+                    help="also run the sparsity x G sweep on the FFN-up shape, write a table (JSON) here")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="counter runs: launch only a copy kernel of known size, then the tw_gemm steps")
     args = ap.parse_args()
@@ -219,6 +221,24 @@ def main() -> int:
                       file=sys.stderr, flush=True)
                 torch.cuda.empty_cache()
         with open(args.report, "w") as f:
+            json.dump(rows, f, indent=1)
+    if args.sweep:
+        rows = []
+        dense_ms = None
+        for G in (32, 64, 128):
+            for sp in (0.0, 0.25, 0.5, 0.625, 0.75, 0.875, 0.95, 0.99):
+                spec_s = W.sweep_spec(G, sp)
+                r, _, _ = bench_gemm(torch, tw, W, spec_s, max(20, args.steps // 4), 5, with_dense=dense_ms is None)
+                if dense_ms is None:
+                    dense_ms = r["dense_ms"]
+                r["dense_ms"] = dense_ms
+                r["speedup_vs_dense"] = dense_ms / r["tw_ms"]
+                rows.append(r)
+                print(f"[sweep] G={G:3d} sparsity {r['sparsity']:.3f} T={r['T']:3d}: tw {r['tw_ms']*1e3:6.1f} us  "
+                      f"x{r['speedup_vs_dense']:.2f} vs dense {dense_ms*1e3:.1f} us  nz {r['tw_tflops_nonzero']:.0f} TF "
+                      f"({100*r['tw_mfma_frac_nonzero']:.1f} % of MFMA peak)  {r['tw_gbs']:.0f} GB/s", file=sys.stderr, flush=True)
+                torch.cuda.empty_cache()
+        with open(args.sweep, "w") as f:
             json.dump(rows, f, indent=1)
     print(json.dumps(line), flush=True)
     return 0

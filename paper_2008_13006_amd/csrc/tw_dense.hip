@@ -4,7 +4,8 @@
 //
 // Workgroup: 256 x 256 block of C, 8 waves as 2 (rows) x 4 (columns), wave tile 128 x 64.
 // K advances 64 at a time through two LDS buffers; global loads of step i+1 are in flight
-// while step i is multiplied.
+// while step i is multiplied.  The activation operand is read from LDS 16 bytes per lane, the
+// weight operand with transposing reads (ds_read_b64_tr_b16) of the row-major B tile.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
@@ -14,14 +15,15 @@
 
 namespace {
 
+typedef short tw_i16x4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 512;
 constexpr int BM = 256, BN = 256, KB = 64;
 constexpr int A_PITCH = KB * 2 + 16;   // 144 B: 16-byte reads of 16 consecutive rows hit distinct banks
-constexpr int B_PITCH = BN * 2 + 8;    // 520 B
+constexpr int B_PITCH = BN * 2 + 64;   // 576 B: four consecutive K rows start 16 banks apart, as the transposing reads want
 constexpr int A_BYTES = BM * A_PITCH;  // 36864
-constexpr int B_BYTES = KB * B_PITCH;  // 33280
+constexpr int B_BYTES = KB * B_PITCH;  // 36864
 constexpr int BUF_BYTES = A_BYTES + B_BYTES;
-constexpr int LDS_BYTES = 2 * BUF_BYTES;  // 140288
+constexpr int LDS_BYTES = 2 * BUF_BYTES;  // 147456
 
 struct DenseParams {
     const unsigned short* A;
@@ -82,9 +84,7 @@ __device__ __forceinline__ void lds_commit(unsigned char* buf, int tid, const St
     for (int i = 0; i < 4; ++i) {
         const int id = tid + kThreads * i;
         const int r = id >> 5, u = id & 31;
-        unsigned char* d = buf + A_BYTES + r * B_PITCH + u * 16;
-        *(tw_u32x2*)d = tw_u32x2{st.b[i].x, st.b[i].y};
-        *(tw_u32x2*)(d + 8) = tw_u32x2{st.b[i].z, st.b[i].w};
+        *(tw_u32x4*)(buf + A_BYTES + r * B_PITCH + u * 16) = st.b[i];
     }
 }
 
@@ -125,15 +125,24 @@ __global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p)
         if (more) global_fetch(p, m0, n0, (kt + 1) * KB, tid, st);
 
         const unsigned char* la = cur + (wm * 128 + l32) * A_PITCH + h * 16;
-        const unsigned char* lb = cur + A_BYTES + (8 * h) * B_PITCH + (wn * 64 + l32) * 2;
+        // weight operand by transposing reads of the row-major (K-major) B tile: in each 16-lane block,
+        // lane j addresses K row 8h + 4r + j/4 at the four columns 4*(j%4) .. of the block's 16 columns
+        const int j = lane & 15;
+        const unsigned char* lb = cur + A_BYTES + (8 * h + (j >> 2)) * B_PITCH +
+                                  (wn * 64 + ((lane >> 4) & 1) * 16 + (j & 3) * 4) * 2;
 #pragma unroll
         for (int ks = 0; ks < KB / 16; ++ks) {
             tw_u16x8 w[2], a[4];
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    w[cb][e] = *(const unsigned short*)(lb + (ks * 16 + e) * B_PITCH + cb * 64);
+            for (int cb = 0; cb < 2; ++cb) {
+                const tw_i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) tw_i16x4*)(lb + (ks * 16) * B_PITCH + cb * 64));
+                const tw_i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) tw_i16x4*)(lb + (ks * 16 + 4) * B_PITCH + cb * 64));
+                w[cb] = tw_u16x8{(unsigned short)lo4[0], (unsigned short)lo4[1], (unsigned short)lo4[2],
+                                 (unsigned short)lo4[3], (unsigned short)hi4[0], (unsigned short)hi4[1],
+                                 (unsigned short)hi4[2], (unsigned short)hi4[3]};
+            }
 #pragma unroll
             for (int ms = 0; ms < 4; ++ms) a[ms] = *(const tw_u16x8*)(la + ms * 32 * A_PITCH + ks * 32);
 #pragma unroll

@@ -201,11 +201,7 @@ __device__ __forceinline__ void issue_b(StepRegs<NCB>& rg, int slot, const unsig
     const unsigned char* b = bl + ((long)s * NCB) * 1024;
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
-#ifdef TW_NT_LOAD
-        rg.bq[slot][cb] = __builtin_nontemporal_load((const tw_u16x8*)(b + cb * 1024));
-#else
         rg.bq[slot][cb] = *(const tw_u16x8*)(b + cb * 1024);
-#endif
     }
 }
 // Requests this lane's two K indices of step s (clamped to `last`) into slot `slot`.
@@ -516,13 +512,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             int i = 0;
             if (lane == 0) i = atomicAdd((int*)&misc[1], 1);
             int ti = seg + uni(i) * p.n_seg;
-#ifdef TW_ROTATE
-            const int rot = (int)((mb * 5u) % (unsigned)p.T);
-#define TW_ROT(t) (((t) + rot) % p.T)
-#else
-#define TW_ROT(t) (t)
-#endif
-            TileU next = fetch_tile(p, ti < p.T ? TW_ROT(ti) : 0);
+            TileU next = fetch_tile(p, ti < p.T ? ti : 0);
 #ifdef TW_EXPERIMENT
             if (!(TWD(p.dbg) & 1))
 #endif
@@ -538,7 +528,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 // claim the next tile now so that its descriptor arrives during this tile's work
                 if (lane == 0) i = atomicAdd((int*)&misc[1], 1);
                 ti = seg + uni(i) * p.n_seg;
-                next = fetch_tile(p, ti < p.T ? TW_ROT(ti) : 0);
+                next = fetch_tile(p, ti < p.T ? ti : 0);
 
                 // destination columns of this lane's packed columns, needed only in the epilogue: request them now
                 unsigned dpos[NCB];
@@ -607,28 +597,60 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 load_a_block<MSB, AB>(p, smem, row0, 0, kw, wave, lane, tid);
                 a_zero_row(p, smem + p.abuf_bytes, BM, tid);
             }
-            __syncthreads();
-            for (int c = 0; c < p.n_chunks; ++c) {
-                unsigned char* cur = smem + (c & 1) * p.abuf_bytes;
-                unsigned char* nxt = smem + ((c + 1) & 1) * p.abuf_bytes;
-                const bool more = c + 1 < p.n_chunks;
-                const int k0n = (c + 1) * p.k_chunk;
-                const int kwn = (p.K - k0n) < p.k_chunk ? (p.K - k0n) : p.k_chunk;
-                ARegs<AB> ar;
-                if (more) {
-                    a_issue<MSB, AB>(p, ar, row0, k0n, kwn, wave, lane);
+            // Requests run kAhead chunks ahead of the steps: two where the registers allow it (narrow
+            // tiles), so that a chunk is always on its way from memory, else one.
+            constexpr int kAhead = (MS * NCB <= 4) ? 2 : 1;
+            auto chunk_width = [&](int c) {
+                const int k0 = c * p.k_chunk;
+                return (p.K - k0) < p.k_chunk ? (p.K - k0) : p.k_chunk;
+            };
+            auto issue_or_zero = [&](ARegs<AB>& ar, int c) {
+                if (c < p.n_chunks) {
+                    a_issue<MSB, AB>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
                 } else {
 #pragma unroll
                     for (int b = 0; b < AB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
                 }
+            };
+            auto steps_of = [&](int c) {
                 const int c0 = uni(sp[c]), c1 = uni(sp[c + 1]);
                 if (active && c0 < c1) {
                     StepRegs<NCB> rg;
                     prefetch_first_steps<NCB>(rg, gt, bt, c0, c1, lane);
-                    run_steps<DT, MS, NCB>(acc, rg, cur + half * 64, p.at_pitch, gt, bt, c0, c1, lane);
+                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes + half * 64, p.at_pitch, gt, bt, c0, c1,
+                                           lane);
                 }
-                if (more) a_commit<MSB, AB>(p, ar, nxt, kwn, wave, lane);
+            };
+            auto commit = [&](const ARegs<AB>& ar, int c) {
+                if (c < p.n_chunks) a_commit<MSB, AB>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), wave, lane);
+            };
+            if constexpr (kAhead == 1) {
                 __syncthreads();
+                for (int c = 0; c < p.n_chunks; ++c) {
+                    ARegs<AB> ar;
+                    issue_or_zero(ar, c + 1);
+                    steps_of(c);
+                    commit(ar, c + 1);
+                    __syncthreads();
+                }
+            } else {
+                // chunk j waits in ring register set j % 2; the loop is unrolled by two so that the sets
+                // are addressed statically
+                ARegs<AB> ar0, ar1;
+                issue_or_zero(ar1, 1);
+                __syncthreads();
+                for (int c = 0; c < p.n_chunks; c += 2) {
+                    issue_or_zero(ar0, c + 2);
+                    steps_of(c);
+                    commit(ar1, c + 1);
+                    __syncthreads();
+                    if (c + 1 < p.n_chunks) {
+                        issue_or_zero(ar1, c + 3);
+                        steps_of(c + 1);
+                        commit(ar0, c + 2);
+                    }
+                    __syncthreads();
+                }
             }
             if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0 + 32 * half, lane);
         }

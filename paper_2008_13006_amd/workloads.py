@@ -239,6 +239,21 @@ def small_spec(name: str, M: int, K: int, N: int, G: int, dtype: str = F16, col_
                     col_prune=col_prune, keep=keep, sparsity=sparsity, seed_offset=seed_offset)
 
 
+def sweep_spec(G: int, sparsity: float, M: int = 16384, K: int = 768, N: int = 3072, dtype: str = F16) -> GemmSpec:
+    """Sparsity x granularity sweep on the BERT-base FFN-up shape (the experiment of Sec. VII-B, Fig. 8b and
+    Fig. 10, on synthetic masks): 5 % of the columns pruned (none at 0 % sparsity), per-tile keep
+    fractions spread between 0.4x and 1.9x of the mean, bisected onto the target."""
+    if sparsity <= 0.0:
+        return GemmSpec(name=f"sweep_G{G}_s0", M=M, K=K, N=N, dtype=dtype, G=G, col_prune=0.0,
+                        keep=("const", 1.0), seed_offset=7000 + G)
+    cp = min(0.05, sparsity / 2)
+    f = (1.0 - sparsity) / (1.0 - cp)
+    lo, hi = max(0.4 * f, 1.0 / K), min(1.9 * f, 1.0)
+    return GemmSpec(name=f"sweep_G{G}_s{int(round(sparsity * 1000))}", M=M, K=K, N=N, dtype=dtype, G=G,
+                    col_prune=cp, keep=("upow", lo, hi), sparsity=sparsity,
+                    seed_offset=7000 + G + int(round(sparsity * 1000)))
+
+
 def nonzero_flops(mask: np.ndarray, M: int) -> int:
     """2*M*(number of kept weights): the work the TW method itself has to do."""
     return 2 * int(M) * int(mask.sum(dtype=np.int64))
