@@ -29,7 +29,7 @@ MFMA_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA
 # HBM bytes per tw_gemm launch on this workload, from the two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) summarised in profiles/tw_gemm_c2_hbm_traffic.txt, each scaled by what the same counter
 # reads for the copy kernel of known size that `--pmc-calibration` launches.
-MEASURED_TRAFFIC_BYTES = 147_297_014      # 35.63 MB read + 111.67 MB written
+MEASURED_TRAFFIC_BYTES = 149_839_612      # 35.59 MB read + 114.25 MB written
 PAPER_CONTEXT = {"tw128_speedup_vs_dense_75pct": 2.26, "hardware": "NVIDIA V100 tensor cores, FP16",
                  "where": "Sec. VII-B, Fig. 8b"}
 
@@ -203,7 +203,7 @@ def main() -> int:
         "torch_matmul_dense_ms_context": res["torch_matmul_ms"], "pack_ms_offline": res["pack_ms"],
         "roofline": {"bound": "hbm", "achieved": res["tw_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": res["tw_hbm_frac"], "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "tw_gemm_kernel<f16, 64 rows, G=128, K resident>",
+                     "kernel": "tw_gemm_kernel<f16, MS=2 (64 rows), NCB=4 (G=128), MODE 0 (K resident)>",
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"]},
         "paper_context": PAPER_CONTEXT,
     }
