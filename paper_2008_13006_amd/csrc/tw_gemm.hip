@@ -129,14 +129,14 @@ struct ATask {
     }
 };
 
-// requests tasks t0, t0+8, ... (BATCH of them) of the block
+// requests tasks t0, t0+stride, ... (BATCH of them) of the block; stride = number of loading waves
 template <int MS, int BATCH>
 __device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int row0, int k0, int kw, int t0,
-                                        int lane_in) {
+                                        int lane_in, int stride = kWaves) {
     const int lane = fresh(lane_in);
 #pragma unroll
     for (int b = 0; b < BATCH; ++b) {
-        const ATask<MS> t(t0 + b * kWaves, kw, lane);
+        const ATask<MS> t(t0 + b * stride, kw, lane);
         int grow = row0 + t.row;
         grow = grow < p.M ? grow : p.M - 1;           // rows past M: any valid row, never stored
         ar.v[b] = *(const tw_u32x4*)(p.A + (long)grow * p.lda + (k0 + t.oc * 8));
@@ -146,13 +146,13 @@ __device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar,
 // writes what a_issue requested into the LDS copy `at`
 template <int MS, int BATCH>
 __device__ __forceinline__ void a_commit(const TwGemmParams& p, const ARegs<BATCH>& ar, unsigned char* at, int kw, int t0,
-                                         int lane_in) {
+                                         int lane_in, int stride = kWaves) {
     const int lane = fresh(lane_in);
     const int dump = p.k_chunk + 1;
     const bool tail = (kw & 7) != 0;                  // wave-uniform
 #pragma unroll
     for (int b = 0; b < BATCH; ++b) {
-        const ATask<MS> t(t0 + b * kWaves, kw, lane);
+        const ATask<MS> t(t0 + b * stride, kw, lane);
         const int kcol = t.have ? t.oc * 8 : dump;
         unsigned char* dst = at + (unsigned)kcol * p.at_pitch + t.row * 2;
         const unsigned w[4] = {ar.v[b].x, ar.v[b].y, ar.v[b].z, ar.v[b].w};
@@ -474,12 +474,13 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 
 // MODE 0: the K extent of a row block of 32*MS rows is resident in LDS, waves pull whole tiles.
 // MODE 1: K streamed through two LDS buffers, row block of 32*MS rows, wave w owns tile 8*set + w.
-// MODE 2: K streamed, row block of 64 rows, for weights with at most four tiles: wave w owns the
-//         32-row half w%2 of tile 4*set + w/2 (MS = 1 is the wave's height).
+// MODE 2: K streamed, row block of 64 rows (MS = 2), for weights with at most four tiles: waves 0-3
+//         multiply (wave w owns tile 4*set + w), waves 4-7 do nothing but bring A into LDS, so the
+//         two kinds of work overlap instead of taking turns.
 template <int DT, int MS, int NCB, int MODE>
 __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int MSB = MODE == 2 ? 2 : MS;      // 32-row blocks in the workgroup's row block
+    constexpr int MSB = MS;                       // 32-row blocks in the workgroup's row block
     constexpr int BM = 32 * MSB;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = uni(tid >> 6);
@@ -571,13 +572,109 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 TW_MARK();
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
+        } else if constexpr (MODE == 2) {
+            // K streamed, multiplying waves and loading waves.  Chunk c is multiplied out of buffer c % 2
+            // while the loading waves write chunk c+1 into the other buffer and request chunk c+3;
+            // one barrier per chunk.
+            constexpr int NMUL = kWaves / 2, NLD = kWaves - NMUL;
+            constexpr int PB = 12;   // requests per loading wave and chunk: 64 rows x 384 columns in 4 waves
+            const int set = item / p.n_mblocks, mb = item - set * p.n_mblocks;
+            const int row0 = mb * BM;
+            const bool loader = wave >= NMUL;
+            const int ti = set * NMUL + wave;
+            const bool active = !loader && ti < p.T;
+            const TileU d = fetch_tile(p, active ? ti : 0);
+            const int* sp = step_ptr + d.step_ptr;
+            const unsigned char* gt = p.blob + p.off_goff + (long)d.first_step * 32;
+            const unsigned char* bt = p.blob + p.off_bvals + (long)d.first_step * NCB * 1024;
+            auto chunk_width = [&](int c) {
+                const int k0 = c * p.k_chunk;
+                return (p.K - k0) < p.k_chunk ? (p.K - k0) : p.k_chunk;
+            };
+            if (tid < BM / 2) {
+                *(unsigned*)(smem + (unsigned)p.k_chunk * p.at_pitch + tid * 4) = 0u;
+                *(unsigned*)(smem + p.abuf_bytes + (unsigned)p.k_chunk * p.at_pitch + tid * 4) = 0u;
+            }
+            if (loader) {
+                const int lw = wave - NMUL;
+                auto issue_or_zero = [&](ARegs<PB>& ar, int c) {
+                    if (c < p.n_chunks) {
+                        a_issue<MSB, PB>(p, ar, row0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < PB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
+                    }
+                };
+                auto commit = [&](const ARegs<PB>& ar, int c) {
+                    if (c < p.n_chunks)
+                        a_commit<MSB, PB>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), lw, lane, NLD);
+                };
+                // chunk j waits in register set j % 2; the loop is unrolled by two so that the sets are
+                // addressed statically
+                ARegs<PB> ar0, ar1;
+                issue_or_zero(ar0, 0);
+                issue_or_zero(ar1, 1);
+                commit(ar0, 0);
+                issue_or_zero(ar0, 2);
+                __syncthreads();
+                for (int c = 0; c < p.n_chunks; c += 2) {
+                    commit(ar1, c + 1);
+                    issue_or_zero(ar1, c + 3);
+                    __syncthreads();
+                    if (c + 1 < p.n_chunks) {
+                        commit(ar0, c + 2);
+                        issue_or_zero(ar0, c + 4);
+                    }
+                    __syncthreads();
+                }
+            } else {
+                unsigned dpos[NCB];
+                {
+                    const unsigned* dp = (const unsigned*)(p.blob + p.off_dpos) + ((long)d.tile * 32 + (lane & 31)) * NCB;
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb) dpos[cb] = dp[cb];
+                }
+                tw_f32x16 acc[MS][NCB];
+                zero_acc<MS, NCB>(acc);
+                // the first steps of a chunk are requested at the end of the previous chunk's steps, so
+                // they arrive while the workgroup meets at the barrier
+                StepRegs<NCB> rg;
+                auto prefetch_chunk = [&](int c) {
+                    int c0 = 0, c1 = 0;
+                    if (c < p.n_chunks) { c0 = uni(sp[c]); c1 = uni(sp[c + 1]); }
+                    if (active && c0 < c1) {
+                        prefetch_first_steps<NCB>(rg, gt, bt, c0, c1, lane);
+                    } else {                               // defined on every path
+#pragma unroll
+                        for (int i = 0; i < kIdxAhead; ++i) rg.kk[i] = 0u;
+#pragma unroll
+                        for (int i = 0; i < kPrefetch; ++i)
+#pragma unroll
+                            for (int cb = 0; cb < NCB; ++cb) rg.bq[i][cb] = tw_u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+                    }
+                };
+                auto steps_of = [&](int c) {
+                    const int c0 = uni(sp[c]), c1 = uni(sp[c + 1]);
+                    if (active && c0 < c1)
+                        run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, c0, c1, lane);
+                    prefetch_chunk(c + 1);
+                };
+                prefetch_chunk(0);
+                __syncthreads();
+                for (int c = 0; c < p.n_chunks; c += 2) {
+                    steps_of(c);
+                    __syncthreads();
+                    if (c + 1 < p.n_chunks) steps_of(c + 1);
+                    __syncthreads();
+                }
+                if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+            }
         } else {
             // K is streamed in chunks through two LDS buffers: the requests for chunk c+1 go out before
             // the steps of chunk c and are written to the other buffer after them, one barrier per chunk
             const int set = item / p.n_mblocks, mb = item - set * p.n_mblocks;
             const int row0 = mb * BM;
-            const int ti = MODE == 2 ? set * (kWaves / 2) + (wave >> 1) : set * kWaves + wave;
-            const int half = MODE == 2 ? (wave & 1) : 0;
+            const int ti = set * kWaves + wave;
             const bool active = ti < p.T;
             const TileU d = fetch_tile(p, active ? ti : 0);
             unsigned dpos[NCB];
@@ -617,7 +714,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (active && c0 < c1) {
                     StepRegs<NCB> rg;
                     prefetch_first_steps<NCB>(rg, gt, bt, c0, c1, lane);
-                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes + half * 64, p.at_pitch, gt, bt, c0, c1,
+                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, c0, c1,
                                            lane);
                 }
             };
@@ -652,7 +749,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     __syncthreads();
                 }
             }
-            if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0 + 32 * half, lane);
+            if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
         }
     }
     // the last workgroup to leave puts the counters back to zero for the next call
@@ -718,9 +815,8 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
     }
     pl.mode = resident ? 0 : 1;
     pl.ms = msb;
-    if (!resident && msb == 2 && T <= kWaves / 2) {   // few tiles: two waves share a tile, 32 rows each
+    if (!resident && msb == 2 && T <= kWaves / 2) {   // few tiles: half of the waves only load A
         pl.mode = 2;
-        pl.ms = 1;
         tpw = kWaves / 2;
     }
     const long items = items_for(msb, tpw, nmb, nseg);
@@ -751,7 +847,7 @@ template <int DT>
 KernelFn pick_mode(int mode, int ms, int ncb) {
     if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0>(ncb) : pick_ncb<DT, 1, 0>(ncb);
     if (mode == 1) return ms == 2 ? pick_ncb<DT, 2, 1>(ncb) : pick_ncb<DT, 1, 1>(ncb);
-    return pick_ncb<DT, 1, 2>(ncb);
+    return pick_ncb<DT, 2, 2>(ncb);
 }
 
 KernelFn pick_kernel(int dt, int mode, int ms, int ncb) {
