@@ -108,11 +108,18 @@ int tw_gemm_workspace(const void* blob_host, int M, size_t* ws_bytes);
  * NULL for the default stream) and returns.
  *   blob_host  host copy of the blob (read during the call only)
  *   blob_dev   device copy of the same bytes, 256-byte aligned
- *   A          device, M x K, lda >= K, lda % 8 == 0, 16-byte aligned base
+ *   A          device, M x K, lda >= K, lda % 8 == 0, 16-byte aligned base.  Rows are read in
+ *              16-byte pieces, i.e. up to the next multiple of 8 columns: the buffer must hold
+ *              M x lda elements (what lies between K and that multiple is read and ignored)
  *   C          device, M x N, ldc >= N; EVERY element of C[0:M, 0:N] is written (zeros in pruned
  *              columns); 2-byte aligned rows suffice
  *   workspace  device, >= tw_gemm_workspace bytes, 256-byte aligned, zeroed as described above
- * M >= 0 (M = 0 enqueues nothing). */
+ * M >= 0 (M = 0 enqueues nothing).  Calls on one workspace must not overlap in time (use one
+ * workspace per stream).  The best speed needs a C base and ldc that are multiples of 64 elements
+ * (128-byte lines); any other layout is correct and slower.
+ * Errors: TW_ERR_ARG (null pointer, negative M, lda/ldc too small), TW_ERR_BUF (not a blob of this
+ * format version, workspace too small), TW_ERR_ALIGN, TW_ERR_UNSUPPORTED (more than 2^31 work items),
+ * TW_ERR_HIP (the launch failed); nothing is enqueued when an error is returned. */
 int tw_gemm(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
             void* C, int ldc, void* workspace, size_t ws_bytes, void* hip_stream);
 
