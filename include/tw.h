@@ -97,6 +97,21 @@ int tw_unpack(const void* blob, void* B_out, int ldb, uint8_t* mask_out);
 /* Fill *out from a host blob. */
 int tw_info(const void* blob, tw_info_t* out);
 
+/* One-shot magnitude pruning of a dense weight into the TW pattern: one stage of the paper's pruning
+ * algorithm (Sec. V, Alg. 1) with the weight magnitude as importance score (the "most intuitive"
+ * score of Sec. V), without apriori tuning and without fine-tuning.  Host only.
+ *   1. column stage: the importance of a column is the sum of its magnitudes; the floor(col_prune*N
+ *      + 0.5) least important columns are pruned (the lower index first among equals);
+ *   2. the surviving columns are regrouped G at a time (Sec. IV-A); the importance of a row segment
+ *      (one row of one tile) is the mean magnitude over its columns;
+ *   3. row stage: row segments of ALL tiles are pruned in ascending importance (tile, then row,
+ *      first among equals) until zeros / (K*N) >= sparsity; every tile keeps at least one row.
+ * B: K x N row-major 16-bit values (ldb elements per row); mask_out: K x N bytes, receives 0/1.
+ * Scores are accumulated in double, k ascending for columns and columns ascending for segments.
+ * Returns TW_ERR_ARG for null pointers, non-positive sizes, or fractions outside [0, 1). */
+int tw_prune(const void* B, int ldb, int K, int N, int G, tw_dtype dt, double col_prune,
+             double sparsity, uint8_t* mask_out);
+
 /* ---- device side ---- */
 
 /* Bytes of device workspace tw_gemm needs for M rows (scheduler counters).  The workspace must be

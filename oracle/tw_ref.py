@@ -144,3 +144,51 @@ def tile_structure(mask: np.ndarray, G: int) -> Dict[str, np.ndarray]:
 def masked_weight_bits(B_bits: np.ndarray, mask: np.ndarray) -> np.ndarray:
     """B where the mask keeps it, the +0 pattern elsewhere."""
     return np.where(np.asarray(mask) != 0, B_bits, np.uint16(0)).astype(np.uint16)
+
+
+def prune_one_shot(B_bits: np.ndarray, G: int, dtype: str, col_prune: float, sparsity: float) -> np.ndarray:
+    """One stage of the paper's pruning algorithm (Sec. V, Alg. 1) with |w| as importance score, no apriori
+    tuning, no fine-tuning: columns first (a column is a K x 1 tile, scored by the sum of its magnitudes; the
+    floor(p*N + 0.5) lowest go, lower index first among equals), then the surviving columns are regrouped
+    G at a time and row segments (1 x G tiles, scored by their mean magnitude) are pruned across all tiles
+    in ascending score until zeros / (K*N) >= sparsity; a tile keeps at least one row.
+    Written out with plain loops over rows and columns; scores accumulate in float64 in index order."""
+    K, N = B_bits.shape
+    absB = np.abs(decode(B_bits, dtype))
+    cscore = np.zeros(N, dtype=np.float64)
+    for k in range(K):
+        cscore += absB[k]
+    n_prune = int(np.floor(col_prune * N + 0.5))
+    order = sorted(range(N), key=lambda n: (cscore[n], n))
+    pruned = set(order[:n_prune])
+    cols = [n for n in range(N) if n not in pruned]
+    mask = np.zeros((K, N), dtype=np.uint8)
+    if not cols:
+        return mask
+    tiles = [cols[i:i + G] for i in range(0, len(cols), G)]
+    segs = []                                   # (score, tile, row, width)
+    for t, tc in enumerate(tiles):
+        acc = np.zeros(K, dtype=np.float64)
+        for n in tc:
+            acc += absB[:, n]
+        sc = acc / len(tc)
+        for k in range(K):
+            segs.append((float(sc[k]), t, k, len(tc)))
+    segs.sort(key=lambda x: (x[0], x[1], x[2]))
+    want = int(np.ceil(sparsity * float(K * N)))
+    zeros = K * (N - len(cols))
+    left = [K] * len(tiles)
+    drop = set()
+    for sc, t, k, w in segs:
+        if zeros >= want:
+            break
+        if left[t] <= 1:
+            continue
+        drop.add((t, k))
+        left[t] -= 1
+        zeros += w
+    for t, tc in enumerate(tiles):
+        for k in range(K):
+            if (t, k) not in drop:
+                mask[k, tc] = 1
+    return mask

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libtw.so")
 TW_F16, TW_BF16 = 0, 1
 _DT = {"f16": TW_F16, "bf16": TW_BF16}
 
-SYMBOLS = ["tw_pack_size", "tw_pack", "tw_unpack", "tw_info", "tw_gemm_workspace", "tw_gemm",
+SYMBOLS = ["tw_pack_size", "tw_pack", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm",
            "tw_dense_gemm", "tw_strerror", "tw_version"]
 
 
@@ -108,6 +108,17 @@ def _aligned_bytes(n: int, align: int) -> np.ndarray:
     raw = np.zeros(n + align, dtype=np.uint8)
     off = (-raw.ctypes.data) % align
     return raw[off:off + n]
+
+
+def tw_prune(B_bits: np.ndarray, G: int, dtype: str, col_prune: float, sparsity: float) -> np.ndarray:
+    """One-shot magnitude pruning into the TW pattern; returns the uint8 [K, N] mask."""
+    assert B_bits.dtype == np.uint16 and B_bits.ndim == 2 and B_bits.strides[1] == 2
+    K, N = B_bits.shape
+    ldb = B_bits.strides[0] // 2 if K > 1 else N
+    mask = np.empty((K, N), dtype=np.uint8)
+    _check(_lib.tw_prune(_np_ptr(B_bits), ldb, K, N, G, _DT[dtype], ctypes.c_double(col_prune),
+                         ctypes.c_double(sparsity), _np_ptr(mask)), "tw_prune")
+    return mask
 
 
 def tw_unpack(blob: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:

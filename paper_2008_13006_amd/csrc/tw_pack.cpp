@@ -6,6 +6,7 @@
 #include "tw_format.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <numeric>
 #include <vector>
@@ -362,3 +363,90 @@ extern "C" const char* tw_strerror(int status) {
 }
 
 extern "C" int tw_version(void) { return TW_FORMAT_VERSION; }
+
+// ---- one-shot magnitude pruning into the TW pattern (one stage of Alg. 1 without fine-tuning) ----
+namespace {
+
+// 16-bit storage value -> double, exactly
+double half_to_double(uint16_t b) {
+    const int sign = b >> 15, e = (b >> 10) & 31, m = b & 1023;
+    double v;
+    if (e == 0) v = std::ldexp((double)m, -24);
+    else if (e == 31) v = m ? NAN : INFINITY;
+    else v = std::ldexp((double)(m | 1024), e - 25);
+    return sign ? -v : v;
+}
+double bf16_to_double(uint16_t b) {
+    const uint32_t u = (uint32_t)b << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+}  // namespace
+
+extern "C" int tw_prune(const void* B, int ldb, int K, int N, int G, tw_dtype dt, double col_prune, double sparsity,
+                        uint8_t* mask_out) {
+    if (!B || !mask_out || K <= 0 || N <= 0 || G <= 0 || ldb < N) return TW_ERR_ARG;
+    if (dt != TW_F16 && dt != TW_BF16) return TW_ERR_ARG;
+    if (!(col_prune >= 0.0 && col_prune < 1.0) || !(sparsity >= 0.0 && sparsity < 1.0)) return TW_ERR_ARG;
+    const uint16_t* Bv = (const uint16_t*)B;
+    auto mag = [&](int k, int n) {
+        const uint16_t b = Bv[(size_t)k * ldb + n];
+        return std::fabs(dt == TW_F16 ? half_to_double(b) : bf16_to_double(b));
+    };
+    // column stage: importance of a column = sum of its magnitudes (k ascending); the floor(p*N + 0.5)
+    // least important go, the lower index first among equals
+    std::vector<double> cscore(N, 0.0);
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n) cscore[n] += mag(k, n);
+    const int n_prune = (int)std::floor(col_prune * N + 0.5);
+    std::vector<int> cord(N);
+    std::iota(cord.begin(), cord.end(), 0);
+    std::stable_sort(cord.begin(), cord.end(), [&](int a, int b) { return cscore[a] < cscore[b]; });
+    std::vector<uint8_t> col_keep(N, 1);
+    for (int i = 0; i < n_prune && i < N; ++i) col_keep[cord[i]] = 0;
+    std::vector<int> cols;
+    for (int n = 0; n < N; ++n)
+        if (col_keep[n]) cols.push_back(n);
+    const int nk = (int)cols.size();
+    std::memset(mask_out, 0, (size_t)K * N);
+    if (nk == 0) return TW_OK;
+    // row stage: the surviving columns are regrouped G at a time; importance of a row segment = mean
+    // magnitude over its columns (columns ascending), compared across ALL tiles, so tiles end up with
+    // different numbers of rows
+    const int T = (nk + G - 1) / G;
+    struct Seg { double score; int t, k, w; };
+    std::vector<Seg> segs((size_t)T * K);
+    for (int t = 0; t < T; ++t) {
+        const int c0 = t * G, w = std::min(G, nk - c0);
+        for (int k = 0; k < K; ++k) {
+            double acc = 0.0;
+            for (int c = 0; c < w; ++c) acc += mag(k, cols[c0 + c]);
+            segs[(size_t)t * K + k] = Seg{acc / w, t, k, w};
+        }
+    }
+    std::vector<size_t> sord(segs.size());
+    std::iota(sord.begin(), sord.end(), (size_t)0);
+    std::stable_sort(sord.begin(), sord.end(), [&](size_t a, size_t b) { return segs[a].score < segs[b].score; });
+    // prune segments, least important first, until the zeros reach the target; one row per tile always stays
+    const long long total = (long long)K * N;
+    const long long want = (long long)std::ceil(sparsity * (double)total);
+    long long zeros = (long long)K * (N - nk);
+    std::vector<int> left(T, K);
+    std::vector<uint8_t> seg_keep(segs.size(), 1);
+    for (size_t i = 0; i < sord.size() && zeros < want; ++i) {
+        const Seg& sg = segs[sord[i]];
+        if (left[sg.t] <= 1) continue;
+        seg_keep[sord[i]] = 0;
+        --left[sg.t];
+        zeros += sg.w;
+    }
+    for (int t = 0; t < T; ++t) {
+        const int c0 = t * G, w = std::min(G, nk - c0);
+        for (int k = 0; k < K; ++k)
+            if (seg_keep[(size_t)t * K + k])
+                for (int c = 0; c < w; ++c) mask_out[(size_t)k * N + cols[c0 + c]] = 1;
+    }
+    return TW_OK;
+}

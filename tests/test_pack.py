@@ -155,3 +155,52 @@ def test_random_tile_wise_masks_round_trip(arg):
     rng = np.random.default_rng(seed + 1)
     B = rng.integers(0, 65536, size=mask.shape).astype(np.uint16)
     _check_against_oracle(mask, B, G, "f16" if seed % 2 else "bf16")
+
+
+# ------------------------------------------------------------------ tw_prune (one-shot magnitude pruning)
+@pytest.mark.parametrize("K,N,G,dtype,cp,sp", [
+    (64, 96, 32, "f16", 0.1, 0.5),
+    (96, 200, 64, "f16", 0.05, 0.75),
+    (128, 300, 128, "bf16", 0.2, 0.875),
+    (40, 70, 32, "bf16", 0.0, 0.3),
+    (33, 129, 128, "f16", 0.5, 0.9),
+])
+def test_tw_prune_matches_oracle_bit_exact(K, N, G, dtype, cp, sp):
+    """Library mask == the oracle's plain-loop version of Alg. 1 (magnitude score), bit for bit."""
+    rng = np.random.default_rng(4242 + K + N)
+    B = W.f32_to_bits((rng.standard_normal((K, N)) * 0.02).astype(np.float32), dtype)
+    got = tw.tw_prune(B, G, dtype, cp, sp)
+    ref = tw_ref.prune_one_shot(B, G, dtype, cp, sp)
+    assert np.array_equal(got, ref)
+
+
+def test_tw_prune_properties():
+    """What Alg. 1 promises: whole columns first, then whole row segments of G regrouped columns; the target
+    sparsity is met with at most one segment to spare; the mask packs as TW with ceil(kept/G) tiles."""
+    rng = np.random.default_rng(777)
+    K, N, G = 96, 260, 64
+    B = W.f32_to_bits((rng.standard_normal((K, N)) * 0.05).astype(np.float32), "f16")
+    mask = tw.tw_prune(B, G, "f16", 0.1, 0.75)
+    kept_cols = np.flatnonzero(mask.any(axis=0))
+    assert N - len(kept_cols) == int(np.floor(0.1 * N + 0.5))
+    # pruned columns are the least important ones
+    cs = np.abs(tw_ref.decode(B, "f16")).sum(axis=0)
+    assert cs[kept_cols].min() >= np.delete(cs, kept_cols).max()
+    zeros = mask.size - int(mask.sum())
+    assert zeros >= 0.75 * mask.size and zeros - G < 0.75 * mask.size
+    # row segments: inside a tile of regrouped columns every row is all-kept or all-pruned
+    for i in range(0, len(kept_cols), G):
+        seg = mask[:, kept_cols[i:i + G]]
+        assert np.all((seg.sum(axis=1) == 0) | (seg.sum(axis=1) == seg.shape[1]))
+        assert seg.any()
+    blob = tw.tw_pack(B, mask, G, "f16")
+    assert tw.tw_info(blob)["T"] <= -(-len(kept_cols) // G) + 1
+    # tiles differ in kept rows (global ranking across tiles), and sparsity 0 keeps everything
+    assert np.array_equal(tw.tw_prune(B, G, "f16", 0.0, 0.0), np.ones((K, N), dtype=np.uint8))
+
+
+def test_tw_prune_refuses_bad_arguments():
+    B = np.zeros((8, 8), dtype=np.uint16)
+    for cp, sp in ((-0.1, 0.5), (1.0, 0.5), (0.1, 1.0), (0.1, -0.2)):
+        with pytest.raises(tw.TwError):
+            tw.tw_prune(B, 32, "f16", cp, sp)
