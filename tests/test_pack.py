@@ -204,3 +204,14 @@ def test_tw_prune_refuses_bad_arguments():
     for cp, sp in ((-0.1, 0.5), (1.0, 0.5), (0.1, 1.0), (0.1, -0.2)):
         with pytest.raises(tw.TwError):
             tw.tw_prune(B, 32, "f16", cp, sp)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/tw.h is the boundary: it must compile as C (no C++ or torch types in the signatures)."""
+    import subprocess
+    src = tmp_path / "use_tw.c"
+    src.write_text('#include "tw.h"\nint f(void) { tw_info_t i; (void)i; return (int)sizeof(tw_info_t) + TW_OK; }\n')
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, "-c", str(src), "-o",
+                        str(tmp_path / "use_tw.o")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
