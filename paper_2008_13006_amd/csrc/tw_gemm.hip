@@ -13,10 +13,11 @@
 //     memory and A is shared by many tiles (the role of batching).
 //   * The compacted tile values are stored offline in MFMA operand order and go from global
 //     memory (L2-resident) straight to registers, a few steps ahead of their use.
-//   * Workgroups are persistent and pull (row block, tile set) items from an atomic counter;
-//     inside a workgroup the waves pull tiles, heaviest first (the role of stream concurrency).
-//   * Pruned columns inside a tile's span are written as zeros together with the kept ones, in
-//     contiguous pieces, through a small per-wave LDS staging area.
+//   * Workgroups are persistent: one (row block, tile set) item each, further ones from an atomic
+//     counter; inside a workgroup the waves pull tiles in the packer's dispatch order (the role of
+//     stream concurrency).  When K does not fit in LDS, A is streamed through two LDS buffers.
+//   * Pruned columns inside a tile's span are written as zeros together with the kept ones, as whole
+//     128-byte lines of C, through a small per-wave LDS staging area.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
