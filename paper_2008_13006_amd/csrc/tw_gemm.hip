@@ -309,54 +309,75 @@ __device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], StepRegs<NC
 
 // Epilogue of one tile for this wave.  In this kernel the activations are the FIRST MFMA operand, so a
 // lane owns one packed column of the tile (n = lane % 32 of every 32-column block) and its registers
-// are rows: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4.
+// are rows: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4, i.e. four consecutive
+// rows per group of four registers.
 //
 // What the stores cost is the number of (128-byte line of C, store instruction) pairs, so every store
 // instruction should cover whole lines.  The wave's LDS staging window therefore starts at the
-// 64-column (128-byte) boundary at or below the tile's span and is up to four lines wide.  Eight rows
-// at a time, every lane writes its rounded values at the DESTINATION column of its packed column
-// (2-byte LDS writes).  The window is cleared once per tile: every pass writes the same columns, so
-// the pruned columns inside the span keep reading back as zeros.  Each staged row is read back as 16-byte
-// groups, eight lanes per line, and a store instruction writes one line of eight rows; groups that
-// straddle the ends of the span go out as 8/4/2-byte pieces.
+// 64-column (128-byte) boundary at or below the tile's span and is up to four lines wide.  It is kept
+// COLUMN-major: per destination column the four rows a lane holds are contiguous, so a lane stages
+// the four rounded values of a register group with ONE 8-byte LDS write at the destination column of
+// its packed column.  Two planes hold rows 0-3 and 4-7 of the eight rows of a pass (the two lane
+// halves), each [256 columns][4 rows] followed by one spare slot per lane for absent columns; the
+// second plane is skewed by 32 bytes so that reads of both planes use disjoint banks.  The window is
+// cleared once per tile: every pass writes the same columns, so the pruned columns inside the span
+// keep reading back as zeros.  The read-back uses the transposing LDS read (ds_read_b64_tr_b16):
+// within 16 lanes, lane 4e+g supplies the address of column (c_g + e), rows (4 values), and lane
+// 4g+x receives row x of columns c_g .. c_g+3.  Two such reads give a lane eight consecutive columns
+// of one row (16 bytes), and a store instruction writes one 128-byte line of eight rows.  Groups that
+// straddle the ends of the span go out as one 2-byte store per lane, end and pass.
 // LDS instructions of one wave execute in order, so the wave needs no waits between its own writes
-// and reads of the staging area, only compiler barriers.
+// and reads of the staging area, only compiler barriers; the writes of pass P+1 are issued behind
+// the reads of pass P and ahead of the wait for them.
 constexpr int kLineCols = 64;                       // columns in a 128-byte line of C
 constexpr int kWinLines = 4;                        // lines per staging window
 constexpr int kWinCols = kWinLines * kLineCols;     // 256
-constexpr int kStagePitch = kWinLines * 128 + 16;   // 528 bytes; the tail takes writes of absent columns
-constexpr int kDummyOff = kWinLines * 128;
-constexpr int kStageRows = 8;
-constexpr unsigned kStageBytes = kStageRows * kStagePitch;   // per wave
+constexpr int kSpareOff = kWinCols * 8;             // spare slots behind the window of a plane
+constexpr int kPlaneBytes = kWinCols * 8 + 32 * 8 + 32;
+constexpr unsigned kStageBytes = 2 * kPlaneBytes;   // per wave
+static_assert(kPlaneBytes % 16 == 0 && (kPlaneBytes / 4) % 16 == 8, "plane skew");
 
 __device__ __forceinline__ void tw_compiler_fence() { asm volatile("" ::: "memory"); }
 
+__device__ __forceinline__ tw_i16x4 tw_lds_read_tr(const unsigned char* a) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tw_i16x4*)a);
+}
+
 // dpos: destination columns of this lane's packed columns (one per 32-column block), counted from the
 // 8-aligned column at or below the span start.
-// The eight (MS = 1: four) passes of 8 rows run as a real loop: only the choice of the pass's 4 x NCB
-// accumulator registers is unrolled, the staging, read-back and store code exists once.  The loop is
-// software-pipelined: the LDS writes of pass P+1 are issued behind the read-back of pass P and ahead
-// of the wait for it (the LDS executes a wave's instructions in order, so the reads still see pass P).
-// The groups that straddle the ends of the span are stored element-wise, one 2-byte store
-// instruction per end and pass: lane (row, element) of 8 x 8.
 template <int DT, int MS, int NCB>
 __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
                                            unsigned char* stage, const unsigned (&dpos)[NCB], int row0, int lane_in) {
     const int lane = fresh(lane_in);
-    const int h = lane >> 5, trow = lane >> 3, tg = lane & 7;
+    const int h = lane >> 5, n = lane & 31;
+    const int blk = lane >> 4, j = lane & 15;
+    // read-back, as the lane that supplies an address: column offset e, group g -> (piece, row quad)
+    const int in_piece = 2 * blk + (j & 1), in_rq = (j >> 1) & 1, in_e = j >> 2;
+    // read-back, as the lane that receives: group g = j / 4, row x = j % 4 of the quad
+    const int piece = 2 * blk + ((j >> 2) & 1), orow = 4 * (j >> 3) + (j & 3);
+    const int trow = lane >> 3, tg = lane & 7;              // element-wise stores: row, element of a group
     const int S = d.span_start, E = d.span_start + d.span_w;
     const int W0 = S & ~(kLineCols - 1);
     const unsigned shift = (unsigned)((S & ~7) - W0);       // dpos counts from S & ~7
     constexpr int NP = 4 * MS;
+    const int rows_left = p.M - (row0 + orow);              // pass P stores this lane's row iff 8P < rows_left
     for (int win0 = W0; win0 < E; win0 += kWinCols) {       // one window unless the span is very wide
         const int left = E - win0;
         const int nl = left >= kWinCols ? kWinLines : (left + kLineCols - 1) / kLineCols;
-        unsigned pos[NCB];
+        unsigned char* wpos[NCB];
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
             const unsigned rel = dpos[cb] + shift - (unsigned)(win0 - W0);   // wraps for columns left of the window
-            pos[cb] = rel < (unsigned)kWinCols ? rel * 2u : (unsigned)kDummyOff;
+            wpos[cb] = stage + h * kPlaneBytes + (rel < (unsigned)kWinCols ? rel * 8u : (unsigned)(kSpareOff + n * 8));
         }
+        const unsigned char* rpos = stage + in_rq * kPlaneBytes + (8 * in_piece + in_e) * 8;
+        bool okl[kWinLines];
+#pragma unroll
+        for (int l = 0; l < kWinLines; ++l) {
+            const int col = win0 + l * kLineCols + piece * 8;
+            okl[l] = l < nl && col >= S && col + 8 <= E;
+        }
+        unsigned short* cptr = p.C + (long)(row0 + orow) * p.ldc + (win0 + piece * 8);
         // partial groups at the two ends of the span, if they lie in this window (window-relative index)
         int g_first = -1, g_last = -1;
         if ((S & 7) != 0 && win0 == W0) g_first = (S - win0) >> 3;
@@ -364,101 +385,73 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
         const int colF = win0 + g_first * 8 + tg, colL = win0 + g_last * 8 + tg;   // this lane's element
         const bool inF = g_first >= 0 && colF >= S && colF < E;
         const bool inL = g_last >= 0 && colL >= S && colL < E;
-        const unsigned char* ragF = stage + trow * kStagePitch + ((g_first < 0 ? 0 : g_first) * 8 + tg) * 2;
-        const unsigned char* ragL = stage + trow * kStagePitch + ((g_last < 0 ? 0 : g_last) * 8 + tg) * 2;
-        unsigned char* wrow = stage + 4 * h * kStagePitch;
-        const unsigned char* rrow = stage + trow * kStagePitch + tg * 16;
+        const unsigned char* ragbase = stage + (trow >> 2) * kPlaneBytes + (trow & 3) * 2;
+        const unsigned char* ragF = ragbase + ((g_first < 0 ? 0 : g_first) * 8 + tg) * 8;
+        const unsigned char* ragL = ragbase + ((g_last < 0 ? 0 : g_last) * 8 + tg) * 8;
+        unsigned short* rptr = p.C + (long)(row0 + trow) * p.ldc;
+        const int rag_left = p.M - (row0 + trow);
 
-        auto extract = [&](int P, float (&t)[NCB][4]) {
-            // pass 0 is the default so that t is defined on every path (an undefined t would be carried
-            // around the tile loop as a live value)
+        auto write_pass = [&](int P) {
+            const int ms = P >> 2, q = P & 3;
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) t[cb][rr] = acc[0][cb][rr];
-#pragma unroll
-            for (int q = 1; q < NP; ++q)
-                if (P == q) {
-#pragma unroll
-                    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-                        for (int rr = 0; rr < 4; ++rr) t[cb][rr] = acc[q >> 2][cb][4 * (q & 3) + rr];
-                }
+            for (int cb = 0; cb < NCB; ++cb) {
+                tw_u32x2 v;
+                v.x = (unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 0]) | ((unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 1]) << 16);
+                v.y = (unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 2]) | ((unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 3]) << 16);
+                *(tw_u32x2*)wpos[cb] = v;
+            }
         };
-        auto write_pass = [&](const float (&t)[NCB][4]) {
-#ifdef TW_EXPERIMENT
-            if (!(TWD(p.dbg) & 1024))
-#endif
+
+        // clear both planes once: the passes all write the same columns
+        tw_compiler_fence();
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb)
+        for (int pl = 0; pl < 2; ++pl)
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    // one conversion per value: a packed conversion of two values followed by 2-byte stores
-                    // of the two halves was miscompiled by hipcc 7.2 (the low half was stored twice)
-                    *(unsigned short*)(wrow + pos[cb] + rr * kStagePitch) = tw_cvt<DT>(t[cb][rr]);
-                }
-        };
-        auto read_pass = [&](tw_u32x4 (&v)[kWinLines], unsigned short& eF, unsigned short& eL) {
-            // all four lines of the window (lines past the span are read, not stored) and this lane's
-            // elements of the two partial groups
+            for (int i = 0; i < kWinCols * 8 / 1024; ++i)
+                *(tw_u32x4*)(stage + pl * kPlaneBytes + i * 1024 + lane * 16) = tw_u32x4{0u, 0u, 0u, 0u};
+        tw_compiler_fence();
+        write_pass(0);
+        tw_compiler_fence();
 #pragma unroll
-            for (int l = 0; l < kWinLines; ++l) v[l] = *(const tw_u32x4*)(rrow + l * 128);
-            eF = *(const unsigned short*)ragF;
-            eL = *(const unsigned short*)ragL;
-        };
-        auto store_pass = [&](int P, const tw_u32x4 (&v)[kWinLines], unsigned short eF, unsigned short eL) {
-            const int grow = row0 + 8 * P + trow;
-            unsigned short* crow = p.C + (long)grow * p.ldc;
+        for (int P = 0; P < NP; ++P) {
+            tw_i16x4 lo[kWinLines], hi[kWinLines];
 #pragma unroll
             for (int l = 0; l < kWinLines; ++l) {
-                const int col = win0 + l * kLineCols + tg * 8;
+                lo[l] = tw_lds_read_tr(rpos + l * (kLineCols * 8));
+                hi[l] = tw_lds_read_tr(rpos + l * (kLineCols * 8) + 32);
+            }
+            const unsigned short eF = *(const unsigned short*)ragF;
+            const unsigned short eL = *(const unsigned short*)ragL;
+            tw_compiler_fence();
+            if (P + 1 < NP) write_pass(P + 1);
+            tw_compiler_fence();
 #ifdef TW_EXPERIMENT
-                if (!(TWD(p.dbg) & 512))
+            if (!(TWD(p.dbg) & 512))
 #endif
-                if (l < nl && grow < p.M && col >= S && col + 8 <= E) *(tw_u32x4_a2*)(crow + col) = v[l];
+#pragma unroll
+            for (int l = 0; l < kWinLines; ++l) {
+                if (okl[l] && 8 * P < rows_left) {
+                    const tw_u32x2 a = __builtin_bit_cast(tw_u32x2, lo[l]), b = __builtin_bit_cast(tw_u32x2, hi[l]);
+                    *(tw_u32x4_a2*)(cptr + (long)(8 * P) * p.ldc + l * kLineCols) = tw_u32x4{a.x, a.y, b.x, b.y};
+                }
             }
 #ifdef TW_EXPERIMENT
             if (!(TWD(p.dbg) & 8))
 #endif
             {
                 if (g_first >= 0) {                          // wave-uniform
-                    if (inF && grow < p.M) crow[colF] = eF;
+                    if (inF && 8 * P < rag_left) rptr[(long)(8 * P) * p.ldc + colF] = eF;
                 }
                 if (g_last >= 0) {
-                    if (inL && grow < p.M) crow[colL] = eL;
+                    if (inL && 8 * P < rag_left) rptr[(long)(8 * P) * p.ldc + colL] = eL;
                 }
             }
-        };
-
-        // clear the window once: the passes all write the same columns
-        tw_compiler_fence();
 #ifdef TW_EXPERIMENT
-        if (!(TWD(p.dbg) & 2048))
+            if (TWD(p.dbg) & 4096) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (TWD(p.dbg) & 8192) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            if (TWD(p.dbg) & 16384) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
 #endif
-#pragma unroll
-        for (int i = 0; i < (kStageRows * kStagePitch + 1023) / 1024; ++i) {
-            const int off = i * 1024 + lane * 16;
-            if (off < kStageRows * kStagePitch) *(tw_u32x4*)(stage + off) = tw_u32x4{0u, 0u, 0u, 0u};
         }
-        tw_compiler_fence();
-        float t[NCB][4];
-        tw_u32x4 v[kWinLines];
-        unsigned short eF, eL;
-        extract(0, t);
-        write_pass(t);
-        tw_compiler_fence();
-#pragma clang loop unroll(disable)
-        for (int P = 0; P < NP - 1; ++P) {
-            read_pass(v, eF, eL);
-            tw_compiler_fence();
-            extract(P + 1, t);
-            write_pass(t);
-            tw_compiler_fence();
-            store_pass(P, v, eF, eL);
-        }
-        read_pass(v, eF, eL);
-        tw_compiler_fence();
-        store_pass(NP - 1, v, eF, eL);
         tw_compiler_fence();
     }
 }
