@@ -446,6 +446,12 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
                     if (inL && 8 * P < rag_left) rptr[(long)(8 * P) * p.ldc + colL] = eL;
                 }
             }
+            // At most a few of this wave's stores stay in flight: a long queue of stores in the CU's memory
+            // pipeline holds up the loads of the waves that are multiplying (no load of this wave is pending here).
+#ifdef TW_EXPERIMENT
+            if (TWD(p.dbg) & 4096) {} else
+#endif
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
 #ifdef TW_EXPERIMENT
             if (TWD(p.dbg) & 4096) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             if (TWD(p.dbg) & 8192) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");

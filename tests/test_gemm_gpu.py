@@ -53,7 +53,9 @@ def _run_tw(tw, w, rows=None, poison=True):
     C = torch.full((M, spec.N), float("nan"), dtype=A.dtype, device="cuda:0") if poison else None
     C = tw.tw_gemm(wt, A, C)
     torch.cuda.synchronize()
-    assert int(wt.workspace.view(torch.int32)[:2].abs().sum().item()) == 0, "scheduler counters not reset"
+    ws = wt.workspace.view(torch.int32)[:4].cpu().tolist()
+    assert ws[0] == 0 and ws[1] == 0, "scheduler counters not reset"
+    assert ws[3] == 0, "a bounded wait inside the kernel ran out"
     return wt, A, C
 
 
