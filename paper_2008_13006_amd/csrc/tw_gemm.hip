@@ -43,6 +43,13 @@ namespace {
 
 constexpr int kWaves = TW_WAVES_PER_WG;
 constexpr int kThreads = kWaves * 64;
+#ifndef TW_PAIR_RESIDENT
+#define TW_PAIR_RESIDENT 1
+#endif
+#ifndef TW_PAIR_STREAM
+#define TW_PAIR_STREAM 0
+#endif
+constexpr bool kPairResident = TW_PAIR_RESIDENT != 0, kPairStream = TW_PAIR_STREAM != 0;
 constexpr int kPrefetch = 3;  // B-operand steps in flight per wave
 constexpr int kIdxAhead = 6;  // steps the K indices are requested ahead (they feed the LDS gather, which itself
                               // runs one step ahead of the MFMAs)
@@ -97,75 +104,136 @@ __device__ __forceinline__ TileU fetch_tile(const TwGemmParams& p, int ti) {
     return u;
 }
 
+// Element idx of a read-only int table, wave-uniform, through a scalar load (see fetch_tile).
+__device__ __forceinline__ int fetch_int(const int* table, int idx) {
+    const uint64_t a = (uint64_t)(table + idx);
+    const uint64_t ua = ((uint64_t)(unsigned)uni((int)(a >> 32)) << 32) | (unsigned)uni((int)(unsigned)a);
+    return *(tw_const_int_ptr)ua;
+}
+
 // Cooperative load of A[row0 .. row0+32*MS) x [k0, k0+kw) into LDS, transposed: LDS row k (pitch
-// at_pitch bytes) holds the 32*MS values A[row0 .. , k0+k].  A wave instruction reads 8 rows x 128
-// contiguous bytes of A (8 lanes x 16 B per row) and scatters them with eight 2-byte LDS writes per
-// lane.  Row k_chunk of the LDS copy is kept zero for padded contraction slots; rows k_chunk+1 ..
-// k_chunk+8 take the writes of absent pieces.
-//
-// Work is cut into tasks of 8 rows x 8 pieces; wave w takes tasks w, w+8, ...  Neither the loads nor
-// the LDS writes carry branches: a request for an absent piece re-reads a valid one and its values go
-// to the spare rows, so all requests of a batch are outstanding together.  A piece is always read as
-// 16 bytes: lda is a multiple of 8 elements, so the bytes past column K-1 of a row still belong to
-// that row's pitch; they are dropped at the LDS write (only a width that is not a multiple of 8 needs
-// that test).
+// at_pitch bytes) holds the 32*MS values A[row0 .. , k0+k].  Row k_chunk of the LDS copy is kept zero
+// for padded contraction slots; rows k_chunk+1 .. k_chunk+8 take the writes of absent pieces.
+// A lane always reads 16-byte pieces (8 columns of one row).  Two ways of cutting the work into tasks:
+//   PAIR = false (streamed K): a task is 8 rows x 64 columns; lane l reads piece l%8 of row l/8 (a wave
+//     instruction reads 128 contiguous bytes of 8 rows, what streams best from HBM) and scatters its
+//     values with eight 2-byte LDS writes.  One request per task.
+//   PAIR = true (resident K): a task is 32 rows x 32 columns; lane l reads piece l/16 of the two rows
+//     2*(l%16) and 2*(l%16)+1, and the two rows' values of a column go into one 32-bit word: eight
+//     4-byte LDS writes per two requests, whose 64 lanes hit 64 different banks (the four pieces lie 16
+//     banks apart, the 16 row pairs in consecutive words).  Two requests per task.
+// Wave w takes tasks w, w+stride, ...  Neither the loads nor the LDS writes carry branches: a request
+// for an absent piece re-reads a valid one and its values go to the spare rows, so all requests of a
+// batch are outstanding together.  lda is a multiple of 8 elements, so the bytes past column K-1 of a
+// row still belong to that row's pitch; they are dropped at the LDS write (only a width that is not a
+// multiple of 8 needs that test).  BATCH counts requests.
 template <int BATCH>
 struct ARegs {
     tw_u32x4 v[BATCH];
 };
 
-template <int MS>
+template <int MS, bool PAIR>
 struct ATask {
-    int row, oc;
+    int row, oc;      // (first) row of the lane, 16-byte piece of the row
     bool have;
     __device__ __forceinline__ ATask(int t, int kw, int lane) {
-        constexpr int RG = 4 * MS;                  // groups of 8 rows
         const int octets = (kw + 7) >> 3;           // 16-byte pieces per row
-        const int tasks = RG * ((octets + 7) >> 3);
-        const int tc = t < tasks ? t : tasks - 1;
-        row = (tc % RG) * 8 + (lane >> 3);
-        const int o = (tc / RG) * 8 + (lane & 7);
-        have = t < tasks && o < octets;
-        oc = o < octets ? o : octets - 1;
+        if constexpr (PAIR) {
+            const int tasks = MS * ((octets + 3) >> 2);
+            const int tc = t < tasks ? t : tasks - 1;
+            row = (tc % MS) * 32 + 2 * (lane & 15);
+            const int o = (tc / MS) * 4 + (lane >> 4);
+            have = t < tasks && o < octets;
+            oc = o < octets ? o : octets - 1;
+        } else {
+            constexpr int RG = 4 * MS;              // groups of 8 rows
+            const int tasks = RG * ((octets + 7) >> 3);
+            const int tc = t < tasks ? t : tasks - 1;
+            row = (tc % RG) * 8 + (lane >> 3);
+            const int o = (tc / RG) * 8 + (lane & 7);
+            have = t < tasks && o < octets;
+            oc = o < octets ? o : octets - 1;
+        }
     }
 };
+template <int MS, bool PAIR>
+__device__ __forceinline__ int a_tasks(int kw) {
+    const int octets = (kw + 7) >> 3;
+    return PAIR ? MS * ((octets + 3) >> 2) : 4 * MS * ((octets + 7) >> 3);
+}
 
-// requests tasks t0, t0+stride, ... (BATCH of them) of the block; stride = number of loading waves
-template <int MS, int BATCH>
+// requests tasks t0, t0+stride, ... of the block (BATCH requests); stride = number of loading waves
+template <int MS, int BATCH, bool PAIR>
 __device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int row0, int k0, int kw, int t0,
                                         int lane_in, int stride = kWaves) {
     const int lane = fresh(lane_in);
+    if constexpr (PAIR) {
+        static_assert(BATCH % 2 == 0, "two requests per task");
 #pragma unroll
-    for (int b = 0; b < BATCH; ++b) {
-        const ATask<MS> t(t0 + b * stride, kw, lane);
-        int grow = row0 + t.row;
-        grow = grow < p.M ? grow : p.M - 1;           // rows past M: any valid row, never stored
-        ar.v[b] = *(const tw_u32x4*)(p.A + (long)grow * p.lda + (k0 + t.oc * 8));
+        for (int b = 0; b < BATCH / 2; ++b) {
+            const ATask<MS, true> t(t0 + b * stride, kw, lane);
+            int g0 = row0 + t.row, g1 = g0 + 1;
+            g0 = g0 < p.M ? g0 : p.M - 1;             // rows past M: any valid row, never stored
+            g1 = g1 < p.M ? g1 : p.M - 1;
+            ar.v[2 * b] = *(const tw_u32x4*)(p.A + (long)g0 * p.lda + (k0 + t.oc * 8));
+            ar.v[2 * b + 1] = *(const tw_u32x4*)(p.A + (long)g1 * p.lda + (k0 + t.oc * 8));
+        }
+    } else {
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const ATask<MS, false> t(t0 + b * stride, kw, lane);
+            int grow = row0 + t.row;
+            grow = grow < p.M ? grow : p.M - 1;
+            ar.v[b] = *(const tw_u32x4*)(p.A + (long)grow * p.lda + (k0 + t.oc * 8));
+        }
     }
 }
 
 // writes what a_issue requested into the LDS copy `at`
-template <int MS, int BATCH>
+template <int MS, int BATCH, bool PAIR>
 __device__ __forceinline__ void a_commit(const TwGemmParams& p, const ARegs<BATCH>& ar, unsigned char* at, int kw, int t0,
                                          int lane_in, int stride = kWaves) {
     const int lane = fresh(lane_in);
     const int dump = p.k_chunk + 1;
     const bool tail = (kw & 7) != 0;                  // wave-uniform
+    if constexpr (PAIR) {
 #pragma unroll
-    for (int b = 0; b < BATCH; ++b) {
-        const ATask<MS> t(t0 + b * stride, kw, lane);
-        const int kcol = t.have ? t.oc * 8 : dump;
-        unsigned char* dst = at + (unsigned)kcol * p.at_pitch + t.row * 2;
-        const unsigned w[4] = {ar.v[b].x, ar.v[b].y, ar.v[b].z, ar.v[b].w};
-        if (!tail) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
-        } else {
+        for (int b = 0; b < BATCH / 2; ++b) {
+            const ATask<MS, true> t(t0 + b * stride, kw, lane);
+            const int kcol = t.have ? t.oc * 8 : dump;
+            unsigned char* dst = at + (unsigned)kcol * p.at_pitch + t.row * 2;
+            const unsigned x[4] = {ar.v[2 * b].x, ar.v[2 * b].y, ar.v[2 * b].z, ar.v[2 * b].w};
+            const unsigned y[4] = {ar.v[2 * b + 1].x, ar.v[2 * b + 1].y, ar.v[2 * b + 1].z, ar.v[2 * b + 1].w};
+            unsigned w[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                if (kcol + i < kw || kcol == dump)
+                w[i] = (i & 1) ? ((x[i >> 1] >> 16) | (y[i >> 1] & 0xFFFF0000u)) : ((x[i >> 1] & 0xFFFFu) | (y[i >> 1] << 16));
+            if (!tail) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) *(unsigned*)(dst + (unsigned)i * p.at_pitch) = w[i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (kcol + i < kw || kcol == dump) *(unsigned*)(dst + (unsigned)i * p.at_pitch) = w[i];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const ATask<MS, false> t(t0 + b * stride, kw, lane);
+            const int kcol = t.have ? t.oc * 8 : dump;
+            unsigned char* dst = at + (unsigned)kcol * p.at_pitch + t.row * 2;
+            const unsigned w[4] = {ar.v[b].x, ar.v[b].y, ar.v[b].z, ar.v[b].w};
+            if (!tail) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
                     *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (kcol + i < kw || kcol == dump)
+                        *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
+            }
         }
     }
 }
@@ -175,14 +243,14 @@ __device__ __forceinline__ void a_zero_row(const TwGemmParams& p, unsigned char*
 }
 
 // whole block, BATCH requests per wave in flight at a time (12 cover 64 rows x 768 columns)
-template <int MS, int BATCH>
+template <int MS, int BATCH, bool PAIR>
 __device__ __forceinline__ void load_a_block(const TwGemmParams& p, unsigned char* at, int row0, int k0, int kw,
                                              int wave, int lane, int tid) {
-    const int tasks = 4 * MS * ((((kw + 7) >> 3) + 7) >> 3);
-    for (int t0 = wave; t0 < tasks; t0 += kWaves * BATCH) {
+    const int tasks = a_tasks<MS, PAIR>(kw);
+    for (int t0 = wave; t0 < tasks; t0 += kWaves * (PAIR ? BATCH / 2 : BATCH)) {
         ARegs<BATCH> ar;
-        a_issue<MS, BATCH>(p, ar, row0, k0, kw, t0, lane);
-        a_commit<MS, BATCH>(p, ar, at, kw, t0, lane);
+        a_issue<MS, BATCH, PAIR>(p, ar, row0, k0, kw, t0, lane);
+        a_commit<MS, BATCH, PAIR>(p, ar, at, kw, t0, lane);
     }
     a_zero_row(p, at, 32 * MS, tid);
 }
@@ -494,16 +562,18 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #endif
     TW_MARK();
     // the first item of a workgroup is its own index, later ones come from the atomic counter
+    int my_next = (int)blockIdx.x;   // thread 0: the item of the coming turn
     for (int turn = 0;; ++turn) {
         if (tid == 0) {
-            // the counter is touched only when there are more items than workgroups
-            misc[0] = turn == 0 ? (int)blockIdx.x
-                                : (p.n_items > (int)gridDim.x ? (int)gridDim.x + atomicAdd(&p.counters[0], 1) : p.n_items);
+            misc[0] = my_next;
             misc[1] = 0;
         }
         __syncthreads();
         const int item = misc[0];
         if (item >= p.n_items) break;
+        // the item after this one is requested now, so that the atomic's latency passes during this item's
+        // work; the counter is touched only when there are more items than workgroups
+        if (tid == 0) my_next = p.n_items > (int)gridDim.x ? (int)gridDim.x + atomicAdd(&p.counters[0], 1) : p.n_items;
 
         if constexpr (MODE == 0) {
             // the whole K extent of the row block stays in LDS; waves pull tiles of this item's set
@@ -517,7 +587,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #ifdef TW_EXPERIMENT
             if (!(TWD(p.dbg) & 1))
 #endif
-            load_a_block<MS, 12>(p, smem, row0, 0, p.K, wave, lane, tid);
+            load_a_block<MS, 12, kPairResident>(p, smem, row0, 0, p.K, wave, lane, tid);
             TW_MARK();
             __syncthreads();
             TW_MARK();
@@ -598,16 +668,24 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             if (loader) {
                 const int lw = wave - NMUL;
                 auto issue_or_zero = [&](ARegs<PB>& ar, int c) {
-                    if (c < p.n_chunks) {
-                        a_issue<MSB, PB>(p, ar, row0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
+                    if (c < p.n_chunks
+#ifdef TW_EXPERIMENT
+                        && !(TWD(p.dbg) & 1)
+#endif
+                    ) {
+                        a_issue<MSB, PB, kPairStream>(p, ar, row0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
                     } else {
 #pragma unroll
                         for (int b = 0; b < PB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
                     }
                 };
                 auto commit = [&](const ARegs<PB>& ar, int c) {
-                    if (c < p.n_chunks)
-                        a_commit<MSB, PB>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), lw, lane, NLD);
+                    if (c < p.n_chunks
+#ifdef TW_EXPERIMENT
+                        && !(TWD(p.dbg) & 1024)
+#endif
+                    )
+                        a_commit<MSB, PB, kPairStream>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), lw, lane, NLD);
                 };
                 // chunk j waits in register set j % 2; the loop is unrolled by two so that the sets are
                 // addressed statically
@@ -639,9 +717,10 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 // the first steps of a chunk are requested at the end of the previous chunk's steps, so
                 // they arrive while the workgroup meets at the barrier
                 StepRegs<NCB> rg;
-                auto prefetch_chunk = [&](int c) {
-                    int c0 = 0, c1 = 0;
-                    if (c < p.n_chunks) { c0 = uni(sp[c]); c1 = uni(sp[c + 1]); }
+                // first steps of the chunks: b0 = first step of chunk c, b1 of chunk c+1, b2 of chunk c+2, read one
+                // chunk ahead with scalar loads so that no chunk waits for them
+                int b0 = fetch_int(sp, 0), b1 = fetch_int(sp, 1), b2 = fetch_int(sp, p.n_chunks < 2 ? p.n_chunks : 2);
+                auto prefetch_steps = [&](int c0, int c1) {
                     if (active && c0 < c1) {
                         prefetch_first_steps<NCB>(rg, gt, bt, c0, c1, lane);
                     } else {                               // defined on every path
@@ -654,12 +733,18 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     }
                 };
                 auto steps_of = [&](int c) {
-                    const int c0 = uni(sp[c]), c1 = uni(sp[c + 1]);
-                    if (active && c0 < c1)
-                        run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, c0, c1, lane);
-                    prefetch_chunk(c + 1);
+                    if (active && b0 < b1
+#ifdef TW_EXPERIMENT
+                        && !(TWD(p.dbg) & 2)
+#endif
+                    )
+                        run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, b0, b1, lane);
+                    // on to chunk c+1
+                    b0 = b1; b1 = b2;
+                    b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
+                    if (c + 1 < p.n_chunks) prefetch_steps(b0, b1); else prefetch_steps(0, 0);
                 };
-                prefetch_chunk(0);
+                prefetch_steps(b0, b1);
                 __syncthreads();
                 for (int c = 0; c < p.n_chunks; c += 2) {
                     steps_of(c);
@@ -667,6 +752,9 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     if (c + 1 < p.n_chunks) steps_of(c + 1);
                     __syncthreads();
                 }
+#ifdef TW_EXPERIMENT
+                if (!(TWD(p.dbg) & 4))
+#endif
                 if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
             }
         } else {
@@ -691,7 +779,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             constexpr int AB = 6;    // requests per wave and chunk: 64 rows x 384 columns in 8 waves
             {
                 const int kw = p.K < p.k_chunk ? p.K : p.k_chunk;
-                load_a_block<MSB, AB>(p, smem, row0, 0, kw, wave, lane, tid);
+                load_a_block<MSB, AB, kPairStream>(p, smem, row0, 0, kw, wave, lane, tid);
                 a_zero_row(p, smem + p.abuf_bytes, BM, tid);
             }
             // Requests run kAhead chunks ahead of the steps: two where the registers allow it (narrow
@@ -703,23 +791,26 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             };
             auto issue_or_zero = [&](ARegs<AB>& ar, int c) {
                 if (c < p.n_chunks) {
-                    a_issue<MSB, AB>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
+                    a_issue<MSB, AB, kPairStream>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
                 } else {
 #pragma unroll
                     for (int b = 0; b < AB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
                 }
             };
+            // first steps of chunk c (b0), c+1 (b1) and c+2 (b2), read one chunk ahead with scalar loads
+            int b0 = fetch_int(sp, 0), b1 = fetch_int(sp, 1), b2 = fetch_int(sp, p.n_chunks < 2 ? p.n_chunks : 2);
             auto steps_of = [&](int c) {
-                const int c0 = uni(sp[c]), c1 = uni(sp[c + 1]);
-                if (active && c0 < c1) {
+                if (active && b0 < b1) {
                     StepRegs<NCB> rg;
-                    prefetch_first_steps<NCB>(rg, gt, bt, c0, c1, lane);
-                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, c0, c1,
+                    prefetch_first_steps<NCB>(rg, gt, bt, b0, b1, lane);
+                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, b0, b1,
                                            lane);
                 }
+                b0 = b1; b1 = b2;
+                b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
             };
             auto commit = [&](const ARegs<AB>& ar, int c) {
-                if (c < p.n_chunks) a_commit<MSB, AB>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), wave, lane);
+                if (c < p.n_chunks) a_commit<MSB, AB, kPairStream>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), wave, lane);
             };
             if constexpr (kAhead == 1) {
                 __syncthreads();
@@ -821,7 +912,7 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
     }
     const long items = items_for(msb, tpw, nmb, nseg);
     if (items > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
-    if (!resident && 4 * msb * ((((h->k_chunk + 7) >> 3) + 7) >> 3) > kWaves * 6) return TW_ERR_UNSUPPORTED;
+    if (!resident && 4 * msb * ((((h->k_chunk + 7) >> 3) + 7) >> 3) > kWaves * 6) return TW_ERR_UNSUPPORTED;   // a chunk is one batch
     pl.n_mblocks = nmb; pl.n_seg = nseg; pl.n_items = (int)items;
     pl.at_pitch = 64u * msb + 8u;
     pl.abuf_bytes = at_bytes(msb, h->k_chunk);
