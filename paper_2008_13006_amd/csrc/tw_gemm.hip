@@ -22,6 +22,7 @@
 
 #include <atomic>
 #include <cstdlib>
+#include <type_traits>
 
 #include "../../include/tw.h"
 #include "tw_device.hpp"
@@ -561,8 +562,16 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
     int nmark = 0;
 #endif
     TW_MARK();
-    // the first item of a workgroup is its own index, later ones come from the atomic counter
+    // The loop over the workgroup's items.  ROLE 0: every wave does the same (MODE 0 and 1); with MODE 2
+    // the multiplying waves (ROLE 1) and the loading waves (ROLE 2) run copies of their own, with the
+    // same barriers, so that neither carries the other's registers.
+    // The first item of a workgroup is its own index, later ones come from the atomic counter.
+    auto run_items = [&](auto role_tag) {
+    constexpr int ROLE = decltype(role_tag)::value;
     int my_next = (int)blockIdx.x;   // thread 0: the item of the coming turn
+    // loading waves: the first chunks of the coming item, requested during this item's epilogue
+    ARegs<12> pre0, pre1;
+    bool preloaded = false;
     for (int turn = 0;; ++turn) {
         if (tid == 0) {
             misc[0] = my_next;
@@ -665,15 +674,16 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 *(unsigned*)(smem + (unsigned)p.k_chunk * p.at_pitch + tid * 4) = 0u;
                 *(unsigned*)(smem + p.abuf_bytes + (unsigned)p.k_chunk * p.at_pitch + tid * 4) = 0u;
             }
-            if (loader) {
+            if constexpr (ROLE == 2) {
                 const int lw = wave - NMUL;
-                auto issue_or_zero = [&](ARegs<PB>& ar, int c) {
+                static_assert(PB == 12, "size of the carried register sets");
+                auto issue_or_zero = [&](ARegs<PB>& ar, int c, int r0) {
                     if (c < p.n_chunks
 #ifdef TW_EXPERIMENT
                         && !(TWD(p.dbg) & 1)
 #endif
                     ) {
-                        a_issue<MSB, PB, kPairStream>(p, ar, row0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
+                        a_issue<MSB, PB, kPairStream>(p, ar, r0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
                     } else {
 #pragma unroll
                         for (int b = 0; b < PB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
@@ -688,23 +698,34 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                         a_commit<MSB, PB, kPairStream>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), lw, lane, NLD);
                 };
                 // chunk j waits in register set j % 2; the loop is unrolled by two so that the sets are
-                // addressed statically
-                ARegs<PB> ar0, ar1;
-                issue_or_zero(ar0, 0);
-                issue_or_zero(ar1, 1);
-                commit(ar0, 0);
-                issue_or_zero(ar0, 2);
+                // addressed statically.  The start of an item (chunk 0 in LDS, chunks 1 and 2 requested) was
+                // done at the end of the previous item where there was one.
+                ARegs<PB>& ar0 = pre0;
+                ARegs<PB>& ar1 = pre1;
+                auto start_item = [&](int r0) {
+                    issue_or_zero(ar0, 0, r0);
+                    issue_or_zero(ar1, 1, r0);
+                    commit(ar0, 0);
+                    issue_or_zero(ar0, 2, r0);
+                };
+                if (!preloaded) start_item(row0);
                 __syncthreads();
                 for (int c = 0; c < p.n_chunks; c += 2) {
                     commit(ar1, c + 1);
-                    issue_or_zero(ar1, c + 3);
+                    issue_or_zero(ar1, c + 3, row0);
                     __syncthreads();
                     if (c + 1 < p.n_chunks) {
                         commit(ar0, c + 2);
-                        issue_or_zero(ar0, c + 4);
+                        issue_or_zero(ar0, c + 4, row0);
                     }
                     __syncthreads();
                 }
+                // the multiplying waves are through with both buffers and have said which item comes next:
+                // its first chunks are brought in while they store this item's tiles
+                __syncthreads();
+                const int nxt = misc[2];
+                preloaded = nxt < p.n_items;
+                if (preloaded) start_item((nxt % p.n_mblocks) * BM);
             } else {
                 unsigned dpos[NCB];
                 {
@@ -752,6 +773,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     if (c + 1 < p.n_chunks) steps_of(c + 1);
                     __syncthreads();
                 }
+                if (tid == 0) misc[2] = my_next;   // requested at the start of the item: here by now
+                __syncthreads();
 #ifdef TW_EXPERIMENT
                 if (!(TWD(p.dbg) & 4))
 #endif
@@ -842,6 +865,13 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             }
             if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
         }
+    }
+    };
+    if constexpr (MODE == 2) {
+        if (wave >= kWaves / 2) run_items(std::integral_constant<int, 2>{});
+        else run_items(std::integral_constant<int, 1>{});
+    } else {
+        run_items(std::integral_constant<int, 0>{});
     }
     // the last workgroup to leave puts the counters back to zero for the next call
     if (tid == 0 && p.n_items > (int)gridDim.x) {
