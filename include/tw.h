@@ -138,11 +138,29 @@ int tw_gemm_workspace(const void* blob_host, int M, size_t* ws_bytes);
 int tw_gemm(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
             void* C, int ldc, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* C = act(A . (B * mask) + bias): tw_gemm with the bias addition and the activation that follow a
+ * weight GEMM inside a Transformer or CNN layer fused into its epilogue (Sec. VI "Kernel Fusion": the
+ * non-GEMM operators around the GEMMs are fused so that they do not eat the GEMM's gain; here the
+ * part that attaches to the GEMM itself is folded into it, the rest of a layer is out of scope).
+ *   bias  device, N elements of the blob's dtype, 2-byte aligned, or NULL for no bias
+ *   act   TW_ACT_NONE, TW_ACT_RELU (max(x, 0)) or TW_ACT_GELU (x/2 * (1 + erf(x / sqrt 2)))
+ * The sum of the fp32 accumulator and the bias, and the activation, are evaluated in fp32 and rounded
+ * once to the storage type.  A pruned column n of C holds act(bias[n]) in every row.  Everything else
+ * as tw_gemm; TW_ERR_ARG also for an unknown act.  tw_gemm is this call with bias = NULL, act = NONE. */
+typedef enum { TW_ACT_NONE = 0, TW_ACT_RELU = 1, TW_ACT_GELU = 2 } tw_act;
+int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
+                     const void* bias, tw_act act, void* C, int ldc, void* workspace, size_t ws_bytes,
+                     void* hip_stream);
+
 /* Dense reference C = A . B on the same MFMA pipeline (the paper's dense baseline, Sec. VI
  * "Tiling" / Sec. VII-A).  A: device M x K (lda % 8 == 0), B: device K x N row-major
  * (ldb % 8 == 0), C: device M x N (ldc % 8 == 0); bases 16-byte aligned. */
 int tw_dense_gemm(const void* A, int lda, const void* B, int ldb, void* C, int ldc,
                   int M, int N, int K, tw_dtype dt, void* hip_stream);
+
+/* C = act(A . B + bias), the dense yardstick with the same fused epilogue (bias: N elements of dt). */
+int tw_dense_gemm_bias_act(const void* A, int lda, const void* B, int ldb, const void* bias, tw_act act,
+                           void* C, int ldc, int M, int N, int K, tw_dtype dt, void* hip_stream);
 
 const char* tw_strerror(int status);
 int tw_version(void);

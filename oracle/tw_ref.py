@@ -7,6 +7,9 @@
                          the stretch of original columns up to the next tile's first column
                          (the "G+4, G+3, G+2, G-9" stretches of the worked example).
 * ``masked_weight_bits`` - what pack -> unpack must give back: B where kept, +0 elsewhere.
+* ``bias_act``         - the fused epilogue's definition: act(C + bias) in fp64 (bias addition and
+                         activation are the operators the paper fuses around its GEMMs, Sec. VI
+                         "Kernel Fusion"; GELU in its exact erf form, as in BERT).
 
 Nothing here imports the HIP package, and the HIP package imports nothing from here.
 Parity status: pinned by tests/test_oracle_pins.py and tests/test_tile_structure_pins.py.
@@ -192,3 +195,19 @@ def prune_one_shot(B_bits: np.ndarray, G: int, dtype: str, col_prune: float, spa
             if (t, k) not in drop:
                 mask[k, tc] = 1
     return mask
+
+
+def bias_act(C: np.ndarray, bias64, act: str = "none") -> np.ndarray:
+    """act(C + bias), fp64.  C: [M, N] fp64 (the masked product), bias64: [N] fp64 or None.
+    relu(x) = max(x, 0); gelu(x) = x/2 * (1 + erf(x / sqrt 2)) = x * Phi(x) (the exact form)."""
+    from scipy.special import erf
+    x = np.asarray(C, dtype=np.float64)
+    if bias64 is not None:
+        x = x + np.asarray(bias64, dtype=np.float64)[None, :]
+    if act in (None, "none"):
+        return x
+    if act == "relu":
+        return np.maximum(x, 0.0)
+    if act == "gelu":
+        return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
+    raise ValueError(f"unknown activation {act!r}")

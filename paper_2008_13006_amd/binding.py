@@ -20,7 +20,9 @@ TW_F16, TW_BF16 = 0, 1
 _DT = {"f16": TW_F16, "bf16": TW_BF16}
 
 SYMBOLS = ["tw_pack_size", "tw_pack", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm",
-           "tw_dense_gemm", "tw_strerror", "tw_version"]
+           "tw_gemm_bias_act", "tw_dense_gemm", "tw_dense_gemm_bias_act", "tw_strerror", "tw_version"]
+TW_ACT_NONE, TW_ACT_RELU, TW_ACT_GELU = 0, 1, 2
+_ACT = {None: TW_ACT_NONE, "none": TW_ACT_NONE, "relu": TW_ACT_RELU, "gelu": TW_ACT_GELU}
 
 
 class TwError(RuntimeError):
@@ -53,6 +55,8 @@ def _load() -> ctypes.CDLL:
     lib.tw_gemm_workspace.argtypes = [vp, i, ctypes.POINTER(sz)]
     lib.tw_gemm.argtypes = [vp, vp, vp, i, i, vp, i, vp, sz, vp]
     lib.tw_dense_gemm.argtypes = [vp, i, vp, i, vp, i, i, i, i, i, vp]
+    lib.tw_gemm_bias_act.argtypes = [vp, vp, vp, i, i, vp, i, vp, i, vp, sz, vp]
+    lib.tw_dense_gemm_bias_act.argtypes = [vp, i, vp, i, vp, i, vp, i, i, i, i, i, vp]
     lib.tw_strerror.argtypes = [i]
     lib.tw_strerror.restype = ctypes.c_char_p
     for name in SYMBOLS:
@@ -205,6 +209,62 @@ def tw_gemm(w: TwWeight, A, C=None, stream=None):
     _check(_lib.tw_gemm(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()), ctypes.c_void_p(A.data_ptr()),
                         M, lda, ctypes.c_void_p(C.data_ptr()), ldc, ctypes.c_void_p(w.workspace.data_ptr()),
                         w.workspace.numel(), _stream_ptr(stream)), "tw_gemm")
+    return C
+
+
+def _act_code(act) -> int:
+    if isinstance(act, int):
+        return act
+    if act not in _ACT:
+        raise ValueError(f"unknown activation {act!r}")
+    return _ACT[act]
+
+
+def tw_gemm_bias_act(w: TwWeight, A, bias=None, act="none", C=None, stream=None):
+    """C = act(A . (B * mask) + bias).  bias: torch tensor [N] of A's dtype on the GPU, or None."""
+    torch = _torch()
+    assert A.is_cuda and A.dtype == _tdtype(w.dtype) and A.dim() == 2 and A.stride(1) == 1
+    M, K = A.shape
+    assert K == w.info["K"]
+    N = w.info["N"]
+    if C is None:
+        C = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    assert C.is_cuda and C.dtype == A.dtype and C.shape == (M, N) and C.stride(1) == 1
+    bptr = ctypes.c_void_p(0)
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == A.dtype and bias.shape == (N,) and bias.stride(0) == 1
+        bptr = ctypes.c_void_p(bias.data_ptr())
+    lda = A.stride(0) if M > 1 else max(K, A.stride(0))
+    ldc = C.stride(0) if M > 1 else max(N, C.stride(0))
+    _check(_lib.tw_gemm_bias_act(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()),
+                                 ctypes.c_void_p(A.data_ptr()), M, lda, bptr, _act_code(act),
+                                 ctypes.c_void_p(C.data_ptr()), ldc, ctypes.c_void_p(w.workspace.data_ptr()),
+                                 w.workspace.numel(), _stream_ptr(stream)), "tw_gemm_bias_act")
+    return C
+
+
+def tw_dense_gemm_bias_act(A, B, bias=None, act="none", C=None, stream=None):
+    """C = act(A . B + bias), both matrices row-major torch tensors on the GPU."""
+    torch = _torch()
+    assert A.is_cuda and B.is_cuda and A.dtype == B.dtype and A.dtype in (torch.float16, torch.bfloat16)
+    assert A.dim() == 2 and B.dim() == 2 and A.stride(1) == 1 and B.stride(1) == 1
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2
+    if C is None:
+        C = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    assert C.shape == (M, N) and C.dtype == A.dtype and C.stride(1) == 1
+    bptr = ctypes.c_void_p(0)
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == A.dtype and bias.shape == (N,) and bias.stride(0) == 1
+        bptr = ctypes.c_void_p(bias.data_ptr())
+    dt = TW_F16 if A.dtype == torch.float16 else TW_BF16
+    lda = A.stride(0) if M > 1 else max(K, A.stride(0))
+    ldb = B.stride(0) if K > 1 else max(N, B.stride(0))
+    ldc = C.stride(0) if M > 1 else max(N, C.stride(0))
+    _check(_lib.tw_dense_gemm_bias_act(ctypes.c_void_p(A.data_ptr()), lda, ctypes.c_void_p(B.data_ptr()), ldb, bptr,
+                                       _act_code(act), ctypes.c_void_p(C.data_ptr()), ldc, M, N, K, dt,
+                                       _stream_ptr(stream)), "tw_dense_gemm_bias_act")
     return C
 
 

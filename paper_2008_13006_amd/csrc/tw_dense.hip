@@ -32,6 +32,8 @@ struct DenseParams {
     long lda, ldb, ldc;
     int M, N, K;
     int nbm, nbn;
+    const unsigned short* bias;   // N values added before the activation, or null
+    int act;                      // tw_act
 };
 
 struct Staged {
@@ -161,7 +163,8 @@ __global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p)
     if (width > 0) {
 #pragma unroll
         for (int ms = 0; ms < 4; ++ms)
-            tw_store_block<DT, 2>(acc[ms], stage, p.C, p.ldc, m0 + wm * 128 + ms * 32, p.M, col0, width, lane);
+            tw_store_block<DT, 2>(acc[ms], stage, p.C, p.ldc, m0 + wm * 128 + ms * 32, p.M, col0, width, lane,
+                                  p.bias, p.act);
     }
 }
 
@@ -169,7 +172,14 @@ __global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p)
 
 extern "C" int tw_dense_gemm(const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
                              tw_dtype dt, void* hip_stream) {
+    return tw_dense_gemm_bias_act(A, lda, B, ldb, nullptr, TW_ACT_NONE, C, ldc, M, N, K, dt, hip_stream);
+}
+
+extern "C" int tw_dense_gemm_bias_act(const void* A, int lda, const void* B, int ldb, const void* bias, tw_act act,
+                                      void* C, int ldc, int M, int N, int K, tw_dtype dt, void* hip_stream) {
     if (!A || !B || !C || M < 0 || N <= 0 || K <= 0) return TW_ERR_ARG;
+    if (act != TW_ACT_NONE && act != TW_ACT_RELU && act != TW_ACT_GELU) return TW_ERR_ARG;
+    if (((uintptr_t)bias & 1) != 0) return TW_ERR_ALIGN;
     if (dt != TW_F16 && dt != TW_BF16) return TW_ERR_ARG;
     if (lda < K || ldb < N || ldc < N) return TW_ERR_ARG;
     if ((lda & 7) || (ldb & 7) || (ldc & 7)) return TW_ERR_ALIGN;
@@ -179,6 +189,7 @@ extern "C" int tw_dense_gemm(const void* A, int lda, const void* B, int ldb, voi
     p.A = (const unsigned short*)A; p.B = (const unsigned short*)B; p.C = (unsigned short*)C;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
     p.M = M; p.N = N; p.K = K;
+    p.bias = (const unsigned short*)bias; p.act = (int)act;
     p.nbm = (M + BM - 1) / BM; p.nbn = (N + BN - 1) / BN;
     const long blocks = (long)p.nbm * p.nbn;
     if (blocks > 0x7fffffffL) return TW_ERR_UNSUPPORTED;

@@ -44,6 +44,42 @@ __device__ __forceinline__ unsigned short tw_cvt(float x) {
     }
 }
 
+// 16-bit storage type -> fp32 (exact).
+template <int DT>
+__device__ __forceinline__ float tw_to_f32(unsigned short bits) {
+    if constexpr (DT == TW_F16) {
+        return (float)__builtin_bit_cast(_Float16, bits);
+    } else {
+        return __builtin_bit_cast(float, (unsigned)bits << 16);
+    }
+}
+
+// erf(x) in fp32 by the rational approximation 7.1.26 of Abramowitz and Stegun,
+//   erf(x) = 1 - (a1 t + a2 t^2 + a3 t^3 + a4 t^4 + a5 t^5) exp(-x^2),  t = 1 / (1 + p x),  x >= 0,
+// absolute error below 1.5e-7: far below the rounding of the 16-bit result, and straight-line code
+// (the library routine is a page of branches, which costs registers when it is inlined 128 times).
+__device__ __forceinline__ float tw_erf(float x) {
+    const float ax = __builtin_fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(1.f + 0.3275911f * ax);
+    float poly = 1.061405429f;
+    poly = poly * t - 1.453152027f;
+    poly = poly * t + 1.421413741f;
+    poly = poly * t - 0.284496736f;
+    poly = poly * t + 0.254829592f;
+    const float e = __expf(-ax * ax);
+    const float r = 1.f - poly * t * e;
+    return __builtin_copysignf(r, x);
+}
+
+__device__ __forceinline__ float tw_gelu(float x) { return 0.5f * x * (1.f + tw_erf(x * 0.70710678118654752f)); }
+
+// Activation of the fused epilogue, in fp32.  act is wave-uniform.
+__device__ __forceinline__ float tw_activate(float x, int act) {
+    if (act == TW_ACT_RELU) return x > 0.f ? x : 0.f;
+    if (act == TW_ACT_GELU) return tw_gelu(x);
+    return x;
+}
+
 // Orders this wave's LDS traffic: everything issued before is complete and visible to the
 // wave's other lanes afterwards.  Not a workgroup barrier.
 __device__ __forceinline__ void tw_wave_lds_sync() {
@@ -65,9 +101,11 @@ typedef unsigned int __attribute__((aligned(2))) tw_u32_a2;
 // Writes one 32-row block of a wave's results to C[row0.., col0 .. col0+width) through the wave's
 // LDS staging area, 64 columns at a time (used where result column c goes to column col0 + c).
 //   acc[cb][r]   fp32 results: lane l owns row (l%32) and column c = 32*cb + 8*(r/4) + 4*(l/32) + r%4
+// bias (may be null): element col0 + c is added to column c before the activation `act`.
 template <int DT, int NCB>
 __device__ __forceinline__ void tw_store_block(const tw_f32x16 (&acc)[NCB], unsigned char* stage, unsigned short* C,
-                                               long ldc, int row0, int M, int col0, int width, int lane) {
+                                               long ldc, int row0, int M, int col0, int width, int lane,
+                                               const unsigned short* bias = nullptr, int act = 0) {
     const int mrow = lane & 31, h = lane >> 5;
     unsigned char* myrow = stage + mrow * TW_STAGE_PITCH;
     for (int w0 = 0; w0 < width; w0 += TW_STAGE_COLS) {
@@ -77,9 +115,20 @@ __device__ __forceinline__ void tw_store_block(const tw_f32x16 (&acc)[NCB], unsi
             for (int q = 0; q < 4; ++q) {
                 const int c_lo = 32 * cb + 8 * q;          // wave-uniform: columns c_lo .. c_lo+7
                 if (c_lo < w0 || c_lo >= w0 + TW_STAGE_COLS) continue;
+                float x[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = acc[cb][4 * q + e];
+                if (bias != nullptr || act != 0) {           // wave-uniform
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int c = c_lo + 4 * h + e;
+                        const float b = (bias != nullptr && c < width) ? tw_to_f32<DT>(bias[col0 + c]) : 0.f;
+                        x[e] = tw_activate(x[e] + b, act);
+                    }
+                }
                 tw_u32x2 v;
-                v.x = (unsigned)tw_cvt<DT>(acc[cb][4 * q + 0]) | ((unsigned)tw_cvt<DT>(acc[cb][4 * q + 1]) << 16);
-                v.y = (unsigned)tw_cvt<DT>(acc[cb][4 * q + 2]) | ((unsigned)tw_cvt<DT>(acc[cb][4 * q + 3]) << 16);
+                v.x = (unsigned)tw_cvt<DT>(x[0]) | ((unsigned)tw_cvt<DT>(x[1]) << 16);
+                v.y = (unsigned)tw_cvt<DT>(x[2]) | ((unsigned)tw_cvt<DT>(x[3]) << 16);
                 *(tw_u32x2*)(myrow + (c_lo + 4 * h - w0) * 2) = v;
             }
         }

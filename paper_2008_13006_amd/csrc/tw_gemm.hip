@@ -62,6 +62,8 @@ struct TwGemmParams {
     const unsigned short* A;
     unsigned short* C;
     int* counters;              // [0] next item, [1] finished workgroups
+    const unsigned short* bias; // fused epilogue: N values of the storage type, or null
+    int act;                    // fused epilogue: tw_act
     long lda, ldc;
     int M, K, N, T;
     int k_chunk, n_chunks, G;
@@ -414,10 +416,84 @@ __device__ __forceinline__ tw_i16x4 tw_lds_read_tr(const unsigned char* a) {
 
 // dpos: destination columns of this lane's packed columns (one per 32-column block), counted from the
 // 8-aligned column at or below the span start.
-template <int DT, int MS, int NCB>
+// Fused epilogue (p.bias and / or p.act): `eb` holds the bias of this lane's packed columns and of the
+// four columns lane, lane+64, .. of the first staging window (see fetch_epi_bias).
+template <int NCB>
+struct EpiBias {
+    float col[NCB];
+    float fill[kWinLines];
+};
+
+// Reads what store_tile needs of the bias.
+template <int DT, int NCB>
+__device__ __forceinline__ void fetch_epi_bias(const TwGemmParams& p, const TileU& d, const unsigned (&dpos)[NCB],
+                                               EpiBias<NCB>& eb, int lane) {
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) eb.col[cb] = 0.f;
+#pragma unroll
+    for (int l = 0; l < kWinLines; ++l) eb.fill[l] = 0.f;
+    if (p.bias != nullptr) {                                // wave-uniform
+        const int origin = d.span_start & ~7, E = d.span_start + d.span_w;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+            if (dpos[cb] != 0xFFFFFFFFu) eb.col[cb] = tw_to_f32<DT>(p.bias[origin + (int)dpos[cb]]);
+        if (d.span_w != d.w) {                              // pruned columns inside the span: they hold act(bias)
+            const int W0 = d.span_start & ~(kLineCols - 1);
+#pragma unroll
+            for (int l = 0; l < kWinLines; ++l) {
+                const int c = W0 + l * kLineCols + lane;
+                if (c >= d.span_start && c < E) eb.fill[l] = tw_to_f32<DT>(p.bias[c]);
+            }
+        }
+    }
+}
+
+// The fused epilogue's arithmetic, in place on the accumulators and kept apart from the store code: one
+// loop per activation, so that the plain path's code and registers stay as they are.
+template <int MS, int NCB>
+__device__ __forceinline__ void apply_bias_act(tw_f32x16 (&acc)[MS][NCB], const EpiBias<NCB>& eb, int act) {
+    if (act == TW_ACT_GELU) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float x = acc[ms][cb][r] + eb.col[cb];
+                    acc[ms][cb][r] = tw_gelu(x);
+                }
+    } else if (act == TW_ACT_RELU) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float x = acc[ms][cb][r] + eb.col[cb];
+                    acc[ms][cb][r] = x > 0.f ? x : 0.f;
+                }
+    } else {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[ms][cb][r] += eb.col[cb];
+    }
+}
+
+// FUSED: the kernel variant with the fused epilogue (a bias and / or an activation); the plain variant
+// carries none of its code.
+template <int DT, int MS, int NCB, bool FUSED>
 __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
                                            unsigned char* stage, const unsigned (&dpos)[NCB], int row0, int lane_in) {
     const int lane = fresh(lane_in);
+    constexpr bool fused = FUSED;
+    EpiBias<NCB> eb;
+    if constexpr (FUSED) {
+        fetch_epi_bias<DT, NCB>(p, d, dpos, eb, lane);
+        apply_bias_act<MS, NCB>(acc, eb, p.act);
+    }
     const int h = lane >> 5, n = lane & 31;
     const int blk = lane >> 4, j = lane & 15;
     // read-back, as the lane that supplies an address: column offset e, group g -> (piece, row quad)
@@ -471,13 +547,27 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
             }
         };
 
-        // clear both planes once: the passes all write the same columns
+        // clear both planes once: the passes all write the same columns.  With a fused epilogue a pruned
+        // column holds act(bias) in every row instead of zero.
         tw_compiler_fence();
+        if (!fused || d.span_w == d.w) {
 #pragma unroll
-        for (int pl = 0; pl < 2; ++pl)
+            for (int pl = 0; pl < 2; ++pl)
 #pragma unroll
-            for (int i = 0; i < kWinCols * 8 / 1024; ++i)
-                *(tw_u32x4*)(stage + pl * kPlaneBytes + i * 1024 + lane * 16) = tw_u32x4{0u, 0u, 0u, 0u};
+                for (int i = 0; i < kWinCols * 8 / 1024; ++i)
+                    *(tw_u32x4*)(stage + pl * kPlaneBytes + i * 1024 + lane * 16) = tw_u32x4{0u, 0u, 0u, 0u};
+        } else {
+#pragma unroll
+            for (int l = 0; l < kWinLines; ++l) {
+                const int c = win0 + l * kLineCols + lane;
+                float b = eb.fill[l];
+                if (win0 != W0) b = (p.bias != nullptr && c >= S && c < E) ? tw_to_f32<DT>(p.bias[c]) : 0.f;   // later windows: read here
+                const unsigned hv = (c >= S && c < E) ? (unsigned)tw_cvt<DT>(tw_activate(b, p.act)) : 0u;
+                const tw_u32x2 v{hv | (hv << 16), hv | (hv << 16)};
+                *(tw_u32x2*)(stage + (l * kLineCols + lane) * 8) = v;
+                *(tw_u32x2*)(stage + kPlaneBytes + (l * kLineCols + lane) * 8) = v;
+            }
+        }
         tw_compiler_fence();
         write_pass(0);
         tw_compiler_fence();
@@ -546,7 +636,7 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 // MODE 2: K streamed, row block of 64 rows (MS = 2), for weights with at most four tiles: waves 0-3
 //         multiply (wave w owns tile 4*set + w), waves 4-7 do nothing but bring A into LDS, so the
 //         two kinds of work overlap instead of taking turns.
-template <int DT, int MS, int NCB, int MODE>
+template <int DT, int MS, int NCB, int MODE, bool FUSED>
 __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int MSB = MS;                       // 32-row blocks in the workgroup's row block
@@ -647,7 +737,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #ifdef TW_EXPERIMENT
                 if (!(TWD(p.dbg) & 4))
 #endif
-                store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+                store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 TW_MARK();
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
@@ -778,7 +868,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #ifdef TW_EXPERIMENT
                 if (!(TWD(p.dbg) & 4))
 #endif
-                if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+                if (active) store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
             }
         } else {
             // K is streamed in chunks through two LDS buffers: the requests for chunk c+1 go out before
@@ -863,7 +953,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     __syncthreads();
                 }
             }
-            if (active) store_tile<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+            if (active) store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
         }
     }
     };
@@ -884,11 +974,15 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
     }
 }
 
-// C[0:M, 0:N] = 0 for a weight with no surviving column.
-__global__ void tw_zero_kernel(unsigned short* C, long ldc, int M, int N) {
+// C[m, n] = act(bias[n]) (zero without a bias) for a weight with no surviving column.
+template <int DT>
+__global__ void tw_fill_kernel(unsigned short* C, long ldc, int M, int N, const unsigned short* bias, int act) {
     const long n = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const long total = (long)M * N;
-    for (long i = n; i < total; i += (long)gridDim.x * blockDim.x) C[(i / N) * ldc + (i % N)] = 0;
+    for (long i = n; i < total; i += (long)gridDim.x * blockDim.x) {
+        const long col = i % N;
+        C[(i / N) * ldc + col] = bias ? tw_cvt<DT>(tw_activate(tw_to_f32<DT>(bias[col]), act)) : (unsigned short)0;
+    }
 }
 
 struct Plan {
@@ -954,25 +1048,26 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
 
 typedef void (*KernelFn)(const TwGemmParams);
 
-template <int DT, int MS, int MODE>
+template <int DT, int MS, int MODE, bool FUSED>
 KernelFn pick_ncb(int ncb) {
     switch (ncb) {
-        case 1: return tw_gemm_kernel<DT, MS, 1, MODE>;
-        case 2: return tw_gemm_kernel<DT, MS, 2, MODE>;
-        case 4: return tw_gemm_kernel<DT, MS, 4, MODE>;
+        case 1: return tw_gemm_kernel<DT, MS, 1, MODE, FUSED>;
+        case 2: return tw_gemm_kernel<DT, MS, 2, MODE, FUSED>;
+        case 4: return tw_gemm_kernel<DT, MS, 4, MODE, FUSED>;
         default: return nullptr;
     }
 }
 
-template <int DT>
+template <int DT, bool FUSED>
 KernelFn pick_mode(int mode, int ms, int ncb) {
-    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0>(ncb) : pick_ncb<DT, 1, 0>(ncb);
-    if (mode == 1) return ms == 2 ? pick_ncb<DT, 2, 1>(ncb) : pick_ncb<DT, 1, 1>(ncb);
-    return pick_ncb<DT, 2, 2>(ncb);
+    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED>(ncb) : pick_ncb<DT, 1, 0, FUSED>(ncb);
+    if (mode == 1) return ms == 2 ? pick_ncb<DT, 2, 1, FUSED>(ncb) : pick_ncb<DT, 1, 1, FUSED>(ncb);
+    return pick_ncb<DT, 2, 2, FUSED>(ncb);
 }
 
-KernelFn pick_kernel(int dt, int mode, int ms, int ncb) {
-    return dt == TW_F16 ? pick_mode<TW_F16>(mode, ms, ncb) : pick_mode<TW_BF16>(mode, ms, ncb);
+KernelFn pick_kernel(int dt, int mode, int ms, int ncb, bool fused) {
+    if (fused) return dt == TW_F16 ? pick_mode<TW_F16, true>(mode, ms, ncb) : pick_mode<TW_BF16, true>(mode, ms, ncb);
+    return dt == TW_F16 ? pick_mode<TW_F16, false>(mode, ms, ncb) : pick_mode<TW_BF16, false>(mode, ms, ncb);
 }
 
 // Per-device facts looked up once (the entries are written with the same value by every thread
@@ -995,7 +1090,7 @@ int device_cus(int dev) {
 }
 
 // The dynamic-LDS limit of a kernel is raised to the hardware maximum once per (device, kernel).
-constexpr int kMaxKernels = 32;
+constexpr int kMaxKernels = 64;
 std::atomic<unsigned> g_lds_set[kMaxDevices][kMaxKernels];
 
 int ensure_lds(int dev, int kernel_id, const void* fn) {
@@ -1018,7 +1113,16 @@ extern "C" int tw_gemm_workspace(const void* blob_host, int M, size_t* ws_bytes)
 
 extern "C" int tw_gemm(const void* blob_host, const void* blob_dev, const void* A, int M, int lda, void* C,
                        int ldc, void* workspace, size_t ws_bytes, void* hip_stream) {
+    return tw_gemm_bias_act(blob_host, blob_dev, A, M, lda, nullptr, TW_ACT_NONE, C, ldc, workspace, ws_bytes,
+                            hip_stream);
+}
+
+extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
+                                const void* bias, tw_act act, void* C, int ldc, void* workspace, size_t ws_bytes,
+                                void* hip_stream) {
     if (!blob_host || !blob_dev || !A || !C || !workspace || M < 0) return TW_ERR_ARG;
+    if (act != TW_ACT_NONE && act != TW_ACT_RELU && act != TW_ACT_GELU) return TW_ERR_ARG;
+    if (((uintptr_t)bias & 1) != 0) return TW_ERR_ALIGN;
     const TwHeader* h = (const TwHeader*)blob_host;
     if (h->magic != TW_MAGIC || h->version != TW_FORMAT_VERSION) return TW_ERR_BUF;
     if (ws_bytes < 256) return TW_ERR_BUF;
@@ -1032,7 +1136,12 @@ extern "C" int tw_gemm(const void* blob_host, const void* blob_dev, const void* 
         const long total = (long)M * h->N;
         int blocks = (int)((total + 255) / 256);
         if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(tw_zero_kernel, dim3(blocks), dim3(256), 0, stream, (unsigned short*)C, (long)ldc, M, h->N);
+        if (h->dtype == TW_F16)
+            hipLaunchKernelGGL(tw_fill_kernel<TW_F16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)C, (long)ldc, M,
+                               h->N, (const unsigned short*)bias, (int)act);
+        else
+            hipLaunchKernelGGL(tw_fill_kernel<TW_BF16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)C, (long)ldc, M,
+                               h->N, (const unsigned short*)bias, (int)act);
         return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
     }
 
@@ -1043,10 +1152,11 @@ extern "C" int tw_gemm(const void* blob_host, const void* blob_dev, const void* 
     Plan pl;
     int rc = make_plan(h, M, n_cu, pl);
     if (rc) return rc;
-    KernelFn fn = pick_kernel(h->dtype, pl.mode, pl.ms, h->ncb);
+    const bool fused = bias != nullptr || act != TW_ACT_NONE;
+    KernelFn fn = pick_kernel(h->dtype, pl.mode, pl.ms, h->ncb, fused);
     if (!fn) return TW_ERR_UNSUPPORTED;
     const int variant = pl.mode == 2 ? 4 : 2 * pl.mode + (pl.ms == 2 ? 0 : 1);      // 0..4
-    const int kernel_id = (h->dtype == TW_F16 ? 0 : 15) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
+    const int kernel_id = (fused ? 30 : 0) + (h->dtype == TW_F16 ? 0 : 15) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, (const void*)fn);
     if (rc) return rc;
 
@@ -1055,6 +1165,7 @@ extern "C" int tw_gemm(const void* blob_host, const void* blob_dev, const void* 
     p.A = (const unsigned short*)A;
     p.C = (unsigned short*)C;
     p.counters = (int*)workspace;
+    p.bias = (const unsigned short*)bias; p.act = (int)act;
     p.lda = lda; p.ldc = ldc;
     p.M = M; p.K = h->K; p.N = h->N; p.T = h->T;
     p.k_chunk = h->k_chunk; p.n_chunks = h->n_chunks; p.G = h->G;

@@ -242,3 +242,102 @@ def test_full_size_workloads_on_sampled_rows(tw, cfg):
             assert _rel_err(_to_f64(Cd[torch.as_tensor(rows, device="cuda:0")]), ref) <= TOL[spec.dtype]
         del wt, A, C
         torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ fused epilogue: act(A.(B*mask) + bias)
+def _bias_bits(N, dtype, seed):
+    rng = np.random.default_rng(seed)
+    return W.f32_to_bits(rng.standard_normal(N, dtype=np.float32) * np.float32(0.5), dtype)
+
+
+FUSED = [
+    # SMALL case name, bias?, activation
+    ("ragged_rows_gaps", True, "gelu"), ("ragged_rows_gaps", True, "none"), ("ragged_rows_gaps", False, "relu"),
+    ("bf16_g64", True, "gelu"), ("g32_many_tiles", True, "relu"), ("several_row_blocks", True, "gelu"),
+    ("streamed_k", True, "gelu"), ("streamed_k_bf16_ragged", True, "relu"), ("wide_spans", True, "gelu"),
+    ("thin_tiles", True, "gelu"), ("odd_everything", True, "relu"), ("one_row", False, "gelu"),
+]
+
+
+@pytest.mark.parametrize("case", FUSED, ids=[f"{c[0]}-{'bias' if c[1] else 'nobias'}-{c[2]}" for c in FUSED])
+def test_tw_gemm_bias_act(tw, case):
+    """tw_gemm_bias_act against the oracle's act(C_ref + bias); pruned columns must hold act(bias)."""
+    cname, with_bias, act = case
+    name, M, K, N, G, dtype, cp, keep = next(c for c in SMALL if c[0] == cname)
+    _say(f"tw_gemm_bias_act {name} bias={with_bias} act={act}")
+    spec = W.small_spec(name, M=M, K=K, N=N, G=G, dtype=dtype, col_prune=cp, keep=keep, seed_offset=9500 + len(name))
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, G, dtype)
+    A = _device_A(tw, w.A, dtype)
+    bbits = _bias_bits(N, dtype, 77 + N) if with_bias else None
+    bias = tw.bits_to_tensor(bbits, dtype) if with_bias else None
+    C = torch.full((M, N), float("nan"), dtype=A.dtype, device="cuda:0")
+    tw.tw_gemm_bias_act(wt, A, bias, act, C)
+    torch.cuda.synchronize()
+    ref = tw_ref.bias_act(tw_ref.masked_gemm(w.A, w.B, w.mask, dtype),
+                          tw_ref.decode(bbits, dtype) if with_bias else None, act)
+    got = _to_f64(C)
+    assert np.isfinite(got).all(), "some element of C was not written"
+    err = _rel_err(got, ref)
+    _say(f"  rel err {err:.3e}")
+    assert err <= TOL[dtype]
+    pruned = np.flatnonzero(~w.mask.any(axis=0))
+    if len(pruned):      # act(bias) there, the same value in every row
+        col = got[:, pruned]
+        assert np.all(col == col[0:1, :])
+        assert np.max(np.abs(col[0] - ref[0, pruned])) <= TOL[dtype] * max(1.0, np.max(np.abs(ref)))
+
+
+def test_tw_gemm_bias_act_empty_weight_and_bad_act(tw):
+    M, K, N, G = 9, 32, 64, 32
+    B_bits = W.f32_to_bits(np.ones((K, N), np.float32), "f16")
+    wt = tw.TwWeight.from_dense(B_bits, np.zeros((K, N), np.uint8), G, "f16")
+    A = torch.ones((M, K), dtype=torch.float16, device="cuda:0")
+    bbits = _bias_bits(N, "f16", 5)
+    C = tw.tw_gemm_bias_act(wt, A, tw.bits_to_tensor(bbits, "f16"), "relu")
+    torch.cuda.synchronize()
+    ref = tw_ref.bias_act(np.zeros((M, N)), tw_ref.decode(bbits, "f16"), "relu")
+    assert np.array_equal(_to_f64(C), ref)          # relu of a 16-bit value is exact
+    with pytest.raises(tw.TwError):
+        tw.tw_gemm_bias_act(wt, A, None, 7)
+
+
+@pytest.mark.parametrize("case", [("d_ragged", "gelu"), ("d_blocks", "relu"), ("d_small", "none")],
+                         ids=["d_ragged-gelu", "d_blocks-relu", "d_small-none"])
+def test_dense_gemm_bias_act(tw, case):
+    dname, act = case
+    name, M, K, N, dtype = next(c for c in DENSE if c[0] == dname)
+    _say(f"tw_dense_gemm_bias_act {name} act={act}")
+    rng = np.random.default_rng(sum(map(ord, name)) + 1)
+    A_bits = W.f32_to_bits(rng.standard_normal((M, K), dtype=np.float32), dtype)
+    B_bits = W.f32_to_bits(rng.standard_normal((K, N), dtype=np.float32) * np.float32(0.05), dtype)
+    bbits = _bias_bits(N, dtype, 11)
+    lda, ldb, ldc = (K + 7) // 8 * 8, (N + 7) // 8 * 8, (N + 7) // 8 * 8 + 8
+    td = torch.float16 if dtype == "f16" else torch.bfloat16
+    A = torch.zeros((M, lda), dtype=td, device="cuda:0"); A[:, :K] = tw.bits_to_tensor(A_bits, dtype)
+    B = torch.zeros((K, ldb), dtype=td, device="cuda:0"); B[:, :N] = tw.bits_to_tensor(B_bits, dtype)
+    Cbuf = torch.full((M, ldc), float("nan"), dtype=td, device="cuda:0")
+    tw.tw_dense_gemm_bias_act(A[:, :K], B[:, :N], tw.bits_to_tensor(bbits, dtype), act, Cbuf[:, :N])
+    torch.cuda.synchronize()
+    ref = tw_ref.bias_act(tw_ref.masked_gemm(A_bits, B_bits, np.ones((K, N), np.uint8), dtype),
+                          tw_ref.decode(bbits, dtype), act)
+    got = _to_f64(Cbuf[:, :N])
+    assert np.isfinite(got).all()
+    assert _rel_err(got, ref) <= TOL[dtype]
+    assert bool(torch.isnan(Cbuf[:, N:].float()).all().item()), "wrote outside C"
+
+
+def test_full_size_ffn_up_with_gelu(tw):
+    """BERT-base FFN-up at full size with its bias and GELU fused, on sampled rows."""
+    spec = W.CONFIGS["c2_bert_base_ffn_up"][0]
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, spec.G, spec.dtype)
+    A = _device_A(tw, w.A, spec.dtype)
+    bbits = _bias_bits(spec.N, spec.dtype, 3)
+    C = tw.tw_gemm_bias_act(wt, A, tw.bits_to_tensor(bbits, spec.dtype), "gelu")
+    torch.cuda.synchronize()
+    rows = _sample_rows(spec.M, n=96, seed=2)
+    ref = tw_ref.bias_act(tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, w.mask, spec.dtype),
+                          tw_ref.decode(bbits, spec.dtype), "gelu")
+    assert _rel_err(_to_f64(C[torch.as_tensor(rows, device="cuda:0")]), ref) <= TOL[spec.dtype]
+    assert bool(torch.isfinite(C.float()).all().item())

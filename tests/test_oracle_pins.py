@@ -167,3 +167,28 @@ def test_bad_arguments_are_rejected():
     B = np.zeros((4, 3), np.uint16)
     with pytest.raises(AssertionError):
         tw_ref.masked_gemm(A, B, np.zeros((3, 4), np.uint8), "f16")
+
+
+# ------------------------------------------------------------------ fused epilogue definition
+def test_bias_act_pins():
+    """bias_act against closed forms: gelu(x) = x * Phi(x) with Phi the standard normal CDF
+    (Phi(1) = 0.8413447460685429..., a table value), gelu(x) - gelu(-x) = x, relu, bias broadcast
+    along rows, and a pruned column (C = 0) holding act(bias)."""
+    import math
+    x = np.array([[-3.0, -1.0, -0.5, 0.0, 0.5, 1.0, 3.0]])
+    g = tw_ref.bias_act(x, None, "gelu")
+    assert abs(g[0, 5] - 0.8413447460685429) < 1e-15
+    assert g[0, 3] == 0.0
+    assert np.allclose(g - tw_ref.bias_act(-x, None, "gelu"), x, rtol=0, atol=1e-15)
+    phi = np.array([0.5 * (1.0 + math.erf(v / math.sqrt(2.0))) for v in x[0]])
+    assert np.allclose(g[0], x[0] * phi, rtol=0, atol=1e-15)
+    assert np.array_equal(tw_ref.bias_act(x, None, "relu"), np.maximum(x, 0.0))
+    assert np.array_equal(tw_ref.bias_act(x, None, "none"), x)
+    C = np.zeros((3, 4)); C[:, 1] = [1.0, -2.0, 0.25]
+    b = np.array([0.5, -0.5, 2.0, -1.0])
+    out = tw_ref.bias_act(C, b, "relu")
+    assert np.array_equal(out[:, 0], [0.5, 0.5, 0.5]) and np.array_equal(out[:, 3], [0.0, 0.0, 0.0])
+    assert np.array_equal(out[:, 1], [0.5, 0.0, 0.0])
+    # a dropped bias or a bias added along the wrong axis fails the line above; a tanh-form GELU fails Phi(1)
+    with pytest.raises(ValueError):
+        tw_ref.bias_act(x, None, "swish")
