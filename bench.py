@@ -29,7 +29,7 @@ MFMA_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA
 # HBM bytes per tw_gemm launch on this workload, from the two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) summarised in profiles/tw_gemm_c2_hbm_traffic.txt, each scaled by what the same counter
 # reads for the copy kernel of known size that `--pmc-calibration` launches.
-MEASURED_TRAFFIC_BYTES = 149_839_612      # 35.59 MB read + 114.25 MB written
+MEASURED_TRAFFIC_BYTES = 149_773_378      # 36.02 MB read + 113.75 MB written
 PAPER_CONTEXT = {"tw128_speedup_vs_dense_75pct": 2.26, "hardware": "NVIDIA V100 tensor cores, FP16",
                  "where": "Sec. VII-B, Fig. 8b"}
 
@@ -220,6 +220,28 @@ def main() -> int:
                       f"x{r['speedup_vs_dense']:.2f}  nz {r['tw_tflops_nonzero']:.0f} TF  {r['tw_gbs']:.0f} GB/s",
                       file=sys.stderr, flush=True)
                 torch.cuda.empty_cache()
+        # the fused epilogue on the headline workload: FFN-up with its bias and GELU inside the GEMM, against
+        # the GEMM followed by a separate bias + GELU pass over C (torch's elementwise kernels)
+        M, N = spec.M, spec.N
+        td = torch.float16
+        wt = tw.TwWeight(tw.tw_pack(w.B, w.mask, spec.G, spec.dtype))
+        n_sets = 4
+        A0 = tw.bits_to_tensor(w.A, spec.dtype)
+        As = [A0] + [A0.clone() for _ in range(n_sets - 1)]
+        Cs = [torch.empty((M, N), dtype=td, device="cuda:0") for _ in range(n_sets)]
+        Bd = tw.bits_to_tensor(w.B, spec.dtype)
+        bias = (torch.randn(N, device="cuda:0") * 0.5).to(td)
+        gelu = torch.nn.functional.gelu
+        st = max(20, args.steps // 4)
+        fused_ms, _ = time_launches(torch, lambda i: tw.tw_gemm_bias_act(wt, As[i], bias, "gelu", Cs[i]), n_sets, st, 5)
+        plain_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wt, As[i], Cs[i]), n_sets, st, 5)
+        sep_ms, _ = time_launches(torch, lambda i: Cs[i].copy_(gelu(tw.tw_gemm(wt, As[i], Cs[i]) + bias)), n_sets, st, 5)
+        dfused_ms, _ = time_launches(torch, lambda i: tw.tw_dense_gemm_bias_act(As[i], Bd, bias, "gelu", Cs[i]), n_sets, st, 5)
+        rows.append({"config": "fused_epilogue_c2", "name": "ffn_up_768x3072 + bias + GELU", "tw_fused_ms": fused_ms,
+                     "tw_plain_ms": plain_ms, "tw_then_separate_bias_gelu_ms": sep_ms, "dense_fused_ms": dfused_ms})
+        print(f"[report] fused epilogue on c2: tw_gemm_bias_act(gelu) {fused_ms*1e3:.1f} us, tw_gemm {plain_ms*1e3:.1f} us, "
+              f"tw_gemm + separate bias/GELU pass {sep_ms*1e3:.1f} us, tw_dense_gemm_bias_act {dfused_ms*1e3:.1f} us",
+              file=sys.stderr, flush=True)
         with open(args.report, "w") as f:
             json.dump(rows, f, indent=1)
     if args.sweep:
