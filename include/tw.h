@@ -152,6 +152,24 @@ int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, const void* A,
                      const void* bias, tw_act act, void* C, int ldc, void* workspace, size_t ws_bytes,
                      void* hip_stream);
 
+/* The same product on the transposed boundary (Sec. VI "Memory Accesses Coalescing": the paper stores
+ * the activations and the result transposed, so that skipping a pruned K position skips a whole row and
+ * the pruned columns of C become whole rows): Ct = (A . (B * mask))^T from At = A^T.
+ *   At  device, K x M row-major (a row per K position, M tokens), ldat >= M, ldat % 8 == 0, 16-byte
+ *       aligned; rows are read in 16-byte pieces up to the pitch
+ *   Ct  device, N x M row-major, ldct >= M, ldct % 8 == 0, 16-byte aligned; EVERY element of
+ *       Ct[0:N, 0:M] is written, rows of pruned columns as zeros.  Fastest with 128-byte aligned rows
+ *       (base and ldct multiples of 64 elements).
+ * Everything else as tw_gemm.  TW_ERR_UNSUPPORTED when K is too large for a block of 64 tokens to stay
+ * in LDS (K above about 900): use tw_gemm there. */
+int tw_gemm_t(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat,
+              void* Ct, int ldct, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* dst[c, r] = src[r, c] for a rows x cols matrix of 16-bit elements (device pointers, row-major, ld in
+ * elements): the transposes at the two ends of a network whose layers run on the transposed boundary
+ * (Sec. VI "Kernel Fusion" counts them, unfused, at about 10 % of the latency). */
+int tw_transpose(const void* src, int ld_src, int rows, int cols, void* dst, int ld_dst, void* hip_stream);
+
 /* Dense reference C = A . B on the same MFMA pipeline (the paper's dense baseline, Sec. VI
  * "Tiling" / Sec. VII-A).  A: device M x K (lda % 8 == 0), B: device K x N row-major
  * (ldb % 8 == 0), C: device M x N (ldc % 8 == 0); bases 16-byte aligned. */

@@ -20,7 +20,8 @@ TW_F16, TW_BF16 = 0, 1
 _DT = {"f16": TW_F16, "bf16": TW_BF16}
 
 SYMBOLS = ["tw_pack_size", "tw_pack", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm",
-           "tw_gemm_bias_act", "tw_dense_gemm", "tw_dense_gemm_bias_act", "tw_strerror", "tw_version"]
+           "tw_gemm_bias_act", "tw_gemm_t", "tw_transpose", "tw_dense_gemm", "tw_dense_gemm_bias_act", "tw_strerror",
+           "tw_version"]
 TW_ACT_NONE, TW_ACT_RELU, TW_ACT_GELU = 0, 1, 2
 _ACT = {None: TW_ACT_NONE, "none": TW_ACT_NONE, "relu": TW_ACT_RELU, "gelu": TW_ACT_GELU}
 
@@ -56,6 +57,8 @@ def _load() -> ctypes.CDLL:
     lib.tw_gemm.argtypes = [vp, vp, vp, i, i, vp, i, vp, sz, vp]
     lib.tw_dense_gemm.argtypes = [vp, i, vp, i, vp, i, i, i, i, i, vp]
     lib.tw_gemm_bias_act.argtypes = [vp, vp, vp, i, i, vp, i, vp, i, vp, sz, vp]
+    lib.tw_gemm_t.argtypes = [vp, vp, vp, i, i, vp, i, vp, sz, vp]
+    lib.tw_transpose.argtypes = [vp, i, i, i, vp, i, vp]
     lib.tw_dense_gemm_bias_act.argtypes = [vp, i, vp, i, vp, i, vp, i, i, i, i, i, vp]
     lib.tw_strerror.argtypes = [i]
     lib.tw_strerror.restype = ctypes.c_char_p
@@ -210,6 +213,41 @@ def tw_gemm(w: TwWeight, A, C=None, stream=None):
                         M, lda, ctypes.c_void_p(C.data_ptr()), ldc, ctypes.c_void_p(w.workspace.data_ptr()),
                         w.workspace.numel(), _stream_ptr(stream)), "tw_gemm")
     return C
+
+
+def tw_gemm_t(w: TwWeight, At, Ct=None, stream=None):
+    """Ct = (A . (B * mask))^T from At = A^T.  At: torch tensor [K, M], Ct: [N, M] (unit column stride)."""
+    torch = _torch()
+    assert At.is_cuda and At.dtype == _tdtype(w.dtype) and At.dim() == 2 and At.stride(1) == 1
+    K, M = At.shape
+    assert K == w.info["K"]
+    N = w.info["N"]
+    if Ct is None:
+        ld = (M + 63) // 64 * 64
+        Ct = torch.empty((N, ld), dtype=At.dtype, device=At.device)[:, :M]
+    assert Ct.is_cuda and Ct.dtype == At.dtype and Ct.shape == (N, M) and Ct.stride(1) == 1
+    ldat = At.stride(0) if K > 1 else max(M, At.stride(0))
+    ldct = Ct.stride(0) if N > 1 else max(M, Ct.stride(0))
+    _check(_lib.tw_gemm_t(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()), ctypes.c_void_p(At.data_ptr()),
+                          M, ldat, ctypes.c_void_p(Ct.data_ptr()), ldct, ctypes.c_void_p(w.workspace.data_ptr()),
+                          w.workspace.numel(), _stream_ptr(stream)), "tw_gemm_t")
+    return Ct
+
+
+def tw_transpose(src, dst=None, stream=None):
+    """dst = src^T for a 2-D torch tensor of a 16-bit type (unit column stride)."""
+    torch = _torch()
+    assert src.is_cuda and src.dim() == 2 and src.stride(1) == 1 and src.element_size() == 2
+    rows, cols = src.shape
+    if dst is None:
+        ld = (rows + 63) // 64 * 64
+        dst = torch.empty((cols, ld), dtype=src.dtype, device=src.device)[:, :rows]
+    assert dst.shape == (cols, rows) and dst.dtype == src.dtype and dst.stride(1) == 1
+    lds = src.stride(0) if rows > 1 else max(cols, src.stride(0))
+    ldd = dst.stride(0) if cols > 1 else max(rows, dst.stride(0))
+    _check(_lib.tw_transpose(ctypes.c_void_p(src.data_ptr()), lds, rows, cols, ctypes.c_void_p(dst.data_ptr()), ldd,
+                             _stream_ptr(stream)), "tw_transpose")
+    return dst
 
 
 def _act_code(act) -> int:

@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define TW_MAGIC 0x31425754u /* "TWB1" */
-#define TW_FORMAT_VERSION 6
+#define TW_FORMAT_VERSION 7
 
 // MFMA step geometry the packed values are laid out for: one step contracts 16 kept rows
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
@@ -39,7 +39,10 @@ struct TwHeader {
                              //   span start; 0xFFFFFFFF for c >= w
     uint64_t off_bvals;      // 16-bit weights: per tile, per step, per column block, per lane 8 values
     uint64_t off_sched_desc; // TwSchedDesc[T], dispatch order (what the kernel walks)
-    uint8_t pad[256 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 6];
+    uint64_t off_zero_ptr;   // int32 [T+1]: per tile (canonical order), start of its list in zero_cols
+    uint64_t off_zero_cols;  // int32 []: the pruned columns inside every tile's span, ascending (the rows of
+                             //   the transposed output that the tile writes as zeros)
+    uint8_t pad[256 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 8];
 };
 static_assert(sizeof(TwHeader) == 256, "header is 256 bytes");
 

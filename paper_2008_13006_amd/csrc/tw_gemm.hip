@@ -72,7 +72,7 @@ struct TwGemmParams {
     unsigned abuf_bytes;        // size of one LDS copy of A (streamed K uses two)
     unsigned stage_off;         // LDS offset of the per-wave staging areas
     unsigned misc_off;          // LDS offset of two ints (item, tile counter)
-    uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals;
+    uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_zero_ptr, off_zero_cols;
 #ifdef TW_EXPERIMENT
     int dbg;  // bit0: no A load, bit1: no main loop, bit2: no epilogue
     unsigned* trace;  // per wave 16 clock samples
@@ -621,6 +621,101 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
     }
 }
 
+// ---- Transposed boundary (MODE 3): At is K x M, Ct is N x M (Sec. VI "Memory Accesses Coalescing") ----
+// With the activations stored transposed, a K row of the workgroup's block is 128 contiguous bytes in
+// global memory and goes to its LDS row as it is: the LDS copy needs no transposition, and skipping a
+// pruned K position skips a row, which is what the paper changes the layout for.  A tile's results are
+// rows of Ct (one per kept column), each a whole 128-byte line per block of 64 tokens: no line of
+// the output is shared between tiles, and pruned columns are whole lines of zeros.
+
+// Stages At[0:K, m0 : m0+64) into LDS (row k at k * at_pitch).  A wave instruction reads 8 rows x 128
+// bytes; pieces past the row's pitch re-read the last piece inside it (they belong to tokens >= M,
+// whose results are never stored).
+template <int BATCH>
+__device__ __forceinline__ void load_at_block(const TwGemmParams& p, unsigned char* at, int m0, int wave, int lane_in,
+                                              int tid) {
+    const int lane = fresh(lane_in);
+    const int tasks = (p.K + 7) >> 3;
+    const int pmax = (int)((p.lda - m0) >> 3) - 1;
+    const int pc = (lane & 7) < pmax ? (lane & 7) : pmax;
+    for (int t0 = wave; t0 < tasks; t0 += kWaves * BATCH) {
+        tw_u32x4 v[BATCH];
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            int k = (t0 + b * kWaves) * 8 + (lane >> 3);
+            k = k < p.K ? k : p.K - 1;
+            v[b] = *(const tw_u32x4*)(p.A + (long)k * p.lda + (m0 + pc * 8));
+        }
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const int k = (t0 + b * kWaves) * 8 + (lane >> 3);
+            const int krow = k < p.K ? k : p.k_chunk + 1 + (lane >> 3);      // absent rows: the spare rows
+            unsigned char* dst = at + (unsigned)krow * p.at_pitch + (lane & 7) * 16;
+            *(tw_u32x2*)dst = tw_u32x2{v[b].x, v[b].y};
+            *(tw_u32x2*)(dst + 8) = tw_u32x2{v[b].z, v[b].w};
+        }
+    }
+    a_zero_row(p, at, 64, tid);
+}
+
+// Epilogue of one tile, transposed output.  Column block by column block, a lane (packed column n, its
+// registers hold 4 consecutive tokens per group) writes its rounded values as 8-byte pieces into the
+// wave's staging area [32 columns][64 tokens]; the rows are read back as 16-byte pieces, 8 lanes per
+// row, and a store instruction writes whole 128-byte lines of 8 rows of Ct.  The destination row of a
+// staged row comes from the lane that owns that packed column (ds_bpermute).  The pruned columns
+// inside the tile's span are written as lines of zeros from the packer's list.
+constexpr int kStagePitchT = 136;
+static_assert(32 * kStagePitchT <= (int)kStageBytes, "transposed staging fits the wave's area");
+
+template <int DT, int NCB>
+__device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[2][NCB],
+                                             unsigned char* stage, const unsigned (&dpos)[NCB], int m0, int lane_in) {
+    const int lane = fresh(lane_in);
+    const int n = lane & 31, h = lane >> 5, r8 = lane >> 3, pc = lane & 7;
+    const int origin = d.span_start & ~7;
+    const int mleft = p.M - m0;                              // tokens of this block that exist
+    const bool whole = 8 * pc + 8 <= mleft;                  // this lane's piece lies inside
+    auto put_piece = [&](long row, tw_u32x4 v) {
+        unsigned short* dst = p.C + row * p.ldc + (m0 + 8 * pc);
+        if (whole) {
+            *(tw_u32x4*)dst = v;
+        } else {
+            const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (8 * pc + e < mleft) dst[e] = (unsigned short)(w[e >> 1] >> (16 * (e & 1)));
+        }
+    };
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+        tw_compiler_fence();
+#pragma unroll
+        for (int ms = 0; ms < 2; ++ms)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                tw_u32x2 v;
+                v.x = (unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 0]) | ((unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 1]) << 16);
+                v.y = (unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 2]) | ((unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 3]) << 16);
+                *(tw_u32x2*)(stage + n * kStagePitchT + (32 * ms + 8 * q + 4 * h) * 2) = v;
+            }
+        tw_compiler_fence();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = r8 + 8 * i;                      // staged row = packed column 32*cb + row
+            const tw_u32x2 lo = *(const tw_u32x2*)(stage + row * kStagePitchT + pc * 16);
+            const tw_u32x2 hi = *(const tw_u32x2*)(stage + row * kStagePitchT + pc * 16 + 8);
+            const unsigned dcol = (unsigned)__builtin_amdgcn_ds_bpermute(row * 4, (int)dpos[cb]);
+            if (dcol != 0xFFFFFFFFu) put_piece((long)origin + (long)dcol, tw_u32x4{lo.x, lo.y, hi.x, hi.y});
+        }
+    }
+    tw_compiler_fence();
+    // lines of zeros for the pruned columns of the span
+    const int* zp = (const int*)(p.blob + p.off_zero_ptr);
+    const int* zc = (const int*)(p.blob + p.off_zero_cols);
+    const int z0 = fetch_int(zp, d.tile), z1 = fetch_int(zp, d.tile + 1);
+    for (int j = z0 + r8; j < z1; j += 8) put_piece((long)zc[j], tw_u32x4{0u, 0u, 0u, 0u});
+}
+
 template <int MS, int NCB>
 __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 #pragma unroll
@@ -674,8 +769,9 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
         // work; the counter is touched only when there are more items than workgroups
         if (tid == 0) my_next = p.n_items > (int)gridDim.x ? (int)gridDim.x + atomicAdd(&p.counters[0], 1) : p.n_items;
 
-        if constexpr (MODE == 0) {
+        if constexpr (MODE == 0 || MODE == 3) {
             // the whole K extent of the row block stays in LDS; waves pull tiles of this item's set
+            // (MODE 3: transposed boundary, a block of 64 tokens)
             const int mb = item / p.n_seg, seg = item - mb * p.n_seg;
             const int row0 = mb * BM;
             // first tile of this wave: its descriptor is requested before A is staged
@@ -686,7 +782,10 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #ifdef TW_EXPERIMENT
             if (!(TWD(p.dbg) & 1))
 #endif
-            load_a_block<MS, 12, kPairResident>(p, smem, row0, 0, p.K, wave, lane, tid);
+            {
+                if constexpr (MODE == 3) load_at_block<12>(p, smem, row0, wave, lane, tid);
+                else load_a_block<MS, 12, kPairResident>(p, smem, row0, 0, p.K, wave, lane, tid);
+            }
             TW_MARK();
             __syncthreads();
             TW_MARK();
@@ -737,7 +836,10 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #ifdef TW_EXPERIMENT
                 if (!(TWD(p.dbg) & 4))
 #endif
-                store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                {
+                    if constexpr (MODE == 3) store_tile_t<DT, NCB>(p, d, acc, stage, dpos, row0, lane);
+                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                }
                 TW_MARK();
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
@@ -1090,7 +1192,7 @@ int device_cus(int dev) {
 }
 
 // The dynamic-LDS limit of a kernel is raised to the hardware maximum once per (device, kernel).
-constexpr int kMaxKernels = 64;
+constexpr int kMaxKernels = 72;
 std::atomic<unsigned> g_lds_set[kMaxDevices][kMaxKernels];
 
 int ensure_lds(int dev, int kernel_id, const void* fn) {
@@ -1174,11 +1276,116 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.stage_off = pl.stage_off; p.misc_off = pl.misc_off;
     p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
+    p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
 #ifdef TW_EXPERIMENT
     p.dbg = getenv("TW_DBG") ? atoi(getenv("TW_DBG")) : 0;
     p.trace = getenv("TW_TRACE_PTR") ? (unsigned*)strtoull(getenv("TW_TRACE_PTR"), nullptr, 16) : nullptr;
 #endif
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), pl.lds_bytes, stream, p);
+    return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
+namespace {
+template <int DT>
+KernelFn pick_transposed(int ncb) {
+    switch (ncb) {
+        case 1: return tw_gemm_kernel<DT, 2, 1, 3, false>;
+        case 2: return tw_gemm_kernel<DT, 2, 2, 3, false>;
+        case 4: return tw_gemm_kernel<DT, 2, 4, 3, false>;
+        default: return nullptr;
+    }
+}
+}  // namespace
+
+extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat, void* Ct,
+                         int ldct, void* workspace, size_t ws_bytes, void* hip_stream) {
+    if (!blob_host || !blob_dev || !At || !Ct || !workspace || M < 0) return TW_ERR_ARG;
+    const TwHeader* h = (const TwHeader*)blob_host;
+    if (h->magic != TW_MAGIC || h->version != TW_FORMAT_VERSION) return TW_ERR_BUF;
+    if (ws_bytes < 256) return TW_ERR_BUF;
+    if (ldat < M || ldct < M) return TW_ERR_ARG;
+    if ((ldat & 7) != 0 || (ldct & 7) != 0 || ((uintptr_t)At & 15) != 0 || ((uintptr_t)Ct & 15) != 0) return TW_ERR_ALIGN;
+    if (((uintptr_t)blob_dev & 255) != 0 || ((uintptr_t)workspace & 255) != 0) return TW_ERR_ALIGN;
+    if (M == 0) return TW_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    if (h->T == 0) {   // every row of Ct is zero
+        const long total = (long)h->N * M;
+        int blocks = (int)((total + 255) / 256);
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(tw_fill_kernel<TW_F16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)Ct, (long)ldct, h->N,
+                           M, (const unsigned short*)nullptr, 0);
+        return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
+    }
+    // the K extent of a block of 64 tokens has to fit in LDS
+    if (h->n_chunks != 1 || lds_need(2, h->k_chunk, 1) > kLdsLimit) return TW_ERR_UNSUPPORTED;
+
+    const int dev = current_device();
+    if (dev < 0) return TW_ERR_HIP;
+    const int n_cu = device_cus(dev);
+    if (n_cu <= 0) return TW_ERR_HIP;
+    const int n_mblocks = (M + 63) / 64;
+    int n_seg = 1;
+    if (n_mblocks < n_cu) n_seg = (n_cu + n_mblocks - 1) / n_mblocks;
+    if (n_seg > h->T) n_seg = h->T;
+    const long items = (long)n_mblocks * n_seg;
+    if (items > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
+    KernelFn fn = h->dtype == TW_F16 ? pick_transposed<TW_F16>(h->ncb) : pick_transposed<TW_BF16>(h->ncb);
+    if (!fn) return TW_ERR_UNSUPPORTED;
+    const int kernel_id = 60 + (h->dtype == TW_F16 ? 0 : 3) + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
+    int rc = ensure_lds(dev, kernel_id, (const void*)fn);
+    if (rc) return rc;
+
+    TwGemmParams p;
+    p.blob = (const unsigned char*)blob_dev;
+    p.A = (const unsigned short*)At;
+    p.C = (unsigned short*)Ct;
+    p.counters = (int*)workspace;
+    p.bias = nullptr; p.act = 0;
+    p.lda = ldat; p.ldc = ldct;
+    p.M = M; p.K = h->K; p.N = h->N; p.T = h->T;
+    p.k_chunk = h->k_chunk; p.n_chunks = h->n_chunks; p.G = h->G;
+    p.n_mblocks = n_mblocks; p.n_seg = n_seg; p.n_items = (int)items;
+    p.at_pitch = 64u * 2 + 8u;
+    p.abuf_bytes = at_bytes(2, h->k_chunk);
+    p.stage_off = p.abuf_bytes;
+    p.misc_off = p.stage_off + kWaves * kStageBytes;
+    p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;
+    p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
+    p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
+#ifdef TW_EXPERIMENT
+    p.dbg = getenv("TW_DBG") ? atoi(getenv("TW_DBG")) : 0;
+    p.trace = nullptr;
+#endif
+    const int grid = (int)items < n_cu ? (int)items : n_cu;
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), p.misc_off + 16u, stream, p);
+    return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
+// ---- the transposes at the two ends of a network that runs on the transposed boundary (Sec. VI) ----
+namespace {
+__global__ __launch_bounds__(256) void tw_transpose_kernel(const unsigned short* src, long lds_, int rows, int cols,
+                                                           unsigned short* dst, long ldd) {
+    // 64 x 64 tile through LDS; the pitch of 65 words keeps the column reads off one bank
+    __shared__ unsigned short tile[64][66];
+    const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4)
+        if (r0 + r < rows && c0 + tx < cols) tile[r][tx] = src[(long)(r0 + r) * lds_ + c0 + tx];
+    __syncthreads();
+    for (int c = ty; c < 64; c += 4)
+        if (c0 + c < cols && r0 + tx < rows) dst[(long)(c0 + c) * ldd + r0 + tx] = tile[tx][c];
+}
+}  // namespace
+
+extern "C" int tw_transpose(const void* src, int ld_src, int rows, int cols, void* dst, int ld_dst, void* hip_stream) {
+    if (!src || !dst || rows < 0 || cols < 0 || ld_src < cols || ld_dst < rows) return TW_ERR_ARG;
+    if (((uintptr_t)src & 1) != 0 || ((uintptr_t)dst & 1) != 0) return TW_ERR_ALIGN;
+    if (rows == 0 || cols == 0) return TW_OK;
+    const long gx = ((long)cols + 63) / 64, gy = ((long)rows + 63) / 64;
+    if (gy > 65535) return TW_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(tw_transpose_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const unsigned short*)src, (long)ld_src, rows, cols, (unsigned short*)dst, (long)ld_dst);
     return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
 }

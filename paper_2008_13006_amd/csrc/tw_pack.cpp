@@ -29,7 +29,8 @@ struct Layout {
     std::vector<int32_t> first_step;  // [T] global step index
     int64_t total_steps = 0;
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
-        off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, bytes;
+        off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, off_zero_ptr,
+        off_zero_cols, bytes;
 };
 
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -123,6 +124,12 @@ void plan(const Tiling& tl, int K, int G, Layout& lo) {
     lo.off_tile_desc = take(sizeof(TwTileDesc) * (size_t)T, 64);
     lo.off_sched_desc = take(sizeof(TwSchedDesc) * (size_t)T, 64);
     lo.off_step_ptr = take(4 * lo.step_ptr.size(), 16);
+    {
+        size_t n_zero = 0;   // pruned columns inside spans = N - kept columns (every column lies in one span)
+        if (T > 0) n_zero = (size_t)tl.tile_span[T] - tl.col_idx.size();
+        lo.off_zero_ptr = take(4 * (size_t)(T + 1), 16);
+        lo.off_zero_cols = take(4 * (n_zero + 1), 16);
+    }
     lo.off_goff = take(2 * 16 * (uint64_t)total, 256);
     lo.off_dpos = take(4 * (uint64_t)T * 32 * lo.ncb, 256);
     lo.off_bvals = take(2 * (uint64_t)total * lo.ncb * 64 * 8, 256);
@@ -190,6 +197,7 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
     h->off_tile_desc = lo.off_tile_desc; h->off_step_ptr = lo.off_step_ptr;
     h->off_goff = lo.off_goff; h->off_dpos = lo.off_dpos; h->off_bvals = lo.off_bvals;
     h->off_sched_desc = lo.off_sched_desc;
+    h->off_zero_ptr = lo.off_zero_ptr; h->off_zero_cols = lo.off_zero_cols;
 
     auto put = [&](uint64_t off, const std::vector<int32_t>& v) {
         if (!v.empty()) std::memcpy(base + off, v.data(), 4 * v.size());
@@ -200,6 +208,21 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
     put(lo.off_row_idx, tl.row_idx);
     put(lo.off_tile_span, tl.tile_span);
     put(lo.off_step_ptr, lo.step_ptr);
+
+    // pruned columns inside every span
+    {
+        std::vector<int32_t> zptr(tl.T + 1, 0), zcols;
+        for (int t = 0; t < tl.T; ++t) {
+            int c = tl.tile_col_ptr[t];
+            for (int n = tl.tile_span[t]; n < tl.tile_span[t + 1]; ++n) {
+                if (c < tl.tile_col_ptr[t + 1] && tl.col_idx[c] == n) ++c;
+                else zcols.push_back(n);
+            }
+            zptr[t + 1] = (int32_t)zcols.size();
+        }
+        put(lo.off_zero_ptr, zptr);
+        put(lo.off_zero_cols, zcols);
+    }
 
     // schedule: heaviest tile (most kept rows) first, ties keep tile order
     std::vector<int32_t> order(tl.T);

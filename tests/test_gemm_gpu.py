@@ -341,3 +341,86 @@ def test_full_size_ffn_up_with_gelu(tw):
                           tw_ref.decode(bbits, spec.dtype), "gelu")
     assert _rel_err(_to_f64(C[torch.as_tensor(rows, device="cuda:0")]), ref) <= TOL[spec.dtype]
     assert bool(torch.isfinite(C.float()).all().item())
+
+
+# ------------------------------------------------------------------ transposed boundary: Ct = (A.(B*mask))^T from At
+def _device_At(tw, A_bits, dtype):
+    """A^T on the GPU (K x M) with a row stride that is a multiple of 8 elements."""
+    M, K = A_bits.shape
+    ld = (M + 7) // 8 * 8
+    buf = torch.zeros((K, ld), dtype=torch.float16 if dtype == "f16" else torch.bfloat16, device="cuda:0")
+    buf[:, :M] = tw.bits_to_tensor(np.ascontiguousarray(A_bits.T), dtype)
+    return buf[:, :M]
+
+
+TRANSPOSED = ["tiny_one_tile", "ragged_rows_gaps", "k_not_mult_of_8", "bf16_g64", "g32_many_tiles", "one_row",
+              "several_row_blocks", "kept_one_row_each", "wide_spans", "wide_spans_bf16_g64", "thin_tiles",
+              "odd_everything"]
+
+
+@pytest.mark.parametrize("cname", TRANSPOSED)
+def test_tw_gemm_t_small_cases(tw, cname):
+    name, M, K, N, G, dtype, cp, keep = next(c for c in SMALL if c[0] == cname)
+    _say(f"tw_gemm_t small {name} M={M} K={K} N={N} G={G} {dtype}")
+    spec = W.small_spec(name, M=M, K=K, N=N, G=G, dtype=dtype, col_prune=cp, keep=keep, seed_offset=9500 + len(name))
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, G, dtype)
+    At = _device_At(tw, w.A, dtype)
+    ldct = (M + 7) // 8 * 8 + 8
+    Cbuf = torch.full((N, ldct), float("nan"), dtype=At.dtype, device="cuda:0")
+    tw.tw_gemm_t(wt, At, Cbuf[:, :M])
+    torch.cuda.synchronize()
+    ref = tw_ref.masked_gemm(w.A, w.B, w.mask, dtype)
+    got = _to_f64(Cbuf[:, :M]).T
+    assert np.isfinite(got).all(), "some element of Ct was not written"
+    err = _rel_err(got, ref)
+    _say(f"  rel err {err:.3e}")
+    assert err <= TOL[dtype]
+    pruned = np.flatnonzero(~w.mask.any(axis=0))
+    if len(pruned):
+        assert float(np.abs(got[:, pruned]).max()) == 0.0
+    assert bool(torch.isnan(Cbuf[:, M:].float()).all().item()), "wrote outside Ct"
+    ws = wt.workspace.view(torch.int32)[:2].cpu().tolist()
+    assert ws == [0, 0], "scheduler counters not reset"
+
+
+def test_tw_gemm_t_matches_tw_gemm_bit_for_bit_and_refuses_large_k(tw):
+    """Same products in the same order: the transposed path must give exactly the bits of tw_gemm."""
+    spec = W.small_spec("t_vs_plain", M=192, K=384, N=520, G=128, dtype="f16", col_prune=0.1, keep=("upow", 0.1, 0.7),
+                        seed_offset=9911)
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, spec.G, spec.dtype)
+    C = tw.tw_gemm(wt, _device_A(tw, w.A, spec.dtype))
+    Ct = tw.tw_gemm_t(wt, _device_At(tw, w.A, spec.dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(C, Ct.T.contiguous())
+    big = W.small_spec("t_big_k", M=64, K=2304, N=128, G=64, dtype="f16", keep=("const", 0.25), seed_offset=9912)
+    wb = W.generate(big)
+    wtb = tw.TwWeight.from_dense(wb.B, wb.mask, big.G, big.dtype)
+    with pytest.raises(tw.TwError):
+        tw.tw_gemm_t(wtb, _device_At(tw, wb.A, big.dtype))
+
+
+def test_tw_transpose(tw):
+    rng = np.random.default_rng(5)
+    for rows, cols in ((1, 1), (70, 130), (64, 64), (257, 33)):
+        x = torch.from_numpy(rng.integers(0, 65536, size=(rows, cols), dtype=np.int64).astype(np.int16)).to("cuda:0").view(torch.float16)
+        y = tw.tw_transpose(x)
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), x.view(torch.int16).T)
+
+
+def test_full_size_ffn_up_transposed(tw):
+    spec = W.CONFIGS["c2_bert_base_ffn_up"][0]
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, spec.G, spec.dtype)
+    At = tw.tw_transpose(_device_A(tw, w.A, spec.dtype))
+    Ct = tw.tw_gemm_t(wt, At)
+    torch.cuda.synchronize()
+    rows = _sample_rows(spec.M, n=96, seed=4)
+    ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, w.mask, spec.dtype)
+    got = _to_f64(Ct[:, torch.as_tensor(rows, device="cuda:0")]).T
+    assert _rel_err(got, ref) <= TOL[spec.dtype]
+    assert bool(torch.isfinite(Ct.float()).all().item())
+    pruned = np.flatnonzero(~w.mask.any(axis=0))
+    assert float(Ct[torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
