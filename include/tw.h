@@ -160,8 +160,7 @@ int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, const void* A,
  *   Ct  device, N x M row-major, ldct >= M, ldct % 8 == 0, 16-byte aligned; EVERY element of
  *       Ct[0:N, 0:M] is written, rows of pruned columns as zeros.  Fastest with 128-byte aligned rows
  *       (base and ldct multiples of 64 elements).
- * Everything else as tw_gemm.  TW_ERR_UNSUPPORTED when K is too large for a block of 64 tokens to stay
- * in LDS (K above about 900): use tw_gemm there. */
+ * Everything else as tw_gemm. */
 int tw_gemm_t(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat,
               void* Ct, int ldct, void* workspace, size_t ws_bytes, void* hip_stream);
 

@@ -628,50 +628,93 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
 // rows of Ct (one per kept column), each a whole 128-byte line per block of 64 tokens: no line of
 // the output is shared between tiles, and pruned columns are whole lines of zeros.
 
-// Stages At[0:K, m0 : m0+64) into LDS (row k at k * at_pitch).  A wave instruction reads 8 rows x 128
-// bytes; pieces past the row's pitch re-read the last piece inside it (they belong to tokens >= M,
-// whose results are never stored).
-template <int BATCH>
-__device__ __forceinline__ void load_at_block(const TwGemmParams& p, unsigned char* at, int m0, int wave, int lane_in,
-                                              int tid) {
-    const int lane = fresh(lane_in);
-    const int tasks = (p.K + 7) >> 3;
-    const int pmax = (int)((p.lda - m0) >> 3) - 1;
-    const int pc = (lane & 7) < pmax ? (lane & 7) : pmax;
-    for (int t0 = wave; t0 < tasks; t0 += kWaves * BATCH) {
-        tw_u32x4 v[BATCH];
-#pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            int k = (t0 + b * kWaves) * 8 + (lane >> 3);
-            k = k < p.K ? k : p.K - 1;
-            v[b] = *(const tw_u32x4*)(p.A + (long)k * p.lda + (m0 + pc * 8));
-        }
-#pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            const int k = (t0 + b * kWaves) * 8 + (lane >> 3);
-            const int krow = k < p.K ? k : p.k_chunk + 1 + (lane >> 3);      // absent rows: the spare rows
-            unsigned char* dst = at + (unsigned)krow * p.at_pitch + (lane & 7) * 16;
-            *(tw_u32x2*)dst = tw_u32x2{v[b].x, v[b].y};
-            *(tw_u32x2*)(dst + 8) = tw_u32x2{v[b].z, v[b].w};
-        }
+// Staging of At[k0 : k0+kw, m0 : m0 + 32*MS) into LDS (row k - k0 at (k - k0) * at_pitch), cut into tasks
+// of 64 / (4*MS) rows: a wave instruction reads whole rows of the block (128 bytes with MS = 2).  Pieces
+// past the row's pitch re-read the last piece inside it (they belong to tokens >= M, whose results
+// are never stored).  One request per task; absent rows go to the spare rows.
+template <int MS>
+struct AtTask {
+    int krow, pc;     // chunk-local K row, 16-byte piece of the block's row
+    bool have;
+    __device__ __forceinline__ AtTask(int t, int kw, int lane) {
+        constexpr int PPR = 4 * MS, RPI = 64 / PPR;      // pieces per row, rows per instruction
+        const int k = t * RPI + lane / PPR;
+        have = k < kw;
+        krow = have ? k : kw - 1;
+        pc = lane % PPR;
     }
-    a_zero_row(p, at, 64, tid);
+};
+template <int MS>
+__device__ __forceinline__ int at_tasks(int kw) { return (kw + 64 / (4 * MS) - 1) / (64 / (4 * MS)); }
+
+template <int MS, int BATCH>
+__device__ __forceinline__ void at_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int m0, int k0, int kw, int t0,
+                                         int lane_in, int stride = kWaves) {
+    const int lane = fresh(lane_in);
+    const int pmax = (int)((p.lda - m0) >> 3) - 1;
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+        const AtTask<MS> t(t0 + b * stride, kw, lane);
+        const int pc = t.pc < pmax ? t.pc : pmax;
+        ar.v[b] = *(const tw_u32x4*)(p.A + (long)(k0 + t.krow) * p.lda + (m0 + pc * 8));
+    }
+}
+
+template <int MS, int BATCH>
+__device__ __forceinline__ void at_commit(const TwGemmParams& p, const ARegs<BATCH>& ar, unsigned char* at, int kw, int t0,
+                                          int lane_in, int stride = kWaves) {
+    const int lane = fresh(lane_in);
+    constexpr int PPR = 4 * MS;
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+        const AtTask<MS> t(t0 + b * stride, kw, lane);
+        const int krow = t.have ? t.krow : p.k_chunk + 1 + (lane / PPR) % 8;   // absent rows: the spare rows
+        unsigned char* dst = at + (unsigned)krow * p.at_pitch + t.pc * 16;
+        *(tw_u32x2*)dst = tw_u32x2{ar.v[b].x, ar.v[b].y};
+        *(tw_u32x2*)(dst + 8) = tw_u32x2{ar.v[b].z, ar.v[b].w};
+    }
+}
+
+template <int MS, int BATCH>
+__device__ __forceinline__ void load_at_block(const TwGemmParams& p, unsigned char* at, int m0, int k0, int kw, int wave,
+                                              int lane, int tid) {
+    const int tasks = at_tasks<MS>(kw);
+    for (int t0 = wave; t0 < tasks; t0 += kWaves * BATCH) {
+        ARegs<BATCH> ar;
+        at_issue<MS, BATCH>(p, ar, m0, k0, kw, t0, lane);
+        at_commit<MS, BATCH>(p, ar, at, kw, t0, lane);
+    }
+    a_zero_row(p, at, 32 * MS, tid);
+}
+
+// The two boundaries behind one name (TRANS: transposed).
+template <int MS, int BATCH, bool TRANS>
+__device__ __forceinline__ void stage_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int r0, int k0, int kw, int t0, int lane,
+                                            int stride = kWaves) {
+    if constexpr (TRANS) at_issue<MS, BATCH>(p, ar, r0, k0, kw, t0, lane, stride);
+    else a_issue<MS, BATCH, kPairStream>(p, ar, r0, k0, kw, t0, lane, stride);
+}
+template <int MS, int BATCH, bool TRANS>
+__device__ __forceinline__ void stage_commit(const TwGemmParams& p, const ARegs<BATCH>& ar, unsigned char* at, int kw, int t0,
+                                             int lane, int stride = kWaves) {
+    if constexpr (TRANS) at_commit<MS, BATCH>(p, ar, at, kw, t0, lane, stride);
+    else a_commit<MS, BATCH, kPairStream>(p, ar, at, kw, t0, lane, stride);
 }
 
 // Epilogue of one tile, transposed output.  Column block by column block, a lane (packed column n, its
 // registers hold 4 consecutive tokens per group) writes its rounded values as 8-byte pieces into the
-// wave's staging area [32 columns][64 tokens]; the rows are read back as 16-byte pieces, 8 lanes per
-// row, and a store instruction writes whole 128-byte lines of 8 rows of Ct.  The destination row of a
-// staged row comes from the lane that owns that packed column (ds_bpermute).  The pruned columns
-// inside the tile's span are written as lines of zeros from the packer's list.
-constexpr int kStagePitchT = 136;
-static_assert(32 * kStagePitchT <= (int)kStageBytes, "transposed staging fits the wave's area");
-
-template <int DT, int NCB>
-__device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[2][NCB],
+// wave's staging area [32 columns][32*MS tokens]; the rows are read back as 16-byte pieces and a store
+// instruction writes whole rows of the block (128-byte lines with MS = 2) of 64 / (4*MS) rows of Ct.
+// The destination row of a staged row comes from the lane that owns that packed column
+// (ds_bpermute).  The pruned columns inside the tile's span are written as lines of zeros from the
+// packer's list.
+template <int DT, int MS, int NCB>
+__device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
                                              unsigned char* stage, const unsigned (&dpos)[NCB], int m0, int lane_in) {
+    constexpr int PPR = 4 * MS, RPI = 64 / PPR, PITCH = 64 * MS + 8;
+    static_assert(32 * PITCH <= (int)kStageBytes, "transposed staging fits the wave's area");
     const int lane = fresh(lane_in);
-    const int n = lane & 31, h = lane >> 5, r8 = lane >> 3, pc = lane & 7;
+    const int n = lane & 31, h = lane >> 5, rr = lane / PPR, pc = lane % PPR;
     const int origin = d.span_start & ~7;
     const int mleft = p.M - m0;                              // tokens of this block that exist
     const bool whole = 8 * pc + 8 <= mleft;                  // this lane's piece lies inside
@@ -690,20 +733,20 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
     for (int cb = 0; cb < NCB; ++cb) {
         tw_compiler_fence();
 #pragma unroll
-        for (int ms = 0; ms < 2; ++ms)
+        for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 tw_u32x2 v;
                 v.x = (unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 0]) | ((unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 1]) << 16);
                 v.y = (unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 2]) | ((unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 3]) << 16);
-                *(tw_u32x2*)(stage + n * kStagePitchT + (32 * ms + 8 * q + 4 * h) * 2) = v;
+                *(tw_u32x2*)(stage + n * PITCH + (32 * ms + 8 * q + 4 * h) * 2) = v;
             }
         tw_compiler_fence();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = r8 + 8 * i;                      // staged row = packed column 32*cb + row
-            const tw_u32x2 lo = *(const tw_u32x2*)(stage + row * kStagePitchT + pc * 16);
-            const tw_u32x2 hi = *(const tw_u32x2*)(stage + row * kStagePitchT + pc * 16 + 8);
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = rr + RPI * i;                    // staged row = packed column 32*cb + row
+            const tw_u32x2 lo = *(const tw_u32x2*)(stage + row * PITCH + pc * 16);
+            const tw_u32x2 hi = *(const tw_u32x2*)(stage + row * PITCH + pc * 16 + 8);
             const unsigned dcol = (unsigned)__builtin_amdgcn_ds_bpermute(row * 4, (int)dpos[cb]);
             if (dcol != 0xFFFFFFFFu) put_piece((long)origin + (long)dcol, tw_u32x4{lo.x, lo.y, hi.x, hi.y});
         }
@@ -713,7 +756,7 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
     const int* zp = (const int*)(p.blob + p.off_zero_ptr);
     const int* zc = (const int*)(p.blob + p.off_zero_cols);
     const int z0 = fetch_int(zp, d.tile), z1 = fetch_int(zp, d.tile + 1);
-    for (int j = z0 + r8; j < z1; j += 8) put_piece((long)zc[j], tw_u32x4{0u, 0u, 0u, 0u});
+    for (int j = z0 + rr; j < z1; j += RPI) put_piece((long)zc[j], tw_u32x4{0u, 0u, 0u, 0u});
 }
 
 template <int MS, int NCB>
@@ -731,7 +774,7 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 // MODE 2: K streamed, row block of 64 rows (MS = 2), for weights with at most four tiles: waves 0-3
 //         multiply (wave w owns tile 4*set + w), waves 4-7 do nothing but bring A into LDS, so the
 //         two kinds of work overlap instead of taking turns.
-template <int DT, int MS, int NCB, int MODE, bool FUSED>
+template <int DT, int MS, int NCB, int MODE, bool FUSED, bool TRANS>
 __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int MSB = MS;                       // 32-row blocks in the workgroup's row block
@@ -769,9 +812,9 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
         // work; the counter is touched only when there are more items than workgroups
         if (tid == 0) my_next = p.n_items > (int)gridDim.x ? (int)gridDim.x + atomicAdd(&p.counters[0], 1) : p.n_items;
 
-        if constexpr (MODE == 0 || MODE == 3) {
+        if constexpr (MODE == 0) {
             // the whole K extent of the row block stays in LDS; waves pull tiles of this item's set
-            // (MODE 3: transposed boundary, a block of 64 tokens)
+            // (TRANS: transposed boundary, the row block is a block of tokens)
             const int mb = item / p.n_seg, seg = item - mb * p.n_seg;
             const int row0 = mb * BM;
             // first tile of this wave: its descriptor is requested before A is staged
@@ -783,7 +826,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             if (!(TWD(p.dbg) & 1))
 #endif
             {
-                if constexpr (MODE == 3) load_at_block<12>(p, smem, row0, wave, lane, tid);
+                if constexpr (TRANS) load_at_block<MS, 12>(p, smem, row0, 0, p.K, wave, lane, tid);
                 else load_a_block<MS, 12, kPairResident>(p, smem, row0, 0, p.K, wave, lane, tid);
             }
             TW_MARK();
@@ -837,7 +880,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (!(TWD(p.dbg) & 4))
 #endif
                 {
-                    if constexpr (MODE == 3) store_tile_t<DT, NCB>(p, d, acc, stage, dpos, row0, lane);
+                    if constexpr (TRANS) store_tile_t<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
                     else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 }
                 TW_MARK();
@@ -875,7 +918,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                         && !(TWD(p.dbg) & 1)
 #endif
                     ) {
-                        a_issue<MSB, PB, kPairStream>(p, ar, r0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
+                        stage_issue<MSB, PB, TRANS>(p, ar, r0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
                     } else {
 #pragma unroll
                         for (int b = 0; b < PB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
@@ -887,7 +930,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                         && !(TWD(p.dbg) & 1024)
 #endif
                     )
-                        a_commit<MSB, PB, kPairStream>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), lw, lane, NLD);
+                        stage_commit<MSB, PB, TRANS>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), lw, lane, NLD);
                 };
                 // chunk j waits in register set j % 2; the loop is unrolled by two so that the sets are
                 // addressed statically.  The start of an item (chunk 0 in LDS, chunks 1 and 2 requested) was
@@ -970,7 +1013,10 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #ifdef TW_EXPERIMENT
                 if (!(TWD(p.dbg) & 4))
 #endif
-                if (active) store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                if (active) {
+                    if constexpr (TRANS) store_tile_t<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                }
             }
         } else {
             // K is streamed in chunks through two LDS buffers: the requests for chunk c+1 go out before
@@ -994,7 +1040,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             constexpr int AB = 6;    // requests per wave and chunk: 64 rows x 384 columns in 8 waves
             {
                 const int kw = p.K < p.k_chunk ? p.K : p.k_chunk;
-                load_a_block<MSB, AB, kPairStream>(p, smem, row0, 0, kw, wave, lane, tid);
+                if constexpr (TRANS) load_at_block<MSB, AB>(p, smem, row0, 0, kw, wave, lane, tid);
+                else load_a_block<MSB, AB, kPairStream>(p, smem, row0, 0, kw, wave, lane, tid);
                 a_zero_row(p, smem + p.abuf_bytes, BM, tid);
             }
             // Requests run kAhead chunks ahead of the steps: two where the registers allow it (narrow
@@ -1006,7 +1053,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             };
             auto issue_or_zero = [&](ARegs<AB>& ar, int c) {
                 if (c < p.n_chunks) {
-                    a_issue<MSB, AB, kPairStream>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
+                    stage_issue<MSB, AB, TRANS>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
                 } else {
 #pragma unroll
                     for (int b = 0; b < AB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
@@ -1025,7 +1072,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
             };
             auto commit = [&](const ARegs<AB>& ar, int c) {
-                if (c < p.n_chunks) a_commit<MSB, AB, kPairStream>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), wave, lane);
+                if (c < p.n_chunks) stage_commit<MSB, AB, TRANS>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), wave, lane);
             };
             if constexpr (kAhead == 1) {
                 __syncthreads();
@@ -1055,7 +1102,10 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     __syncthreads();
                 }
             }
-            if (active) store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+            if (active) {
+                if constexpr (TRANS) store_tile_t<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+                else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+            }
         }
     }
     };
@@ -1104,7 +1154,7 @@ unsigned lds_need(int msb, int k_chunk, int buffers) {
     return buffers * at_bytes(msb, k_chunk) + kWaves * kStageBytes + 16u;
 }
 
-int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
+int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = false) {
     const bool resident = h->n_chunks == 1;
     const int buffers = resident ? 1 : 2;
     if (lds_need(1, h->k_chunk, buffers) > kLdsLimit) return TW_ERR_UNSUPPORTED;
@@ -1126,10 +1176,11 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
     int msb = 2, tpw = kWaves;
     int nmb, nseg;
     if (lds_need(2, h->k_chunk, buffers) > kLdsLimit) msb = 1;
-    if (msb == 2) {
+    if (msb == 2 && !(transposed && !resident)) {   // (the streamed transposed kernels exist for 64 tokens only)
         // 64-row blocks halve the traffic of packed B, but only pay when they still fill the GPU
         if (items_for(2, tpw, nmb, nseg) < n_cu) msb = 1;
     }
+    if (transposed && !resident && msb != 2) return TW_ERR_UNSUPPORTED;
     pl.mode = resident ? 0 : 1;
     pl.ms = msb;
     if (!resident && msb == 2 && T <= kWaves / 2) {   // few tiles: half of the waves only load A
@@ -1150,21 +1201,29 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl) {
 
 typedef void (*KernelFn)(const TwGemmParams);
 
-template <int DT, int MS, int MODE, bool FUSED>
+template <int DT, int MS, int MODE, bool FUSED, bool TRANS>
 KernelFn pick_ncb(int ncb) {
     switch (ncb) {
-        case 1: return tw_gemm_kernel<DT, MS, 1, MODE, FUSED>;
-        case 2: return tw_gemm_kernel<DT, MS, 2, MODE, FUSED>;
-        case 4: return tw_gemm_kernel<DT, MS, 4, MODE, FUSED>;
+        case 1: return tw_gemm_kernel<DT, MS, 1, MODE, FUSED, TRANS>;
+        case 2: return tw_gemm_kernel<DT, MS, 2, MODE, FUSED, TRANS>;
+        case 4: return tw_gemm_kernel<DT, MS, 4, MODE, FUSED, TRANS>;
         default: return nullptr;
     }
 }
 
 template <int DT, bool FUSED>
 KernelFn pick_mode(int mode, int ms, int ncb) {
-    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED>(ncb) : pick_ncb<DT, 1, 0, FUSED>(ncb);
-    if (mode == 1) return ms == 2 ? pick_ncb<DT, 2, 1, FUSED>(ncb) : pick_ncb<DT, 1, 1, FUSED>(ncb);
-    return pick_ncb<DT, 2, 2, FUSED>(ncb);
+    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, false>(ncb) : pick_ncb<DT, 1, 0, FUSED, false>(ncb);
+    if (mode == 1) return ms == 2 ? pick_ncb<DT, 2, 1, FUSED, false>(ncb) : pick_ncb<DT, 1, 1, FUSED, false>(ncb);
+    return pick_ncb<DT, 2, 2, FUSED, false>(ncb);
+}
+
+// transposed boundary: resident K with blocks of 64 or 32 tokens, streamed K always with 64
+template <int DT>
+KernelFn pick_mode_t(int mode, int ms, int ncb) {
+    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, false, true>(ncb) : pick_ncb<DT, 1, 0, false, true>(ncb);
+    if (mode == 1) return pick_ncb<DT, 2, 1, false, true>(ncb);
+    return pick_ncb<DT, 2, 2, false, true>(ncb);
 }
 
 KernelFn pick_kernel(int dt, int mode, int ms, int ncb, bool fused) {
@@ -1192,7 +1251,7 @@ int device_cus(int dev) {
 }
 
 // The dynamic-LDS limit of a kernel is raised to the hardware maximum once per (device, kernel).
-constexpr int kMaxKernels = 72;
+constexpr int kMaxKernels = 96;
 std::atomic<unsigned> g_lds_set[kMaxDevices][kMaxKernels];
 
 int ensure_lds(int dev, int kernel_id, const void* fn) {
@@ -1286,18 +1345,6 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 
-namespace {
-template <int DT>
-KernelFn pick_transposed(int ncb) {
-    switch (ncb) {
-        case 1: return tw_gemm_kernel<DT, 2, 1, 3, false>;
-        case 2: return tw_gemm_kernel<DT, 2, 2, 3, false>;
-        case 4: return tw_gemm_kernel<DT, 2, 4, 3, false>;
-        default: return nullptr;
-    }
-}
-}  // namespace
-
 extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat, void* Ct,
                          int ldct, void* workspace, size_t ws_bytes, void* hip_stream) {
     if (!blob_host || !blob_dev || !At || !Ct || !workspace || M < 0) return TW_ERR_ARG;
@@ -1318,23 +1365,19 @@ extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void
                            M, (const unsigned short*)nullptr, 0);
         return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
     }
-    // the K extent of a block of 64 tokens has to fit in LDS
-    if (h->n_chunks != 1 || lds_need(2, h->k_chunk, 1) > kLdsLimit) return TW_ERR_UNSUPPORTED;
 
     const int dev = current_device();
     if (dev < 0) return TW_ERR_HIP;
     const int n_cu = device_cus(dev);
     if (n_cu <= 0) return TW_ERR_HIP;
-    const int n_mblocks = (M + 63) / 64;
-    int n_seg = 1;
-    if (n_mblocks < n_cu) n_seg = (n_cu + n_mblocks - 1) / n_mblocks;
-    if (n_seg > h->T) n_seg = h->T;
-    const long items = (long)n_mblocks * n_seg;
-    if (items > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
-    KernelFn fn = h->dtype == TW_F16 ? pick_transposed<TW_F16>(h->ncb) : pick_transposed<TW_BF16>(h->ncb);
+    Plan pl;
+    int rc = make_plan(h, M, n_cu, pl, /*transposed=*/true);
+    if (rc) return rc;
+    KernelFn fn = h->dtype == TW_F16 ? pick_mode_t<TW_F16>(pl.mode, pl.ms, h->ncb) : pick_mode_t<TW_BF16>(pl.mode, pl.ms, h->ncb);
     if (!fn) return TW_ERR_UNSUPPORTED;
-    const int kernel_id = 60 + (h->dtype == TW_F16 ? 0 : 3) + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
-    int rc = ensure_lds(dev, kernel_id, (const void*)fn);
+    const int variant = pl.mode == 0 ? (pl.ms == 2 ? 0 : 1) : pl.mode + 1;          // 0..3
+    const int kernel_id = 60 + (h->dtype == TW_F16 ? 0 : 12) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
+    rc = ensure_lds(dev, kernel_id, (const void*)fn);
     if (rc) return rc;
 
     TwGemmParams p;
@@ -1346,11 +1389,9 @@ extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void
     p.lda = ldat; p.ldc = ldct;
     p.M = M; p.K = h->K; p.N = h->N; p.T = h->T;
     p.k_chunk = h->k_chunk; p.n_chunks = h->n_chunks; p.G = h->G;
-    p.n_mblocks = n_mblocks; p.n_seg = n_seg; p.n_items = (int)items;
-    p.at_pitch = 64u * 2 + 8u;
-    p.abuf_bytes = at_bytes(2, h->k_chunk);
-    p.stage_off = p.abuf_bytes;
-    p.misc_off = p.stage_off + kWaves * kStageBytes;
+    p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items;
+    p.at_pitch = pl.at_pitch; p.abuf_bytes = pl.abuf_bytes;
+    p.stage_off = pl.stage_off; p.misc_off = pl.misc_off;
     p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
@@ -1358,8 +1399,8 @@ extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void
     p.dbg = getenv("TW_DBG") ? atoi(getenv("TW_DBG")) : 0;
     p.trace = nullptr;
 #endif
-    const int grid = (int)items < n_cu ? (int)items : n_cu;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), p.misc_off + 16u, stream, p);
+    const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), pl.lds_bytes, stream, p);
     return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 
