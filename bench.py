@@ -29,7 +29,8 @@ MFMA_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA
 # HBM bytes per tw_gemm launch on this workload, from the two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) summarised in profiles/tw_gemm_c2_hbm_traffic.txt, each scaled by what the same counter
 # reads for the copy kernel of known size that `--pmc-calibration` launches.
-MEASURED_TRAFFIC_BYTES = 149_773_378      # 36.02 MB read + 113.75 MB written
+MEASURED_TRAFFIC_BYTES = 149_663_912      # 36.04 MB read + 113.63 MB written
+MEASURED_TRAFFIC_BYTES_T = 136_396_268    # tw_gemm_t: 35.73 MB read + 100.66 MB written (profiles/tw_gemm_t_c2_hbm_traffic.txt)
 PAPER_CONTEXT = {"tw128_speedup_vs_dense_75pct": 2.26, "hardware": "NVIDIA V100 tensor cores, FP16",
                  "where": "Sec. VII-B, Fig. 8b"}
 
@@ -93,9 +94,14 @@ def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = T
     if with_warm:     # same buffers every launch: A and part of C stay in the last-level cache
         warm_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wt, As[0], Cs[0]), 1, steps, warmup)
     med_ms, min_ms = per_launch_stats(torch, lambda i: tw.tw_gemm(wt, As[i], Cs[i]), n_sets, min(steps, 50))
+    # the same product on the transposed boundary (At in, Ct out): same algorithmic bytes
+    Ats = [tw.tw_transpose(a).contiguous() for a in As]
+    Cts = [torch.empty((spec.N, M), dtype=td, device="cuda:0") for _ in range(n_sets)]
+    t_ms, _ = time_launches(torch, lambda i: tw.tw_gemm_t(wt, Ats[i], Cts[i]), n_sets, steps, warmup)
+    del Ats, Cts
     out = dict(name=spec.name, M=M, K=spec.K, N=spec.N, G=spec.G, dtype=spec.dtype, T=int(info["T"]),
                sparsity=w.info["sparsity"], tw_ms=cold_ms, tw_ms_warm=warm_ms, tw_ms_median=med_ms,
-               tw_ms_min=min_ms, tw_wall_ms=cold_wall, pack_ms=pack_ms, n_buffer_sets=n_sets)
+               tw_ms_min=min_ms, tw_wall_ms=cold_wall, pack_ms=pack_ms, n_buffer_sets=n_sets, tw_t_ms=t_ms)
     nz_flops = W.nonzero_flops(w.mask, M)
     dense_flops = 2.0 * M * spec.K * spec.N
     abytes = algorithmic_bytes(info, M)
@@ -103,7 +109,9 @@ def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = T
                tw_mfma_frac_nonzero=nz_flops / (cold_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                padded_mfma_frac=2.0 * M * int(info["padded_macs_per_row"]) / (cold_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                algorithmic_bytes=abytes, tw_gbs=abytes / (cold_ms * 1e-3) / 1e9,
-               tw_hbm_frac=abytes / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS)
+               tw_hbm_frac=abytes / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               tw_t_gbs=abytes / (t_ms * 1e-3) / 1e9, tw_t_hbm_frac=abytes / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               tw_t_tflops_nonzero=nz_flops / (t_ms * 1e-3) / 1e12)
     if with_dense:
         d_ms, _ = time_launches(torch, lambda i: tw.tw_dense_gemm(As[i], Bd, Cs[i]), n_sets, steps, warmup)
         out.update(dense_ms=d_ms, dense_tflops=dense_flops / (d_ms * 1e-3) / 1e12,
@@ -134,7 +142,7 @@ def cpu_baseline(W, w, spec, budget_s: float = 15.0):
                       f"scaled to all rows"}
 
 
-def pmc_calibration(torch, tw, W, spec, steps: int) -> int:
+def pmc_calibration(torch, tw, W, spec, steps: int, transposed: bool = False) -> int:
     """What a hardware-counter run profiles: a plain copy kernel that reads and writes COPY_BYTES each
     (an elementwise pass over int32, larger than the last-level cache), then `steps` tw_gemm launches
     over rotating buffers.  The copy's known size turns counter units into bytes."""
@@ -151,8 +159,15 @@ def pmc_calibration(torch, tw, W, spec, steps: int) -> int:
     A0 = tw.bits_to_tensor(w.A, spec.dtype)
     As = [A0] + [A0.clone() for _ in range(n_sets - 1)]
     Cs = [torch.empty((spec.M, spec.N), dtype=td, device="cuda:0") for _ in range(n_sets)]
-    for i in range(steps):
-        tw.tw_gemm(wt, As[i % n_sets], Cs[i % n_sets])
+    if transposed:
+        Ats = [tw.tw_transpose(a).contiguous() for a in As]
+        Cts = [torch.empty((spec.N, spec.M), dtype=td, device="cuda:0") for _ in range(n_sets)]
+        torch.cuda.synchronize()
+        for i in range(steps):
+            tw.tw_gemm_t(wt, Ats[i % n_sets], Cts[i % n_sets])
+    else:
+        for i in range(steps):
+            tw.tw_gemm(wt, As[i % n_sets], Cs[i % n_sets])
     torch.cuda.synchronize()
     print(json.dumps({"pmc_calibration": {"copy_kernel_reads_bytes": COPY_BYTES, "copy_kernel_writes_bytes": COPY_BYTES,
                                           "copy_launches": 5, "tw_gemm_launches": steps,
@@ -169,6 +184,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", type=str, default=None,
                     help="also run the sparsity x G sweep on the FFN-up shape, write a table (JSON) here")
+    ap.add_argument("--transposed", action="store_true", help="with --pmc-calibration: launch tw_gemm_t instead of tw_gemm")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="counter runs: launch only a copy kernel of known size, then the tw_gemm steps")
     args = ap.parse_args()
@@ -185,7 +201,7 @@ def main() -> int:
 
     spec = W.CONFIGS["c2_bert_base_ffn_up"][0]
     if args.pmc_calibration:
-        return pmc_calibration(torch, tw, W, spec, args.steps)
+        return pmc_calibration(torch, tw, W, spec, args.steps, args.transposed)
     res, w, info = bench_gemm(torch, tw, W, spec, args.steps, args.warmup)
     line = {
         "metric": "tw_gemm_ms (TW-sparse GEMM time, BERT-base FFN-up, 75% tile-wise sparsity)",
@@ -205,6 +221,13 @@ def main() -> int:
                      "frac": res["tw_hbm_frac"], "traffic": MEASURED_TRAFFIC_BYTES,
                      "kernel": "tw_gemm_kernel<f16, MS=2 (64 rows), NCB=4 (G=128), MODE 0 (K resident)>",
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"]},
+        # the same GEMM through tw_gemm_t (activations and result transposed, the paper's layout): not `value`
+        "transposed_boundary": {"tw_gemm_t_ms": res["tw_t_ms"], "speedup_vs_dense": res["dense_ms"] / res["tw_t_ms"],
+                                "tflops_nonzero": res["tw_t_tflops_nonzero"],
+                                "roofline": {"bound": "hbm", "achieved": res["tw_t_gbs"], "peak": HBM_PEAK_GBS,
+                                             "unit": "GB/s", "frac": res["tw_t_hbm_frac"],
+                                             "traffic": MEASURED_TRAFFIC_BYTES_T,
+                                             "kernel": "tw_gemm_kernel<f16, MS=2 (64 tokens), NCB=4, MODE 0, transposed>"}},
         "paper_context": PAPER_CONTEXT,
     }
     if not args.no_cpu_baseline:
@@ -216,7 +239,8 @@ def main() -> int:
                 r, _, _ = bench_gemm(torch, tw, W, s, max(20, args.steps // 4), 5, with_warm=True)
                 r["config"] = cfg
                 rows.append(r)
-                print(f"[report] {cfg}/{s.name}: tw {r['tw_ms']*1e3:.1f} us  dense {r['dense_ms']*1e3:.1f} us  "
+                print(f"[report] {cfg}/{s.name}: tw {r['tw_ms']*1e3:.1f} us  tw_t {r['tw_t_ms']*1e3:.1f} us  "
+                      f"dense {r['dense_ms']*1e3:.1f} us  "
                       f"x{r['speedup_vs_dense']:.2f}  nz {r['tw_tflops_nonzero']:.0f} TF  {r['tw_gbs']:.0f} GB/s",
                       file=sys.stderr, flush=True)
                 torch.cuda.empty_cache()
