@@ -164,6 +164,12 @@ int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, const void* A,
 int tw_gemm_t(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat,
               void* Ct, int ldct, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* Ct = act(A . (B * mask) + bias)^T: tw_gemm_t with the fused epilogue of tw_gemm_bias_act (bias: N elements,
+ * one per ROW of Ct; a pruned column's row holds act(bias[n]) for every token). */
+int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat,
+                       const void* bias, tw_act act, void* Ct, int ldct, void* workspace, size_t ws_bytes,
+                       void* hip_stream);
+
 /* dst[c, r] = src[r, c] for a rows x cols matrix of 16-bit elements (device pointers, row-major, ld in
  * elements): the transposes at the two ends of a network whose layers run on the transposed boundary
  * (Sec. VI "Kernel Fusion" counts them, unfused, at about 10 % of the latency). */

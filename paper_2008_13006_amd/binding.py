@@ -20,7 +20,7 @@ TW_F16, TW_BF16 = 0, 1
 _DT = {"f16": TW_F16, "bf16": TW_BF16}
 
 SYMBOLS = ["tw_pack_size", "tw_pack", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm",
-           "tw_gemm_bias_act", "tw_gemm_t", "tw_transpose", "tw_dense_gemm", "tw_dense_gemm_bias_act", "tw_strerror",
+           "tw_gemm_bias_act", "tw_gemm_t", "tw_gemm_t_bias_act", "tw_transpose", "tw_dense_gemm", "tw_dense_gemm_bias_act", "tw_strerror",
            "tw_version"]
 TW_ACT_NONE, TW_ACT_RELU, TW_ACT_GELU = 0, 1, 2
 _ACT = {None: TW_ACT_NONE, "none": TW_ACT_NONE, "relu": TW_ACT_RELU, "gelu": TW_ACT_GELU}
@@ -58,6 +58,7 @@ def _load() -> ctypes.CDLL:
     lib.tw_dense_gemm.argtypes = [vp, i, vp, i, vp, i, i, i, i, i, vp]
     lib.tw_gemm_bias_act.argtypes = [vp, vp, vp, i, i, vp, i, vp, i, vp, sz, vp]
     lib.tw_gemm_t.argtypes = [vp, vp, vp, i, i, vp, i, vp, sz, vp]
+    lib.tw_gemm_t_bias_act.argtypes = [vp, vp, vp, i, i, vp, i, vp, i, vp, sz, vp]
     lib.tw_transpose.argtypes = [vp, i, i, i, vp, i, vp]
     lib.tw_dense_gemm_bias_act.argtypes = [vp, i, vp, i, vp, i, vp, i, i, i, i, i, vp]
     lib.tw_strerror.argtypes = [i]
@@ -217,6 +218,11 @@ def tw_gemm(w: TwWeight, A, C=None, stream=None):
 
 def tw_gemm_t(w: TwWeight, At, Ct=None, stream=None):
     """Ct = (A . (B * mask))^T from At = A^T.  At: torch tensor [K, M], Ct: [N, M] (unit column stride)."""
+    return tw_gemm_t_bias_act(w, At, None, "none", Ct, stream)
+
+
+def tw_gemm_t_bias_act(w: TwWeight, At, bias=None, act="none", Ct=None, stream=None):
+    """Ct = act(A . (B * mask) + bias)^T from At = A^T; bias: torch tensor [N] or None."""
     torch = _torch()
     assert At.is_cuda and At.dtype == _tdtype(w.dtype) and At.dim() == 2 and At.stride(1) == 1
     K, M = At.shape
@@ -228,9 +234,19 @@ def tw_gemm_t(w: TwWeight, At, Ct=None, stream=None):
     assert Ct.is_cuda and Ct.dtype == At.dtype and Ct.shape == (N, M) and Ct.stride(1) == 1
     ldat = At.stride(0) if K > 1 else max(M, At.stride(0))
     ldct = Ct.stride(0) if N > 1 else max(M, Ct.stride(0))
-    _check(_lib.tw_gemm_t(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()), ctypes.c_void_p(At.data_ptr()),
-                          M, ldat, ctypes.c_void_p(Ct.data_ptr()), ldct, ctypes.c_void_p(w.workspace.data_ptr()),
-                          w.workspace.numel(), _stream_ptr(stream)), "tw_gemm_t")
+    bptr = ctypes.c_void_p(0)
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == At.dtype and bias.shape == (N,) and bias.stride(0) == 1
+        bptr = ctypes.c_void_p(bias.data_ptr())
+    if bias is None and _act_code(act) == TW_ACT_NONE:
+        _check(_lib.tw_gemm_t(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()), ctypes.c_void_p(At.data_ptr()),
+                              M, ldat, ctypes.c_void_p(Ct.data_ptr()), ldct, ctypes.c_void_p(w.workspace.data_ptr()),
+                              w.workspace.numel(), _stream_ptr(stream)), "tw_gemm_t")
+    else:
+        _check(_lib.tw_gemm_t_bias_act(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()),
+                                       ctypes.c_void_p(At.data_ptr()), M, ldat, bptr, _act_code(act),
+                                       ctypes.c_void_p(Ct.data_ptr()), ldct, ctypes.c_void_p(w.workspace.data_ptr()),
+                                       w.workspace.numel(), _stream_ptr(stream)), "tw_gemm_t_bias_act")
     return Ct
 
 

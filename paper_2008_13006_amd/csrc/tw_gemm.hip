@@ -51,7 +51,13 @@ constexpr int kThreads = kWaves * 64;
 #define TW_PAIR_STREAM 0
 #endif
 constexpr bool kPairResident = TW_PAIR_RESIDENT != 0, kPairStream = TW_PAIR_STREAM != 0;
-constexpr int kPrefetch = 3;  // B-operand steps in flight per wave
+// B-operand steps in flight per wave: three; six for narrow tiles (at most two column blocks), whose steps
+// are too short for three to cover the latency of an L2 hit and whose registers allow it
+#ifndef TW_PREFETCH_NARROW
+#define TW_PREFETCH_NARROW 6
+#endif
+template <int NCB>
+constexpr int prefetch_depth() { return NCB <= 2 ? TW_PREFETCH_NARROW : 3; }
 constexpr int kIdxAhead = 6;  // steps the K indices are requested ahead (they feed the LDS gather, which itself
                               // runs one step ahead of the MFMAs)
 
@@ -262,7 +268,7 @@ __device__ __forceinline__ void load_a_block(const TwGemmParams& p, unsigned cha
 // kIdxAhead steps.
 template <int NCB>
 struct StepRegs {
-    tw_u16x8 bq[kPrefetch][NCB];
+    tw_u16x8 bq[prefetch_depth<NCB>()][NCB];
     unsigned kk[kIdxAhead];
 };
 
@@ -293,7 +299,7 @@ __device__ __forceinline__ void prefetch_first_steps(StepRegs<NCB>& rg, const un
 #pragma unroll
     for (int i = 0; i < kIdxAhead; ++i) issue_k<NCB>(rg, i, gk, s0 + i, s1 - 1);
 #pragma unroll
-    for (int i = 0; i < kPrefetch; ++i) issue_b<NCB>(rg, i, bl, s0 + i, s1 - 1);
+    for (int i = 0; i < prefetch_depth<NCB>(); ++i) issue_b<NCB>(rg, i, bl, s0 + i, s1 - 1);
 }
 
 // Steps [s0, s1) (not empty) of one tile for this wave: gather A from LDS, stream packed B from global, MFMA.
@@ -335,6 +341,7 @@ __device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], StepRegs<NC
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms) a[1][ms] = tw_u16x8{0, 0, 0, 0, 0, 0, 0, 0};
     gather(a[0], rg.kk[0]);
+    constexpr int kPrefetch = prefetch_depth<NCB>();
     constexpr int kUnroll = 6;                      // a multiple of 2, kPrefetch and kIdxAhead
     static_assert(kUnroll % 2 == 0 && kUnroll % kPrefetch == 0 && kUnroll % kIdxAhead == 0, "unroll factor");
     auto step = [&](int i, int s) {
@@ -708,12 +715,20 @@ __device__ __forceinline__ void stage_commit(const TwGemmParams& p, const ARegs<
 // The destination row of a staged row comes from the lane that owns that packed column
 // (ds_bpermute).  The pruned columns inside the tile's span are written as lines of zeros from the
 // packer's list.
-template <int DT, int MS, int NCB>
+template <int DT, int MS, int NCB, bool FUSED>
 __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
                                              unsigned char* stage, const unsigned (&dpos)[NCB], int m0, int lane_in) {
     constexpr int PPR = 4 * MS, RPI = 64 / PPR, PITCH = 64 * MS + 8;
     static_assert(32 * PITCH <= (int)kStageBytes, "transposed staging fits the wave's area");
     const int lane = fresh(lane_in);
+    if constexpr (FUSED) {   // bias of this lane's packed columns (rows of Ct), activation in place
+        EpiBias<NCB> eb;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+            eb.col[cb] = (p.bias != nullptr && dpos[cb] != 0xFFFFFFFFu)
+                             ? tw_to_f32<DT>(p.bias[(d.span_start & ~7) + (int)dpos[cb]]) : 0.f;
+        apply_bias_act<MS, NCB>(acc, eb, p.act);
+    }
     const int n = lane & 31, h = lane >> 5, rr = lane / PPR, pc = lane % PPR;
     const int origin = d.span_start & ~7;
     const int mleft = p.M - m0;                              // tokens of this block that exist
@@ -756,7 +771,15 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
     const int* zp = (const int*)(p.blob + p.off_zero_ptr);
     const int* zc = (const int*)(p.blob + p.off_zero_cols);
     const int z0 = fetch_int(zp, d.tile), z1 = fetch_int(zp, d.tile + 1);
-    for (int j = z0 + rr; j < z1; j += RPI) put_piece((long)zc[j], tw_u32x4{0u, 0u, 0u, 0u});
+    for (int j = z0 + rr; j < z1; j += RPI) {
+        const int col = zc[j];
+        unsigned v = 0u;
+        if constexpr (FUSED) {   // a pruned column holds act(bias) for every token
+            const unsigned hv = tw_cvt<DT>(tw_activate(p.bias != nullptr ? tw_to_f32<DT>(p.bias[col]) : 0.f, p.act));
+            v = hv | (hv << 16);
+        }
+        put_piece((long)col, tw_u32x4{v, v, v, v});
+    }
 }
 
 template <int MS, int NCB>
@@ -880,7 +903,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (!(TWD(p.dbg) & 4))
 #endif
                 {
-                    if constexpr (TRANS) store_tile_t<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+                    if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                     else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 }
                 TW_MARK();
@@ -983,7 +1006,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #pragma unroll
                         for (int i = 0; i < kIdxAhead; ++i) rg.kk[i] = 0u;
 #pragma unroll
-                        for (int i = 0; i < kPrefetch; ++i)
+                        for (int i = 0; i < prefetch_depth<NCB>(); ++i)
 #pragma unroll
                             for (int cb = 0; cb < NCB; ++cb) rg.bq[i][cb] = tw_u16x8{0, 0, 0, 0, 0, 0, 0, 0};
                     }
@@ -1014,7 +1037,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (!(TWD(p.dbg) & 4))
 #endif
                 if (active) {
-                    if constexpr (TRANS) store_tile_t<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+                    if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                     else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 }
             }
@@ -1103,7 +1126,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 }
             }
             if (active) {
-                if constexpr (TRANS) store_tile_t<DT, MS, NCB>(p, d, acc, stage, dpos, row0, lane);
+                if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
             }
         }
@@ -1134,6 +1157,17 @@ __global__ void tw_fill_kernel(unsigned short* C, long ldc, int M, int N, const 
     for (long i = n; i < total; i += (long)gridDim.x * blockDim.x) {
         const long col = i % N;
         C[(i / N) * ldc + col] = bias ? tw_cvt<DT>(tw_activate(tw_to_f32<DT>(bias[col]), act)) : (unsigned short)0;
+    }
+}
+
+// Ct[n, m] = act(bias[n]) (zero without a bias): the transposed output of a weight with no surviving column.
+template <int DT>
+__global__ void tw_fill_rows_kernel(unsigned short* Ct, long ldct, int N, int M, const unsigned short* bias, int act) {
+    const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long total = (long)N * M;
+    for (long i = t; i < total; i += (long)gridDim.x * blockDim.x) {
+        const long n = i / M;
+        Ct[n * ldct + (i % M)] = bias ? tw_cvt<DT>(tw_activate(tw_to_f32<DT>(bias[n]), act)) : (unsigned short)0;
     }
 }
 
@@ -1219,11 +1253,15 @@ KernelFn pick_mode(int mode, int ms, int ncb) {
 }
 
 // transposed boundary: resident K with blocks of 64 or 32 tokens, streamed K always with 64
-template <int DT>
+template <int DT, bool FUSED>
 KernelFn pick_mode_t(int mode, int ms, int ncb) {
-    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, false, true>(ncb) : pick_ncb<DT, 1, 0, false, true>(ncb);
-    if (mode == 1) return pick_ncb<DT, 2, 1, false, true>(ncb);
-    return pick_ncb<DT, 2, 2, false, true>(ncb);
+    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, true>(ncb) : pick_ncb<DT, 1, 0, FUSED, true>(ncb);
+    if (mode == 1) return pick_ncb<DT, 2, 1, FUSED, true>(ncb);
+    return pick_ncb<DT, 2, 2, FUSED, true>(ncb);
+}
+KernelFn pick_kernel_t(int dt, int mode, int ms, int ncb, bool fused) {
+    if (fused) return dt == TW_F16 ? pick_mode_t<TW_F16, true>(mode, ms, ncb) : pick_mode_t<TW_BF16, true>(mode, ms, ncb);
+    return dt == TW_F16 ? pick_mode_t<TW_F16, false>(mode, ms, ncb) : pick_mode_t<TW_BF16, false>(mode, ms, ncb);
 }
 
 KernelFn pick_kernel(int dt, int mode, int ms, int ncb, bool fused) {
@@ -1251,7 +1289,7 @@ int device_cus(int dev) {
 }
 
 // The dynamic-LDS limit of a kernel is raised to the hardware maximum once per (device, kernel).
-constexpr int kMaxKernels = 96;
+constexpr int kMaxKernels = 128;
 std::atomic<unsigned> g_lds_set[kMaxDevices][kMaxKernels];
 
 int ensure_lds(int dev, int kernel_id, const void* fn) {
@@ -1347,7 +1385,17 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
 
 extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat, void* Ct,
                          int ldct, void* workspace, size_t ws_bytes, void* hip_stream) {
+    return tw_gemm_t_bias_act(blob_host, blob_dev, At, M, ldat, nullptr, TW_ACT_NONE, Ct, ldct, workspace, ws_bytes,
+                              hip_stream);
+}
+
+extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat,
+                                  const void* bias, tw_act act, void* Ct, int ldct, void* workspace, size_t ws_bytes,
+                                  void* hip_stream) {
     if (!blob_host || !blob_dev || !At || !Ct || !workspace || M < 0) return TW_ERR_ARG;
+    if (act != TW_ACT_NONE && act != TW_ACT_RELU && act != TW_ACT_GELU) return TW_ERR_ARG;
+    if (((uintptr_t)bias & 1) != 0) return TW_ERR_ALIGN;
+    const bool fused = bias != nullptr || act != TW_ACT_NONE;
     const TwHeader* h = (const TwHeader*)blob_host;
     if (h->magic != TW_MAGIC || h->version != TW_FORMAT_VERSION) return TW_ERR_BUF;
     if (ws_bytes < 256) return TW_ERR_BUF;
@@ -1361,8 +1409,12 @@ extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void
         const long total = (long)h->N * M;
         int blocks = (int)((total + 255) / 256);
         if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(tw_fill_kernel<TW_F16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)Ct, (long)ldct, h->N,
-                           M, (const unsigned short*)nullptr, 0);
+        if (h->dtype == TW_F16)
+            hipLaunchKernelGGL(tw_fill_rows_kernel<TW_F16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)Ct, (long)ldct,
+                               h->N, M, (const unsigned short*)bias, (int)act);
+        else
+            hipLaunchKernelGGL(tw_fill_rows_kernel<TW_BF16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)Ct, (long)ldct,
+                               h->N, M, (const unsigned short*)bias, (int)act);
         return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
     }
 
@@ -1373,10 +1425,10 @@ extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void
     Plan pl;
     int rc = make_plan(h, M, n_cu, pl, /*transposed=*/true);
     if (rc) return rc;
-    KernelFn fn = h->dtype == TW_F16 ? pick_mode_t<TW_F16>(pl.mode, pl.ms, h->ncb) : pick_mode_t<TW_BF16>(pl.mode, pl.ms, h->ncb);
+    KernelFn fn = pick_kernel_t(h->dtype, pl.mode, pl.ms, h->ncb, fused);
     if (!fn) return TW_ERR_UNSUPPORTED;
     const int variant = pl.mode == 0 ? (pl.ms == 2 ? 0 : 1) : pl.mode + 1;          // 0..3
-    const int kernel_id = 60 + (h->dtype == TW_F16 ? 0 : 12) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
+    const int kernel_id = 60 + (fused ? 24 : 0) + (h->dtype == TW_F16 ? 0 : 12) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, (const void*)fn);
     if (rc) return rc;
 
@@ -1385,7 +1437,7 @@ extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void
     p.A = (const unsigned short*)At;
     p.C = (unsigned short*)Ct;
     p.counters = (int*)workspace;
-    p.bias = nullptr; p.act = 0;
+    p.bias = (const unsigned short*)bias; p.act = (int)act;
     p.lda = ldat; p.ldc = ldct;
     p.M = M; p.K = h->K; p.N = h->N; p.T = h->T;
     p.k_chunk = h->k_chunk; p.n_chunks = h->n_chunks; p.G = h->G;

@@ -423,3 +423,33 @@ def test_full_size_ffn_up_transposed(tw):
     assert bool(torch.isfinite(Ct.float()).all().item())
     pruned = np.flatnonzero(~w.mask.any(axis=0))
     assert float(Ct[torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
+
+
+FUSED_T = [("ragged_rows_gaps", True, "gelu"), ("bf16_g64", True, "relu"), ("wide_spans", True, "gelu"),
+           ("t_k1024", True, "gelu"), ("t_stream_8tiles", True, "relu"), ("t_stream_3tiles", False, "gelu"),
+           ("thin_tiles", True, "none")]
+
+
+@pytest.mark.parametrize("case", FUSED_T, ids=[f"{c[0]}-{'bias' if c[1] else 'nobias'}-{c[2]}" for c in FUSED_T])
+def test_tw_gemm_t_bias_act(tw, case):
+    cname, with_bias, act = case
+    name, M, K, N, G, dtype, cp, keep = next(c for c in SMALL_T if c[0] == cname)
+    _say(f"tw_gemm_t_bias_act {name} bias={with_bias} act={act}")
+    spec = W.small_spec(name, M=M, K=K, N=N, G=G, dtype=dtype, col_prune=cp, keep=keep, seed_offset=9500 + len(name))
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, G, dtype)
+    At = _device_At(tw, w.A, dtype)
+    bbits = _bias_bits(N, dtype, 78 + N) if with_bias else None
+    bias = tw.bits_to_tensor(bbits, dtype) if with_bias else None
+    ldct = (M + 7) // 8 * 8
+    Cbuf = torch.full((N, ldct + 8), float("nan"), dtype=At.dtype, device="cuda:0")
+    tw.tw_gemm_t_bias_act(wt, At, bias, act, Cbuf[:, :M])
+    torch.cuda.synchronize()
+    ref = tw_ref.bias_act(tw_ref.masked_gemm(w.A, w.B, w.mask, dtype),
+                          tw_ref.decode(bbits, dtype) if with_bias else None, act)
+    got = _to_f64(Cbuf[:, :M]).T
+    assert np.isfinite(got).all(), "some element of Ct was not written"
+    err = _rel_err(got, ref)
+    _say(f"  rel err {err:.3e}")
+    assert err <= TOL[dtype]
+    assert bool(torch.isnan(Cbuf[:, M:].float()).all().item()), "wrote outside Ct"
