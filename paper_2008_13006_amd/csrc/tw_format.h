@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define TW_MAGIC 0x31425754u /* "TWB1" */
-#define TW_FORMAT_VERSION 7
+#define TW_FORMAT_VERSION 8
 
 // MFMA step geometry the packed values are laid out for: one step contracts 16 kept rows
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
@@ -14,6 +14,9 @@
 #define TW_WAVES_PER_WG 8
 #endif
 #define TW_COLBLK 32
+// Tiles per workgroup of the streamed kernels: a wave per tile, or with at most half as many tiles
+// half of the waves multiply and the others only bring A into LDS.
+#define TW_SET_TILES(T) ((T) <= TW_WAVES_PER_WG / 2 ? TW_WAVES_PER_WG / 2 : TW_WAVES_PER_WG)
 // Padded contraction slots gather row `k_chunk` of the LDS copy of A, which the kernel keeps zero.
 
 struct TwHeader {
@@ -42,7 +45,11 @@ struct TwHeader {
     uint64_t off_zero_ptr;   // int32 [T+1]: per tile (canonical order), start of its list in zero_cols
     uint64_t off_zero_cols;  // int32 []: the pruned columns inside every tile's span, ascending (the rows of
                              //   the transposed output that the tile writes as zeros)
-    uint8_t pad[256 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 8];
+    uint64_t off_urow;       // streamed K only: uint16 [n_sets][n_chunks][k_chunk]: per set of tiles that a
+                             //   workgroup of the streamed kernel holds (TW_SET_TILES(T) tiles in dispatch order)
+                             //   and per chunk, the chunk-local K rows that any tile of the set keeps, ascending
+    uint64_t off_ucnt;       // int32 [n_sets][n_chunks]: their number
+    uint8_t pad[256 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 10];
 };
 static_assert(sizeof(TwHeader) == 256, "header is 256 bytes");
 

@@ -78,7 +78,8 @@ struct TwGemmParams {
     unsigned abuf_bytes;        // size of one LDS copy of A (streamed K uses two)
     unsigned stage_off;         // LDS offset of the per-wave staging areas
     unsigned misc_off;          // LDS offset of two ints (item, tile counter)
-    uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_zero_ptr, off_zero_cols;
+    uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_zero_ptr, off_zero_cols, off_urow, off_ucnt;
+    unsigned urow_off;          // LDS offset of the loading waves' row lists (transposed, streamed K, few tiles), 0: none
 #ifdef TW_EXPERIMENT
     int dbg;  // bit0: no A load, bit1: no main loop, bit2: no epilogue
     unsigned* trace;  // per wave 16 clock samples
@@ -682,6 +683,39 @@ __device__ __forceinline__ void at_commit(const TwGemmParams& p, const ARegs<BAT
     }
 }
 
+// The same with a row list: request b of the wave, row lane / 8 of it, stages chunk-local K row
+// rows[8*b + lane/8] if that entry exists (entry number 8*(t0 + b*stride) + lane/8 below cnt).  K rows
+// that no tile of the workgroup's set keeps are never read: with the activations transposed, skipping
+// a K position skips a row of At (Sec. VI "Memory Accesses Coalescing").  `rows` is this wave's own
+// copy in LDS of its entries of the chunk's list.
+template <int BATCH>
+__device__ __forceinline__ void at_issue_rows(const TwGemmParams& p, ARegs<BATCH>& ar, int m0, int k0,
+                                              const unsigned short* rows, int cnt, int t0, int lane_in, int stride) {
+    const int lane = fresh(lane_in);
+    const int pmax = (int)((p.lda - m0) >> 3) - 1;
+    const int pc = (lane & 7) < pmax ? (lane & 7) : pmax;
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+        const int j = 8 * (t0 + b * stride) + (lane >> 3);
+        const int krow = rows[8 * b + (lane >> 3)];
+        ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};
+        if (j < cnt) ar.v[b] = *(const tw_u32x4*)(p.A + (long)(k0 + krow) * p.lda + (m0 + pc * 8));
+    }
+}
+template <int BATCH>
+__device__ __forceinline__ void at_commit_rows(const TwGemmParams& p, const ARegs<BATCH>& ar, unsigned char* at,
+                                               const unsigned short* rows, int cnt, int t0, int lane_in, int stride) {
+    const int lane = fresh(lane_in);
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+        const int j = 8 * (t0 + b * stride) + (lane >> 3);
+        const int krow = j < cnt ? (int)rows[8 * b + (lane >> 3)] : p.k_chunk + 1 + (lane >> 3);
+        unsigned char* dst = at + (unsigned)krow * p.at_pitch + (lane & 7) * 16;
+        *(tw_u32x2*)dst = tw_u32x2{ar.v[b].x, ar.v[b].y};
+        *(tw_u32x2*)(dst + 8) = tw_u32x2{ar.v[b].z, ar.v[b].w};
+    }
+}
+
 template <int MS, int BATCH>
 __device__ __forceinline__ void load_at_block(const TwGemmParams& p, unsigned char* at, int m0, int k0, int kw, int wave,
                                               int lane, int tid) {
@@ -823,6 +857,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
     // loading waves: the first chunks of the coming item, requested during this item's epilogue
     ARegs<12> pre0, pre1;
     bool preloaded = false;
+    int lists_of = -1;               // loading waves: the set whose row lists are in LDS
     for (int turn = 0;; ++turn) {
         if (tid == 0) {
             misc[0] = my_next;
@@ -935,13 +970,31 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             if constexpr (ROLE == 2) {
                 const int lw = wave - NMUL;
                 static_assert(PB == 12, "size of the carried register sets");
+                // Transposed boundary: this wave's entries of the set's row lists, all chunks, in its own
+                // piece of LDS ([chunk][8 * PB] rows, then [chunk] counts); filled when the set changes.
+                constexpr int kListEntries = 8 * PB;
+                unsigned short* my_rows = (unsigned short*)(smem + p.urow_off) + (long)lw * p.n_chunks * (kListEntries + 2);
+                int* my_cnt = (int*)(my_rows + (long)p.n_chunks * kListEntries);
+                const bool use_rows = TRANS && p.urow_off != 0;
+                auto load_lists = [&](int st) {
+                    const unsigned short* g = (const unsigned short*)(p.blob + p.off_urow) + (long)st * p.n_chunks * p.k_chunk;
+                    const int* gc = (const int*)(p.blob + p.off_ucnt) + (long)st * p.n_chunks;
+                    for (int c = 0; c < p.n_chunks; ++c) {
+                        for (int e = lane; e < kListEntries; e += 64)
+                            my_rows[c * kListEntries + e] = g[(long)c * p.k_chunk + 8 * (lw + (e >> 3) * NLD) + (e & 7)];
+                        if (lane == 0) my_cnt[c] = gc[c];
+                    }
+                };
                 auto issue_or_zero = [&](ARegs<PB>& ar, int c, int r0) {
                     if (c < p.n_chunks
 #ifdef TW_EXPERIMENT
                         && !(TWD(p.dbg) & 1)
 #endif
                     ) {
-                        stage_issue<MSB, PB, TRANS>(p, ar, r0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
+                        if (use_rows)
+                            at_issue_rows<PB>(p, ar, r0, c * p.k_chunk, my_rows + c * kListEntries, uni(my_cnt[c]), lw, lane, NLD);
+                        else
+                            stage_issue<MSB, PB, TRANS>(p, ar, r0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
                     } else {
 #pragma unroll
                         for (int b = 0; b < PB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
@@ -952,8 +1005,13 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #ifdef TW_EXPERIMENT
                         && !(TWD(p.dbg) & 1024)
 #endif
-                    )
-                        stage_commit<MSB, PB, TRANS>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), lw, lane, NLD);
+                    ) {
+                        if (use_rows)
+                            at_commit_rows<PB>(p, ar, smem + (c & 1) * p.abuf_bytes, my_rows + c * kListEntries, uni(my_cnt[c]), lw,
+                                               lane, NLD);
+                        else
+                            stage_commit<MSB, PB, TRANS>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), lw, lane, NLD);
+                    }
                 };
                 // chunk j waits in register set j % 2; the loop is unrolled by two so that the sets are
                 // addressed statically.  The start of an item (chunk 0 in LDS, chunks 1 and 2 requested) was
@@ -966,7 +1024,10 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     commit(ar0, 0);
                     issue_or_zero(ar0, 2, r0);
                 };
-                if (!preloaded) start_item(row0);
+                if (!preloaded) {
+                    if (use_rows && set != lists_of) { load_lists(set); lists_of = set; }
+                    start_item(row0);
+                }
                 __syncthreads();
                 for (int c = 0; c < p.n_chunks; c += 2) {
                     commit(ar1, c + 1);
@@ -983,7 +1044,11 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 __syncthreads();
                 const int nxt = misc[2];
                 preloaded = nxt < p.n_items;
-                if (preloaded) start_item((nxt % p.n_mblocks) * BM);
+                if (preloaded) {
+                    const int nset = nxt / p.n_mblocks;
+                    if (use_rows && nset != lists_of) { load_lists(nset); lists_of = nset; }
+                    start_item((nxt % p.n_mblocks) * BM);
+                }
             } else {
                 unsigned dpos[NCB];
                 {
@@ -1374,6 +1439,7 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
+    p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt; p.urow_off = 0;
 #ifdef TW_EXPERIMENT
     p.dbg = getenv("TW_DBG") ? atoi(getenv("TW_DBG")) : 0;
     p.trace = getenv("TW_TRACE_PTR") ? (unsigned*)strtoull(getenv("TW_TRACE_PTR"), nullptr, 16) : nullptr;
@@ -1447,12 +1513,21 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
+    p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt;
+    // few tiles, streamed: the loading waves read only the K rows the tiles keep, from lists they hold in LDS
+    p.urow_off = 0;
+    unsigned lds_bytes = pl.lds_bytes;
+    if (pl.mode == 2) {
+        const unsigned need = (kWaves / 2) * (unsigned)h->n_chunks * (8 * 12 + 2) * 2;
+        if (lds_bytes + need <= kLdsLimit) { p.urow_off = lds_bytes; lds_bytes += need; }
+    }
 #ifdef TW_EXPERIMENT
+    if (getenv("TW_NO_ROWLISTS")) { p.urow_off = 0; }
     p.dbg = getenv("TW_DBG") ? atoi(getenv("TW_DBG")) : 0;
     p.trace = nullptr;
 #endif
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), pl.lds_bytes, stream, p);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), lds_bytes, stream, p);
     return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 

@@ -30,7 +30,7 @@ struct Layout {
     int64_t total_steps = 0;
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
         off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, off_zero_ptr,
-        off_zero_cols, bytes;
+        off_zero_cols, off_urow, off_ucnt, bytes;
 };
 
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -130,6 +130,11 @@ void plan(const Tiling& tl, int K, int G, Layout& lo) {
         lo.off_zero_ptr = take(4 * (size_t)(T + 1), 16);
         lo.off_zero_cols = take(4 * (n_zero + 1), 16);
     }
+    {
+        const size_t n_sets = lo.n_chunks > 1 && T > 0 ? (size_t)(T + TW_SET_TILES(T) - 1) / TW_SET_TILES(T) : 0;
+        lo.off_ucnt = take(4 * (n_sets * lo.n_chunks + 1), 16);
+        lo.off_urow = take(2 * (n_sets * lo.n_chunks * (size_t)lo.k_chunk + 1), 16);
+    }
     lo.off_goff = take(2 * 16 * (uint64_t)total, 256);
     lo.off_dpos = take(4 * (uint64_t)T * 32 * lo.ncb, 256);
     lo.off_bvals = take(2 * (uint64_t)total * lo.ncb * 64 * 8, 256);
@@ -198,6 +203,7 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
     h->off_goff = lo.off_goff; h->off_dpos = lo.off_dpos; h->off_bvals = lo.off_bvals;
     h->off_sched_desc = lo.off_sched_desc;
     h->off_zero_ptr = lo.off_zero_ptr; h->off_zero_cols = lo.off_zero_cols;
+    h->off_urow = lo.off_urow; h->off_ucnt = lo.off_ucnt;
 
     auto put = [&](uint64_t off, const std::vector<int32_t>& v) {
         if (!v.empty()) std::memcpy(base + off, v.data(), 4 * v.size());
@@ -302,6 +308,28 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
         int n = 0;
         for (int i = 0; i < TW_WAVES_PER_WG; ++i) dispatch[n++] = order[tl.T - 1 - i];
         for (int i = 0; i < tl.T - TW_WAVES_PER_WG; ++i) dispatch[n++] = order[i];
+    }
+    // streamed K: the K rows every set of tiles needs, chunk by chunk
+    if (lo.n_chunks > 1 && tl.T > 0) {
+        const int tpw = TW_SET_TILES(tl.T), n_sets = (tl.T + tpw - 1) / tpw;
+        uint16_t* urow = (uint16_t*)(base + lo.off_urow);
+        int32_t* ucnt = (int32_t*)(base + lo.off_ucnt);
+        std::vector<uint8_t> need(K);
+        for (int st = 0; st < n_sets; ++st) {
+            std::fill(need.begin(), need.end(), 0);
+            for (int i = st * tpw; i < std::min(tl.T, (st + 1) * tpw); ++i) {
+                const int t = dispatch[i];
+                for (int r = tl.tile_row_ptr[t]; r < tl.tile_row_ptr[t + 1]; ++r) need[tl.row_idx[r]] = 1;
+            }
+            for (int c = 0; c < lo.n_chunks; ++c) {
+                uint16_t* out = urow + ((size_t)st * lo.n_chunks + c) * lo.k_chunk;
+                int n = 0;
+                for (int k = c * lo.k_chunk; k < std::min(K, (c + 1) * lo.k_chunk); ++k)
+                    if (need[k]) out[n++] = (uint16_t)(k - c * lo.k_chunk);
+                ucnt[(size_t)st * lo.n_chunks + c] = n;
+                for (int j = n; j < lo.k_chunk; ++j) out[j] = n > 0 ? out[n - 1] : 0;   // padding: a valid row
+            }
+        }
     }
     TwSchedDesc* sd = (TwSchedDesc*)(base + lo.off_sched_desc);
     for (int i = 0; i < tl.T; ++i) {
