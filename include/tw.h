@@ -66,7 +66,8 @@ typedef struct tw_info_t {
     int32_t K, N, G, T;
     int32_t n_kept_cols;
     int32_t k_chunk;           /* K rows of A staged in LDS at a time by tw_gemm                  */
-    int64_t nnz;               /* kept weights                                                   */
+    int64_t nnz;               /* kept weights of the tile-wise pattern                          */
+    int64_t ew_nnz;            /* weights of the element-wise residual (tw_pack_tew), else 0     */
     int64_t padded_macs_per_row; /* multiply-adds per row of A the kernel really issues (>= nnz)  */
     uint64_t blob_bytes;
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
@@ -90,8 +91,26 @@ int tw_pack_size(const uint8_t* mask, int K, int N, int G, tw_dtype dt, size_t* 
 int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N, int G, tw_dtype dt,
             void* blob, size_t blob_bytes);
 
+/* The TEW hybrid (Sec. IV-A "Hybrid Pattern"): on top of the tile-wise pattern `mask`, the weights marked
+ * in `ew_mask` (K x N bytes; entries where mask is set as well are ignored) are kept as an element-wise
+ * residual, stored per tile and column (the paper stores it in CSC form per tile) and added by tw_gemm and
+ * its variants in the same launch (by linearity, A.(B*(mask|ew)) = A.(B*mask) + A.(B*ew)).  Restrictions
+ * of this build: residual weights must lie in columns that keep at least one tile-wise weight, and K
+ * must be at most 1536 (else TW_ERR_UNSUPPORTED).  ew_mask = NULL is tw_pack. */
+int tw_pack_tew_size(const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G, tw_dtype dt,
+                     size_t* blob_bytes);
+int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G,
+                tw_dtype dt, void* blob, size_t blob_bytes);
+
+/* Which weights the hybrid puts back: the floor(delta*K*N + 0.5) pruned weights of largest magnitude
+ * among the columns that survive `mask` (magnitude as importance score, ties to the lower (k, n));
+ * ew_mask_out: K x N bytes, receives 0/1.  Host only. */
+int tw_restore_ew(const void* B, int ldb, int K, int N, tw_dtype dt, const uint8_t* mask, double delta,
+                  uint8_t* ew_mask_out);
+
 /* Inverse of tw_pack, bit-exact: B_out (host, K x N, ldb) receives the kept weights and +0 at
- * pruned positions; mask_out (host, K x N bytes) receives 1/0.  Either output may be NULL. */
+ * pruned positions; mask_out (host, K x N bytes) receives 1/0.  Either output may be NULL.
+ * For a TEW blob both include the element-wise residual (mask | ew_mask). */
 int tw_unpack(const void* blob, void* B_out, int ldb, uint8_t* mask_out);
 
 /* Fill *out from a host blob. */

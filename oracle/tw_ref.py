@@ -7,6 +7,10 @@
                          the stretch of original columns up to the next tile's first column
                          (the "G+4, G+3, G+2, G-9" stretches of the worked example).
 * ``masked_weight_bits`` - what pack -> unpack must give back: B where kept, +0 elsewhere.
+* ``restore_ew``       - which pruned weights the TEW hybrid puts back (Sec. IV-A "Hybrid Pattern": prune
+                         alpha + delta tile-wise, then restore the delta most important elements), with the
+                         weight magnitude as importance; the hybrid's product is the masked product over
+                         mask | ew_mask, which ``masked_gemm`` already defines.
 * ``bias_act``         - the fused epilogue's definition: act(C + bias) in fp64 (bias addition and
                          activation are the operators the paper fuses around its GEMMs, Sec. VI
                          "Kernel Fusion"; GELU in its exact erf form, as in BERT).
@@ -211,3 +215,18 @@ def bias_act(C: np.ndarray, bias64, act: str = "none") -> np.ndarray:
     if act == "gelu":
         return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
     raise ValueError(f"unknown activation {act!r}")
+
+
+def restore_ew(B_bits: np.ndarray, mask: np.ndarray, delta: float, dtype: str) -> np.ndarray:
+    """uint8 [K, N]: the floor(delta*K*N + 0.5) pruned weights of largest magnitude among the columns that
+    keep at least one weight in `mask`; ties go to the lower (k, n) (row-major position)."""
+    K, N = mask.shape
+    mag = np.abs(decode(B_bits, dtype))
+    alive = mask.any(axis=0)
+    cand = [(-mag[k, n], k * N + n) for k in range(K) for n in range(N) if alive[n] and not mask[k, n]]
+    cand.sort()
+    want = min(len(cand), int(np.floor(delta * K * N + 0.5)))
+    out = np.zeros((K, N), dtype=np.uint8)
+    for _, pos in cand[:want]:
+        out[pos // N, pos % N] = 1
+    return out

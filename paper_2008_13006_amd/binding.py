@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libtw.so")
 TW_F16, TW_BF16 = 0, 1
 _DT = {"f16": TW_F16, "bf16": TW_BF16}
 
-SYMBOLS = ["tw_pack_size", "tw_pack", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm",
+SYMBOLS = ["tw_pack_size", "tw_pack", "tw_pack_tew_size", "tw_pack_tew", "tw_restore_ew", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm",
            "tw_gemm_bias_act", "tw_gemm_t", "tw_gemm_t_bias_act", "tw_transpose", "tw_dense_gemm", "tw_dense_gemm_bias_act", "tw_strerror",
            "tw_version"]
 TW_ACT_NONE, TW_ACT_RELU, TW_ACT_GELU = 0, 1, 2
@@ -36,7 +36,7 @@ class TwInfo(ctypes.Structure):
     _fields_ = [("version", ctypes.c_int32), ("dtype", ctypes.c_int32), ("K", ctypes.c_int32),
                 ("N", ctypes.c_int32), ("G", ctypes.c_int32), ("T", ctypes.c_int32),
                 ("n_kept_cols", ctypes.c_int32), ("k_chunk", ctypes.c_int32),
-                ("nnz", ctypes.c_int64), ("padded_macs_per_row", ctypes.c_int64),
+                ("nnz", ctypes.c_int64), ("ew_nnz", ctypes.c_int64), ("padded_macs_per_row", ctypes.c_int64),
                 ("blob_bytes", ctypes.c_uint64),
                 ("off_col_idx", ctypes.c_uint64), ("off_tile_col_ptr", ctypes.c_uint64),
                 ("off_tile_row_ptr", ctypes.c_uint64), ("off_row_idx", ctypes.c_uint64),
@@ -52,6 +52,9 @@ def _load() -> ctypes.CDLL:
     lib.tw_pack_size.argtypes = [vp, i, i, i, i, ctypes.POINTER(sz)]
     lib.tw_pack.argtypes = [vp, i, vp, i, i, i, i, vp, sz]
     lib.tw_unpack.argtypes = [vp, vp, i, vp]
+    lib.tw_pack_tew_size.argtypes = [vp, vp, i, i, i, i, ctypes.POINTER(sz)]
+    lib.tw_pack_tew.argtypes = [vp, i, vp, vp, i, i, i, i, vp, sz]
+    lib.tw_restore_ew.argtypes = [vp, i, i, i, i, vp, ctypes.c_double, vp]
     lib.tw_info.argtypes = [vp, ctypes.POINTER(TwInfo)]
     lib.tw_gemm_workspace.argtypes = [vp, i, ctypes.POINTER(sz)]
     lib.tw_gemm.argtypes = [vp, vp, vp, i, i, vp, i, vp, sz, vp]
@@ -110,6 +113,35 @@ def tw_pack(B_bits: np.ndarray, mask: np.ndarray, G: int, dtype: str) -> np.ndar
     _check(_lib.tw_pack(_np_ptr(B_bits), ldb, _np_ptr(mask), K, N, int(G), _DT[dtype], _np_ptr(blob), nbytes),
            "tw_pack")
     return blob
+
+
+def tw_pack_tew(B_bits: np.ndarray, mask: np.ndarray, ew_mask: np.ndarray, G: int, dtype: str) -> np.ndarray:
+    """TW pattern `mask` plus the element-wise residual `ew_mask` (both uint8 [K, N]).  Returns the blob."""
+    assert B_bits.dtype == np.uint16 and B_bits.ndim == 2 and B_bits.strides[1] == 2
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    ew_mask = np.ascontiguousarray(ew_mask, dtype=np.uint8)
+    K, N = mask.shape
+    assert B_bits.shape == (K, N) and ew_mask.shape == (K, N)
+    ldb = B_bits.strides[0] // 2 if K > 1 else N
+    n = ctypes.c_size_t(0)
+    _check(_lib.tw_pack_tew_size(_np_ptr(mask), _np_ptr(ew_mask), K, N, int(G), _DT[dtype], ctypes.byref(n)),
+           "tw_pack_tew_size")
+    blob = _aligned_bytes(int(n.value), 256)
+    _check(_lib.tw_pack_tew(_np_ptr(B_bits), ldb, _np_ptr(mask), _np_ptr(ew_mask), K, N, int(G), _DT[dtype],
+                            _np_ptr(blob), int(n.value)), "tw_pack_tew")
+    return blob
+
+
+def tw_restore_ew(B_bits: np.ndarray, mask: np.ndarray, delta: float, dtype: str) -> np.ndarray:
+    """The delta*K*N pruned weights of largest magnitude in surviving columns, as a uint8 [K, N] mask."""
+    assert B_bits.dtype == np.uint16 and B_bits.ndim == 2 and B_bits.strides[1] == 2
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    K, N = mask.shape
+    ldb = B_bits.strides[0] // 2 if K > 1 else N
+    out = np.empty((K, N), dtype=np.uint8)
+    _check(_lib.tw_restore_ew(_np_ptr(B_bits), ldb, K, N, _DT[dtype], _np_ptr(mask), ctypes.c_double(delta),
+                              _np_ptr(out)), "tw_restore_ew")
+    return out
 
 
 def _aligned_bytes(n: int, align: int) -> np.ndarray:

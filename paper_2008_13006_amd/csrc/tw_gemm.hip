@@ -79,6 +79,8 @@ struct TwGemmParams {
     unsigned stage_off;         // LDS offset of the per-wave staging areas
     unsigned misc_off;          // LDS offset of two ints (item, tile counter)
     uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_zero_ptr, off_zero_cols, off_urow, off_ucnt;
+    uint64_t off_ew_ptr, off_ew_k, off_ew_v;
+    int has_ew;                 // the blob carries an element-wise residual (TEW)
     unsigned urow_off;          // LDS offset of the loading waves' row lists (transposed, streamed K, few tiles), 0: none
 #ifdef TW_EXPERIMENT
     int dbg;  // bit0: no A load, bit1: no main loop, bit2: no epilogue
@@ -816,6 +818,47 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
     }
 }
 
+// Element-wise residual of the TEW hybrid (Sec. IV-A): the weights kept outside the tile-wise pattern are
+// added to the tile's accumulators after the MFMA steps, by linearity.  The paper runs this part as a
+// separate sparse product on the scalar cores; here it rides on the LDS copy of A: a lane owns a packed
+// column, so for each of that column's residual entries (K row k, weight v) it reads the column's 32*MS
+// activations of row k from LDS (8-byte pieces: four consecutive rows of the block) and adds v * A.
+// Entries come in planes of G (one per packed column, padded with weight 0 at the zero row).
+template <int DT, int MS, int NCB>
+__device__ __forceinline__ void add_ew_residual(const TwGemmParams& p, int tile, tw_f32x16 (&acc)[MS][NCB],
+                                                const unsigned char* at, unsigned at_pitch, int lane_in) {
+    const int lane = fresh(lane_in);
+    const int n = lane & 31, h = lane >> 5;
+    const int* ep = (const int*)(p.blob + p.off_ew_ptr);
+    const int e0 = fetch_int(ep, tile), e1 = fetch_int(ep, tile + 1);
+    const unsigned short* ek = (const unsigned short*)(p.blob + p.off_ew_k) + n;
+    const unsigned short* ev = (const unsigned short*)(p.blob + p.off_ew_v) + n;
+    constexpr int G = 32 * NCB;
+    for (int e = e0; e < e1; ++e) {
+        unsigned k[NCB];
+        float v[NCB];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            k[cb] = ek[(long)e * G + 32 * cb];
+            v[cb] = tw_to_f32<DT>(ev[(long)e * G + 32 * cb]);
+        }
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            const unsigned char* row = at + k[cb] * at_pitch + 8 * h;
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const tw_u32x2 a = *(const tw_u32x2*)(row + (32 * ms + 8 * q) * 2);
+                    acc[ms][cb][4 * q + 0] += v[cb] * tw_to_f32<DT>((unsigned short)a.x);
+                    acc[ms][cb][4 * q + 1] += v[cb] * tw_to_f32<DT>((unsigned short)(a.x >> 16));
+                    acc[ms][cb][4 * q + 2] += v[cb] * tw_to_f32<DT>((unsigned short)a.y);
+                    acc[ms][cb][4 * q + 3] += v[cb] * tw_to_f32<DT>((unsigned short)(a.y >> 16));
+                }
+        }
+    }
+}
+
 template <int MS, int NCB>
 __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 #pragma unroll
@@ -921,6 +964,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                                        , p.dbg
 #endif
                                        );
+                if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, acc, smem, p.at_pitch, lane);
 #if defined(TW_EXPERIMENT) && defined(TW_DBG_CONST)
                 if (TW_DBG_CONST & 4) {   // keep the products alive when the epilogue is compiled out
                     float sink = 0.f;
@@ -1440,6 +1484,8 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt; p.urow_off = 0;
+    p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
+    if (p.has_ew && pl.mode != 0) return TW_ERR_UNSUPPORTED;
 #ifdef TW_EXPERIMENT
     p.dbg = getenv("TW_DBG") ? atoi(getenv("TW_DBG")) : 0;
     p.trace = getenv("TW_TRACE_PTR") ? (unsigned*)strtoull(getenv("TW_TRACE_PTR"), nullptr, 16) : nullptr;
@@ -1514,6 +1560,8 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt;
+    p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
+    if (p.has_ew && pl.mode != 0) return TW_ERR_UNSUPPORTED;
     // few tiles, streamed: the loading waves read only the K rows the tiles keep, from lists they hold in LDS
     p.urow_off = 0;
     unsigned lds_bytes = pl.lds_bytes;

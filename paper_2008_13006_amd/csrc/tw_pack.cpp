@@ -30,7 +30,9 @@ struct Layout {
     int64_t total_steps = 0;
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
         off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, off_zero_ptr,
-        off_zero_cols, off_urow, off_ucnt, bytes;
+        off_zero_cols, off_urow, off_ucnt, off_ew_ptr, off_ew_k, off_ew_v, bytes;
+    int64_t ew_nnz = 0;
+    std::vector<int32_t> ew_ptr;   // planes per tile, prefix sums
 };
 
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -82,7 +84,7 @@ int analyse(const uint8_t* mask, int K, int N, int G, Tiling& tl) {
     return TW_OK;
 }
 
-void plan(const Tiling& tl, int K, int G, Layout& lo) {
+void plan(const Tiling& tl, int K, int G, Layout& lo, const uint8_t* mask = nullptr, const uint8_t* ew = nullptr, int N = 0) {
     const int T = tl.T;
     if (K <= TW_K_RESIDENT_MAX) {
         lo.k_chunk = (K + 7) / 8 * 8;
@@ -135,6 +137,28 @@ void plan(const Tiling& tl, int K, int G, Layout& lo) {
         lo.off_ucnt = take(4 * (n_sets * lo.n_chunks + 1), 16);
         lo.off_urow = take(2 * (n_sets * lo.n_chunks * (size_t)lo.k_chunk + 1), 16);
     }
+    {
+        // residual planes per tile: the largest number of residual entries of any of its columns
+        lo.ew_ptr.assign(T + 1, 0);
+        lo.ew_nnz = 0;
+        if (ew) {
+            for (int t = 0; t < T; ++t) {
+                int emax = 0;
+                for (int c = tl.tile_col_ptr[t]; c < tl.tile_col_ptr[t + 1]; ++c) {
+                    const int n = tl.col_idx[c];
+                    int cnt = 0;
+                    for (int k = 0; k < K; ++k) cnt += ew[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0;
+                    lo.ew_nnz += cnt;
+                    emax = std::max(emax, cnt);
+                }
+                lo.ew_ptr[t + 1] = lo.ew_ptr[t] + emax;
+            }
+        }
+        const size_t planes = (size_t)lo.ew_ptr[T];
+        lo.off_ew_ptr = take(4 * (size_t)(T + 1), 16);
+        lo.off_ew_k = take(2 * (planes * G + 1), 16);
+        lo.off_ew_v = take(2 * (planes * G + 1), 16);
+    }
     lo.off_goff = take(2 * 16 * (uint64_t)total, 256);
     lo.off_dpos = take(4 * (uint64_t)T * 32 * lo.ncb, 256);
     lo.off_bvals = take(2 * (uint64_t)total * lo.ncb * 64 * 8, 256);
@@ -158,7 +182,28 @@ const TwHeader* header_of(const void* blob) {
 
 }  // namespace
 
+// residual entries must lie in columns that survive the tile-wise pattern, and K must be resident
+int check_ew(const uint8_t* mask, const uint8_t* ew, int K, int N, const Tiling& tl, const Layout& lo) {
+    if (!ew) return TW_OK;
+    std::vector<uint8_t> alive(N, 0);
+    for (int32_t n : tl.col_idx) alive[n] = 1;
+    bool any = false;
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n)
+            if (ew[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0) {
+                if (!alive[n]) return TW_ERR_UNSUPPORTED;
+                any = true;
+            }
+    if (any && lo.n_chunks != 1) return TW_ERR_UNSUPPORTED;
+    return TW_OK;
+}
+
 extern "C" int tw_pack_size(const uint8_t* mask, int K, int N, int G, tw_dtype dt, size_t* blob_bytes) {
+    return tw_pack_tew_size(mask, nullptr, K, N, G, dt, blob_bytes);
+}
+
+extern "C" int tw_pack_tew_size(const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G, tw_dtype dt,
+                                size_t* blob_bytes) {
     if (!blob_bytes) return TW_ERR_ARG;
     int rc = check_common(mask, K, N, G, (int)dt);
     if (rc) return rc;
@@ -166,13 +211,20 @@ extern "C" int tw_pack_size(const uint8_t* mask, int K, int N, int G, tw_dtype d
     rc = analyse(mask, K, N, G, tl);
     if (rc) return rc;
     Layout lo;
-    plan(tl, K, G, lo);
+    plan(tl, K, G, lo, mask, ew_mask, N);
+    rc = check_ew(mask, ew_mask, K, N, tl, lo);
+    if (rc) return rc;
     *blob_bytes = (size_t)lo.bytes;
     return TW_OK;
 }
 
 extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N, int G, tw_dtype dt,
                        void* blob, size_t blob_bytes) {
+    return tw_pack_tew(B, ldb, mask, nullptr, K, N, G, dt, blob, blob_bytes);
+}
+
+extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G,
+                           tw_dtype dt, void* blob, size_t blob_bytes) {
     if (!B || !blob) return TW_ERR_ARG;
     int rc = check_common(mask, K, N, G, (int)dt);
     if (rc) return rc;
@@ -182,7 +234,9 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
     rc = analyse(mask, K, N, G, tl);
     if (rc) return rc;
     Layout lo;
-    plan(tl, K, G, lo);
+    plan(tl, K, G, lo, mask, ew_mask, N);
+    rc = check_ew(mask, ew_mask, K, N, tl, lo);
+    if (rc) return rc;
     if (blob_bytes < lo.bytes) return TW_ERR_BUF;
 
     uint8_t* base = (uint8_t*)blob;
@@ -204,6 +258,7 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
     h->off_sched_desc = lo.off_sched_desc;
     h->off_zero_ptr = lo.off_zero_ptr; h->off_zero_cols = lo.off_zero_cols;
     h->off_urow = lo.off_urow; h->off_ucnt = lo.off_ucnt;
+    h->ew_nnz = lo.ew_nnz; h->off_ew_ptr = lo.off_ew_ptr; h->off_ew_k = lo.off_ew_k; h->off_ew_v = lo.off_ew_v;
 
     auto put = [&](uint64_t off, const std::vector<int32_t>& v) {
         if (!v.empty()) std::memcpy(base + off, v.data(), 4 * v.size());
@@ -214,6 +269,29 @@ extern "C" int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N
     put(lo.off_row_idx, tl.row_idx);
     put(lo.off_tile_span, tl.tile_span);
     put(lo.off_step_ptr, lo.step_ptr);
+
+    // element-wise residual, planes of G entries per tile
+    put(lo.off_ew_ptr, lo.ew_ptr);
+    if (ew_mask && lo.ew_ptr[tl.T] > 0) {
+        uint16_t* ek = (uint16_t*)(base + lo.off_ew_k);
+        uint16_t* ev = (uint16_t*)(base + lo.off_ew_v);
+        const uint16_t* Bw = (const uint16_t*)B;
+        for (int t = 0; t < tl.T; ++t) {
+            const int c0 = tl.tile_col_ptr[t], w = tl.tile_col_ptr[t + 1] - c0;
+            for (int e = lo.ew_ptr[t]; e < lo.ew_ptr[t + 1]; ++e)
+                for (int c = 0; c < G; ++c) { ek[(size_t)e * G + c] = (uint16_t)lo.k_chunk; ev[(size_t)e * G + c] = 0; }
+            for (int c = 0; c < w; ++c) {
+                const int n = tl.col_idx[c0 + c];
+                int e = lo.ew_ptr[t];
+                for (int k = 0; k < K; ++k)
+                    if (ew_mask[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0) {
+                        ek[(size_t)e * G + c] = (uint16_t)k;
+                        ev[(size_t)e * G + c] = Bw[(size_t)k * ldb + n];
+                        ++e;
+                    }
+            }
+        }
+    }
 
     // pruned columns inside every span
     {
@@ -350,6 +428,7 @@ extern "C" int tw_info(const void* blob, tw_info_t* out) {
     out->n_kept_cols = h->n_kept_cols;
     out->k_chunk = h->k_chunk;
     out->nnz = h->nnz;
+    out->ew_nnz = h->ew_nnz;
     out->padded_macs_per_row = h->total_steps * TW_KSTEP * (int64_t)h->G;
     out->blob_bytes = h->blob_bytes;
     out->off_col_idx = h->off_col_idx; out->off_tile_col_ptr = h->off_tile_col_ptr;
@@ -397,6 +476,49 @@ extern "C" int tw_unpack(const void* blob, void* B_out, int ldb, uint8_t* mask_o
             }
         }
     }
+    // the element-wise residual: part of the weights the GEMM multiplies by
+    if (h->ew_nnz > 0) {
+        const int32_t* ep = (const int32_t*)(base + h->off_ew_ptr);
+        const uint16_t* ek = (const uint16_t*)(base + h->off_ew_k);
+        const uint16_t* ev = (const uint16_t*)(base + h->off_ew_v);
+        for (int t = 0; t < T; ++t) {
+            const int c0 = tcp[t], w = tcp[t + 1] - c0;
+            for (int e = ep[t]; e < ep[t + 1]; ++e)
+                for (int c = 0; c < w; ++c) {
+                    const int k = ek[(size_t)e * h->G + c];
+                    if (k >= K) continue;                   // padding
+                    const int n = col_idx[c0 + c];
+                    if (mask_out) mask_out[(size_t)k * N + n] = 1;
+                    if (Bo) Bo[(size_t)k * ldb + n] = ev[(size_t)e * h->G + c];
+                }
+        }
+    }
+    return TW_OK;
+}
+
+// The delta*K*N pruned weights of largest magnitude inside the surviving columns (the elements the TEW hybrid
+// puts back, Sec. IV-A; magnitude as importance score), ties to the lower (k, n).
+extern "C" int tw_restore_ew(const void* B, int ldb, int K, int N, tw_dtype dt, const uint8_t* mask, double delta,
+                             uint8_t* ew_mask_out) {
+    if (!B || !mask || !ew_mask_out || K <= 0 || N <= 0 || ldb < N) return TW_ERR_ARG;
+    if (dt != TW_F16 && dt != TW_BF16) return TW_ERR_ARG;
+    if (!(delta >= 0.0 && delta < 1.0)) return TW_ERR_ARG;
+    std::memset(ew_mask_out, 0, (size_t)K * N);
+    std::vector<uint8_t> alive(N, 0);
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n) alive[n] |= mask[(size_t)k * N + n] != 0;
+    const uint16_t* Bw = (const uint16_t*)B;
+    std::vector<std::pair<uint16_t, int64_t>> cand;     // (magnitude bits, position)
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n)
+            if (alive[n] && mask[(size_t)k * N + n] == 0)
+                cand.emplace_back((uint16_t)(Bw[(size_t)k * ldb + n] & 0x7FFFu), (int64_t)k * N + n);
+    int64_t want = (int64_t)std::floor(delta * (double)K * (double)N + 0.5);
+    if (want > (int64_t)cand.size()) want = (int64_t)cand.size();
+    // for both 16-bit formats the magnitude order of finite values is the order of the bit patterns
+    std::stable_sort(cand.begin(), cand.end(),
+                     [](const std::pair<uint16_t, int64_t>& a, const std::pair<uint16_t, int64_t>& b) { return a.first > b.first; });
+    for (int64_t i = 0; i < want; ++i) ew_mask_out[cand[i].second] = 1;
     return TW_OK;
 }
 

@@ -453,3 +453,50 @@ def test_tw_gemm_t_bias_act(tw, case):
     _say(f"  rel err {err:.3e}")
     assert err <= TOL[dtype]
     assert bool(torch.isnan(Cbuf[:, M:].float()).all().item()), "wrote outside Ct"
+
+
+# ------------------------------------------------------------------ TEW hybrid: tile-wise pattern + element-wise residual
+TEW = [("ragged_rows_gaps", 0.02), ("bf16_g64", 0.01), ("g32_many_tiles", 0.05), ("several_row_blocks", 0.01),
+       ("wide_spans", 0.03), ("t_k1024", 0.01), ("kept_one_row_each", 0.1)]
+
+
+@pytest.mark.parametrize("case", TEW, ids=[f"{c[0]}-delta{c[1]}" for c in TEW])
+def test_tew_gemm_all_boundaries(tw, case):
+    """A.(B*(mask | ew)) through tw_gemm, tw_gemm_t and the fused epilogue on a TEW blob, against the oracle's
+    masked product over the union mask."""
+    cname, delta = case
+    name, M, K, N, G, dtype, cp, keep = next(c for c in SMALL_T if c[0] == cname)
+    _say(f"TEW {name} delta={delta}")
+    spec = W.small_spec(name, M=M, K=K, N=N, G=G, dtype=dtype, col_prune=cp, keep=keep, seed_offset=9500 + len(name))
+    w = W.generate(spec)
+    ew = tw_ref.restore_ew(w.B, w.mask, delta, dtype)
+    assert ew.any()
+    wt = tw.TwWeight(tw.tw_pack_tew(w.B, w.mask, ew, G, dtype))
+    union = (w.mask | ew).astype(np.uint8)
+    ref = tw_ref.masked_gemm(w.A, w.B, union, dtype)
+    ref_tw_only = tw_ref.masked_gemm(w.A, w.B, w.mask, dtype)
+    assert _rel_err(ref_tw_only, ref) > 10 * TOL[dtype] or delta < 0.02     # the residual matters in this case
+    C = tw.tw_gemm(wt, _device_A(tw, w.A, dtype))
+    Ct = tw.tw_gemm_t(wt, _device_At(tw, w.A, dtype))
+    bbits = _bias_bits(N, dtype, 5)
+    Cg = tw.tw_gemm_bias_act(wt, _device_A(tw, w.A, dtype), tw.bits_to_tensor(bbits, dtype), "relu")
+    torch.cuda.synchronize()
+    assert _rel_err(_to_f64(C), ref) <= TOL[dtype]
+    assert _rel_err(_to_f64(Ct).T, ref) <= TOL[dtype]
+    assert _rel_err(_to_f64(Cg), tw_ref.bias_act(ref, tw_ref.decode(bbits, dtype), "relu")) <= TOL[dtype]
+    pruned = np.flatnonzero(~union.any(axis=0))
+    if len(pruned):
+        assert float(C[:, torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
+
+
+def test_tew_full_size_ffn_up(tw):
+    spec = W.CONFIGS["c2_bert_base_ffn_up"][0]
+    w = W.generate(spec)
+    ew = tw.tw_restore_ew(w.B, w.mask, 0.01, spec.dtype)
+    wt = tw.TwWeight(tw.tw_pack_tew(w.B, w.mask, ew, spec.G, spec.dtype))
+    assert wt.info["ew_nnz"] == int(np.floor(0.01 * spec.K * spec.N + 0.5))
+    C = tw.tw_gemm(wt, _device_A(tw, w.A, spec.dtype))
+    torch.cuda.synchronize()
+    rows = _sample_rows(spec.M, n=64, seed=6)
+    ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, (w.mask | ew).astype(np.uint8), spec.dtype)
+    assert _rel_err(_to_f64(C[torch.as_tensor(rows, device="cuda:0")]), ref) <= TOL[spec.dtype]

@@ -215,3 +215,56 @@ def test_header_is_plain_c(tmp_path):
     r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, "-c", str(src), "-o",
                         str(tmp_path / "use_tw.o")], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+# ------------------------------------------------------------------ TEW hybrid: tile-wise pattern + element-wise residual
+@pytest.mark.parametrize("K,N,G,dtype,delta", [(64, 96, 32, "f16", 0.02), (200, 300, 128, "bf16", 0.01),
+                                               (96, 128, 64, "f16", 0.0), (40, 70, 32, "f16", 0.2)])
+def test_tw_restore_ew_matches_oracle_bit_exact(K, N, G, dtype, delta):
+    spec = W.small_spec("tew", M=4, K=K, N=N, G=G, dtype=dtype, col_prune=0.1, keep=("upow", 0.1, 0.6), seed_offset=4242 + K)
+    w = W.generate(spec)
+    got = tw.tw_restore_ew(w.B, w.mask, delta, dtype)
+    ref = tw_ref.restore_ew(w.B, w.mask, delta, dtype)
+    assert np.array_equal(got, ref)
+    # properties the paper states: only pruned weights come back, exactly delta*K*N of them (if that many are
+    # there), none weaker than one that stays pruned in a surviving column
+    assert not np.any(got & w.mask)
+    alive = w.mask.any(axis=0)
+    n_cand = int(((w.mask == 0) & alive[None, :]).sum())
+    assert int(got.sum()) == min(n_cand, int(np.floor(delta * K * N + 0.5)))
+    assert not np.any(got[:, ~alive])
+    if got.any() and n_cand > got.sum():
+        mag = np.abs(tw_ref.decode(w.B, dtype))
+        left = (w.mask == 0) & (got == 0) & alive[None, :]
+        assert mag[got == 1].min() >= mag[left].max()
+
+
+def test_tew_pack_round_trip_and_errors():
+    spec = W.small_spec("tew_rt", M=4, K=160, N=260, G=64, dtype="f16", col_prune=0.1, keep=("upow", 0.1, 0.5), seed_offset=4300)
+    w = W.generate(spec)
+    ew = tw_ref.restore_ew(w.B, w.mask, 0.03, "f16")
+    blob = tw.tw_pack_tew(w.B, w.mask, ew, spec.G, "f16")
+    inf = tw.tw_info(blob)
+    assert inf["ew_nnz"] == int(ew.sum()) and inf["nnz"] == int(w.mask.sum())
+    # the tile structure is that of the tile-wise pattern alone
+    s = tw_ref.tile_structure(w.mask, spec.G)
+    for key in ("col_idx", "tile_col_ptr", "tile_row_ptr", "row_idx", "tile_span"):
+        assert np.array_equal(inf[key], s[key]), key
+    Bu, mu = tw.tw_unpack(blob)
+    union = (w.mask | ew).astype(np.uint8)
+    assert np.array_equal(mu, union)
+    assert np.array_equal(Bu, tw_ref.masked_weight_bits(w.B, union))
+    # entries that the tile-wise pattern keeps anyway are ignored
+    blob2 = tw.tw_pack_tew(w.B, w.mask, (ew | w.mask).astype(np.uint8), spec.G, "f16")
+    assert tw.tw_info(blob2)["ew_nnz"] == int(ew.sum())
+    # a residual weight in a column without tile-wise weights is refused, and so is a residual with streamed K
+    pruned_cols = np.flatnonzero(~w.mask.any(axis=0))
+    bad = ew.copy(); bad[3, pruned_cols[0]] = 1
+    with pytest.raises(tw.TwError) as e:
+        tw.tw_pack_tew(w.B, w.mask, bad, spec.G, "f16")
+    assert e.value.status == -6
+    big = W.generate(W.small_spec("tew_big", M=4, K=1600, N=64, G=32, dtype="f16", keep=("const", 0.25), seed_offset=4301))
+    ewb = tw_ref.restore_ew(big.B, big.mask, 0.01, "f16")
+    with pytest.raises(tw.TwError) as e:
+        tw.tw_pack_tew(big.B, big.mask, ewb, 32, "f16")
+    assert e.value.status == -6
