@@ -29,8 +29,8 @@ MFMA_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA
 # HBM bytes per tw_gemm launch on this workload, from the two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) summarised in profiles/tw_gemm_c2_hbm_traffic.txt, each scaled by what the same counter
 # reads for the copy kernel of known size that `--pmc-calibration` launches.
-MEASURED_TRAFFIC_BYTES = 149_663_912      # 36.04 MB read + 113.63 MB written
-MEASURED_TRAFFIC_BYTES_T = 136_396_268    # tw_gemm_t: 35.73 MB read + 100.66 MB written (profiles/tw_gemm_t_c2_hbm_traffic.txt)
+MEASURED_TRAFFIC_BYTES = 150_113_144      # 35.97 MB read + 114.14 MB written
+MEASURED_TRAFFIC_BYTES_T = 136_314_147    # tw_gemm_t: 35.65 MB read + 100.66 MB written (profiles/tw_gemm_t_c2_hbm_traffic.txt)
 PAPER_CONTEXT = {"tw128_speedup_vs_dense_75pct": 2.26, "hardware": "NVIDIA V100 tensor cores, FP16",
                  "where": "Sec. VII-B, Fig. 8b"}
 
@@ -266,6 +266,20 @@ def main() -> int:
         print(f"[report] fused epilogue on c2: tw_gemm_bias_act(gelu) {fused_ms*1e3:.1f} us, tw_gemm {plain_ms*1e3:.1f} us, "
               f"tw_gemm + separate bias/GELU pass {sep_ms*1e3:.1f} us, tw_dense_gemm_bias_act {dfused_ms*1e3:.1f} us",
               file=sys.stderr, flush=True)
+        # the TEW hybrid on the headline workload (the experiment of Sec. VII-B, Fig. 9, latency side): the
+        # delta*K*N pruned weights of largest magnitude put back as an element-wise residual
+        Ats = [tw.tw_transpose(a).contiguous() for a in As]
+        Cts = [torch.empty((N, M), dtype=td, device="cuda:0") for _ in range(n_sets)]
+        for delta in (0.0, 0.005, 0.01, 0.02, 0.05):
+            ew = tw.tw_restore_ew(w.B, w.mask, delta, spec.dtype)
+            wte = tw.TwWeight(tw.tw_pack_tew(w.B, w.mask, ew, spec.G, spec.dtype))
+            a_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wte, As[i], Cs[i]), n_sets, st, 5)
+            b_ms, _ = time_launches(torch, lambda i: tw.tw_gemm_t(wte, Ats[i], Cts[i]), n_sets, st, 5)
+            rows.append({"config": "tew_c2", "name": f"ffn_up_768x3072 delta={delta}", "delta": delta,
+                         "ew_nnz": int(wte.info["ew_nnz"]), "tw_ms": a_ms, "tw_t_ms": b_ms})
+            print(f"[report] TEW on c2, delta {delta:.3f} ({int(wte.info['ew_nnz'])} residual weights): tw_gemm {a_ms*1e3:.1f} us, "
+                  f"tw_gemm_t {b_ms*1e3:.1f} us", file=sys.stderr, flush=True)
+        del Ats, Cts
         with open(args.report, "w") as f:
             json.dump(rows, f, indent=1)
     if args.sweep:
@@ -281,6 +295,7 @@ def main() -> int:
                 r["speedup_vs_dense"] = dense_ms / r["tw_ms"]
                 rows.append(r)
                 print(f"[sweep] G={G:3d} sparsity {r['sparsity']:.3f} T={r['T']:3d}: tw {r['tw_ms']*1e3:6.1f} us  "
+                      f"tw_t {r['tw_t_ms']*1e3:6.1f} us  "
                       f"x{r['speedup_vs_dense']:.2f} vs dense {dense_ms*1e3:.1f} us  nz {r['tw_tflops_nonzero']:.0f} TF "
                       f"({100*r['tw_mfma_frac_nonzero']:.1f} % of MFMA peak)  {r['tw_gbs']:.0f} GB/s", file=sys.stderr, flush=True)
                 torch.cuda.empty_cache()
