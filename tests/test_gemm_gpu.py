@@ -500,3 +500,35 @@ def test_tew_full_size_ffn_up(tw):
     rows = _sample_rows(spec.M, n=64, seed=6)
     ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, (w.mask | ew).astype(np.uint8), spec.dtype)
     assert _rel_err(_to_f64(C[torch.as_tensor(rows, device="cuda:0")]), ref) <= TOL[spec.dtype]
+
+
+def test_bad_arguments_of_the_newer_entry_points_are_refused(tw):
+    """Documented error codes of tw_gemm_t, tw_gemm_*_bias_act and tw_transpose; nothing is enqueued on error."""
+    import ctypes
+    spec = W.small_spec("args2", M=16, K=64, N=128, G=64, seed_offset=9951)
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, 64, "f16")
+    lib = tw._lib
+    vp = ctypes.c_void_p
+    At = torch.zeros((64, 24), dtype=torch.float16, device="cuda:0")
+    Ct = torch.full((128, 24), 7.0, dtype=torch.float16, device="cuda:0")
+    blob_h, blob_d, ws = tw._np_ptr(wt.blob), vp(wt.blob_dev.data_ptr()), vp(wt.workspace.data_ptr())
+    def call_t(at_ptr, M, ldat, ct_ptr, ldct, bias=None, act=0):
+        return lib.tw_gemm_t_bias_act(blob_h, blob_d, vp(at_ptr), M, ldat, vp(bias or 0), act, vp(ct_ptr), ldct, ws, 256, None)
+    assert call_t(At.data_ptr(), 16, 24, Ct.data_ptr(), 24) == 0                       # baseline: fine
+    assert call_t(At.data_ptr(), 16, 20, Ct.data_ptr(), 24) == -4                      # ldat % 8 != 0
+    assert call_t(At.data_ptr(), 16, 24, Ct.data_ptr(), 12) == -1                      # ldct < M
+    assert call_t(At.data_ptr() + 2, 16, 24, Ct.data_ptr(), 24) == -4                  # At not 16-byte aligned
+    assert call_t(At.data_ptr(), 16, 24, Ct.data_ptr(), 24, act=9) == -1               # unknown activation
+    assert call_t(At.data_ptr(), 16, 24, Ct.data_ptr(), 24, bias=Ct.data_ptr() + 1) == -4   # odd bias address
+    assert call_t(0, 16, 24, Ct.data_ptr(), 24) == -1                                  # null pointer
+    assert call_t(At.data_ptr(), 0, 24, Ct.data_ptr(), 24) == 0                        # M = 0: nothing to do
+    assert lib.tw_gemm_t(blob_h, blob_d, vp(At.data_ptr()), 16, 24, vp(Ct.data_ptr()), 24, ws, 8, None) == -3   # workspace too small
+    torch.cuda.synchronize()
+    x = torch.zeros((4, 8), dtype=torch.float16, device="cuda:0")
+    y = torch.zeros((8, 4), dtype=torch.float16, device="cuda:0")
+    assert lib.tw_transpose(vp(x.data_ptr()), 4, 4, 8, vp(y.data_ptr()), 4, None) == -1    # ld_src < cols
+    assert lib.tw_transpose(vp(x.data_ptr()), 8, 4, 8, vp(y.data_ptr()), 2, None) == -1    # ld_dst < rows
+    assert lib.tw_transpose(vp(x.data_ptr()), 8, 0, 8, vp(y.data_ptr()), 4, None) == 0
+    with pytest.raises(ValueError):
+        tw.tw_gemm_bias_act(wt, torch.zeros((16, 64), dtype=torch.float16, device="cuda:0"), None, "swish")
