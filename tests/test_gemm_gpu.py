@@ -532,3 +532,28 @@ def test_bad_arguments_of_the_newer_entry_points_are_refused(tw):
     assert lib.tw_transpose(vp(x.data_ptr()), 8, 0, 8, vp(y.data_ptr()), 4, None) == 0
     with pytest.raises(ValueError):
         tw.tw_gemm_bias_act(wt, torch.zeros((16, 64), dtype=torch.float16, device="cuda:0"), None, "swish")
+
+
+@pytest.mark.parametrize("cfg", ["c3_bert_base_layer", "c4_bert_large_skewed", "c5_conv_im2col"])
+def test_full_size_workloads_transposed_on_sampled_rows(tw, cfg):
+    """tw_gemm_t at the sizes bench.py times (resident K with 64- and 32-token blocks, streamed K with a wave
+    per tile and with loading waves that read only the kept rows), on sampled tokens."""
+    for spec in W.CONFIGS[cfg]:
+        _say(f"transposed {cfg} / {spec.name} M={spec.M} K={spec.K} N={spec.N}")
+        w = W.generate(spec)
+        wt = tw.TwWeight.from_dense(w.B, w.mask, spec.G, spec.dtype)
+        At = tw.tw_transpose(_device_A(tw, w.A, spec.dtype))
+        Ct = tw.tw_gemm_t(wt, At)
+        torch.cuda.synchronize()
+        rows = _sample_rows(spec.M, n=96, seed=8)
+        ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, w.mask, spec.dtype)
+        got = _to_f64(Ct[:, torch.as_tensor(rows, device="cuda:0")]).T
+        err = _rel_err(got, ref)
+        _say(f"  rel err {err:.3e}")
+        assert err <= TOL[spec.dtype]
+        assert bool(torch.isfinite(Ct.float()).all().item())
+        pruned = np.flatnonzero(~w.mask.any(axis=0))
+        if len(pruned):
+            assert float(Ct[torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
+        del At, Ct
+        torch.cuda.empty_cache()
