@@ -175,6 +175,38 @@ def pmc_calibration(torch, tw, W, spec, steps: int, transposed: bool = False) ->
     return 0
 
 
+def pmc_sweep(torch, tw, W, reps: int = 3) -> int:
+    """What the counter runs of the sparsity sweep profile (the paper's Fig. 10 on this chip: memory requests
+    and matrix-unit work against sparsity, normalised to dense): on the FFN-up shape with G = 128, `reps` launches
+    each of tw_dense_gemm (first), then per sparsity of tw_gemm and of tw_gemm_t, in this order.  Prints the order."""
+    order = []
+    spec0 = W.sweep_spec(128, 0.0)
+    w0 = W.generate(spec0)
+    td = torch.float16
+    A = tw.bits_to_tensor(w0.A, spec0.dtype)
+    At = tw.tw_transpose(A).contiguous()
+    Bd = tw.bits_to_tensor(w0.B, spec0.dtype)
+    C = torch.empty((spec0.M, spec0.N), dtype=td, device="cuda:0")
+    Ct = torch.empty((spec0.N, spec0.M), dtype=td, device="cuda:0")
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        tw.tw_dense_gemm(A, Bd, C)
+    order.append({"kernel": "tw_dense_gemm", "sparsity": 0.0, "launches": reps})
+    for sp in (0.0, 0.25, 0.5, 0.75, 0.875, 0.95, 0.99):
+        spec = W.sweep_spec(128, sp)
+        w = W.generate(spec)
+        wt = tw.TwWeight(tw.tw_pack(w.B, w.mask, spec.G, spec.dtype))
+        for _ in range(reps):
+            tw.tw_gemm(wt, A, C)
+        for _ in range(reps):
+            tw.tw_gemm_t(wt, At, Ct)
+        torch.cuda.synchronize()
+        order.append({"kernel": "tw_gemm then tw_gemm_t", "sparsity": float(w.info["sparsity"]), "launches": reps,
+                      "nnz": int(wt.info["nnz"]), "T": int(wt.info["T"])})
+    print(json.dumps({"pmc_sweep": order}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -185,6 +217,7 @@ def main() -> int:
     ap.add_argument("--sweep", type=str, default=None,
                     help="also run the sparsity x G sweep on the FFN-up shape, write a table (JSON) here")
     ap.add_argument("--transposed", action="store_true", help="with --pmc-calibration: launch tw_gemm_t instead of tw_gemm")
+    ap.add_argument("--pmc-sweep", action="store_true", help="counter runs of the sparsity sweep (G = 128)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="counter runs: launch only a copy kernel of known size, then the tw_gemm steps")
     args = ap.parse_args()
@@ -200,6 +233,8 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     spec = W.CONFIGS["c2_bert_base_ffn_up"][0]
+    if args.pmc_sweep:
+        return pmc_sweep(torch, tw, W)
     if args.pmc_calibration:
         return pmc_calibration(torch, tw, W, spec, args.steps, args.transposed)
     res, w, info = bench_gemm(torch, tw, W, spec, args.steps, args.warmup)
