@@ -557,3 +557,63 @@ def test_full_size_workloads_transposed_on_sampled_rows(tw, cfg):
             assert float(Ct[torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
         del At, Ct
         torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ seeded random shapes, every boundary per shape
+def _random_case(seed):
+    """Shape, G, dtype and mask recipe drawn from a seeded generator: M spans one to several row blocks with a
+    ragged tail, K spans the resident and both streamed regimes, N spans one to a dozen tiles."""
+    rng = np.random.default_rng(77000 + seed)
+    M = int(rng.choice([1, 7, 31, 64, 65, 130, 257, 333]))
+    K = int(rng.choice([16, 40, 129, 384, 770, 1100, 1536, 1544, 2050, 3000]))
+    G = int(rng.choice([32, 64, 128]))
+    N = int(rng.integers(8, 12 * G))
+    dtype = "f16" if rng.random() < 0.6 else "bf16"
+    cp = float(rng.choice([0.0, 0.05, 0.3, 0.8]))
+    lo = float(rng.choice([0.0, 0.02, 0.1]))
+    hi = float(rng.choice([0.3, 0.6, 1.0]))
+    return M, K, N, G, dtype, cp, ("upow", lo, hi)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_shapes_all_boundaries(tw, seed):
+    M, K, N, G, dtype, cp, keep = _random_case(seed)
+    _say(f"random seed {seed}: M={M} K={K} N={N} G={G} {dtype} col_prune={cp} keep={keep}")
+    spec = W.small_spec(f"rand{seed}", M=M, K=K, N=N, G=G, dtype=dtype, col_prune=cp, keep=keep,
+                        seed_offset=88000 + seed)
+    w = W.generate(spec)
+    ref = tw_ref.masked_gemm(w.A, w.B, w.mask, dtype)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, G, dtype)
+    A = _device_A(tw, w.A, dtype)
+    At = _device_At(tw, w.A, dtype)
+    td = A.dtype
+    # row-major boundary
+    C = torch.full((M, N), float("nan"), dtype=td, device="cuda:0")
+    tw.tw_gemm(wt, A, C)
+    # transposed boundary, output with a padded row stride
+    ldct = (M + 7) // 8 * 8 + 8
+    Ctb = torch.full((N, ldct), float("nan"), dtype=td, device="cuda:0")
+    tw.tw_gemm_t(wt, At, Ctb[:, :M])
+    # fused epilogue on both
+    rng = np.random.default_rng(99000 + seed)
+    bbits = W.f32_to_bits(rng.standard_normal(N).astype(np.float32), dtype)
+    bias = tw.bits_to_tensor(bbits, dtype)
+    Cf = torch.full((M, N), float("nan"), dtype=td, device="cuda:0")
+    tw.tw_gemm_bias_act(wt, A, bias, "gelu", Cf)
+    Cft = torch.full((N, ldct), float("nan"), dtype=td, device="cuda:0")
+    tw.tw_gemm_t_bias_act(wt, At, bias, "relu", Cft[:, :M])
+    torch.cuda.synchronize()
+    ws = wt.workspace.view(torch.int32)[:4].cpu().tolist()
+    assert ws[0] == 0 and ws[1] == 0 and ws[3] == 0, f"workspace after the calls: {ws}"
+
+    got = _to_f64(C)
+    assert np.isfinite(got).all()
+    assert _rel_err(got, ref) <= TOL[dtype]
+    assert torch.equal(Ctb[:, :M].T.contiguous(), C), "the two boundaries differ in some bit"
+    assert bool(torch.isnan(Ctb[:, M:].float()).all().item()), "wrote outside Ct"
+    b64 = tw_ref.decode(bbits, dtype)
+    ref_g = tw_ref.bias_act(ref, b64, "gelu")
+    ref_r = tw_ref.bias_act(ref, b64, "relu")
+    assert _rel_err(_to_f64(Cf), ref_g) <= TOL[dtype]
+    assert _rel_err(_to_f64(Cft[:, :M]).T, ref_r) <= TOL[dtype]
+    assert bool(torch.isnan(Cft[:, M:].float()).all().item()), "wrote outside Ct (fused)"
