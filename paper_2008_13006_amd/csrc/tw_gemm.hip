@@ -28,16 +28,14 @@
 #include "tw_device.hpp"
 #include "tw_format.h"
 
-#if defined(TW_EXPERIMENT) && defined(TW_TRACE)
-#define TW_MARK() do { if (p.trace && nmark < 16) { unsigned long long t_ = __builtin_readcyclecounter(); \
-    if (lane == 0) p.trace[((long)blockIdx.x * kWaves + wave) * 16 + nmark] = (unsigned)t_; ++nmark; } } while (0)
+// Phase probe: a build with -DTW_PHASE_PROBE reads TW_SKIP from the environment at every call and leaves out
+// the phases whose bits are set (1: bringing A in, 2: the multiply loops, 4: the epilogue), so that the time of
+// each phase can be read off as a difference.  Its results are wrong by construction; the library that ships
+// is built without it, and then the tests below are constant-false.
+#ifdef TW_PHASE_PROBE
+#define TW_SKIPS(p, bit) (((p).skip & (bit)) != 0)
 #else
-#define TW_MARK() do {} while (0)
-#endif
-#if defined(TW_EXPERIMENT) && defined(TW_DBG_CONST)
-#define TWD(x) (TW_DBG_CONST)
-#else
-#define TWD(x) (x)
+#define TW_SKIPS(p, bit) false
 #endif
 
 namespace {
@@ -82,9 +80,8 @@ struct TwGemmParams {
     uint64_t off_ew_ptr, off_ew_k, off_ew_v;
     int has_ew;                 // the blob carries an element-wise residual (TEW)
     unsigned urow_off;          // LDS offset of the loading waves' row lists (transposed, streamed K, few tiles), 0: none
-#ifdef TW_EXPERIMENT
-    int dbg;  // bit0: no A load, bit1: no main loop, bit2: no epilogue
-    unsigned* trace;  // per wave 16 clock samples
+#ifdef TW_PHASE_PROBE
+    int skip;
 #endif
 };
 
@@ -314,7 +311,7 @@ __device__ __forceinline__ void prefetch_first_steps(StepRegs<NCB>& rg, const un
 template <int DT, int MS, int NCB>
 __device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], StepRegs<NCB>& rg, const unsigned char* at,
                                           unsigned at_pitch, const unsigned char* goff_tile,
-                                          const unsigned char* bvals_tile, int s0, int s1, int lane_in, int dbg = 0) {
+                                          const unsigned char* bvals_tile, int s0, int s1, int lane_in) {
     const int lane = fresh(lane_in);
     // lane l: 16-lane block b = l/16 covers rows 16*(b%2).. of the 32-row block, contraction half h = l/32;
     // inside the block, lane j addresses the K row of slot 8h + 4r + j/4 at row quad j%4
@@ -350,9 +347,6 @@ __device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], StepRegs<NC
     auto step = [&](int i, int s) {
         // the three stages keep this order: left alone, the instruction scheduler sinks the loads of
         // later steps next to their first use and the prefetch distance is lost
-#ifdef TW_EXPERIMENT
-        if (!(TWD(dbg) & 128))
-#endif
         gather(a[(i + 1) & 1], rg.kk[(i + 1) % kIdxAhead]);
         __builtin_amdgcn_sched_barrier(0);
         // the request for a column block of step s+kPrefetch follows the MFMAs that read its registers:
@@ -365,15 +359,9 @@ __device__ __forceinline__ void run_steps(tw_f32x16 (&acc)[MS][NCB], StepRegs<NC
             for (int ms = 0; ms < MS; ++ms)
                 acc[ms][cb] = tw_mfma<DT>(a[i & 1][ms], rg.bq[i % kPrefetch][cb], acc[ms][cb]);
             __builtin_amdgcn_sched_barrier(0);
-#ifdef TW_EXPERIMENT
-            if (!(TWD(dbg) & 64))
-#endif
             rg.bq[i % kPrefetch][cb] = *(const tw_u16x8*)(bnext + cb * 1024);
             __builtin_amdgcn_sched_barrier(0);
         }
-#ifdef TW_EXPERIMENT
-        if (!(TWD(dbg) & 64))
-#endif
         issue_k<NCB>(rg, i % kIdxAhead, gk, s + kIdxAhead, last);
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -594,9 +582,6 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
             tw_compiler_fence();
             if (P + 1 < NP) write_pass(P + 1);
             tw_compiler_fence();
-#ifdef TW_EXPERIMENT
-            if (!(TWD(p.dbg) & 512))
-#endif
 #pragma unroll
             for (int l = 0; l < kWinLines; ++l) {
                 if (okl[l] && 8 * P < rows_left) {
@@ -604,28 +589,15 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
                     *(tw_u32x4_a2*)(cptr + (long)(8 * P) * p.ldc + l * kLineCols) = tw_u32x4{a.x, a.y, b.x, b.y};
                 }
             }
-#ifdef TW_EXPERIMENT
-            if (!(TWD(p.dbg) & 8))
-#endif
-            {
-                if (g_first >= 0) {                          // wave-uniform
-                    if (inF && 8 * P < rag_left) rptr[(long)(8 * P) * p.ldc + colF] = eF;
-                }
-                if (g_last >= 0) {
-                    if (inL && 8 * P < rag_left) rptr[(long)(8 * P) * p.ldc + colL] = eL;
-                }
+            if (g_first >= 0) {                              // wave-uniform
+                if (inF && 8 * P < rag_left) rptr[(long)(8 * P) * p.ldc + colF] = eF;
+            }
+            if (g_last >= 0) {
+                if (inL && 8 * P < rag_left) rptr[(long)(8 * P) * p.ldc + colL] = eL;
             }
             // At most a few of this wave's stores stay in flight: a long queue of stores in the CU's memory
             // pipeline holds up the loads of the waves that are multiplying (no load of this wave is pending here).
-#ifdef TW_EXPERIMENT
-            if (TWD(p.dbg) & 4096) {} else
-#endif
             asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-#ifdef TW_EXPERIMENT
-            if (TWD(p.dbg) & 4096) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (TWD(p.dbg) & 8192) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            if (TWD(p.dbg) & 16384) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-#endif
         }
         tw_compiler_fence();
     }
@@ -885,11 +857,6 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
     volatile int* misc = (volatile int*)(smem + p.misc_off);
     const int* step_ptr = (const int*)(p.blob + p.off_step_ptr);
 
-#ifdef TW_EXPERIMENT
-    if (TWD(p.dbg) & 16) return;
-    int nmark = 0;
-#endif
-    TW_MARK();
     // The loop over the workgroup's items.  ROLE 0: every wave does the same (MODE 0 and 1); with MODE 2
     // the multiplying waves (ROLE 1) and the loading waves (ROLE 2) run copies of their own, with the
     // same barriers, so that neither carries the other's registers.
@@ -923,19 +890,11 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             if (lane == 0) i = atomicAdd((int*)&misc[1], 1);
             int ti = seg + uni(i) * p.n_seg;
             TileU next = fetch_tile(p, ti < p.T ? ti : 0);
-#ifdef TW_EXPERIMENT
-            if (!(TWD(p.dbg) & 1))
-#endif
-            {
+            if (!TW_SKIPS(p, 1)) {
                 if constexpr (TRANS) load_at_block<MS, 12>(p, smem, row0, 0, p.K, wave, lane, tid);
                 else load_a_block<MS, 12, kPairResident>(p, smem, row0, 0, p.K, wave, lane, tid);
             }
-            TW_MARK();
             __syncthreads();
-            TW_MARK();
-#ifdef TW_EXPERIMENT
-            if (TWD(p.dbg) & 32) ti = p.T;
-#endif
             while (ti < p.T) {
                 const TileU d = next;
                 // claim the next tile now so that its descriptor arrives during this tile's work
@@ -955,37 +914,14 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                                           p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
                 tw_f32x16 acc[MS][NCB];
                 zero_acc<MS, NCB>(acc);
-#ifdef TW_EXPERIMENT
-                if (!(TWD(p.dbg) & 2))
-#endif
-                run_steps<DT, MS, NCB>(acc, rg, smem, p.at_pitch, p.blob + p.off_goff + (long)d.first_step * 32,
-                                       p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane
-#ifdef TW_EXPERIMENT
-                                       , p.dbg
-#endif
-                                       );
+                if (!TW_SKIPS(p, 2))
+                    run_steps<DT, MS, NCB>(acc, rg, smem, p.at_pitch, p.blob + p.off_goff + (long)d.first_step * 32,
+                                           p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
                 if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, acc, smem, p.at_pitch, lane);
-#if defined(TW_EXPERIMENT) && defined(TW_DBG_CONST)
-                if (TW_DBG_CONST & 4) {   // keep the products alive when the epilogue is compiled out
-                    float sink = 0.f;
-#pragma unroll
-                    for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                        for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) sink += acc[ms][cb][r];
-                    if (sink == 1.2345e-30f) p.C[lane] = 1;
-                }
-#endif
-                TW_MARK();
-#ifdef TW_EXPERIMENT
-                if (!(TWD(p.dbg) & 4))
-#endif
-                {
+                if (!TW_SKIPS(p, 4)) {
                     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                     else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 }
-                TW_MARK();
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
         } else if constexpr (MODE == 2) {
@@ -1030,11 +966,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     }
                 };
                 auto issue_or_zero = [&](ARegs<PB>& ar, int c, int r0) {
-                    if (c < p.n_chunks
-#ifdef TW_EXPERIMENT
-                        && !(TWD(p.dbg) & 1)
-#endif
-                    ) {
+                    if (c < p.n_chunks && !TW_SKIPS(p, 1)) {
                         if (use_rows)
                             at_issue_rows<PB>(p, ar, r0, c * p.k_chunk, my_rows + c * kListEntries, uni(my_cnt[c]), lw, lane, NLD);
                         else
@@ -1045,11 +977,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     }
                 };
                 auto commit = [&](const ARegs<PB>& ar, int c) {
-                    if (c < p.n_chunks
-#ifdef TW_EXPERIMENT
-                        && !(TWD(p.dbg) & 1024)
-#endif
-                    ) {
+                    if (c < p.n_chunks) {
                         if (use_rows)
                             at_commit_rows<PB>(p, ar, smem + (c & 1) * p.abuf_bytes, my_rows + c * kListEntries, uni(my_cnt[c]), lw,
                                                lane, NLD);
@@ -1121,11 +1049,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     }
                 };
                 auto steps_of = [&](int c) {
-                    if (active && b0 < b1
-#ifdef TW_EXPERIMENT
-                        && !(TWD(p.dbg) & 2)
-#endif
-                    )
+                    if (active && b0 < b1 && !TW_SKIPS(p, 2))
                         run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, b0, b1, lane);
                     // on to chunk c+1
                     b0 = b1; b1 = b2;
@@ -1142,10 +1066,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 }
                 if (tid == 0) misc[2] = my_next;   // requested at the start of the item: here by now
                 __syncthreads();
-#ifdef TW_EXPERIMENT
-                if (!(TWD(p.dbg) & 4))
-#endif
-                if (active) {
+                if (active && !TW_SKIPS(p, 4)) {
                     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                     else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 }
@@ -1486,9 +1407,8 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt; p.urow_off = 0;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
     if (p.has_ew && pl.mode != 0) return TW_ERR_UNSUPPORTED;
-#ifdef TW_EXPERIMENT
-    p.dbg = getenv("TW_DBG") ? atoi(getenv("TW_DBG")) : 0;
-    p.trace = getenv("TW_TRACE_PTR") ? (unsigned*)strtoull(getenv("TW_TRACE_PTR"), nullptr, 16) : nullptr;
+#ifdef TW_PHASE_PROBE
+    p.skip = getenv("TW_SKIP") ? atoi(getenv("TW_SKIP")) : 0;
 #endif
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), pl.lds_bytes, stream, p);
@@ -1569,10 +1489,8 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
         const unsigned need = (kWaves / 2) * (unsigned)h->n_chunks * (8 * 12 + 2) * 2;
         if (lds_bytes + need <= kLdsLimit) { p.urow_off = lds_bytes; lds_bytes += need; }
     }
-#ifdef TW_EXPERIMENT
-    if (getenv("TW_NO_ROWLISTS")) { p.urow_off = 0; }
-    p.dbg = getenv("TW_DBG") ? atoi(getenv("TW_DBG")) : 0;
-    p.trace = nullptr;
+#ifdef TW_PHASE_PROBE
+    p.skip = getenv("TW_SKIP") ? atoi(getenv("TW_SKIP")) : 0;
 #endif
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), lds_bytes, stream, p);
