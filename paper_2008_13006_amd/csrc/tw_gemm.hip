@@ -1105,7 +1105,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 return (p.K - k0) < p.k_chunk ? (p.K - k0) : p.k_chunk;
             };
             auto issue_or_zero = [&](ARegs<AB>& ar, int c) {
-                if (c < p.n_chunks) {
+                if (c < p.n_chunks && !TW_SKIPS(p, 1)) {
                     stage_issue<MSB, AB, TRANS>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
                 } else {
 #pragma unroll
@@ -1114,16 +1114,29 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             };
             // first steps of chunk c (b0), c+1 (b1) and c+2 (b2), read one chunk ahead with scalar loads
             int b0 = fetch_int(sp, 0), b1 = fetch_int(sp, 1), b2 = fetch_int(sp, p.n_chunks < 2 ? p.n_chunks : 2);
-            auto steps_of = [&](int c) {
-                if (active && b0 < b1) {
-                    StepRegs<NCB> rg;
-                    prefetch_first_steps<NCB>(rg, gt, bt, b0, b1, lane);
-                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, b0, b1,
-                                           lane);
+            // the first steps of a chunk are requested at the end of the previous chunk's steps, so they arrive
+            // while the chunk after it is written to LDS and the workgroup meets at the barrier
+            StepRegs<NCB> rg;
+            auto prefetch_steps = [&](int c0, int c1) {
+                if (active && c0 < c1) {
+                    prefetch_first_steps<NCB>(rg, gt, bt, c0, c1, lane);
+                } else {                               // defined on every path
+#pragma unroll
+                    for (int i = 0; i < kIdxAhead; ++i) rg.kk[i] = 0u;
+#pragma unroll
+                    for (int i = 0; i < prefetch_depth<NCB>(); ++i)
+#pragma unroll
+                        for (int cb = 0; cb < NCB; ++cb) rg.bq[i][cb] = tw_u16x8{0, 0, 0, 0, 0, 0, 0, 0};
                 }
+            };
+            auto steps_of = [&](int c) {
+                if (active && b0 < b1 && !TW_SKIPS(p, 2))
+                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, b0, b1, lane);
                 b0 = b1; b1 = b2;
                 b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
+                if (c + 1 < p.n_chunks) prefetch_steps(b0, b1); else prefetch_steps(0, 0);
             };
+            prefetch_steps(b0, b1);
             auto commit = [&](const ARegs<AB>& ar, int c) {
                 if (c < p.n_chunks) stage_commit<MSB, AB, TRANS>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), wave, lane);
             };
@@ -1155,7 +1168,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     __syncthreads();
                 }
             }
-            if (active) {
+            if (active && !TW_SKIPS(p, 4)) {
                 if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
             }
@@ -1239,15 +1252,21 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     };
     int msb = 2, tpw = kWaves;
     int nmb, nseg;
+    bool sets_of_four = false;
     if (lds_need(2, h->k_chunk, buffers) > kLdsLimit) msb = 1;
-    if (msb == 2 && !(transposed && !resident)) {   // (the streamed transposed kernels exist for 64 tokens only)
-        // 64-row blocks halve the traffic of packed B, but only pay when they still fill the GPU
-        if (items_for(2, tpw, nmb, nseg) < n_cu) msb = 1;
+    if (msb == 2 && items_for(2, tpw, nmb, nseg) < n_cu) {
+        // Too few 64-row blocks to fill the GPU.  Streamed K: sets of four tiles (loading waves, below) double
+        // the items and keep the 64-row blocks, which halve the traffic of packed B and keep the loads of A
+        // out of the multiplying waves; measured 20 % faster than 32-row blocks on the skewed FFN-down of
+        // BERT-large (M = 8192, K = 4096, T = 8).  Otherwise 32-row blocks
+        // (the streamed transposed kernels exist for 64 tokens only).
+        if (!resident && T > kWaves / 2 && items_for(2, kWaves / 2, nmb, nseg) >= n_cu) sets_of_four = true;
+        else if (!(transposed && !resident)) msb = 1;
     }
     if (transposed && !resident && msb != 2) return TW_ERR_UNSUPPORTED;
     pl.mode = resident ? 0 : 1;
     pl.ms = msb;
-    if (!resident && msb == 2 && T <= kWaves / 2) {   // few tiles: half of the waves only load A
+    if (!resident && msb == 2 && (T <= kWaves / 2 || sets_of_four)) {   // half of the waves only load A
         pl.mode = 2;
         tpw = kWaves / 2;
     }
@@ -1485,7 +1504,9 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     // few tiles, streamed: the loading waves read only the K rows the tiles keep, from lists they hold in LDS
     p.urow_off = 0;
     unsigned lds_bytes = pl.lds_bytes;
-    if (pl.mode == 2) {
+    // (the blob's row lists are per set of TW_SET_TILES(T) tiles: with sets of four out of more than four tiles
+    // the loading waves bring in whole chunks)
+    if (pl.mode == 2 && h->T <= kWaves / 2) {
         const unsigned need = (kWaves / 2) * (unsigned)h->n_chunks * (8 * 12 + 2) * 2;
         if (lds_bytes + need <= kLdsLimit) { p.urow_off = lds_bytes; lds_bytes += need; }
     }

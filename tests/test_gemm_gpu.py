@@ -617,3 +617,42 @@ def test_random_shapes_all_boundaries(tw, seed):
     assert _rel_err(_to_f64(Cf), ref_g) <= TOL[dtype]
     assert _rel_err(_to_f64(Cft[:, :M]).T, ref_r) <= TOL[dtype]
     assert bool(torch.isnan(Cft[:, M:].float()).all().item()), "wrote outside Ct (fused)"
+
+
+def test_streamed_k_sets_of_four_tiles(tw):
+    """More than four tiles, K streamed, and too few 64-row blocks to give every compute unit one with eight tiles
+    per workgroup: the plan then carves sets of four tiles (half of the waves only load A).  20 tiles, 52 row
+    blocks: 3 sets of eight would make 156 items, 5 sets of four make 260."""
+    M, K, N, G, dtype = 3300, 1600, 660, 32, "f16"
+    _say(f"sets of four: M={M} K={K} N={N} G={G} {dtype}")
+    spec = W.small_spec("sets_of_four", M=M, K=K, N=N, G=G, dtype=dtype, col_prune=0.04, keep=("upow", 0.05, 0.6),
+                        seed_offset=9977)
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, G, dtype)
+    assert wt.info["T"] > 4
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([np.arange(0, 70), np.arange(M - 70, M), rng.integers(0, M, 260)]))
+    ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, w.mask, dtype)
+    ridx = torch.as_tensor(rows, device="cuda:0")
+    A = _device_A(tw, w.A, dtype)
+    C = torch.full((M, N), float("nan"), dtype=A.dtype, device="cuda:0")
+    tw.tw_gemm(wt, A, C)
+    At = _device_At(tw, w.A, dtype)
+    ldct = (M + 7) // 8 * 8 + 8
+    Ctb = torch.full((N, ldct), float("nan"), dtype=A.dtype, device="cuda:0")
+    tw.tw_gemm_t(wt, At, Ctb[:, :M])
+    bbits = W.f32_to_bits(rng.standard_normal(N).astype(np.float32), dtype)
+    Cf = torch.full((M, N), float("nan"), dtype=A.dtype, device="cuda:0")
+    tw.tw_gemm_bias_act(wt, A, tw.bits_to_tensor(bbits, dtype), "relu", Cf)
+    torch.cuda.synchronize()
+    ws = wt.workspace.view(torch.int32)[:4].cpu().tolist()
+    assert ws[0] == 0 and ws[1] == 0 and ws[3] == 0, f"workspace after the calls: {ws}"
+    assert bool(torch.isfinite(C.float()).all().item())
+    assert _rel_err(_to_f64(C[ridx]), ref) <= TOL[dtype]
+    assert torch.equal(Ctb[:, :M].T.contiguous(), C), "the two boundaries differ in some bit"
+    assert bool(torch.isnan(Ctb[:, M:].float()).all().item()), "wrote outside Ct"
+    ref_r = tw_ref.bias_act(ref, tw_ref.decode(bbits, dtype), "relu")
+    assert _rel_err(_to_f64(Cf[ridx]), ref_r) <= TOL[dtype]
+    pruned = np.flatnonzero(~w.mask.any(axis=0))
+    if len(pruned):
+        assert float(C[:, torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
