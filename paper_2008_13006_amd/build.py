@@ -26,26 +26,36 @@ def needs_build() -> bool:
     return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
 
 
+# (source, -D flags, object): tw_gemm.hip is compiled as its host code (part 0) and four groups of kernels
+# (parts 1..4: fp16 / bf16 x plain / fused epilogue), all at once
+UNITS = [("tw_pack.cpp", [], "tw_pack.cpp.o"), ("tw_dense.hip", [], "tw_dense.hip.o")] + [
+    ("tw_gemm.hip", [f"-DTW_PART={i}"], f"tw_gemm.part{i}.o") for i in range(5)]
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile for gfx950.  Packed-FP32 instruction selection is switched off for device code."""
     if not force and not needs_build():
         return LIB
-    objs = []
-    for src in SOURCES:
-        obj = os.path.join(CSRC, src + ".o")
+    procs = []
+    for src, defs, obj in UNITS:
         cmd = [hipcc(), "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wno-unused-command-line-argument"] + os.environ.get("TW_BUILD_FLAGS", "").split() + [
-               "-c", os.path.join(CSRC, src), "-o", obj]
+               "-Wno-unused-command-line-argument"] + defs + os.environ.get("TW_BUILD_FLAGS", "").split() + [
+               "-c", os.path.join(CSRC, src), "-o", os.path.join(CSRC, obj)]
         if verbose:
             print(" ".join(cmd), flush=True)
-        r = subprocess.run(cmd, capture_output=True, text=True)
-        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
-        if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{err}")
-        if verbose and err.strip():
+        procs.append((src, defs, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)))
+    failed = []
+    for src, defs, pr in procs:
+        _, stderr = pr.communicate()
+        err = "\n".join(l for l in stderr.splitlines() if "packed-fp32-ops" not in l)
+        if pr.returncode != 0:
+            failed.append(f"hipcc failed on {src} {' '.join(defs)}:\n{err}")
+        elif verbose and err.strip():
             print(err, file=sys.stderr)
-        objs.append(obj)
+    if failed:
+        raise RuntimeError("\n".join(failed))
+    objs = [os.path.join(CSRC, obj) for _, _, obj in UNITS]
     cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

@@ -843,9 +843,13 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 
 // MODE 0: the K extent of a row block of 32*MS rows is resident in LDS, waves pull whole tiles.
 // MODE 1: K streamed through two LDS buffers, row block of 32*MS rows, wave w owns tile 8*set + w.
-// MODE 2: K streamed, row block of 64 rows (MS = 2), for weights with at most four tiles: waves 0-3
-//         multiply (wave w owns tile 4*set + w), waves 4-7 do nothing but bring A into LDS, so the
-//         two kinds of work overlap instead of taking turns.
+// MODE 2: K streamed, row block of 64 rows (MS = 2), sets of four tiles: waves 0-3 multiply (wave w owns
+//         tile 4*set + w), waves 4-7 do nothing but bring A into LDS, so the two kinds of work overlap
+//         instead of taking turns (a wave's loads retire in order: a wave that waits for its packed B also
+//         waits for every request for A it made before).
+//         (Six multiplying and two loading waves were tried for weights of five or six tiles: the two
+//         loading waves cannot keep up with the transposing LDS writes of the row-major boundary, 9 % slower
+//         than MODE 1 on the FFN-down of BERT-base, and no gain on the transposed boundary.)
 template <int DT, int MS, int NCB, int MODE, bool FUSED, bool TRANS>
 __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -1192,6 +1196,68 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
     }
 }
 
+}  // namespace
+
+// ---- kernel tables
+// The kernels can be compiled as four translation units (-DTW_PART=1..4: fp16 / bf16 x plain / fused epilogue)
+// beside the host code (-DTW_PART=0), so that a build runs them in parallel; without TW_PART one unit holds
+// everything.  The tables hand out host-side kernel addresses, so no type of this file crosses a unit boundary.
+namespace tw_parts {
+template <int DT, bool FUSED> const void* pick_mode(int mode, int ms, int ncb);     // row-major boundary
+template <int DT, bool FUSED> const void* pick_mode_t(int mode, int ms, int ncb);   // transposed boundary
+}  // namespace tw_parts
+
+#if !defined(TW_PART) || TW_PART != 0
+namespace {
+template <int DT, int MS, int MODE, bool FUSED, bool TRANS>
+const void* pick_ncb(int ncb) {
+    switch (ncb) {
+        case 1: return (const void*)tw_gemm_kernel<DT, MS, 1, MODE, FUSED, TRANS>;
+        case 2: return (const void*)tw_gemm_kernel<DT, MS, 2, MODE, FUSED, TRANS>;
+        case 4: return (const void*)tw_gemm_kernel<DT, MS, 4, MODE, FUSED, TRANS>;
+        default: return nullptr;
+    }
+}
+}  // namespace
+namespace tw_parts {
+template <int DT, bool FUSED>
+const void* pick_mode(int mode, int ms, int ncb) {
+    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, false>(ncb) : pick_ncb<DT, 1, 0, FUSED, false>(ncb);
+    if (mode == 1) return ms == 2 ? pick_ncb<DT, 2, 1, FUSED, false>(ncb) : pick_ncb<DT, 1, 1, FUSED, false>(ncb);
+    return pick_ncb<DT, 2, 2, FUSED, false>(ncb);
+}
+// transposed boundary: resident K with blocks of 64 or 32 tokens, streamed K always with 64
+template <int DT, bool FUSED>
+const void* pick_mode_t(int mode, int ms, int ncb) {
+    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, true>(ncb) : pick_ncb<DT, 1, 0, FUSED, true>(ncb);
+    if (mode == 1) return pick_ncb<DT, 2, 1, FUSED, true>(ncb);
+    return pick_ncb<DT, 2, 2, FUSED, true>(ncb);
+}
+}  // namespace tw_parts
+#endif
+
+#ifdef TW_PART
+#define TW_TABLES(KW, DT, FUSED)                                            \
+    KW template const void* tw_parts::pick_mode<DT, FUSED>(int, int, int);  \
+    KW template const void* tw_parts::pick_mode_t<DT, FUSED>(int, int, int);
+#if TW_PART == 0
+TW_TABLES(extern, TW_F16, false) TW_TABLES(extern, TW_F16, true) TW_TABLES(extern, TW_BF16, false) TW_TABLES(extern, TW_BF16, true)
+#elif TW_PART == 1
+TW_TABLES(, TW_F16, false)
+#elif TW_PART == 2
+TW_TABLES(, TW_F16, true)
+#elif TW_PART == 3
+TW_TABLES(, TW_BF16, false)
+#elif TW_PART == 4
+TW_TABLES(, TW_BF16, true)
+#else
+#error "TW_PART is 0 (host code) or 1..4 (kernels)"
+#endif
+#endif
+
+#if !defined(TW_PART) || TW_PART == 0
+namespace {
+
 // C[m, n] = act(bias[n]) (zero without a bias) for a weight with no surviving column.
 template <int DT>
 __global__ void tw_fill_kernel(unsigned short* C, long ldc, int M, int N, const unsigned short* bias, int act) {
@@ -1282,38 +1348,14 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     return TW_OK;
 }
 
-typedef void (*KernelFn)(const TwGemmParams);
-
-template <int DT, int MS, int MODE, bool FUSED, bool TRANS>
-KernelFn pick_ncb(int ncb) {
-    switch (ncb) {
-        case 1: return tw_gemm_kernel<DT, MS, 1, MODE, FUSED, TRANS>;
-        case 2: return tw_gemm_kernel<DT, MS, 2, MODE, FUSED, TRANS>;
-        case 4: return tw_gemm_kernel<DT, MS, 4, MODE, FUSED, TRANS>;
-        default: return nullptr;
-    }
-}
-
-template <int DT, bool FUSED>
-KernelFn pick_mode(int mode, int ms, int ncb) {
-    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, false>(ncb) : pick_ncb<DT, 1, 0, FUSED, false>(ncb);
-    if (mode == 1) return ms == 2 ? pick_ncb<DT, 2, 1, FUSED, false>(ncb) : pick_ncb<DT, 1, 1, FUSED, false>(ncb);
-    return pick_ncb<DT, 2, 2, FUSED, false>(ncb);
-}
-
-// transposed boundary: resident K with blocks of 64 or 32 tokens, streamed K always with 64
-template <int DT, bool FUSED>
-KernelFn pick_mode_t(int mode, int ms, int ncb) {
-    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, true>(ncb) : pick_ncb<DT, 1, 0, FUSED, true>(ncb);
-    if (mode == 1) return pick_ncb<DT, 2, 1, FUSED, true>(ncb);
-    return pick_ncb<DT, 2, 2, FUSED, true>(ncb);
-}
-KernelFn pick_kernel_t(int dt, int mode, int ms, int ncb, bool fused) {
+// the kernel for (dtype, mode, MS, NCB, fused epilogue): a host-side address for hipLaunchKernel and hipFuncSetAttribute
+const void* pick_kernel_t(int dt, int mode, int ms, int ncb, bool fused) {
+    using namespace tw_parts;
     if (fused) return dt == TW_F16 ? pick_mode_t<TW_F16, true>(mode, ms, ncb) : pick_mode_t<TW_BF16, true>(mode, ms, ncb);
     return dt == TW_F16 ? pick_mode_t<TW_F16, false>(mode, ms, ncb) : pick_mode_t<TW_BF16, false>(mode, ms, ncb);
 }
-
-KernelFn pick_kernel(int dt, int mode, int ms, int ncb, bool fused) {
+const void* pick_kernel(int dt, int mode, int ms, int ncb, bool fused) {
+    using namespace tw_parts;
     if (fused) return dt == TW_F16 ? pick_mode<TW_F16, true>(mode, ms, ncb) : pick_mode<TW_BF16, true>(mode, ms, ncb);
     return dt == TW_F16 ? pick_mode<TW_F16, false>(mode, ms, ncb) : pick_mode<TW_BF16, false>(mode, ms, ncb);
 }
@@ -1401,11 +1443,11 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     int rc = make_plan(h, M, n_cu, pl);
     if (rc) return rc;
     const bool fused = bias != nullptr || act != TW_ACT_NONE;
-    KernelFn fn = pick_kernel(h->dtype, pl.mode, pl.ms, h->ncb, fused);
+    const void* fn = pick_kernel(h->dtype, pl.mode, pl.ms, h->ncb, fused);
     if (!fn) return TW_ERR_UNSUPPORTED;
     const int variant = pl.mode == 2 ? 4 : 2 * pl.mode + (pl.ms == 2 ? 0 : 1);      // 0..4
     const int kernel_id = (fused ? 30 : 0) + (h->dtype == TW_F16 ? 0 : 15) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
-    rc = ensure_lds(dev, kernel_id, (const void*)fn);
+    rc = ensure_lds(dev, kernel_id, fn);
     if (rc) return rc;
 
     TwGemmParams p;
@@ -1430,8 +1472,8 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.skip = getenv("TW_SKIP") ? atoi(getenv("TW_SKIP")) : 0;
 #endif
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), pl.lds_bytes, stream, p);
-    return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
+    void* args[] = {(void*)&p};
+    return hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, pl.lds_bytes, stream) == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 
 extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat, void* Ct,
@@ -1476,11 +1518,11 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     Plan pl;
     int rc = make_plan(h, M, n_cu, pl, /*transposed=*/true);
     if (rc) return rc;
-    KernelFn fn = pick_kernel_t(h->dtype, pl.mode, pl.ms, h->ncb, fused);
+    const void* fn = pick_kernel_t(h->dtype, pl.mode, pl.ms, h->ncb, fused);
     if (!fn) return TW_ERR_UNSUPPORTED;
     const int variant = pl.mode == 0 ? (pl.ms == 2 ? 0 : 1) : pl.mode + 1;          // 0..3
     const int kernel_id = 60 + (fused ? 24 : 0) + (h->dtype == TW_F16 ? 0 : 12) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
-    rc = ensure_lds(dev, kernel_id, (const void*)fn);
+    rc = ensure_lds(dev, kernel_id, fn);
     if (rc) return rc;
 
     TwGemmParams p;
@@ -1514,8 +1556,8 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.skip = getenv("TW_SKIP") ? atoi(getenv("TW_SKIP")) : 0;
 #endif
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), lds_bytes, stream, p);
-    return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
+    void* args[] = {(void*)&p};
+    return hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, lds_bytes, stream) == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 
 // ---- the transposes at the two ends of a network that runs on the transposed boundary (Sec. VI) ----
@@ -1544,3 +1586,4 @@ extern "C" int tw_transpose(const void* src, int ld_src, int rows, int cols, voi
                        (const unsigned short*)src, (long)ld_src, rows, cols, (unsigned short*)dst, (long)ld_dst);
     return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
+#endif  // host code
