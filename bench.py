@@ -269,7 +269,7 @@ def main() -> int:
         line["cpu_baseline"] = cpu_baseline(W, w, spec)
     if args.report:
         rows = []
-        for cfg, specs in W.CONFIGS.items():
+        for cfg, specs in list(W.CONFIGS.items()) + [("c2_fixed_grid_mask", [W.C2_FIXED_GRID])]:
             for s in specs:
                 r, _, _ = bench_gemm(torch, tw, W, s, max(20, args.steps // 4), 5, with_warm=True)
                 r["config"] = cfg

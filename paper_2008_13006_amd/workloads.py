@@ -68,6 +68,8 @@ class GemmSpec:
     keep: Tuple = ("const", 0.5)    # ("const", f) | ("upow", lo, hi) | ("zipf", lo, hi, s)
     sparsity: Optional[float] = None  # overall target (zeros / (K*N)); None = whatever keep gives
     seed_offset: int = 0
+    grid: str = "regrouped"         # "regrouped": tiles of G SURVIVING columns | "fixed": the survivors of every
+                                    # block of G original columns form a tile (the other description in Sec. IV-A)
 
 
 def _bert_base(M: int) -> List[GemmSpec]:
@@ -161,7 +163,7 @@ def _keep_fractions(kind: Tuple, widths: np.ndarray, K: int, N: int, target_spar
 
 
 def tw_mask_from_scores(absB: np.ndarray, G: int, col_prune: float, keep: Tuple,
-                        target_sparsity, rng) -> Tuple[np.ndarray, dict]:
+                        target_sparsity, rng, grid: str = "regrouped") -> Tuple[np.ndarray, dict]:
     """Column pruning, re-grouping, then per-group row pruning (Sec. IV-A), with L1 scores.
 
     absB: float64 |B| of the already rounded weights.  Ties: the smaller index is the more
@@ -172,8 +174,12 @@ def tw_mask_from_scores(absB: np.ndarray, G: int, col_prune: float, keep: Tuple,
     order = np.argsort(col_score, kind="stable")          # ascending, ties -> smaller n first
     pruned_cols = np.sort(order[:n_prune])
     kept_cols = np.setdiff1d(np.arange(N), pruned_cols)
-    T = (len(kept_cols) + G - 1) // G
-    groups = [kept_cols[t * G:(t + 1) * G] for t in range(T)]
+    if grid == "fixed":
+        groups = [kept_cols[(kept_cols >= t * G) & (kept_cols < (t + 1) * G)] for t in range((N + G - 1) // G)]
+        groups = [g for g in groups if len(g)]
+    else:
+        groups = [kept_cols[t * G:(t + 1) * G] for t in range((len(kept_cols) + G - 1) // G)]
+    T = len(groups)
     widths = np.array([len(g) for g in groups], dtype=np.float64)
     f = _keep_fractions(keep, widths, K, N, target_sparsity, rng)
     mask = np.zeros((K, N), dtype=np.uint8)
@@ -225,7 +231,7 @@ def generate(spec: GemmSpec, with_A: bool = True, M: Optional[int] = None) -> Wo
     if spec.a_dist == "smallint":
         # break the many ties of integer weights deterministically without touching B itself
         absB = absB + 1e-3 * rng.random(absB.shape)
-    mask, info = tw_mask_from_scores(absB, spec.G, spec.col_prune, spec.keep, spec.sparsity, rng)
+    mask, info = tw_mask_from_scores(absB, spec.G, spec.col_prune, spec.keep, spec.sparsity, rng, spec.grid)
     info.update(seed=BASE_SEED + spec.seed_offset, M=rows, K=spec.K, N=spec.N, G=spec.G,
                 dtype=spec.dtype, name=spec.name)
     return Workload(spec=spec, A=A_bits, B=B_bits, mask=mask, info=info)
@@ -252,6 +258,13 @@ def sweep_spec(G: int, sparsity: float, M: int = 16384, K: int = 768, N: int = 3
     return GemmSpec(name=f"sweep_G{G}_s{int(round(sparsity * 1000))}", M=M, K=K, N=N, dtype=dtype, G=G,
                     col_prune=cp, keep=("upow", lo, hi), sparsity=sparsity,
                     seed_offset=7000 + G + int(round(sparsity * 1000)))
+
+
+# The headline workload under the other description of the pattern in Sec. IV-A: B is cut into tiles of G original
+# columns first and every tile prunes columns and rows of its own, so a tile's span is a whole number of 128-byte
+# lines of C.  Reported next to the five workloads, not one of them.
+C2_FIXED_GRID = GemmSpec(name="ffn_up_768x3072_fixed_grid", M=16384, K=768, N=3072, dtype=F16, G=128, col_prune=0.05,
+                         keep=("upow", 0.10, 0.50), sparsity=0.75, seed_offset=2000, grid="fixed")
 
 
 def nonzero_flops(mask: np.ndarray, M: int) -> int:

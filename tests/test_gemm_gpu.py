@@ -244,6 +244,14 @@ def test_full_size_workloads_on_sampled_rows(tw, cfg):
         torch.cuda.empty_cache()
 
 
+def test_full_size_fixed_grid_mask_on_sampled_rows(tw):
+    """The headline shape with tiles cut on a fixed grid of G original columns (spans are whole lines of C)."""
+    spec = W.C2_FIXED_GRID
+    _say(f"fixed grid / {spec.name} M={spec.M} K={spec.K} N={spec.N}")
+    _check_tw(tw, W.generate(spec), rows=_sample_rows(spec.M))
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ fused epilogue: act(A.(B*mask) + bias)
 def _bias_bits(N, dtype, seed):
     rng = np.random.default_rng(seed)

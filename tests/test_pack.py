@@ -52,6 +52,17 @@ def test_pack_matches_oracle_on_the_paper_shaped_workloads(cfg):
         assert inf["T"] == w.info["T"]
 
 
+def test_pack_matches_oracle_on_the_fixed_grid_mask():
+    """Tiles cut on a fixed grid of G original columns (the other description in Sec. IV-A): one tile per grid
+    block, and every span starts at its block's first surviving column."""
+    spec = W.C2_FIXED_GRID
+    w = W.generate(spec, with_A=False)
+    inf = _check_against_oracle(w.mask, w.B, spec.G, spec.dtype)
+    assert inf["T"] == w.info["T"] == spec.N // spec.G
+    ts = tw_ref.tile_structure(w.mask, spec.G)
+    assert all(spec.G * t <= int(ts["tile_span"][t]) < spec.G * (t + 1) for t in range(1, ts["T"]))
+
+
 def test_pack_matches_oracle_bert_base_layer():
     for spec in W.CONFIGS["c3_bert_base_layer"]:
         w = W.generate(spec, with_A=False)
