@@ -138,6 +138,28 @@ int tw_prune(const void* B, int ldb, int K, int N, int G, tw_dtype dt, double co
  * zeroed buffer serves any number of calls that do not overlap in time. */
 int tw_gemm_workspace(const void* blob_host, int M, size_t* ws_bytes);
 
+/* How tw_gemm (transposed = 0) or tw_gemm_t (transposed != 0) would run this weight on M rows (tokens) on a GPU
+ * with n_cu compute units: the host-side decision only, no GPU call.  Sec. VI ("Load Imbalance Mitigation",
+ * "Tiling") leaves the thread-block shape and the distribution of tiles to the implementation; this is this one's. */
+typedef struct tw_plan_t {
+    int32_t mode;            /* 0: the K extent of a row block stays in on-chip memory, waves pull whole tiles;
+                                1: K streamed in chunks, a wave per tile;
+                                2: K streamed, four waves multiply (a tile each), four only load A */
+    int32_t rows_per_block;  /* rows of A (tokens) of a work item: 64 or 32 */
+    int32_t tiles_per_set;   /* streamed K: tiles a workgroup holds (8 or 4); 0 with mode 0 */
+    int32_t n_row_blocks;    /* ceil(M / rows_per_block) */
+    int32_t n_sets;          /* mode 0: workgroups that share the tiles of a row block; else sets of tiles */
+    int32_t n_items;         /* work items = n_row_blocks * n_sets */
+    int32_t grid;            /* workgroups launched: min(n_items, n_cu), each pulls items until none is left */
+    uint32_t lds_bytes;      /* on-chip memory per workgroup */
+    int32_t row_lists;       /* tw_gemm_t, mode 2: the loading waves read only the K rows that the tiles keep */
+    int32_t reserved[7];
+} tw_plan_t;
+/* Errors: TW_ERR_ARG (null pointer, negative M, n_cu <= 0), TW_ERR_BUF (not a blob of this format version),
+ * TW_ERR_UNSUPPORTED (what tw_gemm / tw_gemm_t would refuse for this blob and M).  M = 0 or a blob without
+ * tiles gives an all-zero plan. */
+int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transposed, tw_plan_t* plan);
+
 /* C = A . (B * mask) (Sec. VI, Listing 1's role).  Enqueues on `hip_stream` (a hipStream_t, may be
  * NULL for the default stream) and returns.
  *   blob_host  host copy of the blob (read during the call only)

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libtw.so")
 TW_F16, TW_BF16 = 0, 1
 _DT = {"f16": TW_F16, "bf16": TW_BF16}
 
-SYMBOLS = ["tw_pack_size", "tw_pack", "tw_pack_tew_size", "tw_pack_tew", "tw_restore_ew", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm",
+SYMBOLS = ["tw_pack_size", "tw_pack", "tw_pack_tew_size", "tw_pack_tew", "tw_restore_ew", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm_plan", "tw_gemm",
            "tw_gemm_bias_act", "tw_gemm_t", "tw_gemm_t_bias_act", "tw_transpose", "tw_dense_gemm", "tw_dense_gemm_bias_act", "tw_strerror",
            "tw_version"]
 TW_ACT_NONE, TW_ACT_RELU, TW_ACT_GELU = 0, 1, 2
@@ -43,6 +43,13 @@ class TwInfo(ctypes.Structure):
                 ("off_tile_span", ctypes.c_uint64), ("off_sched_order", ctypes.c_uint64)]
 
 
+class TwPlan(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int32), ("rows_per_block", ctypes.c_int32), ("tiles_per_set", ctypes.c_int32),
+                ("n_row_blocks", ctypes.c_int32), ("n_sets", ctypes.c_int32), ("n_items", ctypes.c_int32),
+                ("grid", ctypes.c_int32), ("lds_bytes", ctypes.c_uint32), ("row_lists", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 7)]
+
+
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -57,6 +64,7 @@ def _load() -> ctypes.CDLL:
     lib.tw_restore_ew.argtypes = [vp, i, i, i, i, vp, ctypes.c_double, vp]
     lib.tw_info.argtypes = [vp, ctypes.POINTER(TwInfo)]
     lib.tw_gemm_workspace.argtypes = [vp, i, ctypes.POINTER(sz)]
+    lib.tw_gemm_plan.argtypes = [vp, i, i, i, ctypes.POINTER(TwPlan)]
     lib.tw_gemm.argtypes = [vp, vp, vp, i, i, vp, i, vp, sz, vp]
     lib.tw_dense_gemm.argtypes = [vp, i, vp, i, vp, i, i, i, i, i, vp]
     lib.tw_gemm_bias_act.argtypes = [vp, vp, vp, i, i, vp, i, vp, i, vp, sz, vp]
@@ -188,6 +196,14 @@ def tw_info(blob: np.ndarray) -> Dict:
     out["tile_span"] = arr(ti.off_tile_span, T + 1)
     out["sched_order"] = arr(ti.off_sched_order, T)
     return out
+
+
+def tw_gemm_plan(blob: np.ndarray, M: int, n_cu: int = 256, transposed: bool = False) -> Dict:
+    """How tw_gemm / tw_gemm_t would run this weight on M rows on a GPU of n_cu compute units (host only)."""
+    assert blob.dtype == np.uint8 and blob.flags["C_CONTIGUOUS"]
+    pl = TwPlan()
+    _check(_lib.tw_gemm_plan(_np_ptr(blob), int(M), int(n_cu), int(bool(transposed)), ctypes.byref(pl)), "tw_gemm_plan")
+    return {f: getattr(pl, f) for f, _ in TwPlan._fields_ if f != "reserved"}
 
 
 # --------------------------------------------------------------------------- device side

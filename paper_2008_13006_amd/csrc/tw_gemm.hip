@@ -22,6 +22,7 @@
 
 #include <atomic>
 #include <cstdlib>
+#include <cstring>
 #include <type_traits>
 
 #include "../../include/tw.h"
@@ -1284,7 +1285,9 @@ struct Plan {
     int mode;       // kernel MODE
     int ms;         // the kernel's MS
     int n_mblocks, n_seg, n_items;
+    int tiles_per_set;   // streamed K: tiles a workgroup holds
     unsigned at_pitch, abuf_bytes, stage_off, misc_off, lds_bytes;
+    unsigned urow_off;   // transposed boundary, loading waves: LDS offset of their row lists (0: whole chunks are read)
 };
 
 constexpr unsigned kLdsLimit = 160 * 1024;
@@ -1345,6 +1348,15 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     pl.stage_off = buffers * pl.abuf_bytes;
     pl.misc_off = pl.stage_off + kWaves * kStageBytes;
     pl.lds_bytes = pl.misc_off + 16u;
+    pl.tiles_per_set = resident ? 0 : tpw;
+    // Transposed boundary, at most four tiles, streamed: the loading waves read only the K rows the tiles keep,
+    // from lists they hold in LDS.  (The blob's row lists are per set of TW_SET_TILES(T) tiles: with sets of four
+    // out of more than four tiles the loading waves bring in whole chunks.)
+    pl.urow_off = 0;
+    if (transposed && pl.mode == 2 && T <= kWaves / 2) {
+        const unsigned need = (kWaves / 2) * (unsigned)h->n_chunks * (8 * 12 + 2) * 2;
+        if (pl.lds_bytes + need <= kLdsLimit) { pl.urow_off = pl.lds_bytes; pl.lds_bytes += need; }
+    }
     return TW_OK;
 }
 
@@ -1398,6 +1410,28 @@ extern "C" int tw_gemm_workspace(const void* blob_host, int M, size_t* ws_bytes)
     const TwHeader* h = (const TwHeader*)blob_host;
     if (h->magic != TW_MAGIC || h->version != TW_FORMAT_VERSION) return TW_ERR_BUF;
     *ws_bytes = 256;
+    return TW_OK;
+}
+
+extern "C" int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transposed, tw_plan_t* plan) {
+    if (!blob_host || !plan || M < 0 || n_cu <= 0) return TW_ERR_ARG;
+    const TwHeader* h = (const TwHeader*)blob_host;
+    if (h->magic != TW_MAGIC || h->version != TW_FORMAT_VERSION) return TW_ERR_BUF;
+    memset(plan, 0, sizeof(*plan));
+    if (M == 0 || h->T == 0) return TW_OK;      // nothing to multiply: a fill kernel at most
+    Plan pl;
+    const int rc = make_plan(h, M, n_cu, pl, transposed != 0);
+    if (rc) return rc;
+    if (h->ew_nnz > 0 && pl.mode != 0) return TW_ERR_UNSUPPORTED;
+    plan->mode = pl.mode;
+    plan->rows_per_block = 32 * pl.ms;
+    plan->tiles_per_set = pl.tiles_per_set;
+    plan->n_row_blocks = pl.n_mblocks;
+    plan->n_sets = pl.n_seg;
+    plan->n_items = pl.n_items;
+    plan->grid = pl.n_items < n_cu ? pl.n_items : n_cu;
+    plan->lds_bytes = pl.lds_bytes;
+    plan->row_lists = pl.urow_off != 0;
     return TW_OK;
 }
 
@@ -1543,15 +1577,8 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
     if (p.has_ew && pl.mode != 0) return TW_ERR_UNSUPPORTED;
-    // few tiles, streamed: the loading waves read only the K rows the tiles keep, from lists they hold in LDS
-    p.urow_off = 0;
-    unsigned lds_bytes = pl.lds_bytes;
-    // (the blob's row lists are per set of TW_SET_TILES(T) tiles: with sets of four out of more than four tiles
-    // the loading waves bring in whole chunks)
-    if (pl.mode == 2 && h->T <= kWaves / 2) {
-        const unsigned need = (kWaves / 2) * (unsigned)h->n_chunks * (8 * 12 + 2) * 2;
-        if (lds_bytes + need <= kLdsLimit) { p.urow_off = lds_bytes; lds_bytes += need; }
-    }
+    p.urow_off = pl.urow_off;
+    const unsigned lds_bytes = pl.lds_bytes;
 #ifdef TW_PHASE_PROBE
     p.skip = getenv("TW_SKIP") ? atoi(getenv("TW_SKIP")) : 0;
 #endif

@@ -638,6 +638,12 @@ def test_streamed_k_sets_of_four_tiles(tw):
     w = W.generate(spec)
     wt = tw.TwWeight.from_dense(w.B, w.mask, G, dtype)
     assert wt.info["T"] > 4
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    for tr in (False, True):
+        pl = tw.tw_gemm_plan(tw.tw_pack(w.B, w.mask, G, dtype), M, n_cu=n_cu, transposed=tr)
+        _say(f"  plan on {n_cu} compute units, transposed={tr}: {pl}")
+        if n_cu == 256:
+            assert pl["mode"] == 2 and pl["tiles_per_set"] == 4 and pl["rows_per_block"] == 64
     rng = np.random.default_rng(5)
     rows = np.unique(np.concatenate([np.arange(0, 70), np.arange(M - 70, M), rng.integers(0, M, 260)]))
     ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, w.mask, dtype)

@@ -279,3 +279,67 @@ def test_tew_pack_round_trip_and_errors():
     with pytest.raises(tw.TwError) as e:
         tw.tw_pack_tew(big.B, big.mask, ewb, 32, "f16")
     assert e.value.status == -6
+
+
+# ------------------------------------------------------------------ the launch plan (host logic, no GPU call)
+def _plan(cfg, idx, **kw):
+    spec = W.CONFIGS[cfg][idx]
+    w = W.generate(spec, with_A=False)
+    blob = tw.tw_pack(w.B, w.mask, spec.G, spec.dtype)
+    return spec, tw.tw_info(blob), tw.tw_gemm_plan(blob, spec.M, **kw)
+
+
+def test_plan_of_the_paper_shaped_workloads():
+    """What the host decides for the five workloads on 256 compute units."""
+    spec, inf, pl = _plan("c2_bert_base_ffn_up", 0)
+    assert (pl["mode"], pl["rows_per_block"], pl["n_items"], pl["grid"]) == (0, 64, 256, 256)       # K = 768 resident
+    spec, inf, pl = _plan("c1_single", 0)
+    # 256 rows are 4 blocks of 64: too few, so 8 blocks of 32 whose 6 tiles are shared out over workgroups
+    assert pl["mode"] == 0 and pl["rows_per_block"] == 32 and pl["n_row_blocks"] == 8 and pl["n_sets"] == inf["T"]
+    assert pl["n_items"] == 8 * inf["T"] and pl["grid"] == pl["n_items"]
+    spec, inf, pl = _plan("c3_bert_base_layer", 3)            # FFN-down, K = 3072 streamed, 6 tiles, 256 row blocks
+    assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["n_sets"], pl["n_items"]) == (1, 64, 8, 1, 256)
+    spec, inf, pl = _plan("c4_bert_large_skewed", 1)          # K = 4096, 8 tiles, only 128 blocks of 64 rows
+    assert inf["T"] == 8
+    assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["n_sets"], pl["n_items"]) == (2, 64, 4, 2, 256)
+    spec, inf, pl = _plan("c5_conv_im2col", 0)                # K = 2304, 4 tiles
+    assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["n_sets"]) == (2, 64, 4, 1)
+    assert pl["n_items"] == (spec.M + 63) // 64 and pl["grid"] == 256 and pl["row_lists"] == 0
+    spec, inf, plt = _plan("c5_conv_im2col", 0, transposed=True)
+    assert plt["mode"] == 2 and plt["row_lists"] == 1 and plt["lds_bytes"] > pl["lds_bytes"]
+    spec, inf, plt = _plan("c4_bert_large_skewed", 1, transposed=True)
+    assert plt["mode"] == 2 and plt["n_sets"] == 2 and plt["row_lists"] == 0     # the lists are per set of eight tiles
+
+
+def test_plan_limits_and_errors():
+    rng = np.random.default_rng(3)
+    for K, N, G in [(64, 256, 128), (1536, 128, 32), (1544, 128, 64), (3000, 300, 128)]:
+        B = rng.integers(1, 1000, size=(K, N)).astype(np.uint16)
+        mask = np.ones((K, N), dtype=np.uint8)
+        blob = tw.tw_pack(B, mask, G, "f16")
+        for M in (1, 31, 64, 65, 1000, 100000):
+            for n_cu in (1, 8, 256, 304):
+                for tr in (False, True):
+                    pl = tw.tw_gemm_plan(blob, M, n_cu=n_cu, transposed=tr)
+                    if tr and K > 1536:
+                        assert pl["rows_per_block"] == 64      # the streamed transposed kernels take 64 tokens
+                    assert pl["lds_bytes"] <= 160 * 1024
+                    assert pl["rows_per_block"] in (32, 64)
+                    assert pl["n_row_blocks"] == (M + pl["rows_per_block"] - 1) // pl["rows_per_block"]
+                    assert pl["n_items"] == pl["n_row_blocks"] * pl["n_sets"] and pl["grid"] == min(pl["n_items"], n_cu)
+                    assert (pl["mode"] == 0) == (K <= 1536)
+                    if pl["mode"] != 0:
+                        T = tw.tw_info(blob)["T"]
+                        assert pl["n_sets"] == (T + pl["tiles_per_set"] - 1) // pl["tiles_per_set"]
+    assert tw.tw_gemm_plan(blob, 0) == {k: 0 for k in tw.tw_gemm_plan(blob, 0)}
+    with pytest.raises(tw.TwError) as e:
+        tw.tw_gemm_plan(blob, -1)
+    assert e.value.status == -1                            # TW_ERR_ARG
+    with pytest.raises(tw.TwError) as e:
+        tw.tw_gemm_plan(blob, 5, n_cu=0)
+    assert e.value.status == -1
+    bad = blob.copy()
+    bad[:4] = 0
+    with pytest.raises(tw.TwError) as e:
+        tw.tw_gemm_plan(bad, 5)
+    assert e.value.status == -3                            # TW_ERR_BUF: not a blob
