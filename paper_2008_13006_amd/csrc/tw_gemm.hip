@@ -1590,16 +1590,40 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
 // ---- the transposes at the two ends of a network that runs on the transposed boundary (Sec. VI) ----
 namespace {
 __global__ __launch_bounds__(256) void tw_transpose_kernel(const unsigned short* src, long lds_, int rows, int cols,
-                                                           unsigned short* dst, long ldd) {
-    // 64 x 64 tile through LDS; the pitch of 65 words keeps the column reads off one bank
-    __shared__ unsigned short tile[64][66];
+                                                           unsigned short* dst, long ldd, int vec) {
+    // 64 x 64 tile through LDS, kept TRANSPOSED there: tile[c][r], rows of 144 bytes (16-byte aligned pieces, and
+    // consecutive rows 4 banks apart)
+    constexpr int kPitch = 144;
+    __shared__ __attribute__((aligned(16))) unsigned char tile[64 * kPitch];
     const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int t = threadIdx.x;
+    if (vec && r0 + 64 <= rows && c0 + 64 <= cols) {
+        // whole tile, 16-byte aligned rows on both sides: 16-byte loads and stores, 2-byte LDS writes in between
+        const int j = t & 7;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = (t >> 3) + 32 * i;
+            const tw_u32x4 v = *(const tw_u32x4*)(src + (long)(r0 + r) * lds_ + c0 + 8 * j);
+            const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                *(unsigned short*)(tile + (8 * j + e) * kPitch + r * 2) = (unsigned short)(w[e >> 1] >> (16 * (e & 1)));
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = (t >> 3) + 32 * i;
+            *(tw_u32x4*)(dst + (long)(c0 + c) * ldd + r0 + 8 * j) = *(const tw_u32x4*)(tile + c * kPitch + j * 16);
+        }
+        return;
+    }
+    // edge tiles and unaligned matrices: element by element
+    const int tx = t & 63, ty = t >> 6;
     for (int r = ty; r < 64; r += 4)
-        if (r0 + r < rows && c0 + tx < cols) tile[r][tx] = src[(long)(r0 + r) * lds_ + c0 + tx];
+        if (r0 + r < rows && c0 + tx < cols) *(unsigned short*)(tile + tx * kPitch + r * 2) = src[(long)(r0 + r) * lds_ + c0 + tx];
     __syncthreads();
     for (int c = ty; c < 64; c += 4)
-        if (c0 + c < cols && r0 + tx < rows) dst[(long)(c0 + c) * ldd + r0 + tx] = tile[tx][c];
+        if (c0 + c < cols && r0 + tx < rows) dst[(long)(c0 + c) * ldd + r0 + tx] = *(const unsigned short*)(tile + c * kPitch + tx * 2);
 }
 }  // namespace
 
@@ -1609,8 +1633,9 @@ extern "C" int tw_transpose(const void* src, int ld_src, int rows, int cols, voi
     if (rows == 0 || cols == 0) return TW_OK;
     const long gx = ((long)cols + 63) / 64, gy = ((long)rows + 63) / 64;
     if (gy > 65535) return TW_ERR_UNSUPPORTED;
+    const int vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0 && (ld_src & 7) == 0 && (ld_dst & 7) == 0;
     hipLaunchKernelGGL(tw_transpose_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, (hipStream_t)hip_stream,
-                       (const unsigned short*)src, (long)ld_src, rows, cols, (unsigned short*)dst, (long)ld_dst);
+                       (const unsigned short*)src, (long)ld_src, rows, cols, (unsigned short*)dst, (long)ld_dst, vec);
     return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 #endif  // host code

@@ -410,11 +410,20 @@ def test_tw_gemm_t_matches_tw_gemm_bit_for_bit(tw):
 
 def test_tw_transpose(tw):
     rng = np.random.default_rng(5)
-    for rows, cols in ((1, 1), (70, 130), (64, 64), (257, 33)):
+    # (whole 64 x 64 tiles on aligned rows take 16-byte loads and stores, everything else goes element by element)
+    for rows, cols in ((1, 1), (70, 130), (64, 64), (257, 33), (192, 320), (200, 136), (128, 72)):
         x = torch.from_numpy(rng.integers(0, 65536, size=(rows, cols), dtype=np.int64).astype(np.int16)).to("cuda:0").view(torch.float16)
         y = tw.tw_transpose(x)
         torch.cuda.synchronize()
         assert torch.equal(y.view(torch.int16), x.view(torch.int16).T)
+    # a view with an odd offset: rows that are not 16-byte aligned
+    big = torch.from_numpy(rng.integers(0, 65536, size=(130, 200), dtype=np.int64).astype(np.int16)).to("cuda:0").view(torch.float16)
+    x = big[1:129, 3:131]
+    out = torch.full((128, 136), float("nan"), dtype=torch.float16, device="cuda:0")
+    tw.tw_transpose(x, out[:, :128])
+    torch.cuda.synchronize()
+    assert torch.equal(out[:, :128].view(torch.int16), x.view(torch.int16).T)
+    assert bool(torch.isnan(out[:, 128:]).all().item())
 
 
 def test_full_size_ffn_up_transposed(tw):
