@@ -94,9 +94,9 @@ int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N, int G, tw
 /* The TEW hybrid (Sec. IV-A "Hybrid Pattern"): on top of the tile-wise pattern `mask`, the weights marked
  * in `ew_mask` (K x N bytes; entries where mask is set as well are ignored) are kept as an element-wise
  * residual, stored per tile and column (the paper stores it in CSC form per tile) and added by tw_gemm and
- * its variants in the same launch (by linearity, A.(B*(mask|ew)) = A.(B*mask) + A.(B*ew)).  Restrictions
- * of this build: residual weights must lie in columns that keep at least one tile-wise weight, and K
- * must be at most 1536 (else TW_ERR_UNSUPPORTED).  ew_mask = NULL is tw_pack. */
+ * its variants in the same launch (by linearity, A.(B*(mask|ew)) = A.(B*mask) + A.(B*ew)).  Restriction
+ * of this build: residual weights must lie in columns that keep at least one tile-wise weight (else
+ * TW_ERR_UNSUPPORTED).  ew_mask = NULL is tw_pack. */
 int tw_pack_tew_size(const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G, tw_dtype dt,
                      size_t* blob_bytes);
 int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G,

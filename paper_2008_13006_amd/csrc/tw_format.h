@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define TW_MAGIC 0x31425754u /* "TWB1" */
-#define TW_FORMAT_VERSION 9
+#define TW_FORMAT_VERSION 10
 
 // MFMA step geometry the packed values are laid out for: one step contracts 16 kept rows
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
@@ -47,13 +47,15 @@ struct TwHeader {
                              //   the transposed output that the tile writes as zeros)
     uint64_t off_urow;       // streamed K only: uint16 [n_sets][n_chunks][k_chunk]: per set of tiles that a
                              //   workgroup of the streamed kernel holds (TW_SET_TILES(T) tiles in dispatch order)
-                             //   and per chunk, the chunk-local K rows that any tile of the set keeps, ascending
+                             //   and per chunk, the chunk-local K rows that any tile of the set keeps (in its tile-wise
+                             //   pattern or in its element-wise residual), ascending
     uint64_t off_ucnt;       // int32 [n_sets][n_chunks]: their number
     // element-wise residual of the TEW hybrid (Sec. IV-A): the weights kept outside the tile-wise pattern, per
-    // tile as planes of G entries (one per packed column): plane e holds every column's e-th residual entry,
+    // tile and K chunk as planes of G entries (one per packed column): plane e of a (tile, chunk) holds every
+    // column's e-th residual entry inside that chunk,
     int64_t ew_nnz;          //   number of residual weights (0: none)
-    uint64_t off_ew_ptr;     //   int32 [T+1]: first plane of every tile (canonical order)
-    uint64_t off_ew_k;       //   uint16 [planes][G]: K row of the entry; k_chunk (the zero row) where a column has fewer
+    uint64_t off_ew_ptr;     //   int32 [T*n_chunks+1]: first plane of every (tile, chunk), tiles in canonical order
+    uint64_t off_ew_k;       //   uint16 [planes][G]: chunk-local K row of the entry; k_chunk (the zero row) where a column has fewer
     uint64_t off_ew_v;       //   16-bit [planes][G]: its weight; 0 for padding
     uint8_t pad[256 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 14];
 };

@@ -798,12 +798,13 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
 // activations of row k from LDS (8-byte pieces: four consecutive rows of the block) and adds v * A.
 // Entries come in planes of G (one per packed column, padded with weight 0 at the zero row).
 template <int DT, int MS, int NCB>
-__device__ __forceinline__ void add_ew_residual(const TwGemmParams& p, int tile, tw_f32x16 (&acc)[MS][NCB],
+__device__ __forceinline__ void add_ew_residual(const TwGemmParams& p, int tile, int chunk, tw_f32x16 (&acc)[MS][NCB],
                                                 const unsigned char* at, unsigned at_pitch, int lane_in) {
     const int lane = fresh(lane_in);
     const int n = lane & 31, h = lane >> 5;
     const int* ep = (const int*)(p.blob + p.off_ew_ptr);
-    const int e0 = fetch_int(ep, tile), e1 = fetch_int(ep, tile + 1);
+    const int pi = tile * p.n_chunks + chunk;      // planes of this tile inside this K chunk (`at` holds the chunk)
+    const int e0 = fetch_int(ep, pi), e1 = fetch_int(ep, pi + 1);
     const unsigned short* ek = (const unsigned short*)(p.blob + p.off_ew_k) + n;
     const unsigned short* ev = (const unsigned short*)(p.blob + p.off_ew_v) + n;
     constexpr int G = 32 * NCB;
@@ -922,7 +923,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (!TW_SKIPS(p, 2))
                     run_steps<DT, MS, NCB>(acc, rg, smem, p.at_pitch, p.blob + p.off_goff + (long)d.first_step * 32,
                                            p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
-                if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, acc, smem, p.at_pitch, lane);
+                if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, p.at_pitch, lane);
                 if (!TW_SKIPS(p, 4)) {
                     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                     else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
@@ -1056,6 +1057,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 auto steps_of = [&](int c) {
                     if (active && b0 < b1 && !TW_SKIPS(p, 2))
                         run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, b0, b1, lane);
+                    if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, p.at_pitch, lane);
                     // on to chunk c+1
                     b0 = b1; b1 = b2;
                     b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
@@ -1137,6 +1139,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             auto steps_of = [&](int c) {
                 if (active && b0 < b1 && !TW_SKIPS(p, 2))
                     run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, b0, b1, lane);
+                if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, p.at_pitch, lane);
                 b0 = b1; b1 = b2;
                 b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
                 if (c + 1 < p.n_chunks) prefetch_steps(b0, b1); else prefetch_steps(0, 0);
@@ -1422,7 +1425,6 @@ extern "C" int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transpos
     Plan pl;
     const int rc = make_plan(h, M, n_cu, pl, transposed != 0);
     if (rc) return rc;
-    if (h->ew_nnz > 0 && pl.mode != 0) return TW_ERR_UNSUPPORTED;
     plan->mode = pl.mode;
     plan->rows_per_block = 32 * pl.ms;
     plan->tiles_per_set = pl.tiles_per_set;
@@ -1501,7 +1503,6 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt; p.urow_off = 0;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
-    if (p.has_ew && pl.mode != 0) return TW_ERR_UNSUPPORTED;
 #ifdef TW_PHASE_PROBE
     p.skip = getenv("TW_SKIP") ? atoi(getenv("TW_SKIP")) : 0;
 #endif
@@ -1576,7 +1577,6 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
-    if (p.has_ew && pl.mode != 0) return TW_ERR_UNSUPPORTED;
     p.urow_off = pl.urow_off;
     const unsigned lds_bytes = pl.lds_bytes;
 #ifdef TW_PHASE_PROBE

@@ -32,7 +32,7 @@ struct Layout {
         off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, off_zero_ptr,
         off_zero_cols, off_urow, off_ucnt, off_ew_ptr, off_ew_k, off_ew_v, bytes;
     int64_t ew_nnz = 0;
-    std::vector<int32_t> ew_ptr;   // planes per tile, prefix sums
+    std::vector<int32_t> ew_ptr;   // planes per (tile, chunk), prefix sums
 };
 
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -138,24 +138,28 @@ void plan(const Tiling& tl, int K, int G, Layout& lo, const uint8_t* mask = null
         lo.off_urow = take(2 * (n_sets * lo.n_chunks * (size_t)lo.k_chunk + 1), 16);
     }
     {
-        // residual planes per tile: the largest number of residual entries of any of its columns
-        lo.ew_ptr.assign(T + 1, 0);
+        // residual planes per (tile, chunk): the largest number of residual entries that any of the tile's
+        // columns has inside the chunk
+        const int nc = lo.n_chunks;
+        lo.ew_ptr.assign((size_t)T * nc + 1, 0);
         lo.ew_nnz = 0;
         if (ew) {
-            for (int t = 0; t < T; ++t) {
-                int emax = 0;
-                for (int c = tl.tile_col_ptr[t]; c < tl.tile_col_ptr[t + 1]; ++c) {
-                    const int n = tl.col_idx[c];
-                    int cnt = 0;
-                    for (int k = 0; k < K; ++k) cnt += ew[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0;
-                    lo.ew_nnz += cnt;
-                    emax = std::max(emax, cnt);
+            for (int t = 0; t < T; ++t)
+                for (int ch = 0; ch < nc; ++ch) {
+                    const int k0 = ch * lo.k_chunk, k1 = std::min(K, k0 + lo.k_chunk);
+                    int emax = 0;
+                    for (int c = tl.tile_col_ptr[t]; c < tl.tile_col_ptr[t + 1]; ++c) {
+                        const int n = tl.col_idx[c];
+                        int cnt = 0;
+                        for (int k = k0; k < k1; ++k) cnt += ew[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0;
+                        lo.ew_nnz += cnt;
+                        emax = std::max(emax, cnt);
+                    }
+                    lo.ew_ptr[(size_t)t * nc + ch + 1] = lo.ew_ptr[(size_t)t * nc + ch] + emax;
                 }
-                lo.ew_ptr[t + 1] = lo.ew_ptr[t] + emax;
-            }
         }
-        const size_t planes = (size_t)lo.ew_ptr[T];
-        lo.off_ew_ptr = take(4 * (size_t)(T + 1), 16);
+        const size_t planes = (size_t)lo.ew_ptr[(size_t)T * nc];
+        lo.off_ew_ptr = take(4 * ((size_t)T * nc + 1), 16);
         lo.off_ew_k = take(2 * (planes * G + 1), 16);
         lo.off_ew_v = take(2 * (planes * G + 1), 16);
     }
@@ -182,19 +186,15 @@ const TwHeader* header_of(const void* blob) {
 
 }  // namespace
 
-// residual entries must lie in columns that survive the tile-wise pattern, and K must be resident
+// residual entries must lie in columns that survive the tile-wise pattern
 int check_ew(const uint8_t* mask, const uint8_t* ew, int K, int N, const Tiling& tl, const Layout& lo) {
     if (!ew) return TW_OK;
     std::vector<uint8_t> alive(N, 0);
     for (int32_t n : tl.col_idx) alive[n] = 1;
-    bool any = false;
+    (void)lo;
     for (int k = 0; k < K; ++k)
         for (int n = 0; n < N; ++n)
-            if (ew[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0) {
-                if (!alive[n]) return TW_ERR_UNSUPPORTED;
-                any = true;
-            }
-    if (any && lo.n_chunks != 1) return TW_ERR_UNSUPPORTED;
+            if (ew[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0 && !alive[n]) return TW_ERR_UNSUPPORTED;
     return TW_OK;
 }
 
@@ -270,25 +270,29 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
     put(lo.off_tile_span, tl.tile_span);
     put(lo.off_step_ptr, lo.step_ptr);
 
-    // element-wise residual, planes of G entries per tile
+    // element-wise residual, planes of G entries per (tile, chunk)
     put(lo.off_ew_ptr, lo.ew_ptr);
-    if (ew_mask && lo.ew_ptr[tl.T] > 0) {
+    if (ew_mask && lo.ew_ptr[(size_t)tl.T * lo.n_chunks] > 0) {
         uint16_t* ek = (uint16_t*)(base + lo.off_ew_k);
         uint16_t* ev = (uint16_t*)(base + lo.off_ew_v);
         const uint16_t* Bw = (const uint16_t*)B;
+        const int nc = lo.n_chunks;
         for (int t = 0; t < tl.T; ++t) {
             const int c0 = tl.tile_col_ptr[t], w = tl.tile_col_ptr[t + 1] - c0;
-            for (int e = lo.ew_ptr[t]; e < lo.ew_ptr[t + 1]; ++e)
+            for (int e = lo.ew_ptr[(size_t)t * nc]; e < lo.ew_ptr[(size_t)(t + 1) * nc]; ++e)
                 for (int c = 0; c < G; ++c) { ek[(size_t)e * G + c] = (uint16_t)lo.k_chunk; ev[(size_t)e * G + c] = 0; }
-            for (int c = 0; c < w; ++c) {
-                const int n = tl.col_idx[c0 + c];
-                int e = lo.ew_ptr[t];
-                for (int k = 0; k < K; ++k)
-                    if (ew_mask[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0) {
-                        ek[(size_t)e * G + c] = (uint16_t)k;
-                        ev[(size_t)e * G + c] = Bw[(size_t)k * ldb + n];
-                        ++e;
-                    }
+            for (int ch = 0; ch < nc; ++ch) {
+                const int k0 = ch * lo.k_chunk, k1 = std::min(K, k0 + lo.k_chunk);
+                for (int c = 0; c < w; ++c) {
+                    const int n = tl.col_idx[c0 + c];
+                    int e = lo.ew_ptr[(size_t)t * nc + ch];
+                    for (int k = k0; k < k1; ++k)
+                        if (ew_mask[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0) {
+                            ek[(size_t)e * G + c] = (uint16_t)(k - k0);
+                            ev[(size_t)e * G + c] = Bw[(size_t)k * ldb + n];
+                            ++e;
+                        }
+                }
             }
         }
     }
@@ -398,6 +402,12 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
             for (int i = st * tpw; i < std::min(tl.T, (st + 1) * tpw); ++i) {
                 const int t = dispatch[i];
                 for (int r = tl.tile_row_ptr[t]; r < tl.tile_row_ptr[t + 1]; ++r) need[tl.row_idx[r]] = 1;
+                if (ew_mask)   // and the rows of the tile's element-wise residual
+                    for (int c = tl.tile_col_ptr[t]; c < tl.tile_col_ptr[t + 1]; ++c) {
+                        const int n = tl.col_idx[c];
+                        for (int k = 0; k < K; ++k)
+                            if (ew_mask[(size_t)k * N + n] != 0) need[k] = 1;
+                    }
             }
             for (int c = 0; c < lo.n_chunks; ++c) {
                 uint16_t* out = urow + ((size_t)st * lo.n_chunks + c) * lo.k_chunk;
@@ -481,16 +491,19 @@ extern "C" int tw_unpack(const void* blob, void* B_out, int ldb, uint8_t* mask_o
         const int32_t* ep = (const int32_t*)(base + h->off_ew_ptr);
         const uint16_t* ek = (const uint16_t*)(base + h->off_ew_k);
         const uint16_t* ev = (const uint16_t*)(base + h->off_ew_v);
+        const int nc = h->n_chunks;
         for (int t = 0; t < T; ++t) {
             const int c0 = tcp[t], w = tcp[t + 1] - c0;
-            for (int e = ep[t]; e < ep[t + 1]; ++e)
-                for (int c = 0; c < w; ++c) {
-                    const int k = ek[(size_t)e * h->G + c];
-                    if (k >= K) continue;                   // padding
-                    const int n = col_idx[c0 + c];
-                    if (mask_out) mask_out[(size_t)k * N + n] = 1;
-                    if (Bo) Bo[(size_t)k * ldb + n] = ev[(size_t)e * h->G + c];
-                }
+            for (int ch = 0; ch < nc; ++ch)
+                for (int e = ep[(size_t)t * nc + ch]; e < ep[(size_t)t * nc + ch + 1]; ++e)
+                    for (int c = 0; c < w; ++c) {
+                        const int kl = ek[(size_t)e * h->G + c];
+                        if (kl >= h->k_chunk) continue;     // padding
+                        const int k = ch * h->k_chunk + kl;
+                        const int n = col_idx[c0 + c];
+                        if (mask_out) mask_out[(size_t)k * N + n] = 1;
+                        if (Bo) Bo[(size_t)k * ldb + n] = ev[(size_t)e * h->G + c];
+                    }
         }
     }
     return TW_OK;

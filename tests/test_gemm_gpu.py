@@ -474,7 +474,9 @@ def test_tw_gemm_t_bias_act(tw, case):
 
 # ------------------------------------------------------------------ TEW hybrid: tile-wise pattern + element-wise residual
 TEW = [("ragged_rows_gaps", 0.02), ("bf16_g64", 0.01), ("g32_many_tiles", 0.05), ("several_row_blocks", 0.01),
-       ("wide_spans", 0.03), ("t_k1024", 0.01), ("kept_one_row_each", 0.1)]
+       ("wide_spans", 0.03), ("t_k1024", 0.01), ("kept_one_row_each", 0.1),
+       # streamed K: a wave per tile with 32- and 64-row blocks, loading waves; the residual is added chunk by chunk
+       ("streamed_k", 0.01), ("streamed_k_bf16_ragged", 0.02), ("t_stream_8tiles", 0.01), ("t_stream_3tiles", 0.02)]
 
 
 @pytest.mark.parametrize("case", TEW, ids=[f"{c[0]}-delta{c[1]}" for c in TEW])
@@ -517,6 +519,36 @@ def test_tew_full_size_ffn_up(tw):
     rows = _sample_rows(spec.M, n=64, seed=6)
     ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, (w.mask | ew).astype(np.uint8), spec.dtype)
     assert _rel_err(_to_f64(C[torch.as_tensor(rows, device="cuda:0")]), ref) <= TOL[spec.dtype]
+
+
+@pytest.mark.parametrize("cfg,idx", [("c3_bert_base_layer", 3), ("c4_bert_large_skewed", 1), ("c5_conv_im2col", 0)],
+                         ids=["ffn_down_wave_per_tile", "ffn_down_skewed_sets_of_four", "conv_loading_waves"])
+def test_tew_full_size_streamed_k(tw, cfg, idx):
+    """The hybrid on the workloads whose K is streamed (64-row blocks: a wave per tile, sets of four tiles, loading
+    waves), both boundaries, on sampled rows.  The residual comes from the library's tw_restore_ew, which the CPU
+    tests hold bit for bit against the oracle's."""
+    spec = W.CONFIGS[cfg][idx]
+    _say(f"TEW streamed {cfg} / {spec.name}")
+    w = W.generate(spec)
+    ew = tw.tw_restore_ew(w.B, w.mask, 0.005, spec.dtype)
+    wt = tw.TwWeight(tw.tw_pack_tew(w.B, w.mask, ew, spec.G, spec.dtype))
+    assert wt.info["ew_nnz"] == int(np.floor(0.005 * spec.K * spec.N + 0.5)) and wt.info["k_chunk"] < spec.K
+    C = tw.tw_gemm(wt, _device_A(tw, w.A, spec.dtype))
+    Ct = tw.tw_gemm_t(wt, _device_At(tw, w.A, spec.dtype))
+    torch.cuda.synchronize()
+    ws = wt.workspace.view(torch.int32)[:4].cpu().tolist()
+    assert ws[0] == 0 and ws[1] == 0 and ws[3] == 0, f"workspace after the calls: {ws}"
+    rows = _sample_rows(spec.M, n=64, seed=7)
+    ridx = torch.as_tensor(rows, device="cuda:0")
+    union = (w.mask | ew).astype(np.uint8)
+    ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, union, spec.dtype)
+    ref_tw_only = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, w.mask, spec.dtype)
+    assert _rel_err(ref_tw_only, ref) > TOL[spec.dtype], "the residual should matter in this case"
+    assert _rel_err(_to_f64(C[ridx]), ref) <= TOL[spec.dtype]
+    assert _rel_err(_to_f64(Ct[:, ridx]).T, ref) <= TOL[spec.dtype]
+    assert bool(torch.isfinite(C.float()).all().item()) and bool(torch.isfinite(Ct.float()).all().item())
+    del C, Ct, wt
+    torch.cuda.empty_cache()
 
 
 def test_bad_arguments_of_the_newer_entry_points_are_refused(tw):

@@ -268,17 +268,24 @@ def test_tew_pack_round_trip_and_errors():
     # entries that the tile-wise pattern keeps anyway are ignored
     blob2 = tw.tw_pack_tew(w.B, w.mask, (ew | w.mask).astype(np.uint8), spec.G, "f16")
     assert tw.tw_info(blob2)["ew_nnz"] == int(ew.sum())
-    # a residual weight in a column without tile-wise weights is refused, and so is a residual with streamed K
+    # a residual weight in a column without tile-wise weights is refused
     pruned_cols = np.flatnonzero(~w.mask.any(axis=0))
-    bad = ew.copy(); bad[3, pruned_cols[0]] = 1
+    bad = ew.copy()
+    bad[3, pruned_cols[0]] = 1
     with pytest.raises(tw.TwError) as e:
         tw.tw_pack_tew(w.B, w.mask, bad, spec.G, "f16")
     assert e.value.status == -6
-    big = W.generate(W.small_spec("tew_big", M=4, K=1600, N=64, G=32, dtype="f16", keep=("const", 0.25), seed_offset=4301))
-    ewb = tw_ref.restore_ew(big.B, big.mask, 0.01, "f16")
-    with pytest.raises(tw.TwError) as e:
-        tw.tw_pack_tew(big.B, big.mask, ewb, 32, "f16")
-    assert e.value.status == -6
+    # streamed K (several chunks of 384 rows, the last one ragged): the residual is stored per tile and chunk
+    big = W.generate(W.small_spec("tew_big", M=4, K=1600, N=200, G=32, dtype="bf16", col_prune=0.1, keep=("upow", 0.05, 0.4),
+                                  seed_offset=4301))
+    ewb = tw_ref.restore_ew(big.B, big.mask, 0.01, "bf16")
+    blob = tw.tw_pack_tew(big.B, big.mask, ewb, 32, "bf16")
+    inf = tw.tw_info(blob)
+    assert inf["k_chunk"] == 384 and inf["ew_nnz"] == int(ewb.sum()) > 0
+    Bu, mu = tw.tw_unpack(blob)
+    union = (big.mask | ewb).astype(np.uint8)
+    assert np.array_equal(mu, union)
+    assert np.array_equal(Bu, tw_ref.masked_weight_bits(big.B, union))
 
 
 # ------------------------------------------------------------------ the launch plan (host logic, no GPU call)
