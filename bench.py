@@ -315,6 +315,38 @@ def main() -> int:
             print(f"[report] TEW on c2, delta {delta:.3f} ({int(wte.info['ew_nnz'])} residual weights): tw_gemm {a_ms*1e3:.1f} us, "
                   f"tw_gemm_t {b_ms*1e3:.1f} us", file=sys.stderr, flush=True)
         del Ats, Cts
+        # The four weight GEMMs of a BERT-base layer chained on one stream (QKV, attention output on a strided view,
+        # FFN-up with bias + GELU, FFN-down), launch by launch and as one HIP graph: at small M the launches bound it.
+        for Ml in (512, 16384):
+            lspecs = W.CONFIGS["c3_bert_base_layer"]
+            lws = [W.generate(s_, M=Ml) for s_ in lspecs]
+            lwt = [tw.TwWeight(tw.tw_pack(w_.B, w_.mask, s_.G, s_.dtype)) for w_, s_ in zip(lws, lspecs)]
+            X = tw.bits_to_tensor(lws[0].A, lspecs[0].dtype)
+            QKV = torch.empty((Ml, 2304), dtype=td, device="cuda:0")
+            AO = torch.empty((Ml, 768), dtype=td, device="cuda:0")
+            Hh = torch.empty((Ml, 3072), dtype=td, device="cuda:0")
+            Y = torch.empty((Ml, 768), dtype=td, device="cuda:0")
+
+            def chain():
+                tw.tw_gemm(lwt[0], X, QKV)
+                tw.tw_gemm(lwt[1], QKV[:, :768], AO)
+                tw.tw_gemm_bias_act(lwt[2], AO, bias, "gelu", Hh)
+                tw.tw_gemm(lwt[3], Hh, Y)
+
+            chain()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                chain()
+            torch.cuda.synchronize()
+            eager_ms, _ = time_launches(torch, lambda i: chain(), 1, st, 5)
+            graph_ms, _ = time_launches(torch, lambda i: graph.replay(), 1, st, 5)
+            rows.append({"config": "layer_chain", "name": f"bert_base_layer_M{Ml}", "M": Ml, "eager_ms": eager_ms,
+                         "graph_ms": graph_ms})
+            print(f"[report] BERT-base layer chain, M={Ml}: four launches {eager_ms*1e3:.1f} us, one HIP graph replay "
+                  f"{graph_ms*1e3:.1f} us", file=sys.stderr, flush=True)
+            del lwt, X, QKV, AO, Hh, Y, graph
+            torch.cuda.empty_cache()
         with open(args.report, "w") as f:
             json.dump(rows, f, indent=1)
     if args.sweep:

@@ -73,6 +73,7 @@ struct TwGemmParams {
     int M, K, N, T;
     int k_chunk, n_chunks, G;
     int n_mblocks, n_seg, n_items;
+    int tiles_per_set;          // MODE 2: tiles a workgroup holds (1..4: that many of the multiplying waves have one)
     unsigned at_pitch;          // bytes between K rows of the LDS copy of A (32*MS rows of A wide, padded)
     unsigned abuf_bytes;        // size of one LDS copy of A (streamed K uses two)
     unsigned stage_off;         // LDS offset of the per-wave staging areas
@@ -844,11 +845,11 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 }
 
 // MODE 0: the K extent of a row block of 32*MS rows is resident in LDS, waves pull whole tiles.
-// MODE 1: K streamed through two LDS buffers, row block of 32*MS rows, wave w owns tile 8*set + w.
-// MODE 2: K streamed, row block of 64 rows (MS = 2), sets of four tiles: waves 0-3 multiply (wave w owns
-//         tile 4*set + w), waves 4-7 do nothing but bring A into LDS, so the two kinds of work overlap
-//         instead of taking turns (a wave's loads retire in order: a wave that waits for its packed B also
-//         waits for every request for A it made before).
+// MODE 1: K streamed through two LDS buffers, row block of 64 rows (MS = 2), wave w owns tile 8*set + w.
+// MODE 2: K streamed, row block of 64 rows (MS = 2), sets of 1, 2 or 4 tiles: of waves 0-3 wave w owns tile
+//         tiles_per_set*set + w and multiplies, waves 4-7 do nothing but bring A into LDS, so the two kinds of
+//         work overlap instead of taking turns (a wave's loads retire in order: a wave that waits for its packed
+//         B also waits for every request for A it made before).
 //         (Six multiplying and two loading waves were tried for weights of five or six tiles: the two
 //         loading waves cannot keep up with the transposing LDS writes of the row-major boundary, 9 % slower
 //         than MODE 1 on the FFN-down of BERT-base, and no gain on the transposed boundary.)
@@ -939,8 +940,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             const int set = item / p.n_mblocks, mb = item - set * p.n_mblocks;
             const int row0 = mb * BM;
             const bool loader = wave >= NMUL;
-            const int ti = set * NMUL + wave;
-            const bool active = !loader && ti < p.T;
+            const int ti = set * p.tiles_per_set + wave;
+            const bool active = wave < p.tiles_per_set && ti < p.T;      // (tiles_per_set <= NMUL: never a loading wave)
             const TileU d = fetch_tile(p, active ? ti : 0);
             const int* sp = step_ptr + d.step_ptr;
             const unsigned char* gt = p.blob + p.off_goff + (long)d.first_step * 32;
@@ -1227,13 +1228,15 @@ namespace tw_parts {
 template <int DT, bool FUSED>
 const void* pick_mode(int mode, int ms, int ncb) {
     if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, false>(ncb) : pick_ncb<DT, 1, 0, FUSED, false>(ncb);
-    if (mode == 1) return ms == 2 ? pick_ncb<DT, 2, 1, FUSED, false>(ncb) : pick_ncb<DT, 1, 1, FUSED, false>(ncb);
+    if (ms != 2) return nullptr;                  // the streamed kernels take 64-row blocks
+    if (mode == 1) return pick_ncb<DT, 2, 1, FUSED, false>(ncb);
     return pick_ncb<DT, 2, 2, FUSED, false>(ncb);
 }
 // transposed boundary: resident K with blocks of 64 or 32 tokens, streamed K always with 64
 template <int DT, bool FUSED>
 const void* pick_mode_t(int mode, int ms, int ncb) {
     if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, true>(ncb) : pick_ncb<DT, 1, 0, FUSED, true>(ncb);
+    if (ms != 2) return nullptr;
     if (mode == 1) return pick_ncb<DT, 2, 1, FUSED, true>(ncb);
     return pick_ncb<DT, 2, 2, FUSED, true>(ncb);
 }
@@ -1324,24 +1327,26 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     };
     int msb = 2, tpw = kWaves;
     int nmb, nseg;
-    bool sets_of_four = false;
     if (lds_need(2, h->k_chunk, buffers) > kLdsLimit) msb = 1;
-    if (msb == 2 && items_for(2, tpw, nmb, nseg) < n_cu) {
-        // Too few 64-row blocks to fill the GPU.  Streamed K: sets of four tiles (loading waves, below) double
-        // the items and keep the 64-row blocks, which halve the traffic of packed B and keep the loads of A
-        // out of the multiplying waves; measured 20 % faster than 32-row blocks on the skewed FFN-down of
-        // BERT-large (M = 8192, K = 4096, T = 8).  Otherwise 32-row blocks
-        // (the streamed transposed kernels exist for 64 tokens only).
-        if (!resident && T > kWaves / 2 && items_for(2, kWaves / 2, nmb, nseg) >= n_cu) sets_of_four = true;
-        else if (!(transposed && !resident)) msb = 1;
-    }
-    if (transposed && !resident && msb != 2) return TW_ERR_UNSUPPORTED;
     pl.mode = resident ? 0 : 1;
-    pl.ms = msb;
-    if (!resident && msb == 2 && (T <= kWaves / 2 || sets_of_four)) {   // half of the waves only load A
-        pl.mode = 2;
-        tpw = kWaves / 2;
+    if (resident) {
+        // 64-row blocks halve the traffic of packed B, but only pay when they still fill the GPU
+        if (msb == 2 && items_for(2, tpw, nmb, nseg) < n_cu) msb = 1;
+    } else if (msb == 2) {
+        // Streamed K, 64-row blocks.  Eight tiles per workgroup (a wave per tile) when that gives every compute
+        // unit an item and there are more than four tiles.  Else four waves multiply and four only load A
+        // (MODE 2), with as many tiles per workgroup (4, 2, 1) as still fill the GPU: fewer tiles per workgroup
+        // mean more workgroups per row block, each reading the block's rows of A again (from the caches).
+        // Measured: skewed FFN-down of BERT-large, M = 8192, T = 8: 45 us with sets of four against 57 us with
+        // 32-row blocks and a wave per tile; FFN-down of BERT-base, M = 512: see the design notes.
+        if (T <= kWaves / 2 || items_for(2, kWaves, nmb, nseg) < n_cu) {
+            pl.mode = 2;
+            tpw = kWaves / 2;
+            while (tpw > 1 && items_for(2, tpw, nmb, nseg) < n_cu) tpw >>= 1;
+        }
     }
+    if (!resident && msb != 2) return TW_ERR_UNSUPPORTED;   // (the streamed kernels take 64-row blocks; 384-row chunks fit)
+    pl.ms = msb;
     const long items = items_for(msb, tpw, nmb, nseg);
     if (items > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
     if (!resident && 4 * msb * ((((h->k_chunk + 7) >> 3) + 7) >> 3) > kWaves * 6) return TW_ERR_UNSUPPORTED;   // a chunk is one batch
@@ -1353,10 +1358,10 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     pl.lds_bytes = pl.misc_off + 16u;
     pl.tiles_per_set = resident ? 0 : tpw;
     // Transposed boundary, at most four tiles, streamed: the loading waves read only the K rows the tiles keep,
-    // from lists they hold in LDS.  (The blob's row lists are per set of TW_SET_TILES(T) tiles: with sets of four
-    // out of more than four tiles the loading waves bring in whole chunks.)
+    // from lists they hold in LDS.  (The blob's row lists are per set of TW_SET_TILES(T) tiles: with other sets
+    // the loading waves bring in whole chunks.)
     pl.urow_off = 0;
-    if (transposed && pl.mode == 2 && T <= kWaves / 2) {
+    if (transposed && pl.mode == 2 && T <= kWaves / 2 && tpw == kWaves / 2) {
         const unsigned need = (kWaves / 2) * (unsigned)h->n_chunks * (8 * 12 + 2) * 2;
         if (pl.lds_bytes + need <= kLdsLimit) { pl.urow_off = pl.lds_bytes; pl.lds_bytes += need; }
     }
@@ -1481,7 +1486,7 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     const bool fused = bias != nullptr || act != TW_ACT_NONE;
     const void* fn = pick_kernel(h->dtype, pl.mode, pl.ms, h->ncb, fused);
     if (!fn) return TW_ERR_UNSUPPORTED;
-    const int variant = pl.mode == 2 ? 4 : 2 * pl.mode + (pl.ms == 2 ? 0 : 1);      // 0..4
+    const int variant = pl.mode == 2 ? 4 : 2 * pl.mode + (pl.ms == 2 ? 0 : 1);      // 0, 1, 2, 4
     const int kernel_id = (fused ? 30 : 0) + (h->dtype == TW_F16 ? 0 : 15) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, fn);
     if (rc) return rc;
@@ -1495,7 +1500,7 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.lda = lda; p.ldc = ldc;
     p.M = M; p.K = h->K; p.N = h->N; p.T = h->T;
     p.k_chunk = h->k_chunk; p.n_chunks = h->n_chunks; p.G = h->G;
-    p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items;
+    p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items; p.tiles_per_set = pl.tiles_per_set;
     p.at_pitch = pl.at_pitch; p.abuf_bytes = pl.abuf_bytes;
     p.stage_off = pl.stage_off; p.misc_off = pl.misc_off;
     p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;
@@ -1569,7 +1574,7 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.lda = ldat; p.ldc = ldct;
     p.M = M; p.K = h->K; p.N = h->N; p.T = h->T;
     p.k_chunk = h->k_chunk; p.n_chunks = h->n_chunks; p.G = h->G;
-    p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items;
+    p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items; p.tiles_per_set = pl.tiles_per_set;
     p.at_pitch = pl.at_pitch; p.abuf_bytes = pl.abuf_bytes;
     p.stage_off = pl.stage_off; p.misc_off = pl.misc_off;
     p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;

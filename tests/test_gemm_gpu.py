@@ -711,3 +711,67 @@ def test_streamed_k_sets_of_four_tiles(tw):
     pruned = np.flatnonzero(~w.mask.any(axis=0))
     if len(pruned):
         assert float(C[:, torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
+
+
+# ------------------------------------------------------------------ a chain of launches inside a HIP graph
+def test_hip_graph_replays_match_eager(tw):
+    """The four weight GEMMs of a BERT-base layer (QKV, attention output on a strided view, FFN-up with bias and
+    GELU, FFN-down) chained on one stream, captured in a HIP graph and replayed with new inputs; eager work of the
+    same library runs between the replays.  Every replay must give the bits of the eager chain, and the eager
+    chain's last output is held against the oracle.  (The library enqueues kernels only: the scheduler counters
+    in the workspace are put back by the kernel itself, so a capture records no memset.)"""
+    M = 512
+    specs = W.CONFIGS["c3_bert_base_layer"]
+    ws = [W.generate(s, M=M) for s in specs]
+    wts = [tw.TwWeight.from_dense(w.B, w.mask, s.G, s.dtype) for w, s in zip(ws, specs)]
+    dtype = specs[0].dtype
+    bbits = _bias_bits(specs[2].N, dtype, 11)
+    bias = tw.bits_to_tensor(bbits, dtype)
+    td = torch.float16
+    X = torch.empty((M, 768), dtype=td, device="cuda:0")
+    QKV = torch.empty((M, 2304), dtype=td, device="cuda:0")
+    AO = torch.empty((M, 768), dtype=td, device="cuda:0")
+    H = torch.empty((M, 3072), dtype=td, device="cuda:0")
+    Y = torch.empty((M, 768), dtype=td, device="cuda:0")
+
+    def chain():
+        tw.tw_gemm(wts[0], X, QKV)
+        tw.tw_gemm(wts[1], QKV[:, :768], AO)          # row stride 2304
+        tw.tw_gemm_bias_act(wts[2], AO, bias, "gelu", H)
+        tw.tw_gemm(wts[3], H, Y)
+
+    rng = np.random.default_rng(21)
+    inputs = [W.f32_to_bits(rng.standard_normal((M, 768)).astype(np.float32), dtype) for _ in range(3)]
+    X.copy_(tw.bits_to_tensor(inputs[0], dtype))
+    chain()                                            # warm-up outside the capture (first-use attribute calls)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        chain()
+    torch.cuda.synchronize()
+    for i, xb in enumerate(inputs):
+        _say(f"  replay {i}")
+        X.copy_(tw.bits_to_tensor(xb, dtype))
+        chain()
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in (QKV, AO, H, Y)]
+        for t in (QKV, AO, H, Y):
+            t.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("QKV", "AO", "H", "Y"), eager, (QKV, AO, H, Y)):
+            assert torch.equal(a, b), f"replay {i}: {name} differs from the eager chain"
+        for wt in wts:
+            assert wt.workspace.view(torch.int32)[:4].cpu().tolist() == [0, 0, 0, 0]
+        # unrelated eager work of the library between replays
+        tw.tw_gemm(wts[1], X)
+        torch.cuda.synchronize()
+    # the last eager chain against the oracle, stage by stage on the device's own intermediate results
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    ref_y = tw_ref.masked_gemm(bits(H), ws[3].B, ws[3].mask, dtype)
+    assert _rel_err(_to_f64(Y), ref_y) <= TOL[dtype]
+    ref_h = tw_ref.bias_act(tw_ref.masked_gemm(bits(AO), ws[2].B, ws[2].mask, dtype), tw_ref.decode(bbits, dtype), "gelu")
+    assert _rel_err(_to_f64(H), ref_h) <= TOL[dtype]
+    ref_ao = tw_ref.masked_gemm(bits(QKV[:, :768]), ws[1].B, ws[1].mask, dtype)
+    assert _rel_err(_to_f64(AO), ref_ao) <= TOL[dtype]
