@@ -448,38 +448,31 @@ __device__ __forceinline__ void fetch_epi_bias(const TwGemmParams& p, const Tile
     }
 }
 
-// The fused epilogue's arithmetic, in place on the accumulators and kept apart from the store code: one
-// loop per activation, so that the plain path's code and registers stay as they are.
+// The fused epilogue's arithmetic, in place on the accumulators and kept apart from the store code, so that
+// the plain path's code and registers stay as they are.
 template <int MS, int NCB>
 __device__ __forceinline__ void apply_bias_act(tw_f32x16 (&acc)[MS][NCB], const EpiBias<NCB>& eb, int act) {
-    if (act == TW_ACT_GELU) {
+    // The (wave-uniform) choice of the activation is taken once per 32 x 32 block, not once around three loops
+    // over all accumulators: with one big three-way branch the register allocator moves accumulators out to
+    // scratch memory on every path, the plain bias included.
 #pragma unroll
-        for (int ms = 0; ms < MS; ++ms)
+    for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb)
+        for (int cb = 0; cb < NCB; ++cb) {
+            if (act == TW_ACT_GELU) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float x = acc[ms][cb][r] + eb.col[cb];
-                    acc[ms][cb][r] = tw_gelu(x);
-                }
-    } else if (act == TW_ACT_RELU) {
-#pragma unroll
-        for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb)
+                for (int r = 0; r < 16; ++r) acc[ms][cb][r] = tw_gelu(acc[ms][cb][r] + eb.col[cb]);
+            } else if (act == TW_ACT_RELU) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const float x = acc[ms][cb][r] + eb.col[cb];
                     acc[ms][cb][r] = x > 0.f ? x : 0.f;
                 }
-    } else {
-#pragma unroll
-        for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb)
+            } else {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[ms][cb][r] += eb.col[cb];
-    }
+            }
+        }
 }
 
 // FUSED: the kernel variant with the fused epilogue (a bias and / or an activation); the plain variant
