@@ -54,24 +54,26 @@ __device__ __forceinline__ float tw_to_f32(unsigned short bits) {
     }
 }
 
-// erf(x) in fp32 by the rational approximation 7.1.26 of Abramowitz and Stegun,
-//   erf(x) = 1 - (a1 t + a2 t^2 + a3 t^3 + a4 t^4 + a5 t^5) exp(-x^2),  t = 1 / (1 + p x),  x >= 0,
-// absolute error below 1.5e-7: far below the rounding of the 16-bit result, and straight-line code
-// (the library routine is a page of branches, which costs registers when it is inlined 128 times).
-__device__ __forceinline__ float tw_erf(float x) {
+// GELU in its exact form x * Phi(x) = x/2 * (1 + erf(x / sqrt 2)), in fp32, with erf by the rational
+// approximation 7.1.26 of Abramowitz and Stegun,
+//   erf(y) = 1 - (a1 t + a2 t^2 + a3 t^3 + a4 t^4 + a5 t^5) exp(-y^2),  t = 1 / (1 + p y),  y >= 0,
+// absolute error below 1.5e-7: far below the rounding of the 16-bit result, and straight-line code (the library
+// routine is a page of branches, which costs registers when it is inlined 128 times).  With y = |x| / sqrt 2 and
+// q = (a1 t + ... + a5 t^5) exp(-x^2 / 2) / 2 both signs of x give  gelu(x) = max(x, 0) - |x| q,  which needs no
+// sign transfer and no 1 + erf; the constants carry the factors 1/2, 1/sqrt 2 and log2(e), the exponential is the
+// hardware's base-2 one.  The vector ALU bounds the fused GELU, so every operation here shows in the time.
+__device__ __forceinline__ float tw_gelu(float x) {
     const float ax = __builtin_fabsf(x);
-    const float t = __builtin_amdgcn_rcpf(1.f + 0.3275911f * ax);
-    float poly = 1.061405429f;
-    poly = poly * t - 1.453152027f;
-    poly = poly * t + 1.421413741f;
-    poly = poly * t - 0.284496736f;
-    poly = poly * t + 0.254829592f;
-    const float e = __expf(-ax * ax);
-    const float r = 1.f - poly * t * e;
-    return __builtin_copysignf(r, x);
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.23164189f, ax, 1.f));        // p / sqrt 2
+    float poly = 0.5307027145f;                                                           // a5 / 2, a4 / 2, ...
+    poly = __builtin_fmaf(poly, t, -0.7265760135f);
+    poly = __builtin_fmaf(poly, t, 0.7107068705f);
+    poly = __builtin_fmaf(poly, t, -0.142248368f);
+    poly = __builtin_fmaf(poly, t, 0.127414796f);
+    const float e = __builtin_amdgcn_exp2f(-0.72134752f * (x * x));                       // exp(-x^2 / 2)
+    const float q = poly * t * e;
+    return __builtin_fmaf(-ax, q, __builtin_fmaxf(x, 0.f));
 }
-
-__device__ __forceinline__ float tw_gelu(float x) { return 0.5f * x * (1.f + tw_erf(x * 0.70710678118654752f)); }
 
 // Activation of the fused epilogue, in fp32.  act is wave-uniform.
 __device__ __forceinline__ float tw_activate(float x, int act) {
