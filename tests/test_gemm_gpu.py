@@ -775,3 +775,54 @@ def test_hip_graph_replays_match_eager(tw):
     assert _rel_err(_to_f64(H), ref_h) <= TOL[dtype]
     ref_ao = tw_ref.masked_gemm(bits(QKV[:, :768]), ws[1].B, ws[1].mask, dtype)
     assert _rel_err(_to_f64(AO), ref_ao) <= TOL[dtype]
+
+
+# ------------------------------------------------------------------ seeded random shapes at full occupancy
+def _random_big_case(seed):
+    """Enough rows to give every compute unit a 64-row block (so the 64-row kernels of all three modes run), a
+    ragged last block, K in the resident and the streamed regime, few and many tiles."""
+    rng = np.random.default_rng(55000 + seed)
+    M = int(rng.choice([16384, 16411, 20001, 33000]))
+    K = int(rng.choice([200, 768, 1536, 1600, 2304, 3100]))
+    G = int(rng.choice([32, 64, 128]))
+    N = int(rng.choice([G * 2 + 5, G * 4, G * 6 - 3, G * 9 + 1]))
+    dtype = "f16" if rng.random() < 0.5 else "bf16"
+    cp = float(rng.choice([0.0, 0.05, 0.25]))
+    return M, K, N, G, dtype, cp, ("upow", 0.05, float(rng.choice([0.3, 0.7])))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_big_shapes_on_sampled_rows(tw, seed):
+    M, K, N, G, dtype, cp, keep = _random_big_case(seed)
+    spec = W.small_spec(f"randbig{seed}", M=M, K=K, N=N, G=G, dtype=dtype, col_prune=cp, keep=keep,
+                        seed_offset=66000 + seed)
+    w = W.generate(spec)
+    blob = tw.tw_pack(w.B, w.mask, G, dtype)
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    pl, plt = tw.tw_gemm_plan(blob, M, n_cu=n_cu), tw.tw_gemm_plan(blob, M, n_cu=n_cu, transposed=True)
+    _say(f"random big seed {seed}: M={M} K={K} N={N} G={G} {dtype} col_prune={cp} keep={keep} "
+         f"plan mode {pl['mode']}/{plt['mode']} rows {pl['rows_per_block']} tiles per set {pl['tiles_per_set']}")
+    wt = tw.TwWeight(blob)
+    rows = np.unique(np.concatenate([_sample_rows(M, n=80, seed=seed), np.arange(M - 70, M)]))
+    ridx = torch.as_tensor(rows, device="cuda:0")
+    ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, w.mask, dtype)
+    A = _device_A(tw, w.A, dtype)
+    C = torch.full((M, N), float("nan"), dtype=A.dtype, device="cuda:0")
+    tw.tw_gemm(wt, A, C)
+    At = _device_At(tw, w.A, dtype)
+    del A
+    ldct = (M + 7) // 8 * 8 + 8
+    Ctb = torch.full((N, ldct), float("nan"), dtype=C.dtype, device="cuda:0")
+    tw.tw_gemm_t(wt, At, Ctb[:, :M])
+    torch.cuda.synchronize()
+    ws = wt.workspace.view(torch.int32)[:4].cpu().tolist()
+    assert ws[0] == 0 and ws[1] == 0 and ws[3] == 0, f"workspace after the calls: {ws}"
+    assert bool(torch.isfinite(C.float()).all().item())
+    assert _rel_err(_to_f64(C[ridx]), ref) <= TOL[dtype]
+    assert torch.equal(Ctb[:, :M].T.contiguous(), C), "the two boundaries differ in some bit"
+    assert bool(torch.isnan(Ctb[:, M:].float()).all().item()), "wrote outside Ct"
+    pruned = np.flatnonzero(~w.mask.any(axis=0))
+    if len(pruned):
+        assert float(C[:, torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
+    del C, Ctb, At, wt
+    torch.cuda.empty_cache()
