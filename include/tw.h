@@ -145,7 +145,8 @@ typedef struct tw_plan_t {
     int32_t mode;            /* 0: the K extent of a row block stays in on-chip memory, waves pull whole tiles;
                                 1: K streamed in chunks, a wave per tile;
                                 2: K streamed, four waves multiply (a tile each), four only load A */
-    int32_t rows_per_block;  /* rows of A (tokens) of a work item: 64 or 32 */
+    int32_t rows_per_block;  /* rows of A (tokens) of a work item: 64 or 32; tw_gemm may take a multiple of 8
+                                between them so that the row blocks fill the last round of workgroups */
     int32_t tiles_per_set;   /* streamed K: tiles a workgroup holds (8 or 4); 0 with mode 0 */
     int32_t n_row_blocks;    /* ceil(M / rows_per_block) */
     int32_t n_sets;          /* mode 0: workgroups that share the tiles of a row block; else sets of tiles */

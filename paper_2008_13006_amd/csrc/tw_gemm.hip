@@ -74,6 +74,8 @@ struct TwGemmParams {
     int k_chunk, n_chunks, G;
     int n_mblocks, n_seg, n_items;
     int tiles_per_set;          // MODE 2: tiles a workgroup holds (1..4: that many of the multiplying waves have one)
+    int row_step;               // rows (tokens) from one row block to the next: 32*MS, or fewer (row-major boundary) so
+                                // that the row blocks fill the last round of workgroups; rows past it are not stored
     unsigned at_pitch;          // bytes between K rows of the LDS copy of A (32*MS rows of A wide, padded)
     unsigned abuf_bytes;        // size of one LDS copy of A (streamed K uses two)
     unsigned stage_off;         // LDS offset of the per-wave staging areas
@@ -88,6 +90,11 @@ struct TwGemmParams {
 };
 
 __device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+// one past the last row of the row block that starts at row0
+__device__ __forceinline__ int block_end(const TwGemmParams& p, int row0) {
+    const int e = row0 + p.row_step;
+    return e < p.M ? e : p.M;
+}
 // Returns x, but hides where it came from: values derived from the result are recomputed where they
 // are used instead of being hoisted out of the persistent loop and kept (or spilled) across phases.
 __device__ __forceinline__ int fresh(int x) {
@@ -178,14 +185,15 @@ template <int MS, int BATCH, bool PAIR>
 __device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int row0, int k0, int kw, int t0,
                                         int lane_in, int stride = kWaves) {
     const int lane = fresh(lane_in);
+    const int mend = block_end(p, row0);
     if constexpr (PAIR) {
         static_assert(BATCH % 2 == 0, "two requests per task");
 #pragma unroll
         for (int b = 0; b < BATCH / 2; ++b) {
             const ATask<MS, true> t(t0 + b * stride, kw, lane);
             int g0 = row0 + t.row, g1 = g0 + 1;
-            g0 = g0 < p.M ? g0 : p.M - 1;             // rows past M: any valid row, never stored
-            g1 = g1 < p.M ? g1 : p.M - 1;
+            g0 = g0 < mend ? g0 : mend - 1;           // rows past the block's end: any valid row, never stored
+            g1 = g1 < mend ? g1 : mend - 1;
             ar.v[2 * b] = *(const tw_u32x4*)(p.A + (long)g0 * p.lda + (k0 + t.oc * 8));
             ar.v[2 * b + 1] = *(const tw_u32x4*)(p.A + (long)g1 * p.lda + (k0 + t.oc * 8));
         }
@@ -194,7 +202,7 @@ __device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar,
         for (int b = 0; b < BATCH; ++b) {
             const ATask<MS, false> t(t0 + b * stride, kw, lane);
             int grow = row0 + t.row;
-            grow = grow < p.M ? grow : p.M - 1;
+            grow = grow < mend ? grow : mend - 1;
             ar.v[b] = *(const tw_u32x4*)(p.A + (long)grow * p.lda + (k0 + t.oc * 8));
         }
     }
@@ -498,7 +506,7 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
     const int W0 = S & ~(kLineCols - 1);
     const unsigned shift = (unsigned)((S & ~7) - W0);       // dpos counts from S & ~7
     constexpr int NP = 4 * MS;
-    const int rows_left = p.M - (row0 + orow);              // pass P stores this lane's row iff 8P < rows_left
+    const int rows_left = block_end(p, row0) - (row0 + orow);   // pass P stores this lane's row iff 8P < rows_left
     for (int win0 = W0; win0 < E; win0 += kWinCols) {       // one window unless the span is very wide
         const int left = E - win0;
         const int nl = left >= kWinCols ? kWinLines : (left + kLineCols - 1) / kLineCols;
@@ -527,7 +535,7 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
         const unsigned char* ragF = ragbase + ((g_first < 0 ? 0 : g_first) * 8 + tg) * 8;
         const unsigned char* ragL = ragbase + ((g_last < 0 ? 0 : g_last) * 8 + tg) * 8;
         unsigned short* rptr = p.C + (long)(row0 + trow) * p.ldc;
-        const int rag_left = p.M - (row0 + trow);
+        const int rag_left = block_end(p, row0) - (row0 + trow);
 
         auto write_pass = [&](int P) {
             const int ms = P >> 2, q = P & 3;
@@ -884,7 +892,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             // the whole K extent of the row block stays in LDS; waves pull tiles of this item's set
             // (TRANS: transposed boundary, the row block is a block of tokens)
             const int mb = item / p.n_seg, seg = item - mb * p.n_seg;
-            const int row0 = mb * BM;
+            const int row0 = mb * p.row_step;
             // first tile of this wave: its descriptor is requested before A is staged
             int i = 0;
             if (lane == 0) i = atomicAdd((int*)&misc[1], 1);
@@ -931,7 +939,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             constexpr int NMUL = kWaves / 2, NLD = kWaves - NMUL;
             constexpr int PB = 12;   // requests per loading wave and chunk: 64 rows x 384 columns in 4 waves
             const int set = item / p.n_mblocks, mb = item - set * p.n_mblocks;
-            const int row0 = mb * BM;
+            const int row0 = mb * p.row_step;
             const bool loader = wave >= NMUL;
             const int ti = set * p.tiles_per_set + wave;
             const bool active = wave < p.tiles_per_set && ti < p.T;      // (tiles_per_set <= NMUL: never a loading wave)
@@ -1019,7 +1027,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (preloaded) {
                     const int nset = nxt / p.n_mblocks;
                     if (use_rows && nset != lists_of) { load_lists(nset); lists_of = nset; }
-                    start_item((nxt % p.n_mblocks) * BM);
+                    start_item((nxt % p.n_mblocks) * p.row_step);
                 }
             } else {
                 unsigned dpos[NCB];
@@ -1076,7 +1084,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             // K is streamed in chunks through two LDS buffers: the requests for chunk c+1 go out before
             // the steps of chunk c and are written to the other buffer after them, one barrier per chunk
             const int set = item / p.n_mblocks, mb = item - set * p.n_mblocks;
-            const int row0 = mb * BM;
+            const int row0 = mb * p.row_step;
             const int ti = set * kWaves + wave;
             const bool active = ti < p.T;
             const TileU d = fetch_tile(p, active ? ti : 0);
@@ -1285,6 +1293,7 @@ struct Plan {
     int ms;         // the kernel's MS
     int n_mblocks, n_seg, n_items;
     int tiles_per_set;   // streamed K: tiles a workgroup holds
+    int row_step;        // rows per row block (see TwGemmParams)
     unsigned at_pitch, abuf_bytes, stage_off, misc_off, lds_bytes;
     unsigned urow_off;   // transposed boundary, loading waves: LDS offset of their row lists (0: whole chunks are read)
 };
@@ -1340,8 +1349,23 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     }
     if (!resident && msb != 2) return TW_ERR_UNSUPPORTED;   // (the streamed kernels take 64-row blocks; 384-row chunks fit)
     pl.ms = msb;
-    const long items = items_for(msb, tpw, nmb, nseg);
+    long items = items_for(msb, tpw, nmb, nseg);
     if (items > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
+    pl.row_step = 32 * msb;
+    // Row-major boundary, several rounds of 64-row blocks, the last one partly empty (the conv workload: 1568
+    // blocks on 256 compute units are 6.1 rounds): slightly lower row blocks fill the last round, and every
+    // block then brings in and stores fewer rows (56 instead of 64: 7 full rounds of 7/8 the traffic each).
+    // The transposed boundary keeps 64 tokens: a block's tokens are whole 128-byte lines of the output there.
+    if (!transposed && msb == 2 && items > n_cu && items % n_cu != 0) {
+        const long rounds = (items + n_cu - 1) / n_cu;
+        const long blocks = rounds * n_cu / nseg;                 // row blocks that fit into that many rounds
+        int rows = (int)(((M + blocks - 1) / blocks + 7) / 8 * 8);
+        if (rows > 32 && rows < 64) {
+            pl.row_step = rows;
+            nmb = (M + rows - 1) / rows;
+            items = (long)nmb * nseg;
+        }
+    }
     if (!resident && 4 * msb * ((((h->k_chunk + 7) >> 3) + 7) >> 3) > kWaves * 6) return TW_ERR_UNSUPPORTED;   // a chunk is one batch
     pl.n_mblocks = nmb; pl.n_seg = nseg; pl.n_items = (int)items;
     pl.at_pitch = 64u * msb + 8u;
@@ -1424,7 +1448,7 @@ extern "C" int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transpos
     const int rc = make_plan(h, M, n_cu, pl, transposed != 0);
     if (rc) return rc;
     plan->mode = pl.mode;
-    plan->rows_per_block = 32 * pl.ms;
+    plan->rows_per_block = pl.row_step;
     plan->tiles_per_set = pl.tiles_per_set;
     plan->n_row_blocks = pl.n_mblocks;
     plan->n_sets = pl.n_seg;
@@ -1493,7 +1517,7 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.lda = lda; p.ldc = ldc;
     p.M = M; p.K = h->K; p.N = h->N; p.T = h->T;
     p.k_chunk = h->k_chunk; p.n_chunks = h->n_chunks; p.G = h->G;
-    p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items; p.tiles_per_set = pl.tiles_per_set;
+    p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items; p.tiles_per_set = pl.tiles_per_set; p.row_step = pl.row_step;
     p.at_pitch = pl.at_pitch; p.abuf_bytes = pl.abuf_bytes;
     p.stage_off = pl.stage_off; p.misc_off = pl.misc_off;
     p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;
@@ -1567,7 +1591,7 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.lda = ldat; p.ldc = ldct;
     p.M = M; p.K = h->K; p.N = h->N; p.T = h->T;
     p.k_chunk = h->k_chunk; p.n_chunks = h->n_chunks; p.G = h->G;
-    p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items; p.tiles_per_set = pl.tiles_per_set;
+    p.n_mblocks = pl.n_mblocks; p.n_seg = pl.n_seg; p.n_items = pl.n_items; p.tiles_per_set = pl.tiles_per_set; p.row_step = pl.row_step;
     p.at_pitch = pl.at_pitch; p.abuf_bytes = pl.abuf_bytes;
     p.stage_off = pl.stage_off; p.misc_off = pl.misc_off;
     p.off_sched_desc = h->off_sched_desc; p.off_step_ptr = h->off_step_ptr; p.off_goff = h->off_goff;

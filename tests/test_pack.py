@@ -310,10 +310,12 @@ def test_plan_of_the_paper_shaped_workloads():
     assert inf["T"] == 8
     assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["n_sets"], pl["n_items"]) == (2, 64, 4, 2, 256)
     spec, inf, pl = _plan("c5_conv_im2col", 0)                # K = 2304, 4 tiles
-    assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["n_sets"]) == (2, 64, 4, 1)
-    assert pl["n_items"] == (spec.M + 63) // 64 and pl["grid"] == 256 and pl["row_lists"] == 0
-    spec, inf, plt = _plan("c5_conv_im2col", 0, transposed=True)
-    assert plt["mode"] == 2 and plt["row_lists"] == 1 and plt["lds_bytes"] > pl["lds_bytes"]
+    # 1568 blocks of 64 rows would be 6.1 rounds on 256 compute units: 1792 blocks of 56 rows are 7 full ones
+    assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["n_sets"]) == (2, 56, 4, 1)
+    assert pl["n_items"] == 7 * 256 == (spec.M + 55) // 56 and pl["grid"] == 256 and pl["row_lists"] == 0
+    spec, inf, plt = _plan("c5_conv_im2col", 0, transposed=True)       # whole 128-byte lines of tokens: 64 stay
+    assert plt["mode"] == 2 and plt["rows_per_block"] == 64 and plt["n_items"] == (spec.M + 63) // 64
+    assert plt["row_lists"] == 1 and plt["lds_bytes"] > pl["lds_bytes"]
     spec, inf, plt = _plan("c4_bert_large_skewed", 1, transposed=True)
     assert plt["mode"] == 2 and plt["n_sets"] == 2 and plt["row_lists"] == 0     # the lists are per set of eight tiles
 
@@ -331,7 +333,8 @@ def test_plan_limits_and_errors():
                     if tr and K > 1536:
                         assert pl["rows_per_block"] == 64      # the streamed transposed kernels take 64 tokens
                     assert pl["lds_bytes"] <= 160 * 1024
-                    assert pl["rows_per_block"] in (32, 64)
+                    assert 32 <= pl["rows_per_block"] <= 64 and pl["rows_per_block"] % 8 == 0
+                    assert pl["rows_per_block"] in (32, 64) or not tr
                     assert pl["n_row_blocks"] == (M + pl["rows_per_block"] - 1) // pl["rows_per_block"]
                     assert pl["n_items"] == pl["n_row_blocks"] * pl["n_sets"] and pl["grid"] == min(pl["n_items"], n_cu)
                     assert (pl["mode"] == 0) == (K <= 1536)
