@@ -29,8 +29,8 @@ MFMA_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA
 # HBM bytes per tw_gemm launch on this workload, from the two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) summarised in profiles/tw_gemm_c2_hbm_traffic.txt, each scaled by what the same counter
 # reads for the copy kernel of known size that `--pmc-calibration` launches.
-MEASURED_TRAFFIC_BYTES = 149_806_418      # 35.81 MB read + 114.00 MB written
-MEASURED_TRAFFIC_BYTES_T = 136_405_639    # tw_gemm_t: 35.74 MB read + 100.66 MB written (profiles/tw_gemm_t_c2_hbm_traffic.txt)
+MEASURED_TRAFFIC_BYTES = 149_766_644      # 35.91 MB read + 113.86 MB written
+MEASURED_TRAFFIC_BYTES_T = 136_375_040    # tw_gemm_t: 35.71 MB read + 100.66 MB written (profiles/tw_gemm_t_c2_hbm_traffic.txt)
 PAPER_CONTEXT = {"tw128_speedup_vs_dense_75pct": 2.26, "hardware": "NVIDIA V100 tensor cores, FP16",
                  "where": "Sec. VII-B, Fig. 8b"}
 

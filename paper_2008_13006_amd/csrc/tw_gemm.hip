@@ -1352,11 +1352,13 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     long items = items_for(msb, tpw, nmb, nseg);
     if (items > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
     pl.row_step = 32 * msb;
-    // Row-major boundary, several rounds of 64-row blocks, the last one partly empty (the conv workload: 1568
-    // blocks on 256 compute units are 6.1 rounds): slightly lower row blocks fill the last round, and every
-    // block then brings in and stores fewer rows (56 instead of 64: 7 full rounds of 7/8 the traffic each).
-    // The transposed boundary keeps 64 tokens: a block's tokens are whole 128-byte lines of the output there.
-    if (!transposed && msb == 2 && items > n_cu && items % n_cu != 0) {
+    // Row-major boundary, two to four rounds of 64-row blocks, the last one partly empty (M = 20001: 313 blocks
+    // on 256 compute units): lower row blocks fill the last round, and every block then brings in and stores
+    // fewer rows (40 instead of 64: 86 us instead of 100 us on the FFN-up of BERT-base).  With more rounds the
+    // empty part of the last one weighs little and the extra blocks cost as much as they gain (the conv
+    // workload, 6.1 rounds: no change with 56-row blocks).  The transposed boundary keeps 64 tokens: a block's
+    // tokens are whole 128-byte lines of the output there.
+    if (!transposed && msb == 2 && items > n_cu && items <= 4L * n_cu && items % n_cu != 0) {
         const long rounds = (items + n_cu - 1) / n_cu;
         const long blocks = rounds * n_cu / nseg;                 // row blocks that fit into that many rounds
         int rows = (int)(((M + blocks - 1) / blocks + 7) / 8 * 8);

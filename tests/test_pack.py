@@ -310,14 +310,27 @@ def test_plan_of_the_paper_shaped_workloads():
     assert inf["T"] == 8
     assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["n_sets"], pl["n_items"]) == (2, 64, 4, 2, 256)
     spec, inf, pl = _plan("c5_conv_im2col", 0)                # K = 2304, 4 tiles
-    # 1568 blocks of 64 rows would be 6.1 rounds on 256 compute units: 1792 blocks of 56 rows are 7 full ones
-    assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["n_sets"]) == (2, 56, 4, 1)
-    assert pl["n_items"] == 7 * 256 == (spec.M + 55) // 56 and pl["grid"] == 256 and pl["row_lists"] == 0
+    assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["n_sets"]) == (2, 64, 4, 1)
+    assert pl["n_items"] == (spec.M + 63) // 64 and pl["grid"] == 256 and pl["row_lists"] == 0
     spec, inf, plt = _plan("c5_conv_im2col", 0, transposed=True)       # whole 128-byte lines of tokens: 64 stay
     assert plt["mode"] == 2 and plt["rows_per_block"] == 64 and plt["n_items"] == (spec.M + 63) // 64
     assert plt["row_lists"] == 1 and plt["lds_bytes"] > pl["lds_bytes"]
     spec, inf, plt = _plan("c4_bert_large_skewed", 1, transposed=True)
     assert plt["mode"] == 2 and plt["n_sets"] == 2 and plt["row_lists"] == 0     # the lists are per set of eight tiles
+
+
+def test_plan_fills_the_last_round_on_the_row_major_boundary():
+    """Two to four rounds of 64-row blocks with a partly empty last one: lower row blocks (a multiple of 8 rows)
+    that fill it; the transposed boundary keeps 64 tokens."""
+    spec = W.CONFIGS["c2_bert_base_ffn_up"][0]
+    w = W.generate(spec, with_A=False)
+    blob = tw.tw_pack(w.B, w.mask, spec.G, spec.dtype)
+    for M, rows in ((16384, 64), (17000, 40), (20001, 40), (24576, 48), (32768, 64), (33000, 48), (100352, 64)):
+        pl = tw.tw_gemm_plan(blob, M, n_cu=256)
+        assert pl["rows_per_block"] == rows and pl["n_row_blocks"] == (M + rows - 1) // rows, (M, pl)
+        rounds64 = ((M + 63) // 64 + 255) // 256
+        assert (pl["n_items"] + 255) // 256 == rounds64, "no more rounds than 64-row blocks would make"
+        assert tw.tw_gemm_plan(blob, M, n_cu=256, transposed=True)["rows_per_block"] == 64
 
 
 def test_plan_limits_and_errors():
