@@ -172,7 +172,9 @@ int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transposed, tw_plan
  *              columns); 2-byte aligned rows suffice
  *   workspace  device, >= tw_gemm_workspace bytes, 256-byte aligned, zeroed as described above
  * M >= 0 (M = 0 enqueues nothing).  Calls on one workspace must not overlap in time (use one
- * workspace per stream).  The best speed needs a C base and ldc that are multiples of 64 elements
+ * workspace per stream).  The call enqueues kernels only (no memset, no copy, no allocation), so it can be
+ * recorded into a HIP graph; the first call that uses a kernel variant on a device raises that kernel's
+ * dynamic-LDS limit (a function attribute), so make one call of each kind before a stream capture.  The best speed needs a C base and ldc that are multiples of 64 elements
  * (128-byte lines); any other layout is correct and slower.
  * Errors: TW_ERR_ARG (null pointer, negative M, lda/ldc too small), TW_ERR_BUF (not a blob of this
  * format version, workspace too small), TW_ERR_ALIGN, TW_ERR_UNSUPPORTED (more than 2^31 work items),
