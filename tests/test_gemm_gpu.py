@@ -827,5 +827,20 @@ def test_random_big_shapes_on_sampled_rows(tw, seed):
     pruned = np.flatnonzero(~w.mask.any(axis=0))
     if len(pruned):
         assert float(C[:, torch.as_tensor(pruned, device="cuda:0")].float().abs().max().item()) == 0.0
-    del C, Ctb, At, wt
+    del Ctb, At
+    # the fused epilogue and, where K is resident or streamed alike, the hybrid's residual on the same plan
+    bbits = _bias_bits(N, dtype, 100 + seed)
+    C.fill_(float("nan"))
+    tw.tw_gemm_bias_act(wt, _device_A(tw, w.A, dtype), tw.bits_to_tensor(bbits, dtype), "relu", C)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(C.float()).all().item())
+    assert _rel_err(_to_f64(C[ridx]), tw_ref.bias_act(ref, tw_ref.decode(bbits, dtype), "relu")) <= TOL[dtype]
+    ew = tw.tw_restore_ew(w.B, w.mask, 0.004, dtype)
+    wte = tw.TwWeight(tw.tw_pack_tew(w.B, w.mask, ew, G, dtype))
+    C.fill_(float("nan"))
+    tw.tw_gemm(wte, _device_A(tw, w.A, dtype), C)
+    torch.cuda.synchronize()
+    ref_e = tw_ref.masked_gemm(np.ascontiguousarray(w.A[rows]), w.B, (w.mask | ew).astype(np.uint8), dtype)
+    assert _rel_err(_to_f64(C[ridx]), ref_e) <= TOL[dtype]
+    del C, wt, wte
     torch.cuda.empty_cache()
