@@ -90,6 +90,9 @@ struct TwGemmParams {
 };
 
 __device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+// bytes between K rows of the LDS copy of A: 32*MS rows of A wide, padded by 8 (a compile-time value, so that the
+// eight K rows a staging request writes to are immediate offsets of its LDS writes, not a multiplication each)
+template <int MS> constexpr unsigned at_pitch_of() { return 64u * MS + 8u; }
 // one past the last row of the row block that starts at row0
 __device__ __forceinline__ int block_end(const TwGemmParams& p, int row0) {
     const int e = row0 + p.row_step;
@@ -220,7 +223,7 @@ __device__ __forceinline__ void a_commit(const TwGemmParams& p, const ARegs<BATC
         for (int b = 0; b < BATCH / 2; ++b) {
             const ATask<MS, true> t(t0 + b * stride, kw, lane);
             const int kcol = t.have ? t.oc * 8 : dump;
-            unsigned char* dst = at + (unsigned)kcol * p.at_pitch + t.row * 2;
+            unsigned char* dst = at + (unsigned)kcol * at_pitch_of<MS>() + t.row * 2;
             const unsigned x[4] = {ar.v[2 * b].x, ar.v[2 * b].y, ar.v[2 * b].z, ar.v[2 * b].w};
             const unsigned y[4] = {ar.v[2 * b + 1].x, ar.v[2 * b + 1].y, ar.v[2 * b + 1].z, ar.v[2 * b + 1].w};
             unsigned w[8];
@@ -229,11 +232,11 @@ __device__ __forceinline__ void a_commit(const TwGemmParams& p, const ARegs<BATC
                 w[i] = (i & 1) ? ((x[i >> 1] >> 16) | (y[i >> 1] & 0xFFFF0000u)) : ((x[i >> 1] & 0xFFFFu) | (y[i >> 1] << 16));
             if (!tail) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) *(unsigned*)(dst + (unsigned)i * p.at_pitch) = w[i];
+                for (int i = 0; i < 8; ++i) *(unsigned*)(dst + (unsigned)i * at_pitch_of<MS>()) = w[i];
             } else {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
-                    if (kcol + i < kw || kcol == dump) *(unsigned*)(dst + (unsigned)i * p.at_pitch) = w[i];
+                    if (kcol + i < kw || kcol == dump) *(unsigned*)(dst + (unsigned)i * at_pitch_of<MS>()) = w[i];
             }
         }
     } else {
@@ -241,17 +244,17 @@ __device__ __forceinline__ void a_commit(const TwGemmParams& p, const ARegs<BATC
         for (int b = 0; b < BATCH; ++b) {
             const ATask<MS, false> t(t0 + b * stride, kw, lane);
             const int kcol = t.have ? t.oc * 8 : dump;
-            unsigned char* dst = at + (unsigned)kcol * p.at_pitch + t.row * 2;
+            unsigned char* dst = at + (unsigned)kcol * at_pitch_of<MS>() + t.row * 2;
             const unsigned w[4] = {ar.v[b].x, ar.v[b].y, ar.v[b].z, ar.v[b].w};
             if (!tail) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
-                    *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
+                    *(unsigned short*)(dst + (unsigned)i * at_pitch_of<MS>()) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
             } else {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
                     if (kcol + i < kw || kcol == dump)
-                        *(unsigned short*)(dst + (unsigned)i * p.at_pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
+                        *(unsigned short*)(dst + (unsigned)i * at_pitch_of<MS>()) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
             }
         }
     }
@@ -654,7 +657,7 @@ __device__ __forceinline__ void at_commit(const TwGemmParams& p, const ARegs<BAT
     for (int b = 0; b < BATCH; ++b) {
         const AtTask<MS> t(t0 + b * stride, kw, lane);
         const int krow = t.have ? t.krow : p.k_chunk + 1 + (lane / PPR) % 8;   // absent rows: the spare rows
-        unsigned char* dst = at + (unsigned)krow * p.at_pitch + t.pc * 16;
+        unsigned char* dst = at + (unsigned)krow * at_pitch_of<MS>() + t.pc * 16;
         *(tw_u32x2*)dst = tw_u32x2{ar.v[b].x, ar.v[b].y};
         *(tw_u32x2*)(dst + 8) = tw_u32x2{ar.v[b].z, ar.v[b].w};
     }
@@ -687,7 +690,7 @@ __device__ __forceinline__ void at_commit_rows(const TwGemmParams& p, const AReg
     for (int b = 0; b < BATCH; ++b) {
         const int j = 8 * (t0 + b * stride) + (lane >> 3);
         const int krow = j < cnt ? (int)rows[8 * b + (lane >> 3)] : p.k_chunk + 1 + (lane >> 3);
-        unsigned char* dst = at + (unsigned)krow * p.at_pitch + (lane & 7) * 16;
+        unsigned char* dst = at + (unsigned)krow * at_pitch_of<2>() + (lane & 7) * 16;   // (64 tokens: MS = 2)
         *(tw_u32x2*)dst = tw_u32x2{ar.v[b].x, ar.v[b].y};
         *(tw_u32x2*)(dst + 8) = tw_u32x2{ar.v[b].z, ar.v[b].w};
     }
@@ -706,17 +709,65 @@ __device__ __forceinline__ void load_at_block(const TwGemmParams& p, unsigned ch
 }
 
 // The two boundaries behind one name (TRANS: transposed).
+// The common case of the streamed row-major staging written out (used where all eight waves stage): a chunk of
+// 64 rows whose width is exactly what BATCH requests of STRIDE waves cover (8 * BATCH * STRIDE columns, 384 for
+// 6 x 8), wave t0 < STRIDE.
+// Same tasks and same LDS layout as a_issue / a_commit without row pairs (task t0 + b * STRIDE: rows
+// 8 * (t % 8) .. + 7, columns 64 * (t / 8) .. + 63), but everything that does not depend on the lane is a
+// constant here: one or two row pointers per chunk, one LDS address, immediate offsets (the general code
+// spends about 75 instructions per request on its bookkeeping): 5 % on the FFN-down of BERT-base.
+template <int BATCH, int STRIDE>
+__device__ __forceinline__ void a_issue_full(const TwGemmParams& p, ARegs<BATCH>& ar, int row0, int k0, int t0, int lane_in) {
+    static_assert(STRIDE == 4 || STRIDE == 8, "waves that share a chunk");
+    const int lane = fresh(lane_in);
+    const int mend = block_end(p, row0);
+    constexpr int NRG = 8 / STRIDE;                       // row groups of this wave: t0, t0 + STRIDE, ..
+    const unsigned short* rp[NRG];
+#pragma unroll
+    for (int g = 0; g < NRG; ++g) {
+        int grow = row0 + (t0 + g * STRIDE) * 8 + (lane >> 3);
+        grow = grow < mend ? grow : mend - 1;             // rows past the block's end: any valid row, never stored
+        rp[g] = p.A + (long)grow * p.lda + (k0 + (lane & 7) * 8);
+    }
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b)
+        ar.v[b] = *(const tw_u32x4*)(rp[((b * STRIDE) & 7) / STRIDE] + ((b * STRIDE) >> 3) * 64);
+}
+template <int BATCH, int STRIDE>
+__device__ __forceinline__ void a_commit_full(const ARegs<BATCH>& ar, unsigned char* at, int t0, int lane_in) {
+    const int lane = fresh(lane_in);
+    constexpr unsigned pitch = at_pitch_of<2>();
+    unsigned char* base = at + (unsigned)((lane & 7) * 8) * pitch + (lane >> 3) * 2 + t0 * 16;
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+        unsigned char* dst = base + (unsigned)(((b * STRIDE) >> 3) * 64) * pitch + ((b * STRIDE) & 7) * 16;
+        const unsigned w[4] = {ar.v[b].x, ar.v[b].y, ar.v[b].z, ar.v[b].w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *(unsigned short*)(dst + (unsigned)i * pitch) = (unsigned short)(w[i >> 1] >> (16 * (i & 1)));
+    }
+}
+
 template <int MS, int BATCH, bool TRANS>
 __device__ __forceinline__ void stage_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int r0, int k0, int kw, int t0, int lane,
                                             int stride = kWaves) {
-    if constexpr (TRANS) at_issue<MS, BATCH>(p, ar, r0, k0, kw, t0, lane, stride);
-    else a_issue<MS, BATCH, kPairStream>(p, ar, r0, k0, kw, t0, lane, stride);
+    if constexpr (TRANS) {
+        at_issue<MS, BATCH>(p, ar, r0, k0, kw, t0, lane, stride);
+    } else {
+        // (with four loading waves the written-out form measured no faster, 1.6 % slower on the conv workload)
+        if (MS == 2 && stride == 8 && kw == 64 * BATCH) a_issue_full<BATCH, 8>(p, ar, r0, k0, t0, lane);
+        else a_issue<MS, BATCH, kPairStream>(p, ar, r0, k0, kw, t0, lane, stride);
+    }
 }
 template <int MS, int BATCH, bool TRANS>
 __device__ __forceinline__ void stage_commit(const TwGemmParams& p, const ARegs<BATCH>& ar, unsigned char* at, int kw, int t0,
                                              int lane, int stride = kWaves) {
-    if constexpr (TRANS) at_commit<MS, BATCH>(p, ar, at, kw, t0, lane, stride);
-    else a_commit<MS, BATCH, kPairStream>(p, ar, at, kw, t0, lane, stride);
+    if constexpr (TRANS) {
+        at_commit<MS, BATCH>(p, ar, at, kw, t0, lane, stride);
+    } else {
+        if (MS == 2 && stride == 8 && kw == 64 * BATCH) a_commit_full<BATCH, 8>(ar, at, t0, lane);
+        else a_commit<MS, BATCH, kPairStream>(p, ar, at, kw, t0, lane, stride);
+    }
 }
 
 // Epilogue of one tile, transposed output.  Column block by column block, a lane (packed column n, its
@@ -923,9 +974,9 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 tw_f32x16 acc[MS][NCB];
                 zero_acc<MS, NCB>(acc);
                 if (!TW_SKIPS(p, 2))
-                    run_steps<DT, MS, NCB>(acc, rg, smem, p.at_pitch, p.blob + p.off_goff + (long)d.first_step * 32,
+                    run_steps<DT, MS, NCB>(acc, rg, smem, at_pitch_of<MS>(), p.blob + p.off_goff + (long)d.first_step * 32,
                                            p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
-                if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, p.at_pitch, lane);
+                if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, at_pitch_of<MS>(), lane);
                 if (!TW_SKIPS(p, 4)) {
                     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                     else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
@@ -1058,8 +1109,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 };
                 auto steps_of = [&](int c) {
                     if (active && b0 < b1 && !TW_SKIPS(p, 2))
-                        run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, b0, b1, lane);
-                    if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, p.at_pitch, lane);
+                        run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
+                    if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
                     // on to chunk c+1
                     b0 = b1; b1 = b2;
                     b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
@@ -1140,8 +1191,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             };
             auto steps_of = [&](int c) {
                 if (active && b0 < b1 && !TW_SKIPS(p, 2))
-                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, p.at_pitch, gt, bt, b0, b1, lane);
-                if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, p.at_pitch, lane);
+                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
+                if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
                 b0 = b1; b1 = b2;
                 b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
                 if (c + 1 < p.n_chunks) prefetch_steps(b0, b1); else prefetch_steps(0, 0);
