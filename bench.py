@@ -26,13 +26,47 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 MFMA_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA
-# HBM bytes per tw_gemm launch on this workload, from the two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE) summarised in profiles/tw_gemm_c2_hbm_traffic.txt, each scaled by what the same counter
-# reads for the copy kernel of known size that `--pmc-calibration` launches.
-MEASURED_TRAFFIC_BYTES = 149_766_644      # 35.91 MB read + 113.86 MB written
-MEASURED_TRAFFIC_BYTES_T = 136_375_040    # tw_gemm_t: 35.71 MB read + 100.66 MB written (profiles/tw_gemm_t_c2_hbm_traffic.txt)
+# HBM bytes per launch on this workload come from the two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE)
+# summarised in these files, each counter scaled by what it reads for the copy kernel of known size that
+# `--pmc-calibration` launches.  A summary names the kernel sources it was measured on (`source_sha256:`); if the
+# sources in this tree are different ones, the figure is stale and `traffic` is reported as null.
+TRAFFIC_FILES = {False: os.path.join(ROOT, "profiles", "tw_gemm_c2_hbm_traffic.txt"),
+                 True: os.path.join(ROOT, "profiles", "tw_gemm_t_c2_hbm_traffic.txt")}
+KERNEL_SOURCES = ["paper_2008_13006_amd/csrc/tw_gemm.hip", "paper_2008_13006_amd/csrc/tw_device.hpp",
+                  "paper_2008_13006_amd/csrc/tw_format.h", "paper_2008_13006_amd/csrc/tw_pack.cpp"]
 PAPER_CONTEXT = {"tw128_speedup_vs_dense_75pct": 2.26, "hardware": "NVIDIA V100 tensor cores, FP16",
                  "where": "Sec. VII-B, Fig. 8b"}
+
+
+def kernel_source_hash() -> str:
+    """sha256 over the sources of the TW kernel and the packer (what decides the kernel's memory traffic)."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(transposed: bool):
+    """(bytes per launch, note) from the counter summary under profiles/, or (None, why) if it was measured on
+    other sources than the ones in this tree."""
+    path = TRAFFIC_FILES[transposed]
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, f"{os.path.relpath(path, ROOT)} missing"
+    fields = {}
+    for line in text.splitlines():
+        if ":" in line:
+            k, v = line.split(":", 1)
+            fields[k.strip()] = v.strip()
+    if fields.get("source_sha256") != kernel_source_hash():
+        return None, f"{os.path.relpath(path, ROOT)} was measured on other kernel sources (stale)"
+    try:
+        return int(fields["traffic_bytes_per_launch"]), os.path.relpath(path, ROOT)
+    except (KeyError, ValueError):
+        return None, f"{os.path.relpath(path, ROOT)} has no traffic_bytes_per_launch line"
 
 
 def algorithmic_bytes(info: dict, M: int) -> int:
@@ -72,7 +106,7 @@ def per_launch_stats(torch, fn, n_sets: int, steps: int):
 
 
 def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = True, n_sets=None,
-               with_warm: bool = False):
+               with_warm: bool = False, with_steady: bool = False):
     w = W.generate(spec)
     t0 = time.perf_counter()
     blob = tw.tw_pack(w.B, w.mask, spec.G, spec.dtype)
@@ -94,6 +128,9 @@ def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = T
     if with_warm:     # same buffers every launch: A and part of C stay in the last-level cache
         warm_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wt, As[0], Cs[0]), 1, steps, warmup)
     med_ms, min_ms = per_launch_stats(torch, lambda i: tw.tw_gemm(wt, As[i], Cs[i]), n_sets, min(steps, 50))
+    steady_ms = None
+    if with_steady:   # whatever --steps says: 200 launches after 50 warm-ups, clocks and queues settled
+        steady_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wt, As[i], Cs[i]), n_sets, 200, 50)
     # the same product on the transposed boundary (At in, Ct out): same algorithmic bytes
     Ats = [tw.tw_transpose(a).contiguous() for a in As]
     Cts = [torch.empty((spec.N, M), dtype=td, device="cuda:0") for _ in range(n_sets)]
@@ -101,7 +138,8 @@ def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = T
     del Ats, Cts
     out = dict(name=spec.name, M=M, K=spec.K, N=spec.N, G=spec.G, dtype=spec.dtype, T=int(info["T"]),
                sparsity=w.info["sparsity"], tw_ms=cold_ms, tw_ms_warm=warm_ms, tw_ms_median=med_ms,
-               tw_ms_min=min_ms, tw_wall_ms=cold_wall, pack_ms=pack_ms, n_buffer_sets=n_sets, tw_t_ms=t_ms)
+               tw_ms_min=min_ms, tw_wall_ms=cold_wall, pack_ms=pack_ms, n_buffer_sets=n_sets, tw_t_ms=t_ms,
+               tw_ms_steady=steady_ms)
     nz_flops = W.nonzero_flops(w.mask, M)
     dense_flops = 2.0 * M * spec.K * spec.N
     abytes = algorithmic_bytes(info, M)
@@ -119,7 +157,7 @@ def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = T
                    speedup_vs_dense=d_ms / cold_ms)
         # context only: the vendor library's dense GEMM through torch
         t_ms, _ = time_launches(torch, lambda i: torch.matmul(As[i], Bd, out=Cs[i]), n_sets, steps, warmup)
-        out.update(torch_matmul_ms=t_ms)
+        out.update(torch_matmul_ms=t_ms, speedup_vs_vendor_dense=t_ms / cold_ms)
     return out, w, info
 
 
@@ -218,9 +256,13 @@ def main() -> int:
                     help="also run the sparsity x G sweep on the FFN-up shape, write a table (JSON) here")
     ap.add_argument("--transposed", action="store_true", help="with --pmc-calibration: launch tw_gemm_t instead of tw_gemm")
     ap.add_argument("--pmc-sweep", action="store_true", help="counter runs of the sparsity sweep (G = 128)")
+    ap.add_argument("--source-hash", action="store_true", help="print the hash that the counter summaries record")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="counter runs: launch only a copy kernel of known size, then the tw_gemm steps")
     args = ap.parse_args()
+    if args.source_hash:
+        print(kernel_source_hash())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (rows of A and C are independent, so the path would "
               "shard over M with no collective); re-run with --gpus 1", file=sys.stderr)
@@ -237,7 +279,9 @@ def main() -> int:
         return pmc_sweep(torch, tw, W)
     if args.pmc_calibration:
         return pmc_calibration(torch, tw, W, spec, args.steps, args.transposed)
-    res, w, info = bench_gemm(torch, tw, W, spec, args.steps, args.warmup)
+    res, w, info = bench_gemm(torch, tw, W, spec, args.steps, args.warmup, with_steady=True)
+    traffic, traffic_note = measured_traffic(False)
+    traffic_t, traffic_t_note = measured_traffic(True)
     line = {
         "metric": "tw_gemm_ms (TW-sparse GEMM time, BERT-base FFN-up, 75% tile-wise sparsity)",
         "value": res["tw_ms"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -246,14 +290,16 @@ def main() -> int:
         "config": {"workload": "c2_bert_base_ffn_up: M=16384 K=768 N=3072 fp16 G=128, 75% TW sparsity, "
                                "5% columns pruned, tiles 10-50% kept", "T": res["T"],
                    "sparsity": round(res["sparsity"], 4), "cache": f"cold: {res['n_buffer_sets']} rotating (A,C) sets"},
-        "speedup_vs_dense": res["speedup_vs_dense"], "dense_ms": res["dense_ms"],
+        "speedup_vs_dense": res["speedup_vs_dense"], "speedup_vs_vendor_dense": res["speedup_vs_vendor_dense"],
+        "dense_ms": res["dense_ms"],
         "dense_tflops": res["dense_tflops"], "dense_mfma_frac": res["dense_mfma_frac"],
         "tw_tflops_nonzero": res["tw_tflops_nonzero"], "mfma_util_nonzero": res["tw_mfma_frac_nonzero"],
         "mfma_util_issued": res["padded_mfma_frac"],
-        "tw_ms_median": res["tw_ms_median"], "tw_ms_min": res["tw_ms_min"],
+        "tw_ms_median": res["tw_ms_median"], "tw_ms_min": res["tw_ms_min"], "tw_ms_steady": res["tw_ms_steady"],
         "torch_matmul_dense_ms_context": res["torch_matmul_ms"], "pack_ms_offline": res["pack_ms"],
         "roofline": {"bound": "hbm", "achieved": res["tw_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": res["tw_hbm_frac"], "traffic": MEASURED_TRAFFIC_BYTES,
+                     "frac": res["tw_hbm_frac"], "traffic": traffic, "traffic_source": traffic_note,
+                     "frac_steady": res["algorithmic_bytes"] / (res["tw_ms_steady"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "kernel": "tw_gemm_kernel<f16, MS=2 (64 rows), NCB=4 (G=128), MODE 0 (K resident)>",
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"]},
         # the same GEMM through tw_gemm_t (activations and result transposed, the paper's layout): not `value`
@@ -261,7 +307,7 @@ def main() -> int:
                                 "tflops_nonzero": res["tw_t_tflops_nonzero"],
                                 "roofline": {"bound": "hbm", "achieved": res["tw_t_gbs"], "peak": HBM_PEAK_GBS,
                                              "unit": "GB/s", "frac": res["tw_t_hbm_frac"],
-                                             "traffic": MEASURED_TRAFFIC_BYTES_T,
+                                             "traffic": traffic_t, "traffic_source": traffic_t_note,
                                              "kernel": "tw_gemm_kernel<f16, MS=2 (64 tokens), NCB=4, MODE 0, transposed>"}},
         "paper_context": PAPER_CONTEXT,
     }

@@ -93,17 +93,18 @@ int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N, int G, tw
 
 /* The TEW hybrid (Sec. IV-A "Hybrid Pattern"): on top of the tile-wise pattern `mask`, the weights marked
  * in `ew_mask` (K x N bytes; entries where mask is set as well are ignored) are kept as an element-wise
- * residual, stored per tile and column (the paper stores it in CSC form per tile) and added by tw_gemm and
- * its variants in the same launch (by linearity, A.(B*(mask|ew)) = A.(B*mask) + A.(B*ew)).  Restriction
- * of this build: residual weights must lie in columns that keep at least one tile-wise weight (else
- * TW_ERR_UNSUPPORTED).  ew_mask = NULL is tw_pack. */
+ * residual and added by tw_gemm and its variants (by linearity, A.(B*(mask|ew)) = A.(B*mask) + A.(B*ew)).
+ * Residual weights in a column that keeps tile-wise weights are stored per tile and packed column and added
+ * inside the tiles' kernel; residual weights in a column that the tile-wise pattern prunes altogether are
+ * stored by column (the CSC form the paper names) and added by a second, small kernel that tw_gemm enqueues
+ * behind the first.  ew_mask = NULL is tw_pack. */
 int tw_pack_tew_size(const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G, tw_dtype dt,
                      size_t* blob_bytes);
 int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G,
                 tw_dtype dt, void* blob, size_t blob_bytes);
 
-/* Which weights the hybrid puts back: the floor(delta*K*N + 0.5) pruned weights of largest magnitude
- * among the columns that survive `mask` (magnitude as importance score, ties to the lower (k, n));
+/* Which weights the hybrid puts back: the floor(delta*K*N + 0.5) weights of largest magnitude among all the
+ * weights that `mask` prunes, wherever they lie (magnitude as importance score, ties to the lower (k, n));
  * ew_mask_out: K x N bytes, receives 0/1.  Host only. */
 int tw_restore_ew(const void* B, int ldb, int K, int N, tw_dtype dt, const uint8_t* mask, double delta,
                   uint8_t* ew_mask_out);
@@ -172,7 +173,8 @@ int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transposed, tw_plan
  *              columns); 2-byte aligned rows suffice
  *   workspace  device, >= tw_gemm_workspace bytes, 256-byte aligned, zeroed as described above
  * M >= 0 (M = 0 enqueues nothing).  Calls on one workspace must not overlap in time (use one
- * workspace per stream).  The call enqueues kernels only (no memset, no copy, no allocation), so it can be
+ * workspace per stream).  The call enqueues kernels only (one; two for a TEW blob with residual weights in
+ * pruned columns) (no memset, no copy, no allocation), so it can be
  * recorded into a HIP graph; the first call that uses a kernel variant on a device raises that kernel's
  * dynamic-LDS limit (a function attribute), so make one call of each kind before a stream capture.  The best speed needs a C base and ldc that are multiples of 64 elements
  * (128-byte lines); any other layout is correct and slower.

@@ -15,8 +15,13 @@
  * paper's tensor-core runs use, Sec. VII-A, or bf16), widened exactly to double; the sum is
  * taken in double, in ascending k.  A column with no kept weight yields exactly 0.
  *
+ * two_bias_act is the definition of the fused epilogue (Sec. VI "Kernel Fusion": the bias addition and the
+ * activation that follow a weight GEMM): act(C + bias) in double, GELU in its exact form
+ * x/2 * (1 + erf(x / sqrt 2)) with the C library's erf.
+ *
  * Parity status: pinned (see tests/test_oracle_pins.py): decode tables against numpy/torch,
- * dense special case against BLAS dgemm, closed forms, selector inputs, linearity.
+ * dense special case against BLAS dgemm, closed forms, selector inputs, linearity; two_bias_act
+ * against the table value Phi(1), the odd-part identity and hand-made cases.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -115,5 +120,26 @@ int two_masked_gemm(const uint16_t *A, long lda, const uint16_t *B, long ldb,
         }
     }
     free(Bd);
+    return 0;
+}
+
+/*
+ * In place: C[m][n] = act(C[m][n] + bias[n]) in double; bias may be NULL (no bias).
+ * act: 0 none, 1 relu (max(x, 0)), 2 gelu (x/2 * (1 + erf(x / sqrt 2)) = x * Phi(x)).
+ * Returns 0, or -1 on a bad argument.
+ */
+int two_bias_act(double *C, long M, long N, long ldc, const double *bias, int act)
+{
+    if (!C || M < 0 || N <= 0 || ldc < N || act < 0 || act > 2) return -1;
+#pragma omp parallel for schedule(static)
+    for (long m = 0; m < M; ++m) {
+        double *c = C + m * ldc;
+        for (long n = 0; n < N; ++n) {
+            double x = c[n] + (bias ? bias[n] : 0.0);
+            if (act == 1) x = x > 0.0 ? x : 0.0;
+            else if (act == 2) x = 0.5 * x * (1.0 + erf(x / sqrt(2.0)));
+            c[n] = x;
+        }
+    }
     return 0;
 }

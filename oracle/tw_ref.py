@@ -7,16 +7,21 @@
                          the stretch of original columns up to the next tile's first column
                          (the "G+4, G+3, G+2, G-9" stretches of the worked example).
 * ``masked_weight_bits`` - what pack -> unpack must give back: B where kept, +0 elsewhere.
+* ``prune_one_shot``   - one stage of Alg. 1 (Sec. V) with the weight magnitude as importance score: columns
+                         first, then row segments of the regrouped tiles ranked across all tiles.
 * ``restore_ew``       - which pruned weights the TEW hybrid puts back (Sec. IV-A "Hybrid Pattern": prune
-                         alpha + delta tile-wise, then restore the delta most important elements), with the
-                         weight magnitude as importance; the hybrid's product is the masked product over
-                         mask | ew_mask, which ``masked_gemm`` already defines.
+                         alpha + delta tile-wise, then restore the delta most important elements): ANY
+                         pruned weight may come back, also one in a column the tile-wise pattern removed;
+                         the weight magnitude is the importance; the hybrid's product is the masked product
+                         over mask | ew_mask, which ``masked_gemm`` already defines.
 * ``bias_act``         - the fused epilogue's definition: act(C + bias) in fp64 (bias addition and
                          activation are the operators the paper fuses around its GEMMs, Sec. VI
-                         "Kernel Fusion"; GELU in its exact erf form, as in BERT).
+                         "Kernel Fusion"; GELU in its exact erf form, as in BERT), evaluated by
+                         ``two_bias_act`` in tw_oracle.c with the C library's erf.
 
 Nothing here imports the HIP package, and the HIP package imports nothing from here.
-Parity status: pinned by tests/test_oracle_pins.py and tests/test_tile_structure_pins.py.
+Parity status: every function is pinned by tests/test_oracle_pins.py and tests/test_tile_structure_pins.py
+(``prune_one_shot`` and ``restore_ew`` by hand-worked cases written out in the tests).
 """
 from __future__ import annotations
 
@@ -57,6 +62,9 @@ def _load():
         lib.two_decode.restype = ctypes.c_int
         lib.two_decode.argtypes = [u16p, ctypes.c_long, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
         lib.two_num_threads.restype = ctypes.c_int
+        lib.two_bias_act.restype = ctypes.c_int
+        lib.two_bias_act.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_long, ctypes.c_long, ctypes.c_long,
+                                     ctypes.POINTER(ctypes.c_double), ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -204,26 +212,33 @@ def prune_one_shot(B_bits: np.ndarray, G: int, dtype: str, col_prune: float, spa
 def bias_act(C: np.ndarray, bias64, act: str = "none") -> np.ndarray:
     """act(C + bias), fp64.  C: [M, N] fp64 (the masked product), bias64: [N] fp64 or None.
     relu(x) = max(x, 0); gelu(x) = x/2 * (1 + erf(x / sqrt 2)) = x * Phi(x) (the exact form)."""
-    from scipy.special import erf
-    x = np.asarray(C, dtype=np.float64)
+    codes = {None: 0, "none": 0, "relu": 1, "gelu": 2}
+    if act not in codes:
+        raise ValueError(f"unknown activation {act!r}")
+    x = np.array(C, dtype=np.float64, order="C", copy=True)
+    assert x.ndim == 2
+    M, N = x.shape
+    b = None
     if bias64 is not None:
-        x = x + np.asarray(bias64, dtype=np.float64)[None, :]
-    if act in (None, "none"):
+        b = np.ascontiguousarray(bias64, dtype=np.float64)
+        assert b.shape == (N,)
+    if M == 0:
         return x
-    if act == "relu":
-        return np.maximum(x, 0.0)
-    if act == "gelu":
-        return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
-    raise ValueError(f"unknown activation {act!r}")
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = _load().two_bias_act(x.ctypes.data_as(dp), M, N, N, b.ctypes.data_as(dp) if b is not None else None,
+                              codes[act])
+    if rc != 0:
+        raise RuntimeError(f"two_bias_act failed: {rc}")
+    return x
 
 
 def restore_ew(B_bits: np.ndarray, mask: np.ndarray, delta: float, dtype: str) -> np.ndarray:
-    """uint8 [K, N]: the floor(delta*K*N + 0.5) pruned weights of largest magnitude among the columns that
-    keep at least one weight in `mask`; ties go to the lower (k, n) (row-major position)."""
+    """uint8 [K, N]: the floor(delta*K*N + 0.5) weights of largest magnitude among ALL weights that `mask`
+    prunes (Sec. IV-A "Hybrid Pattern" restores the most important pruned elements, wherever they lie: also in
+    columns that the tile-wise pattern removed altogether); ties go to the lower (k, n) (row-major position)."""
     K, N = mask.shape
     mag = np.abs(decode(B_bits, dtype))
-    alive = mask.any(axis=0)
-    cand = [(-mag[k, n], k * N + n) for k in range(K) for n in range(N) if alive[n] and not mask[k, n]]
+    cand = [(-mag[k, n], k * N + n) for k in range(K) for n in range(N) if not mask[k, n]]
     cand.sort()
     want = min(len(cand), int(np.floor(delta * K * N + 0.5)))
     out = np.zeros((K, N), dtype=np.uint8)

@@ -40,7 +40,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     for src, defs, obj in UNITS:
         cmd = [hipcc(), "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wno-unused-command-line-argument"] + defs + os.environ.get("TW_BUILD_FLAGS", "").split() + [
+               "-Wno-unused-command-line-argument"] + defs + [
                "-c", os.path.join(CSRC, src), "-o", os.path.join(CSRC, obj)]
         if verbose:
             print(" ".join(cmd), flush=True)

@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define TW_MAGIC 0x31425754u /* "TWB1" */
-#define TW_FORMAT_VERSION 10
+#define TW_FORMAT_VERSION 11
 
 // MFMA step geometry the packed values are laid out for: one step contracts 16 kept rows
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
@@ -28,7 +28,7 @@ struct TwHeader {
     int32_t k_chunk;      // K rows of A resident in LDS at a time
     int32_t n_chunks;     // ceil(K / k_chunk)
     int32_t ncb;          // column blocks per tile = G / 32
-    int32_t reserved0;
+    int32_t xc_n;         // columns that hold only element-wise residual weights (see off_xc_col)
     int64_t total_steps;  // sum over tiles of 16-row steps (incl. padding)
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
         off_sched_order;
@@ -57,9 +57,15 @@ struct TwHeader {
     uint64_t off_ew_ptr;     //   int32 [T*n_chunks+1]: first plane of every (tile, chunk), tiles in canonical order
     uint64_t off_ew_k;       //   uint16 [planes][G]: chunk-local K row of the entry; k_chunk (the zero row) where a column has fewer
     uint64_t off_ew_v;       //   16-bit [planes][G]: its weight; 0 for padding
-    uint8_t pad[256 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 14];
+    // residual weights in columns that the tile-wise pattern prunes altogether: stored by column (the CSC form the
+    // paper names for the element-wise part, Sec. IV-A) and added by a pass of their own after the tiles' kernel
+    uint64_t off_xc_col;     //   int32 [xc_n]: original column, ascending
+    uint64_t off_xc_ptr;     //   int32 [xc_n+1]: first entry of every such column
+    uint64_t off_xc_k;       //   int32 [entries]: K row of the entry, ascending within a column
+    uint64_t off_xc_v;       //   16-bit [entries]: its weight
+    uint8_t pad[384 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 18];
 };
-static_assert(sizeof(TwHeader) == 256, "header is 256 bytes");
+static_assert(sizeof(TwHeader) == 384, "header is 384 bytes");
 
 struct TwTileDesc {
     int32_t w;           // kept columns (1..G)

@@ -29,34 +29,16 @@
 #include "tw_device.hpp"
 #include "tw_format.h"
 
-// Phase probe: a build with -DTW_PHASE_PROBE reads TW_SKIP from the environment at every call and leaves out
-// the phases whose bits are set (1: bringing A in, 2: the multiply loops, 4: the epilogue), so that the time of
-// each phase can be read off as a difference.  Its results are wrong by construction; the library that ships
-// is built without it, and then the tests below are constant-false.
-#ifdef TW_PHASE_PROBE
-#define TW_SKIPS(p, bit) (((p).skip & (bit)) != 0)
-#else
-#define TW_SKIPS(p, bit) false
-#endif
-
 namespace {
 
 constexpr int kWaves = TW_WAVES_PER_WG;
 constexpr int kThreads = kWaves * 64;
-#ifndef TW_PAIR_RESIDENT
-#define TW_PAIR_RESIDENT 1
-#endif
-#ifndef TW_PAIR_STREAM
-#define TW_PAIR_STREAM 0
-#endif
-constexpr bool kPairResident = TW_PAIR_RESIDENT != 0, kPairStream = TW_PAIR_STREAM != 0;
+// staging of A: resident K packs row pairs into 4-byte LDS writes, streamed K writes 2-byte values (see ATask)
+constexpr bool kPairResident = true, kPairStream = false;
 // B-operand steps in flight per wave: three; six for narrow tiles (at most two column blocks), whose steps
 // are too short for three to cover the latency of an L2 hit and whose registers allow it
-#ifndef TW_PREFETCH_NARROW
-#define TW_PREFETCH_NARROW 6
-#endif
 template <int NCB>
-constexpr int prefetch_depth() { return NCB <= 2 ? TW_PREFETCH_NARROW : 3; }
+constexpr int prefetch_depth() { return NCB <= 2 ? 6 : 3; }
 constexpr int kIdxAhead = 6;  // steps the K indices are requested ahead (they feed the LDS gather, which itself
                               // runs one step ahead of the MFMAs)
 
@@ -84,9 +66,6 @@ struct TwGemmParams {
     uint64_t off_ew_ptr, off_ew_k, off_ew_v;
     int has_ew;                 // the blob carries an element-wise residual (TEW)
     unsigned urow_off;          // LDS offset of the loading waves' row lists (transposed, streamed K, few tiles), 0: none
-#ifdef TW_PHASE_PROBE
-    int skip;
-#endif
 };
 
 __device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -949,10 +928,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             if (lane == 0) i = atomicAdd((int*)&misc[1], 1);
             int ti = seg + uni(i) * p.n_seg;
             TileU next = fetch_tile(p, ti < p.T ? ti : 0);
-            if (!TW_SKIPS(p, 1)) {
-                if constexpr (TRANS) load_at_block<MS, 12>(p, smem, row0, 0, p.K, wave, lane, tid);
-                else load_a_block<MS, 12, kPairResident>(p, smem, row0, 0, p.K, wave, lane, tid);
-            }
+            if constexpr (TRANS) load_at_block<MS, 12>(p, smem, row0, 0, p.K, wave, lane, tid);
+            else load_a_block<MS, 12, kPairResident>(p, smem, row0, 0, p.K, wave, lane, tid);
             __syncthreads();
             while (ti < p.T) {
                 const TileU d = next;
@@ -973,14 +950,11 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                                           p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
                 tw_f32x16 acc[MS][NCB];
                 zero_acc<MS, NCB>(acc);
-                if (!TW_SKIPS(p, 2))
-                    run_steps<DT, MS, NCB>(acc, rg, smem, at_pitch_of<MS>(), p.blob + p.off_goff + (long)d.first_step * 32,
+                run_steps<DT, MS, NCB>(acc, rg, smem, at_pitch_of<MS>(), p.blob + p.off_goff + (long)d.first_step * 32,
                                            p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
                 if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, at_pitch_of<MS>(), lane);
-                if (!TW_SKIPS(p, 4)) {
-                    if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
-                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
-                }
+                if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
         } else if constexpr (MODE == 2) {
@@ -1025,7 +999,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     }
                 };
                 auto issue_or_zero = [&](ARegs<PB>& ar, int c, int r0) {
-                    if (c < p.n_chunks && !TW_SKIPS(p, 1)) {
+                    if (c < p.n_chunks) {
                         if (use_rows)
                             at_issue_rows<PB>(p, ar, r0, c * p.k_chunk, my_rows + c * kListEntries, uni(my_cnt[c]), lw, lane, NLD);
                         else
@@ -1108,7 +1082,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     }
                 };
                 auto steps_of = [&](int c) {
-                    if (active && b0 < b1 && !TW_SKIPS(p, 2))
+                    if (active && b0 < b1)
                         run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
                     if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
                     // on to chunk c+1
@@ -1126,7 +1100,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 }
                 if (tid == 0) misc[2] = my_next;   // requested at the start of the item: here by now
                 __syncthreads();
-                if (active && !TW_SKIPS(p, 4)) {
+                if (active) {
                     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                     else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 }
@@ -1165,7 +1139,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 return (p.K - k0) < p.k_chunk ? (p.K - k0) : p.k_chunk;
             };
             auto issue_or_zero = [&](ARegs<AB>& ar, int c) {
-                if (c < p.n_chunks && !TW_SKIPS(p, 1)) {
+                if (c < p.n_chunks) {
                     stage_issue<MSB, AB, TRANS>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
                 } else {
 #pragma unroll
@@ -1190,7 +1164,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 }
             };
             auto steps_of = [&](int c) {
-                if (active && b0 < b1 && !TW_SKIPS(p, 2))
+                if (active && b0 < b1)
                     run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
                 if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
                 b0 = b1; b1 = b2;
@@ -1229,7 +1203,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     __syncthreads();
                 }
             }
-            if (active && !TW_SKIPS(p, 4)) {
+            if (active) {
                 if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                 else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
             }
@@ -1337,6 +1311,124 @@ __global__ void tw_fill_rows_kernel(unsigned short* Ct, long ldct, int N, int M,
         const long n = i / M;
         Ct[n * ldct + (i % M)] = bias ? tw_cvt<DT>(tw_activate(tw_to_f32<DT>(bias[n]), act)) : (unsigned short)0;
     }
+}
+
+// ---- residual weights of a TEW blob in columns that keep no tile-wise weight (Sec. IV-A "Hybrid Pattern") ----
+// The paper stores the element-wise part in CSC form and runs it as a sparse product of its own, added by
+// linearity.  For the columns that own a packed column of a tile that happens inside the tiles' kernel; a
+// column that the tile-wise pattern pruned altogether has none, so its few entries run here, after that
+// kernel (which wrote the column's zeros, or act(bias)): C[m, n] = act(bias[n] + sum_e v_e * A[m, k_e]).
+struct XcolParams {
+    const unsigned short* A;
+    unsigned short* C;
+    const unsigned short* bias;
+    const int* col;
+    const int* ptr;
+    const int* k;
+    const unsigned short* v;
+    long lda, ldc;
+    int M, K, n_cols, act;
+};
+
+// Row-major boundary.  A workgroup takes 64 rows of A and 64 of the columns; wave w, lane r: row r, columns
+// 16*w .. 16*w+15 of the group.  A comes through LDS in chunks of 256 K positions (coalesced 16-byte loads),
+// so that a lane's scattered 2-byte reads hit LDS, not memory; the entries of a column are walked in
+// ascending K, chunk by chunk.
+constexpr int kXcChunk = 256, kXcPitch = 2 * kXcChunk + 8, kXcColsPerWg = 64;
+template <int DT>
+__global__ __launch_bounds__(256) void tw_xcol_kernel(const XcolParams p) {
+    __shared__ __attribute__((aligned(16))) unsigned char at[64 * kXcPitch];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row0 = blockIdx.x * 64;
+    const int j0 = blockIdx.y * kXcColsPerWg + 16 * wave;      // this wave's first column of the list
+    float acc[16];
+    int e[16], e1[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int j = j0 + i;
+        acc[i] = 0.f;
+        e[i] = j < p.n_cols ? p.ptr[j] : 0;
+        e1[i] = j < p.n_cols ? p.ptr[j + 1] : 0;
+    }
+    const int kpad = (p.K + 7) & ~7;                             // rows are readable up to the next multiple of 8
+    for (int c0 = 0; c0 < p.K; c0 += kXcChunk) {
+        __syncthreads();
+        // 64 rows x 32 pieces of 16 bytes
+        for (int id = tid; id < 64 * (kXcChunk / 8); id += 256) {
+            const int r = id / (kXcChunk / 8), pc = id % (kXcChunk / 8);
+            int g = row0 + r;
+            g = g < p.M ? g : p.M - 1;
+            tw_u32x4 v = tw_u32x4{0u, 0u, 0u, 0u};
+            if (c0 + 8 * pc < kpad) v = *(const tw_u32x4*)(p.A + (long)g * p.lda + c0 + 8 * pc);
+            *(tw_u32x2*)(at + r * kXcPitch + pc * 16) = tw_u32x2{v.x, v.y};
+            *(tw_u32x2*)(at + r * kXcPitch + pc * 16 + 8) = tw_u32x2{v.z, v.w};
+        }
+        __syncthreads();
+        const int cend = c0 + kXcChunk;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            while (e[i] < e1[i]) {                               // wave-uniform: the wave shares its columns
+                const int k = p.k[e[i]];
+                if (k >= cend) break;
+                const float a = tw_to_f32<DT>(*(const unsigned short*)(at + lane * kXcPitch + (k - c0) * 2));
+                acc[i] += tw_to_f32<DT>(p.v[e[i]]) * a;
+                ++e[i];
+            }
+        }
+    }
+    const int m = row0 + lane;
+    if (m < p.M) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int j = j0 + i;
+            if (j < p.n_cols) {
+                const int n = p.col[j];
+                const float b = p.bias ? tw_to_f32<DT>(p.bias[n]) : 0.f;
+                p.C[(long)m * p.ldc + n] = tw_cvt<DT>(tw_activate(acc[i] + b, p.act));
+            }
+        }
+    }
+}
+
+// Transposed boundary: a column of C is a row of Ct and a K position a row of At, so a thread takes one token
+// and the reads are coalesced as they are.  blockIdx.y walks the columns of the list.
+template <int DT>
+__global__ __launch_bounds__(256) void tw_xcol_t_kernel(const XcolParams p) {
+    const long m = (long)blockIdx.x * 256 + threadIdx.x;
+    if (m >= p.M) return;
+    for (int j = blockIdx.y; j < p.n_cols; j += gridDim.y) {
+        float acc = 0.f;
+        for (int e = p.ptr[j]; e < p.ptr[j + 1]; ++e)
+            acc += tw_to_f32<DT>(p.v[e]) * tw_to_f32<DT>(p.A[(long)p.k[e] * p.lda + m]);
+        const int n = p.col[j];
+        const float b = p.bias ? tw_to_f32<DT>(p.bias[n]) : 0.f;
+        p.C[(long)n * p.ldc + m] = tw_cvt<DT>(tw_activate(acc + b, p.act));
+    }
+}
+
+// Enqueues the pass over the residual's columns without tile-wise weights, if the blob has any.
+int launch_xcols(const TwHeader* h, const void* blob_dev, const void* A, long lda, void* C, long ldc, int M,
+                 const void* bias, int act, bool transposed, hipStream_t stream) {
+    if (h->xc_n <= 0 || M <= 0) return TW_OK;
+    const unsigned char* b = (const unsigned char*)blob_dev;
+    XcolParams p;
+    p.A = (const unsigned short*)A; p.C = (unsigned short*)C; p.bias = (const unsigned short*)bias;
+    p.col = (const int*)(b + h->off_xc_col); p.ptr = (const int*)(b + h->off_xc_ptr);
+    p.k = (const int*)(b + h->off_xc_k); p.v = (const unsigned short*)(b + h->off_xc_v);
+    p.lda = lda; p.ldc = ldc; p.M = M; p.K = h->K; p.n_cols = h->xc_n; p.act = act;
+    void* args[] = {(void*)&p};
+    hipError_t rc;
+    if (transposed) {
+        const unsigned gy = (unsigned)(h->xc_n < 65535 ? h->xc_n : 65535);
+        const void* fn = h->dtype == TW_F16 ? (const void*)tw_xcol_t_kernel<TW_F16> : (const void*)tw_xcol_t_kernel<TW_BF16>;
+        rc = hipLaunchKernel(fn, dim3((unsigned)((M + 255) / 256), gy), dim3(256), args, 0, stream);
+    } else {
+        const long gy = ((long)h->xc_n + kXcColsPerWg - 1) / kXcColsPerWg;
+        if (gy > 65535) return TW_ERR_UNSUPPORTED;
+        const void* fn = h->dtype == TW_F16 ? (const void*)tw_xcol_kernel<TW_F16> : (const void*)tw_xcol_kernel<TW_BF16>;
+        rc = hipLaunchKernel(fn, dim3((unsigned)((M + 63) / 64), (unsigned)gy), dim3(256), args, 0, stream);
+    }
+    return rc == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 
 struct Plan {
@@ -1518,9 +1610,10 @@ extern "C" int tw_gemm(const void* blob_host, const void* blob_dev, const void* 
                             hip_stream);
 }
 
-extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
-                                const void* bias, tw_act act, void* C, int ldc, void* workspace, size_t ws_bytes,
-                                void* hip_stream) {
+namespace {
+// what tw_gemm and its variants on the row-major boundary refuse before anything is enqueued
+int check_gemm_args(const void* blob_host, const void* blob_dev, const void* A, int M, int lda, const void* bias,
+                    tw_act act, const void* C, int ldc, const void* workspace, size_t ws_bytes) {
     if (!blob_host || !blob_dev || !A || !C || !workspace || M < 0) return TW_ERR_ARG;
     if (act != TW_ACT_NONE && act != TW_ACT_RELU && act != TW_ACT_GELU) return TW_ERR_ARG;
     if (((uintptr_t)bias & 1) != 0) return TW_ERR_ALIGN;
@@ -1530,6 +1623,19 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     if (lda < h->K || ldc < h->N) return TW_ERR_ARG;
     if ((lda & 7) != 0 || ((uintptr_t)A & 15) != 0 || ((uintptr_t)C & 1) != 0) return TW_ERR_ALIGN;
     if (((uintptr_t)blob_dev & 255) != 0 || ((uintptr_t)workspace & 255) != 0) return TW_ERR_ALIGN;
+    return TW_OK;
+}
+
+}  // namespace
+
+extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
+                                const void* bias, tw_act act, void* C, int ldc, void* workspace, size_t ws_bytes,
+                                void* hip_stream) {
+    {
+        const int rc0 = check_gemm_args(blob_host, blob_dev, A, M, lda, bias, act, C, ldc, workspace, ws_bytes);
+        if (rc0) return rc0;
+    }
+    const TwHeader* h = (const TwHeader*)blob_host;
     if (M == 0) return TW_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
 
@@ -1537,13 +1643,14 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
         const long total = (long)M * h->N;
         int blocks = (int)((total + 255) / 256);
         if (blocks > 4096) blocks = 4096;
-        if (h->dtype == TW_F16)
-            hipLaunchKernelGGL(tw_fill_kernel<TW_F16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)C, (long)ldc, M,
-                               h->N, (const unsigned short*)bias, (int)act);
-        else
-            hipLaunchKernelGGL(tw_fill_kernel<TW_BF16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)C, (long)ldc, M,
-                               h->N, (const unsigned short*)bias, (int)act);
-        return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
+        unsigned short* c_ = (unsigned short*)C;
+        long ldc_ = ldc;
+        int m_ = M, n_ = h->N, act_ = (int)act;
+        const unsigned short* bias_ = (const unsigned short*)bias;
+        void* fargs[] = {(void*)&c_, (void*)&ldc_, (void*)&m_, (void*)&n_, (void*)&bias_, (void*)&act_};
+        const void* ffn = h->dtype == TW_F16 ? (const void*)tw_fill_kernel<TW_F16> : (const void*)tw_fill_kernel<TW_BF16>;
+        if (hipLaunchKernel(ffn, dim3(blocks), dim3(256), fargs, 0, stream) != hipSuccess) return TW_ERR_HIP;
+        return launch_xcols(h, blob_dev, A, lda, C, ldc, M, bias, (int)act, false, stream);
     }
 
     const int dev = current_device();
@@ -1578,12 +1685,10 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt; p.urow_off = 0;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
-#ifdef TW_PHASE_PROBE
-    p.skip = getenv("TW_SKIP") ? atoi(getenv("TW_SKIP")) : 0;
-#endif
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     void* args[] = {(void*)&p};
-    return hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, pl.lds_bytes, stream) == hipSuccess ? TW_OK : TW_ERR_HIP;
+    if (hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, pl.lds_bytes, stream) != hipSuccess) return TW_ERR_HIP;
+    return launch_xcols(h, blob_dev, A, lda, C, ldc, M, bias, (int)act, false, stream);
 }
 
 extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat, void* Ct,
@@ -1612,13 +1717,14 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
         const long total = (long)h->N * M;
         int blocks = (int)((total + 255) / 256);
         if (blocks > 4096) blocks = 4096;
-        if (h->dtype == TW_F16)
-            hipLaunchKernelGGL(tw_fill_rows_kernel<TW_F16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)Ct, (long)ldct,
-                               h->N, M, (const unsigned short*)bias, (int)act);
-        else
-            hipLaunchKernelGGL(tw_fill_rows_kernel<TW_BF16>, dim3(blocks), dim3(256), 0, stream, (unsigned short*)Ct, (long)ldct,
-                               h->N, M, (const unsigned short*)bias, (int)act);
-        return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
+        unsigned short* c_ = (unsigned short*)Ct;
+        long ldc_ = ldct;
+        int n_ = h->N, m_ = M, act_ = (int)act;
+        const unsigned short* bias_ = (const unsigned short*)bias;
+        void* fargs[] = {(void*)&c_, (void*)&ldc_, (void*)&n_, (void*)&m_, (void*)&bias_, (void*)&act_};
+        const void* ffn = h->dtype == TW_F16 ? (const void*)tw_fill_rows_kernel<TW_F16> : (const void*)tw_fill_rows_kernel<TW_BF16>;
+        if (hipLaunchKernel(ffn, dim3(blocks), dim3(256), fargs, 0, stream) != hipSuccess) return TW_ERR_HIP;
+        return launch_xcols(h, blob_dev, At, ldat, Ct, ldct, M, bias, (int)act, true, stream);
     }
 
     const int dev = current_device();
@@ -1654,12 +1760,10 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
     p.urow_off = pl.urow_off;
     const unsigned lds_bytes = pl.lds_bytes;
-#ifdef TW_PHASE_PROBE
-    p.skip = getenv("TW_SKIP") ? atoi(getenv("TW_SKIP")) : 0;
-#endif
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     void* args[] = {(void*)&p};
-    return hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, lds_bytes, stream) == hipSuccess ? TW_OK : TW_ERR_HIP;
+    if (hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, lds_bytes, stream) != hipSuccess) return TW_ERR_HIP;
+    return launch_xcols(h, blob_dev, At, ldat, Ct, ldct, M, bias, (int)act, true, stream);
 }
 
 // ---- the transposes at the two ends of a network that runs on the transposed boundary (Sec. VI) ----
@@ -1709,8 +1813,12 @@ extern "C" int tw_transpose(const void* src, int ld_src, int rows, int cols, voi
     const long gx = ((long)cols + 63) / 64, gy = ((long)rows + 63) / 64;
     if (gy > 65535) return TW_ERR_UNSUPPORTED;
     const int vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0 && (ld_src & 7) == 0 && (ld_dst & 7) == 0;
-    hipLaunchKernelGGL(tw_transpose_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, (hipStream_t)hip_stream,
-                       (const unsigned short*)src, (long)ld_src, rows, cols, (unsigned short*)dst, (long)ld_dst, vec);
-    return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_HIP;
+    const unsigned short* s_ = (const unsigned short*)src;
+    unsigned short* d_ = (unsigned short*)dst;
+    long lds2 = ld_src, ldd2 = ld_dst;
+    int vec_ = vec;
+    void* targs[] = {(void*)&s_, (void*)&lds2, (void*)&rows, (void*)&cols, (void*)&d_, (void*)&ldd2, (void*)&vec_};
+    return hipLaunchKernel((const void*)tw_transpose_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), targs, 0,
+                           (hipStream_t)hip_stream) == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 #endif  // host code

@@ -30,9 +30,11 @@ struct Layout {
     int64_t total_steps = 0;
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
         off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, off_zero_ptr,
-        off_zero_cols, off_urow, off_ucnt, off_ew_ptr, off_ew_k, off_ew_v, bytes;
+        off_zero_cols, off_urow, off_ucnt, off_ew_ptr, off_ew_k, off_ew_v, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v, bytes;
     int64_t ew_nnz = 0;
     std::vector<int32_t> ew_ptr;   // planes per (tile, chunk), prefix sums
+    // residual weights in columns without tile-wise weights, by column
+    std::vector<int32_t> xc_col, xc_ptr, xc_k;
 };
 
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -162,6 +164,27 @@ void plan(const Tiling& tl, int K, int G, Layout& lo, const uint8_t* mask = null
         lo.off_ew_ptr = take(4 * ((size_t)T * nc + 1), 16);
         lo.off_ew_k = take(2 * (planes * G + 1), 16);
         lo.off_ew_v = take(2 * (planes * G + 1), 16);
+        // residual weights in columns that keep no tile-wise weight
+        lo.xc_ptr.assign(1, 0);
+        if (ew) {
+            std::vector<uint8_t> alive(N, 0);
+            for (int32_t n : tl.col_idx) alive[n] = 1;
+            for (int n = 0; n < N; ++n) {
+                if (alive[n]) continue;
+                const size_t before = lo.xc_k.size();
+                for (int k = 0; k < K; ++k)
+                    if (ew[(size_t)k * N + n] != 0) lo.xc_k.push_back(k);
+                if (lo.xc_k.size() != before) {
+                    lo.xc_col.push_back(n);
+                    lo.xc_ptr.push_back((int32_t)lo.xc_k.size());
+                }
+            }
+            lo.ew_nnz += (int64_t)lo.xc_k.size();
+        }
+        lo.off_xc_col = take(4 * (lo.xc_col.size() + 1), 16);
+        lo.off_xc_ptr = take(4 * lo.xc_ptr.size(), 16);
+        lo.off_xc_k = take(4 * (lo.xc_k.size() + 1), 16);
+        lo.off_xc_v = take(2 * (lo.xc_k.size() + 1), 16);
     }
     lo.off_goff = take(2 * 16 * (uint64_t)total, 256);
     lo.off_dpos = take(4 * (uint64_t)T * 32 * lo.ncb, 256);
@@ -186,18 +209,6 @@ const TwHeader* header_of(const void* blob) {
 
 }  // namespace
 
-// residual entries must lie in columns that survive the tile-wise pattern
-int check_ew(const uint8_t* mask, const uint8_t* ew, int K, int N, const Tiling& tl, const Layout& lo) {
-    if (!ew) return TW_OK;
-    std::vector<uint8_t> alive(N, 0);
-    for (int32_t n : tl.col_idx) alive[n] = 1;
-    (void)lo;
-    for (int k = 0; k < K; ++k)
-        for (int n = 0; n < N; ++n)
-            if (ew[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0 && !alive[n]) return TW_ERR_UNSUPPORTED;
-    return TW_OK;
-}
-
 extern "C" int tw_pack_size(const uint8_t* mask, int K, int N, int G, tw_dtype dt, size_t* blob_bytes) {
     return tw_pack_tew_size(mask, nullptr, K, N, G, dt, blob_bytes);
 }
@@ -212,8 +223,6 @@ extern "C" int tw_pack_tew_size(const uint8_t* mask, const uint8_t* ew_mask, int
     if (rc) return rc;
     Layout lo;
     plan(tl, K, G, lo, mask, ew_mask, N);
-    rc = check_ew(mask, ew_mask, K, N, tl, lo);
-    if (rc) return rc;
     *blob_bytes = (size_t)lo.bytes;
     return TW_OK;
 }
@@ -235,8 +244,6 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
     if (rc) return rc;
     Layout lo;
     plan(tl, K, G, lo, mask, ew_mask, N);
-    rc = check_ew(mask, ew_mask, K, N, tl, lo);
-    if (rc) return rc;
     if (blob_bytes < lo.bytes) return TW_ERR_BUF;
 
     uint8_t* base = (uint8_t*)blob;
@@ -259,6 +266,8 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
     h->off_zero_ptr = lo.off_zero_ptr; h->off_zero_cols = lo.off_zero_cols;
     h->off_urow = lo.off_urow; h->off_ucnt = lo.off_ucnt;
     h->ew_nnz = lo.ew_nnz; h->off_ew_ptr = lo.off_ew_ptr; h->off_ew_k = lo.off_ew_k; h->off_ew_v = lo.off_ew_v;
+    h->xc_n = (int32_t)lo.xc_col.size();
+    h->off_xc_col = lo.off_xc_col; h->off_xc_ptr = lo.off_xc_ptr; h->off_xc_k = lo.off_xc_k; h->off_xc_v = lo.off_xc_v;
 
     auto put = [&](uint64_t off, const std::vector<int32_t>& v) {
         if (!v.empty()) std::memcpy(base + off, v.data(), 4 * v.size());
@@ -295,6 +304,18 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
                 }
             }
         }
+    }
+
+    // the residual's columns without tile-wise weights
+    put(lo.off_xc_col, lo.xc_col);
+    put(lo.off_xc_ptr, lo.xc_ptr);
+    put(lo.off_xc_k, lo.xc_k);
+    {
+        uint16_t* xv = (uint16_t*)(base + lo.off_xc_v);
+        const uint16_t* Bw = (const uint16_t*)B;
+        for (size_t j = 0; j < lo.xc_col.size(); ++j)
+            for (int32_t e = lo.xc_ptr[j]; e < lo.xc_ptr[j + 1]; ++e)
+                xv[e] = Bw[(size_t)lo.xc_k[e] * ldb + lo.xc_col[j]];
     }
 
     // pruned columns inside every span
@@ -505,26 +526,32 @@ extern "C" int tw_unpack(const void* blob, void* B_out, int ldb, uint8_t* mask_o
                         if (Bo) Bo[(size_t)k * ldb + n] = ev[(size_t)e * h->G + c];
                     }
         }
+        const int32_t* xcol = (const int32_t*)(base + h->off_xc_col);
+        const int32_t* xptr = (const int32_t*)(base + h->off_xc_ptr);
+        const int32_t* xk = (const int32_t*)(base + h->off_xc_k);
+        const uint16_t* xv = (const uint16_t*)(base + h->off_xc_v);
+        for (int j = 0; j < h->xc_n; ++j)
+            for (int32_t e = xptr[j]; e < xptr[j + 1]; ++e) {
+                if (mask_out) mask_out[(size_t)xk[e] * N + xcol[j]] = 1;
+                if (Bo) Bo[(size_t)xk[e] * ldb + xcol[j]] = xv[e];
+            }
     }
     return TW_OK;
 }
 
-// The delta*K*N pruned weights of largest magnitude inside the surviving columns (the elements the TEW hybrid
-// puts back, Sec. IV-A; magnitude as importance score), ties to the lower (k, n).
+// The delta*K*N pruned weights of largest magnitude, wherever they lie (the elements the TEW hybrid puts back,
+// Sec. IV-A; magnitude as importance score), ties to the lower (k, n).
 extern "C" int tw_restore_ew(const void* B, int ldb, int K, int N, tw_dtype dt, const uint8_t* mask, double delta,
                              uint8_t* ew_mask_out) {
     if (!B || !mask || !ew_mask_out || K <= 0 || N <= 0 || ldb < N) return TW_ERR_ARG;
     if (dt != TW_F16 && dt != TW_BF16) return TW_ERR_ARG;
     if (!(delta >= 0.0 && delta < 1.0)) return TW_ERR_ARG;
     std::memset(ew_mask_out, 0, (size_t)K * N);
-    std::vector<uint8_t> alive(N, 0);
-    for (int k = 0; k < K; ++k)
-        for (int n = 0; n < N; ++n) alive[n] |= mask[(size_t)k * N + n] != 0;
     const uint16_t* Bw = (const uint16_t*)B;
     std::vector<std::pair<uint16_t, int64_t>> cand;     // (magnitude bits, position)
     for (int k = 0; k < K; ++k)
         for (int n = 0; n < N; ++n)
-            if (alive[n] && mask[(size_t)k * N + n] == 0)
+            if (mask[(size_t)k * N + n] == 0)
                 cand.emplace_back((uint16_t)(Bw[(size_t)k * ldb + n] & 0x7FFFu), (int64_t)k * N + n);
     int64_t want = (int64_t)std::floor(delta * (double)K * (double)N + 0.5);
     if (want > (int64_t)cand.size()) want = (int64_t)cand.size();

@@ -192,3 +192,120 @@ def test_bias_act_pins():
     # a dropped bias or a bias added along the wrong axis fails the line above; a tanh-form GELU fails Phi(1)
     with pytest.raises(ValueError):
         tw_ref.bias_act(x, None, "swish")
+
+
+# ------------------------------------------------------------------ one-shot pruning (Alg. 1, one stage, magnitude score)
+# Hand-worked case.  K = 3, N = 6, G = 2.  Magnitudes |B| (B[2,1] is negative: the score is the magnitude):
+#         n=0  1  2  3  4  5
+#   k=0    1   4  1  2  8  3
+#   k=1    2   5  1  6  1  3
+#   k=2    3   6  4  1  3  4
+# Column stage, one column to prune (floor(6/6 + 0.5) = 1): column sums 6, 15, 6, 9, 12, 10; columns 0 and 2 tie
+# for the lowest score and the lower index goes: column 0.  Survivors 1..5 regroup as t0 = {1,2}, t1 = {3,4},
+# t2 = {5} (the narrower last tile).  Row-segment scores = MEAN magnitude over the tile's columns:
+#   t0: 2.5, 3, 5     t1: 5, 3.5, 2     t2: 3, 3, 4
+# ascending, ties by (tile, row): (t1,k2) 2, (t0,k0) 2.5, (t0,k1) 3, (t2,k0) 3, (t2,k1) 3, (t1,k1) 3.5, (t2,k2) 4,
+# (t0,k2) 5, (t1,k0) 5.  Zeros start at 3 (the pruned column) of K*N = 18.
+_PRUNE_B = np.array([[1, 4, 1, 2, 8, 3], [2, 5, 1, 6, 1, 3], [3, -6, 4, 1, 3, 4]], np.float32)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_prune_one_shot_hand_worked_half(dtype):
+    """Target 0.5: 9 zeros wanted.  (t1,k2) -> 5 zeros, (t0,k0) -> 7, (t0,k1) -> 9: stop.  t2 is untouched, which a
+    SUM score would not give (t2's sums 3, 3, 4 are the lowest of all), and (t0,k1) goes before the equally scored
+    (t2,k0), (t2,k1), which a tie order by row first or by descending tile would not give."""
+    B = W.f32_to_bits(_PRUNE_B, dtype)
+    want = np.array([[0, 0, 0, 1, 1, 1],
+                     [0, 0, 0, 1, 1, 1],
+                     [0, 1, 1, 0, 0, 1]], np.uint8)
+    assert np.array_equal(tw_ref.prune_one_shot(B, 2, dtype, 1.0 / 6.0, 0.5), want)
+
+
+def test_prune_one_shot_hand_worked_keep_one_row():
+    """Target 0.75: 14 zeros wanted, which cannot be reached.  After the three segments above: (t2,k0) -> 10,
+    (t2,k1) -> 11 and t2 is down to one row; (t1,k1) -> 13 and t1 is down to one row; (t2,k2), (t0,k2), (t1,k0) are
+    the last rows of their tiles and stay.  Every tile keeps exactly its most important row."""
+    B = W.f32_to_bits(_PRUNE_B, "f16")
+    want = np.array([[0, 0, 0, 1, 1, 0],
+                     [0, 0, 0, 0, 0, 0],
+                     [0, 1, 1, 0, 0, 1]], np.uint8)
+    assert np.array_equal(tw_ref.prune_one_shot(B, 2, "f16", 1.0 / 6.0, 0.75), want)
+
+
+def test_prune_one_shot_degenerate_targets():
+    B = W.f32_to_bits(_PRUNE_B, "f16")
+    assert np.array_equal(tw_ref.prune_one_shot(B, 2, "f16", 0.0, 0.0), np.ones((3, 6), np.uint8))
+    # whole-matrix granularity: one tile, rows ranked by their mean magnitude: 19/6, 18/6, 21/6 -> k1 goes first
+    m = tw_ref.prune_one_shot(B, 6, "f16", 0.0, 1.0 / 3.0)
+    assert np.array_equal(m, np.array([[1] * 6, [0] * 6, [1] * 6], np.uint8))
+
+
+def test_prune_one_shot_properties():
+    """What Alg. 1 states, checked on the oracle's own output: whole columns go first (the least important ones),
+    then whole row segments of the regrouped tiles; the target is met with less than one segment to spare;
+    every tile keeps a row."""
+    rng = np.random.default_rng(777)
+    K, N, G = 96, 260, 64
+    B = W.f32_to_bits((rng.standard_normal((K, N)) * 0.05).astype(np.float32), "f16")
+    mask = tw_ref.prune_one_shot(B, G, "f16", 0.1, 0.75)
+    kept_cols = np.flatnonzero(mask.any(axis=0))
+    assert N - len(kept_cols) == int(np.floor(0.1 * N + 0.5))
+    cs = np.abs(B.view(np.float16).astype(np.float64)).sum(axis=0)
+    assert cs[kept_cols].min() >= np.delete(cs, kept_cols).max()
+    zeros = mask.size - int(mask.sum())
+    assert zeros >= 0.75 * mask.size and zeros - G < 0.75 * mask.size
+    kts = []
+    for i in range(0, len(kept_cols), G):
+        seg = mask[:, kept_cols[i:i + G]]
+        assert np.all((seg.sum(axis=1) == 0) | (seg.sum(axis=1) == seg.shape[1]))
+        assert seg.any()
+        kts.append(int(seg.any(axis=1).sum()))
+    assert len(set(kts)) > 1                      # ranking across tiles: tiles end up with different heights
+    s = tw_ref.tile_structure(mask, G)
+    assert s["T"] <= -(-len(kept_cols) // G) + 1
+
+
+# ------------------------------------------------------------------ TEW: which pruned weights come back
+# Hand-worked case.  K = 4, N = 6; the tile-wise pattern (G = 3) keeps rows {0,1} of columns 0..2, prunes column 3
+# altogether and keeps rows {2,3} of columns 4..5:
+#         n=0  1  2  3  4  5                 mask
+#   k=0    1  -9  2  7  3  1              1 1 1 0 0 0
+#   k=1    5   2 -8  7  1  2              1 1 1 0 0 0
+#   k=2   -3   4  6 -7  2  3              0 0 0 0 1 1
+#   k=3    2   1  5  1  8  4              0 0 0 0 1 1
+# Pruned weights by magnitude: 7 at (0,3), (1,3), (2,3) (a three-way tie, all in the pruned column), 6 at (2,2),
+# 5 at (3,2), 4 at (2,1), 3 at (2,0) and (0,4), ...
+_TEW_B = np.array([[1, -9, 2, 7, 3, 1], [5, 2, -8, 7, 1, 2], [-3, 4, 6, -7, 2, 3], [2, 1, 5, 1, 8, 4]], np.float32)
+_TEW_MASK = np.array([[1, 1, 1, 0, 0, 0], [1, 1, 1, 0, 0, 0], [0, 0, 0, 0, 1, 1], [0, 0, 0, 0, 1, 1]], np.uint8)
+
+
+@pytest.mark.parametrize("n_restore,want_pos", [
+    (2, [(0, 3), (1, 3)]),                                   # the tie goes to the lower (k, n)
+    (4, [(0, 3), (1, 3), (2, 3), (2, 2)]),
+    (5, [(0, 3), (1, 3), (2, 3), (2, 2), (3, 2)]),
+    (8, [(0, 3), (1, 3), (2, 3), (2, 2), (3, 2), (2, 1), (2, 0), (0, 4)]),   # both weights of magnitude 3
+])
+def test_restore_ew_hand_worked(n_restore, want_pos):
+    """The most important pruned elements come back wherever they lie: here the first three are in the column
+    that the tile-wise pattern pruned altogether."""
+    B = W.f32_to_bits(_TEW_B, "f16")
+    got = tw_ref.restore_ew(B, _TEW_MASK, n_restore / 24.0, "f16")
+    want = np.zeros((4, 6), np.uint8)
+    for k, n in want_pos:
+        want[k, n] = 1
+    assert np.array_equal(got, want)
+    assert not np.any(got & _TEW_MASK)
+
+
+def test_restore_ew_tie_order_is_row_major():
+    """Seven restored weights: 7,7,7,6,5,4 and ONE of the two 3s - the one at the lower row-major position, (0,4)."""
+    B = W.f32_to_bits(_TEW_B, "bf16")
+    got = tw_ref.restore_ew(B, _TEW_MASK, 7 / 24.0, "bf16")
+    assert got[0, 4] == 1 and got[2, 0] == 0 and int(got.sum()) == 7
+
+
+def test_restore_ew_limits():
+    B = W.f32_to_bits(_TEW_B, "f16")
+    assert not tw_ref.restore_ew(B, _TEW_MASK, 0.0, "f16").any()
+    everything = tw_ref.restore_ew(B, _TEW_MASK, 0.99, "f16")          # more than there are pruned weights
+    assert np.array_equal(everything, 1 - _TEW_MASK)

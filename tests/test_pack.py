@@ -238,16 +238,27 @@ def test_tw_restore_ew_matches_oracle_bit_exact(K, N, G, dtype, delta):
     ref = tw_ref.restore_ew(w.B, w.mask, delta, dtype)
     assert np.array_equal(got, ref)
     # properties the paper states: only pruned weights come back, exactly delta*K*N of them (if that many are
-    # there), none weaker than one that stays pruned in a surviving column
+    # there), none weaker than one that stays pruned - wherever they lie, also in columns pruned altogether
     assert not np.any(got & w.mask)
-    alive = w.mask.any(axis=0)
-    n_cand = int(((w.mask == 0) & alive[None, :]).sum())
+    n_cand = int((w.mask == 0).sum())
     assert int(got.sum()) == min(n_cand, int(np.floor(delta * K * N + 0.5)))
-    assert not np.any(got[:, ~alive])
     if got.any() and n_cand > got.sum():
         mag = np.abs(tw_ref.decode(w.B, dtype))
-        left = (w.mask == 0) & (got == 0) & alive[None, :]
+        left = (w.mask == 0) & (got == 0)
         assert mag[got == 1].min() >= mag[left].max()
+
+
+def test_tw_restore_ew_matches_the_hand_worked_case():
+    """The library on the oracle's hand-worked case (tests/test_oracle_pins.py): the three strongest pruned weights
+    lie in the column that the tile-wise pattern removed."""
+    B = W.f32_to_bits(np.array([[1, -9, 2, 7, 3, 1], [5, 2, -8, 7, 1, 2], [-3, 4, 6, -7, 2, 3], [2, 1, 5, 1, 8, 4]],
+                               np.float32), "f16")
+    mask = np.array([[1, 1, 1, 0, 0, 0], [1, 1, 1, 0, 0, 0], [0, 0, 0, 0, 1, 1], [0, 0, 0, 0, 1, 1]], np.uint8)
+    got = tw.tw_restore_ew(B, mask, 4 / 24.0, "f16")
+    want = np.zeros((4, 6), np.uint8)
+    for k, n in [(0, 3), (1, 3), (2, 3), (2, 2)]:
+        want[k, n] = 1
+    assert np.array_equal(got, want)
 
 
 def test_tew_pack_round_trip_and_errors():
@@ -268,13 +279,25 @@ def test_tew_pack_round_trip_and_errors():
     # entries that the tile-wise pattern keeps anyway are ignored
     blob2 = tw.tw_pack_tew(w.B, w.mask, (ew | w.mask).astype(np.uint8), spec.G, "f16")
     assert tw.tw_info(blob2)["ew_nnz"] == int(ew.sum())
-    # a residual weight in a column without tile-wise weights is refused
+    # residual weights in columns without tile-wise weights are part of the blob too (stored by column)
     pruned_cols = np.flatnonzero(~w.mask.any(axis=0))
-    bad = ew.copy()
-    bad[3, pruned_cols[0]] = 1
-    with pytest.raises(tw.TwError) as e:
-        tw.tw_pack_tew(w.B, w.mask, bad, spec.G, "f16")
-    assert e.value.status == -6
+    assert ew[:, pruned_cols].any()                     # the restored set reaches into pruned columns by itself
+    only = np.zeros_like(ew)
+    only[3, pruned_cols[0]] = 1
+    only[7, pruned_cols[-1]] = 1
+    only[150, pruned_cols[-1]] = 1
+    blob3 = tw.tw_pack_tew(w.B, w.mask, only, spec.G, "f16")
+    assert tw.tw_info(blob3)["ew_nnz"] == 3
+    Bu3, mu3 = tw.tw_unpack(blob3)
+    assert np.array_equal(mu3, (w.mask | only).astype(np.uint8))
+    assert np.array_equal(Bu3, tw_ref.masked_weight_bits(w.B, w.mask | only))
+    # a weight without any tile-wise weight at all: every column is of that kind
+    none = np.zeros_like(w.mask)
+    blob4 = tw.tw_pack_tew(w.B, none, ew, spec.G, "f16")
+    inf4 = tw.tw_info(blob4)
+    assert inf4["T"] == 0 and inf4["ew_nnz"] == int(ew.sum())
+    Bu4, mu4 = tw.tw_unpack(blob4)
+    assert np.array_equal(mu4, ew) and np.array_equal(Bu4, tw_ref.masked_weight_bits(w.B, ew))
     # streamed K (several chunks of 384 rows, the last one ragged): the residual is stored per tile and chunk
     big = W.generate(W.small_spec("tew_big", M=4, K=1600, N=200, G=32, dtype="bf16", col_prune=0.1, keep=("upow", 0.05, 0.4),
                                   seed_offset=4301))
