@@ -184,6 +184,19 @@ int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transposed, tw_plan
 int tw_gemm(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
             void* C, int ldc, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* tw_gemm for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The scheduler's counters (the scratch memory
+ * that tw_gemm takes from the caller's workspace) live in a device array inside the library instead,
+ * TW_STATIC_SCRATCH_BYTES per GPU, held until the process ends; the call allocates nothing and frees nothing.
+ * It enqueues a one-workgroup kernel that zeroes the counters, then what tw_gemm enqueues.  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads) race and give
+ * wrong results; calls on one stream, one after the other, are fine.  Arguments and results as tw_gemm;
+ * TW_ERR_UNSUPPORTED if the blob and M need more scratch than the array holds (tw_gemm_workspace says how
+ * much; today 256 bytes for every blob and M), TW_ERR_HIP if the array's address cannot be obtained. */
+#define TW_STATIC_SCRATCH_BYTES 4096
+int tw_gemm_static(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
+                   void* C, int ldc, void* hip_stream);
+
 /* C = act(A . (B * mask) + bias): tw_gemm with the bias addition and the activation that follow a
  * weight GEMM inside a Transformer or CNN layer fused into its epilogue (Sec. VI "Kernel Fusion": the
  * non-GEMM operators around the GEMMs are fused so that they do not eat the GEMM's gain; here the

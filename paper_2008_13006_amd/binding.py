@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libtw.so")
 TW_F16, TW_BF16 = 0, 1
 _DT = {"f16": TW_F16, "bf16": TW_BF16}
 
-SYMBOLS = ["tw_pack_size", "tw_pack", "tw_pack_tew_size", "tw_pack_tew", "tw_restore_ew", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm_plan", "tw_gemm",
+SYMBOLS = ["tw_pack_size", "tw_pack", "tw_pack_tew_size", "tw_pack_tew", "tw_restore_ew", "tw_unpack", "tw_info", "tw_prune", "tw_gemm_workspace", "tw_gemm_plan", "tw_gemm", "tw_gemm_static",
            "tw_gemm_bias_act", "tw_gemm_t", "tw_gemm_t_bias_act", "tw_transpose", "tw_dense_gemm", "tw_dense_gemm_bias_act", "tw_strerror",
            "tw_version"]
 TW_ACT_NONE, TW_ACT_RELU, TW_ACT_GELU = 0, 1, 2
@@ -66,6 +66,7 @@ def _load() -> ctypes.CDLL:
     lib.tw_gemm_workspace.argtypes = [vp, i, ctypes.POINTER(sz)]
     lib.tw_gemm_plan.argtypes = [vp, i, i, i, ctypes.POINTER(TwPlan)]
     lib.tw_gemm.argtypes = [vp, vp, vp, i, i, vp, i, vp, sz, vp]
+    lib.tw_gemm_static.argtypes = [vp, vp, vp, i, i, vp, i, vp]
     lib.tw_dense_gemm.argtypes = [vp, i, vp, i, vp, i, i, i, i, i, vp]
     lib.tw_gemm_bias_act.argtypes = [vp, vp, vp, i, i, vp, i, vp, i, vp, sz, vp]
     lib.tw_gemm_t.argtypes = [vp, vp, vp, i, i, vp, i, vp, sz, vp]
@@ -261,6 +262,21 @@ def tw_gemm(w: TwWeight, A, C=None, stream=None):
     _check(_lib.tw_gemm(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()), ctypes.c_void_p(A.data_ptr()),
                         M, lda, ctypes.c_void_p(C.data_ptr()), ldc, ctypes.c_void_p(w.workspace.data_ptr()),
                         w.workspace.numel(), _stream_ptr(stream)), "tw_gemm")
+    return C
+
+
+def tw_gemm_static(w: TwWeight, A, C, stream=None):
+    """tw_gemm without a workspace and without any allocation: the library's own per-GPU scratch array holds the
+    scheduler's counters.  C must be given (the caller owns every buffer).  Calls must not overlap on one GPU."""
+    assert A.is_cuda and A.dtype == _tdtype(w.dtype) and A.dim() == 2 and A.stride(1) == 1
+    M, K = A.shape
+    N = w.info["N"]
+    assert K == w.info["K"]
+    assert C.is_cuda and C.dtype == A.dtype and C.shape == (M, N) and C.stride(1) == 1
+    lda = A.stride(0) if M > 1 else max(K, A.stride(0))
+    ldc = C.stride(0) if M > 1 else max(N, C.stride(0))
+    _check(_lib.tw_gemm_static(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()), ctypes.c_void_p(A.data_ptr()),
+                               M, lda, ctypes.c_void_p(C.data_ptr()), ldc, _stream_ptr(stream)), "tw_gemm_static")
     return C
 
 

@@ -1626,7 +1626,52 @@ int check_gemm_args(const void* blob_host, const void* blob_dev, const void* A, 
     return TW_OK;
 }
 
+// ---- scratch memory of the entry point that allocates nothing and takes no workspace (tw_gemm_static) ----
+// The scheduler's counters live in this array instead of a buffer of the caller.  Every GPU holds its own
+// copy at its own address; host code must use the address that hipGetSymbolAddress returns with that GPU
+// current (the array's name is only a host-side stand-in), so it is looked up once per device and kept.
+__device__ __align__(256) unsigned char tw_static_scratch[TW_STATIC_SCRATCH_BYTES];
+std::atomic<void*> g_static_scratch[kMaxDevices];
+
+int static_scratch(int dev, void** out) {
+    void* ptr = g_static_scratch[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(tw_static_scratch)) != hipSuccess || !ptr) return TW_ERR_HIP;
+        g_static_scratch[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return TW_OK;
+}
+
+// the counters start every call at zero, whatever an earlier call left behind (a kernel, not a memset: the
+// call may be recorded into a graph)
+__global__ void tw_clear_kernel(unsigned* w, int n) {
+    if ((int)threadIdx.x < n) w[threadIdx.x] = 0u;
+}
 }  // namespace
+
+extern "C" int tw_gemm_static(const void* blob_host, const void* blob_dev, const void* A, int M, int lda, void* C,
+                              int ldc, void* hip_stream) {
+    size_t need = 0;
+    int rc = tw_gemm_workspace(blob_host, M < 0 ? 0 : M, &need);
+    if (rc) return rc;
+    if (need > TW_STATIC_SCRATCH_BYTES) return TW_ERR_UNSUPPORTED;     // more scratch than the array holds
+    const int dev = current_device();
+    if (dev < 0) return TW_ERR_HIP;
+    void* scratch = nullptr;
+    rc = static_scratch(dev, &scratch);
+    if (rc) return rc;
+    rc = check_gemm_args(blob_host, blob_dev, A, M, lda, nullptr, TW_ACT_NONE, C, ldc, scratch, TW_STATIC_SCRATCH_BYTES);
+    if (rc) return rc;
+    if (M == 0) return TW_OK;
+    unsigned* w_ = (unsigned*)scratch;
+    int n_ = 64;
+    void* cargs[] = {(void*)&w_, (void*)&n_};
+    if (hipLaunchKernel((const void*)tw_clear_kernel, dim3(1), dim3(64), cargs, 0, (hipStream_t)hip_stream) != hipSuccess)
+        return TW_ERR_HIP;
+    return tw_gemm_bias_act(blob_host, blob_dev, A, M, lda, nullptr, TW_ACT_NONE, C, ldc, scratch, TW_STATIC_SCRATCH_BYTES,
+                            hip_stream);
+}
 
 extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
                                 const void* bias, tw_act act, void* C, int ldc, void* workspace, size_t ws_bytes,
