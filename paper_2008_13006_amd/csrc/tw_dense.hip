@@ -34,6 +34,7 @@ struct DenseParams {
     int nbm, nbn;
     const unsigned short* bias;   // N values added before the activation, or null
     int act;                      // tw_act
+    int stream;                   // rows of C start on 128-byte boundaries: whole lines go out as streaming stores
 };
 
 struct Staged {
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p)
 #pragma unroll
         for (int ms = 0; ms < 4; ++ms)
             tw_store_block<DT, 2>(acc[ms], stage, p.C, p.ldc, m0 + wm * 128 + ms * 32, p.M, col0, width, lane,
-                                  p.bias, p.act);
+                                  p.bias, p.act, p.stream != 0);
     }
 }
 
@@ -190,6 +191,7 @@ extern "C" int tw_dense_gemm_bias_act(const void* A, int lda, const void* B, int
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
     p.M = M; p.N = N; p.K = K;
     p.bias = (const unsigned short*)bias; p.act = (int)act;
+    p.stream = ((uintptr_t)C & 127) == 0 && (ldc & 63) == 0;
     p.nbm = (M + BM - 1) / BM; p.nbn = (N + BN - 1) / BN;
     const long blocks = (long)p.nbm * p.nbn;
     if (blocks > 0x7fffffffL) return TW_ERR_UNSUPPORTED;

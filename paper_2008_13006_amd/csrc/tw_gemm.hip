@@ -65,6 +65,8 @@ struct TwGemmParams {
     uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_zero_ptr, off_zero_cols, off_urow, off_ucnt;
     uint64_t off_ew_ptr, off_ew_k, off_ew_v;
     int has_ew;                 // the blob carries an element-wise residual (TEW)
+    int stream_stores;          // rows of the output start on 128-byte boundaries: stores that complete whole lines
+                                // may carry the streaming hint
     unsigned urow_off;          // LDS offset of the loading waves' row lists (transposed, streamed K, few tiles), 0: none
 };
 
@@ -176,6 +178,8 @@ __device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar,
             int g0 = row0 + t.row, g1 = g0 + 1;
             g0 = g0 < mend ? g0 : mend - 1;           // rows past the block's end: any valid row, never stored
             g1 = g1 < mend ? g1 : mend - 1;
+            // (plain loads: with K resident the streaming hint measured 1.5 us slower on the BERT-base shapes;
+            // the streamed paths below gain 2 to 6 us from it)
             ar.v[2 * b] = *(const tw_u32x4*)(p.A + (long)g0 * p.lda + (k0 + t.oc * 8));
             ar.v[2 * b + 1] = *(const tw_u32x4*)(p.A + (long)g1 * p.lda + (k0 + t.oc * 8));
         }
@@ -185,7 +189,7 @@ __device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar,
             const ATask<MS, false> t(t0 + b * stride, kw, lane);
             int grow = row0 + t.row;
             grow = grow < mend ? grow : mend - 1;
-            ar.v[b] = *(const tw_u32x4*)(p.A + (long)grow * p.lda + (k0 + t.oc * 8));
+            ar.v[b] = tw_load16_stream(p.A + (long)grow * p.lda + (k0 + t.oc * 8));
         }
     }
 }
@@ -499,11 +503,13 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
             wpos[cb] = stage + h * kPlaneBytes + (rel < (unsigned)kWinCols ? rel * 8u : (unsigned)(kSpareOff + n * 8));
         }
         const unsigned char* rpos = stage + in_rq * kPlaneBytes + (8 * in_piece + in_e) * 8;
-        bool okl[kWinLines];
+        bool okl[kWinLines], whole[kWinLines];
 #pragma unroll
         for (int l = 0; l < kWinLines; ++l) {
             const int col = win0 + l * kLineCols + piece * 8;
             okl[l] = l < nl && col >= S && col + 8 <= E;
+            // the span covers this line from end to end (wave-uniform): nobody else writes into it
+            whole[l] = p.stream_stores != 0 && win0 + l * kLineCols >= S && win0 + (l + 1) * kLineCols <= E;
         }
         unsigned short* cptr = p.C + (long)(row0 + orow) * p.ldc + (win0 + piece * 8);
         // partial groups at the two ends of the span, if they lie in this window (window-relative index)
@@ -571,7 +577,8 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
             for (int l = 0; l < kWinLines; ++l) {
                 if (okl[l] && 8 * P < rows_left) {
                     const tw_u32x2 a = __builtin_bit_cast(tw_u32x2, lo[l]), b = __builtin_bit_cast(tw_u32x2, hi[l]);
-                    *(tw_u32x4_a2*)(cptr + (long)(8 * P) * p.ldc + l * kLineCols) = tw_u32x4{a.x, a.y, b.x, b.y};
+                    if (whole[l]) tw_store16_stream(cptr + (long)(8 * P) * p.ldc + l * kLineCols, tw_u32x4{a.x, a.y, b.x, b.y});
+                    else *(tw_u32x4_a2*)tw_opaque(cptr + (long)(8 * P) * p.ldc + l * kLineCols) = tw_u32x4{a.x, a.y, b.x, b.y};
                 }
             }
             if (g_first >= 0) {                              // wave-uniform
@@ -623,7 +630,7 @@ __device__ __forceinline__ void at_issue(const TwGemmParams& p, ARegs<BATCH>& ar
     for (int b = 0; b < BATCH; ++b) {
         const AtTask<MS> t(t0 + b * stride, kw, lane);
         const int pc = t.pc < pmax ? t.pc : pmax;
-        ar.v[b] = *(const tw_u32x4*)(p.A + (long)(k0 + t.krow) * p.lda + (m0 + pc * 8));
+        ar.v[b] = tw_load16_stream(p.A + (long)(k0 + t.krow) * p.lda + (m0 + pc * 8));
     }
 }
 
@@ -658,7 +665,7 @@ __device__ __forceinline__ void at_issue_rows(const TwGemmParams& p, ARegs<BATCH
         const int j = 8 * (t0 + b * stride) + (lane >> 3);
         const int krow = rows[8 * b + (lane >> 3)];
         ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};
-        if (j < cnt) ar.v[b] = *(const tw_u32x4*)(p.A + (long)(k0 + krow) * p.lda + (m0 + pc * 8));
+        if (j < cnt) ar.v[b] = tw_load16_stream(p.A + (long)(k0 + krow) * p.lda + (m0 + pc * 8));
     }
 }
 template <int BATCH>
@@ -710,7 +717,7 @@ __device__ __forceinline__ void a_issue_full(const TwGemmParams& p, ARegs<BATCH>
     }
 #pragma unroll
     for (int b = 0; b < BATCH; ++b)
-        ar.v[b] = *(const tw_u32x4*)(rp[((b * STRIDE) & 7) / STRIDE] + ((b * STRIDE) >> 3) * 64);
+        ar.v[b] = tw_load16_stream(rp[((b * STRIDE) & 7) / STRIDE] + ((b * STRIDE) >> 3) * 64);
 }
 template <int BATCH, int STRIDE>
 __device__ __forceinline__ void a_commit_full(const ARegs<BATCH>& ar, unsigned char* at, int t0, int lane_in) {
@@ -774,10 +781,14 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
     const int origin = d.span_start & ~7;
     const int mleft = p.M - m0;                              // tokens of this block that exist
     const bool whole = 8 * pc + 8 <= mleft;                  // this lane's piece lies inside
+    // a block of 64 tokens that exists in full is a whole 128-byte line of every row of Ct (wave-uniform)
+    const bool stream = p.stream_stores != 0 && MS == 2 && mleft >= 64;
     auto put_piece = [&](long row, tw_u32x4 v) {
         unsigned short* dst = p.C + row * p.ldc + (m0 + 8 * pc);
-        if (whole) {
-            *(tw_u32x4*)dst = v;
+        if (stream) {
+            tw_store16_stream(dst, v);
+        } else if (whole) {
+            *(tw_u32x4*)tw_opaque(dst) = v;
         } else {
             const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -1359,7 +1370,7 @@ __global__ __launch_bounds__(256) void tw_xcol_kernel(const XcolParams p) {
             int g = row0 + r;
             g = g < p.M ? g : p.M - 1;
             tw_u32x4 v = tw_u32x4{0u, 0u, 0u, 0u};
-            if (c0 + 8 * pc < kpad) v = *(const tw_u32x4*)(p.A + (long)g * p.lda + c0 + 8 * pc);
+            if (c0 + 8 * pc < kpad) v = tw_load16_stream(p.A + (long)g * p.lda + c0 + 8 * pc);
             *(tw_u32x2*)(at + r * kXcPitch + pc * 16) = tw_u32x2{v.x, v.y};
             *(tw_u32x2*)(at + r * kXcPitch + pc * 16 + 8) = tw_u32x2{v.z, v.w};
         }
@@ -1730,6 +1741,7 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt; p.urow_off = 0;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
+    p.stream_stores = ((uintptr_t)C & 127) == 0 && (ldc & 63) == 0;
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     void* args[] = {(void*)&p};
     if (hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, pl.lds_bytes, stream) != hipSuccess) return TW_ERR_HIP;
@@ -1804,6 +1816,7 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
     p.urow_off = pl.urow_off;
+    p.stream_stores = ((uintptr_t)Ct & 127) == 0 && (ldct & 63) == 0;
     const unsigned lds_bytes = pl.lds_bytes;
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     void* args[] = {(void*)&p};
