@@ -106,7 +106,7 @@ def per_launch_stats(torch, fn, n_sets: int, steps: int):
 
 
 def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = True, n_sets=None,
-               with_warm: bool = False, with_steady: bool = False):
+               with_warm: bool = False, with_steady: bool = False, settle: int = 0):
     w = W.generate(spec)
     t0 = time.perf_counter()
     blob = tw.tw_pack(w.B, w.mask, spec.G, spec.dtype)
@@ -123,6 +123,11 @@ def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = T
     Cs = [torch.empty((M, spec.N), dtype=td, device="cuda:0") for _ in range(n_sets)]
     Bd = tw.bits_to_tensor(w.B, spec.dtype)
 
+    # Clocks and queues settle during the first few hundred launches of a process (the same launch is 10 % slower
+    # before): they are spent here, untimed, before the warm-up steps and the timed steps that the caller asked for.
+    for i in range(settle):
+        tw.tw_gemm(wt, As[i % n_sets], Cs[i % n_sets])
+    torch.cuda.synchronize()
     cold_ms, cold_wall = time_launches(torch, lambda i: tw.tw_gemm(wt, As[i], Cs[i]), n_sets, steps, warmup)
     warm_ms = None
     if with_warm:     # same buffers every launch: A and part of C stay in the last-level cache
@@ -279,7 +284,7 @@ def main() -> int:
         return pmc_sweep(torch, tw, W)
     if args.pmc_calibration:
         return pmc_calibration(torch, tw, W, spec, args.steps, args.transposed)
-    res, w, info = bench_gemm(torch, tw, W, spec, args.steps, args.warmup, with_steady=True)
+    res, w, info = bench_gemm(torch, tw, W, spec, args.steps, args.warmup, with_steady=True, settle=400)
     traffic, traffic_note = measured_traffic(False)
     traffic_t, traffic_t_note = measured_traffic(True)
     line = {
