@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define TW_MAGIC 0x31425754u /* "TWB1" */
-#define TW_FORMAT_VERSION 11
+#define TW_FORMAT_VERSION 12
 
 // MFMA step geometry the packed values are laid out for: one step contracts 16 kept rows
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
@@ -14,6 +14,8 @@
 #define TW_WAVES_PER_WG 8
 #endif
 #define TW_COLBLK 32
+// Residual-only columns (TEW) that a tile's epilogue computes itself, per tile (see off_xc_rank).
+#define TW_XC_INLINE 16
 // Tiles per workgroup of the streamed kernels: a wave per tile, or with at most half as many tiles
 // half of the waves multiply and the others only bring A into LDS.
 #define TW_SET_TILES(T) ((T) <= TW_WAVES_PER_WG / 2 ? TW_WAVES_PER_WG / 2 : TW_WAVES_PER_WG)
@@ -63,7 +65,14 @@ struct TwHeader {
     uint64_t off_xc_ptr;     //   int32 [xc_n+1]: first entry of every such column
     uint64_t off_xc_k;       //   int32 [entries]: K row of the entry, ascending within a column
     uint64_t off_xc_v;       //   16-bit [entries]: its weight
-    uint8_t pad[384 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 18];
+    uint64_t off_xc_tile_ptr;//   int32 [T+1]: the columns of the list that lie in the span of tile t (canonical order) are
+                             //   [xc_tile_ptr[t], xc_tile_ptr[t+1]) (the list is ascending and spans are disjoint)
+    uint64_t off_xc_rank;    //   int32 [xc_n]: position of the column among those of its tile; the kernel with K resident
+                             //   adds the first TW_XC_INLINE of a tile in that tile's epilogue, the rest (and everything
+                             //   in the other kernel modes) goes to the pass of its own
+    int32_t xc_overflow;     //   columns with rank >= TW_XC_INLINE
+    int32_t reserved1;
+    uint8_t pad[384 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 20 - 4 * 2];
 };
 static_assert(sizeof(TwHeader) == 384, "header is 384 bytes");
 

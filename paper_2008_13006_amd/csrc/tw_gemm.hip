@@ -65,6 +65,9 @@ struct TwGemmParams {
     uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_zero_ptr, off_zero_cols, off_urow, off_ucnt;
     uint64_t off_ew_ptr, off_ew_k, off_ew_v;
     int has_ew;                 // the blob carries an element-wise residual (TEW)
+    uint64_t off_xc_tile_ptr, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v;
+    unsigned xbuf_off;          // LDS offset of the per-wave areas for residual-only columns (TEW), 0: the tiles' kernel
+                                // leaves those columns to the pass of their own
     int stream_stores;          // rows of the output start on 128-byte boundaries: stores that complete whole lines
                                 // may carry the streaming hint
     unsigned urow_off;          // LDS offset of the loading waves' row lists (transposed, streamed K, few tiles), 0: none
@@ -473,9 +476,40 @@ __device__ __forceinline__ void apply_bias_act(tw_f32x16 (&acc)[MS][NCB], const 
 // carries none of its code.
 template <int DT, int MS, int NCB, bool FUSED>
 __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
-                                           unsigned char* stage, const unsigned (&dpos)[NCB], int row0, int lane_in) {
+                                           unsigned char* stage, const unsigned (&dpos)[NCB], int row0, int lane_in,
+                                           const unsigned char* at_resident = nullptr, unsigned short* xbuf = nullptr) {
     const int lane = fresh(lane_in);
     constexpr bool fused = FUSED;
+    // Residual-only columns of a TEW blob inside this tile's span (Sec. IV-A "Hybrid Pattern": weights restored in a
+    // column that the tile-wise pattern pruned altogether).  With K resident the tile that owns the span computes
+    // them here, from the LDS copy of A, lane = row: C[row, n] = sum_e v_e * A[row, k_e]; the results wait in
+    // `xbuf` ([column][row], 16-bit) and every pass puts its eight rows of them into the staging window, where the
+    // pruned columns otherwise read back as zeros - so they leave with the tile's own stores.
+    int nx = 0, x0 = 0;
+    if (xbuf != nullptr) {                                   // wave-uniform
+        const int* xtp = (const int*)(p.blob + p.off_xc_tile_ptr);
+        x0 = fetch_int(xtp, d.tile);
+        nx = fetch_int(xtp, d.tile + 1) - x0;
+        nx = nx < TW_XC_INLINE ? nx : TW_XC_INLINE;
+        const int* xcol = (const int*)(p.blob + p.off_xc_col);
+        const int* xptr = (const int*)(p.blob + p.off_xc_ptr);
+        const int* xk = (const int*)(p.blob + p.off_xc_k);
+        const unsigned short* xv = (const unsigned short*)(p.blob + p.off_xc_v);
+        for (int j = 0; j < nx; ++j) {
+            const int e0 = fetch_int(xptr, x0 + j), e1 = fetch_int(xptr, x0 + j + 1);
+            float sum = 0.f;
+            for (int e = e0; e < e1; ++e) {
+                const int k = fetch_int(xk, e);
+                const float v = tw_to_f32<DT>(xv[e]);
+                sum += v * tw_to_f32<DT>(*(const unsigned short*)(at_resident + (unsigned)k * at_pitch_of<MS>() + lane * 2));
+            }
+            if constexpr (FUSED) {
+                const int n = fetch_int(xcol, x0 + j);
+                sum = tw_activate(sum + (p.bias != nullptr ? tw_to_f32<DT>(p.bias[n]) : 0.f), p.act);
+            }
+            xbuf[j * 64 + lane] = tw_cvt<DT>(sum);
+        }
+    }
     EpiBias<NCB> eb;
     if constexpr (FUSED) {
         fetch_epi_bias<DT, NCB>(p, d, dpos, eb, lane);
@@ -525,6 +559,17 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
         unsigned short* rptr = p.C + (long)(row0 + trow) * p.ldc;
         const int rag_left = block_end(p, row0) - (row0 + trow);
 
+        // residual-only columns: lane l handles column l / 8 (and l / 8 + 8) of the tile's list, row l % 8 of a pass
+        unsigned char* xpos[TW_XC_INLINE / 8];
+#pragma unroll
+        for (int g = 0; g < TW_XC_INLINE / 8; ++g) {
+            xpos[g] = nullptr;
+            const int j = 8 * g + (lane >> 3);
+            if (j < nx) {
+                const unsigned rel = (unsigned)(((const int*)(p.blob + p.off_xc_col))[x0 + j] - win0);
+                if (rel < (unsigned)kWinCols) xpos[g] = stage + ((lane >> 2) & 1) * kPlaneBytes + rel * 8u + (lane & 3) * 2;
+            }
+        }
         auto write_pass = [&](int P) {
             const int ms = P >> 2, q = P & 3;
 #pragma unroll
@@ -533,6 +578,12 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
                 v.x = (unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 0]) | ((unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 1]) << 16);
                 v.y = (unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 2]) | ((unsigned)tw_cvt<DT>(acc[ms][cb][4 * q + 3]) << 16);
                 *(tw_u32x2*)wpos[cb] = v;
+            }
+            if (nx > 0) {                                    // wave-uniform
+#pragma unroll
+                for (int g = 0; g < TW_XC_INLINE / 8; ++g)
+                    if (xpos[g] != nullptr)
+                        *(unsigned short*)xpos[g] = xbuf[(8 * g + (lane >> 3)) * 64 + 8 * P + (lane & 7)];
             }
         };
 
@@ -965,7 +1016,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                                            p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
                 if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, at_pitch_of<MS>(), lane);
                 if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
-                else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, smem,
+                                                    p.xbuf_off != 0 ? (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64) : nullptr);
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
         } else if constexpr (MODE == 2) {
@@ -1337,8 +1389,10 @@ struct XcolParams {
     const int* ptr;
     const int* k;
     const unsigned short* v;
+    const int* rank;            // position of a column among those of its tile
     long lda, ldc;
     int M, K, n_cols, act;
+    int skip_below;             // columns with rank < skip_below were added by the tiles' kernel already
 };
 
 // Row-major boundary.  A workgroup takes 64 rows of A and 64 of the columns; wave w, lane r: row r, columns
@@ -1358,8 +1412,9 @@ __global__ __launch_bounds__(256) void tw_xcol_kernel(const XcolParams p) {
     for (int i = 0; i < 16; ++i) {
         const int j = j0 + i;
         acc[i] = 0.f;
-        e[i] = j < p.n_cols ? p.ptr[j] : 0;
-        e1[i] = j < p.n_cols ? p.ptr[j + 1] : 0;
+        const bool mine = j < p.n_cols && p.rank[j] >= p.skip_below;
+        e[i] = mine ? p.ptr[j] : 0;
+        e1[i] = mine ? p.ptr[j + 1] : 0;
     }
     const int kpad = (p.K + 7) & ~7;                             // rows are readable up to the next multiple of 8
     for (int c0 = 0; c0 < p.K; c0 += kXcChunk) {
@@ -1392,7 +1447,7 @@ __global__ __launch_bounds__(256) void tw_xcol_kernel(const XcolParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int j = j0 + i;
-            if (j < p.n_cols) {
+            if (j < p.n_cols && p.rank[j] >= p.skip_below) {
                 const int n = p.col[j];
                 const float b = p.bias ? tw_to_f32<DT>(p.bias[n]) : 0.f;
                 p.C[(long)m * p.ldc + n] = tw_cvt<DT>(tw_activate(acc[i] + b, p.act));
@@ -1408,6 +1463,7 @@ __global__ __launch_bounds__(256) void tw_xcol_t_kernel(const XcolParams p) {
     const long m = (long)blockIdx.x * 256 + threadIdx.x;
     if (m >= p.M) return;
     for (int j = blockIdx.y; j < p.n_cols; j += gridDim.y) {
+        if (p.rank[j] < p.skip_below) continue;
         float acc = 0.f;
         for (int e = p.ptr[j]; e < p.ptr[j + 1]; ++e)
             acc += tw_to_f32<DT>(p.v[e]) * tw_to_f32<DT>(p.A[(long)p.k[e] * p.lda + m]);
@@ -1419,14 +1475,17 @@ __global__ __launch_bounds__(256) void tw_xcol_t_kernel(const XcolParams p) {
 
 // Enqueues the pass over the residual's columns without tile-wise weights, if the blob has any.
 int launch_xcols(const TwHeader* h, const void* blob_dev, const void* A, long lda, void* C, long ldc, int M,
-                 const void* bias, int act, bool transposed, hipStream_t stream) {
+                 const void* bias, int act, bool transposed, hipStream_t stream, bool inline_done = false) {
     if (h->xc_n <= 0 || M <= 0) return TW_OK;
+    if (inline_done && h->xc_overflow == 0) return TW_OK;   // the tiles' kernel added them all
     const unsigned char* b = (const unsigned char*)blob_dev;
     XcolParams p;
     p.A = (const unsigned short*)A; p.C = (unsigned short*)C; p.bias = (const unsigned short*)bias;
     p.col = (const int*)(b + h->off_xc_col); p.ptr = (const int*)(b + h->off_xc_ptr);
     p.k = (const int*)(b + h->off_xc_k); p.v = (const unsigned short*)(b + h->off_xc_v);
+    p.rank = (const int*)(b + h->off_xc_rank);
     p.lda = lda; p.ldc = ldc; p.M = M; p.K = h->K; p.n_cols = h->xc_n; p.act = act;
+    p.skip_below = inline_done ? TW_XC_INLINE : 0;
     void* args[] = {(void*)&p};
     hipError_t rc;
     if (transposed) {
@@ -1450,6 +1509,7 @@ struct Plan {
     int row_step;        // rows per row block (see TwGemmParams)
     unsigned at_pitch, abuf_bytes, stage_off, misc_off, lds_bytes;
     unsigned urow_off;   // transposed boundary, loading waves: LDS offset of their row lists (0: whole chunks are read)
+    unsigned xbuf_off;   // row-major boundary, K resident, TEW blob with residual-only columns: LDS offset of the waves' areas for them
 };
 
 constexpr unsigned kLdsLimit = 160 * 1024;
@@ -1533,6 +1593,11 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     // Transposed boundary, at most four tiles, streamed: the loading waves read only the K rows the tiles keep,
     // from lists they hold in LDS.  (The blob's row lists are per set of TW_SET_TILES(T) tiles: with other sets
     // the loading waves bring in whole chunks.)
+    pl.xbuf_off = 0;
+    if (!transposed && resident && h->xc_n > 0) {
+        const unsigned need = kWaves * TW_XC_INLINE * 64 * 2;
+        if (pl.lds_bytes + need <= kLdsLimit) { pl.xbuf_off = pl.lds_bytes; pl.lds_bytes += need; }
+    }
     pl.urow_off = 0;
     if (transposed && pl.mode == 2 && T <= kWaves / 2 && tpw == kWaves / 2) {
         const unsigned need = (kWaves / 2) * (unsigned)h->n_chunks * (8 * 12 + 2) * 2;
@@ -1742,10 +1807,12 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt; p.urow_off = 0;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
     p.stream_stores = ((uintptr_t)C & 127) == 0 && (ldc & 63) == 0;
+    p.off_xc_tile_ptr = h->off_xc_tile_ptr; p.off_xc_col = h->off_xc_col; p.off_xc_ptr = h->off_xc_ptr;
+    p.off_xc_k = h->off_xc_k; p.off_xc_v = h->off_xc_v; p.xbuf_off = pl.xbuf_off;
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     void* args[] = {(void*)&p};
     if (hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, pl.lds_bytes, stream) != hipSuccess) return TW_ERR_HIP;
-    return launch_xcols(h, blob_dev, A, lda, C, ldc, M, bias, (int)act, false, stream);
+    return launch_xcols(h, blob_dev, A, lda, C, ldc, M, bias, (int)act, false, stream, pl.xbuf_off != 0);
 }
 
 extern "C" int tw_gemm_t(const void* blob_host, const void* blob_dev, const void* At, int M, int ldat, void* Ct,
@@ -1816,6 +1883,8 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
     p.urow_off = pl.urow_off;
+    p.off_xc_tile_ptr = h->off_xc_tile_ptr; p.off_xc_col = h->off_xc_col; p.off_xc_ptr = h->off_xc_ptr;
+    p.off_xc_k = h->off_xc_k; p.off_xc_v = h->off_xc_v; p.xbuf_off = 0;
     p.stream_stores = ((uintptr_t)Ct & 127) == 0 && (ldct & 63) == 0;
     const unsigned lds_bytes = pl.lds_bytes;
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;

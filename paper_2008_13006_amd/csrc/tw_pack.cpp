@@ -30,11 +30,12 @@ struct Layout {
     int64_t total_steps = 0;
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
         off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, off_zero_ptr,
-        off_zero_cols, off_urow, off_ucnt, off_ew_ptr, off_ew_k, off_ew_v, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v, bytes;
+        off_zero_cols, off_urow, off_ucnt, off_ew_ptr, off_ew_k, off_ew_v, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v, off_xc_tile_ptr, off_xc_rank, bytes;
     int64_t ew_nnz = 0;
     std::vector<int32_t> ew_ptr;   // planes per (tile, chunk), prefix sums
     // residual weights in columns without tile-wise weights, by column
-    std::vector<int32_t> xc_col, xc_ptr, xc_k;
+    std::vector<int32_t> xc_col, xc_ptr, xc_k, xc_tile_ptr, xc_rank;
+    int32_t xc_overflow = 0;
 };
 
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -181,6 +182,24 @@ void plan(const Tiling& tl, int K, int G, Layout& lo, const uint8_t* mask = null
             }
             lo.ew_nnz += (int64_t)lo.xc_k.size();
         }
+        // which tile's span holds each of these columns, and its position among that tile's
+        lo.xc_tile_ptr.assign((size_t)T + 1, 0);
+        lo.xc_rank.assign(lo.xc_col.size(), 0);
+        {
+            size_t j = 0;
+            for (int t = 0; t < T; ++t) {
+                lo.xc_tile_ptr[t] = (int32_t)j;
+                while (j < lo.xc_col.size() && lo.xc_col[j] < tl.tile_span[t + 1]) {
+                    lo.xc_rank[j] = (int32_t)j - lo.xc_tile_ptr[t];
+                    if (lo.xc_rank[j] >= TW_XC_INLINE) ++lo.xc_overflow;
+                    ++j;
+                }
+            }
+            lo.xc_tile_ptr[T] = (int32_t)j;
+            if (T == 0) lo.xc_overflow = (int32_t)lo.xc_col.size();
+        }
+        lo.off_xc_tile_ptr = take(4 * ((size_t)T + 1), 16);
+        lo.off_xc_rank = take(4 * (lo.xc_rank.size() + 1), 16);
         lo.off_xc_col = take(4 * (lo.xc_col.size() + 1), 16);
         lo.off_xc_ptr = take(4 * lo.xc_ptr.size(), 16);
         lo.off_xc_k = take(4 * (lo.xc_k.size() + 1), 16);
@@ -268,6 +287,7 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
     h->ew_nnz = lo.ew_nnz; h->off_ew_ptr = lo.off_ew_ptr; h->off_ew_k = lo.off_ew_k; h->off_ew_v = lo.off_ew_v;
     h->xc_n = (int32_t)lo.xc_col.size();
     h->off_xc_col = lo.off_xc_col; h->off_xc_ptr = lo.off_xc_ptr; h->off_xc_k = lo.off_xc_k; h->off_xc_v = lo.off_xc_v;
+    h->off_xc_tile_ptr = lo.off_xc_tile_ptr; h->off_xc_rank = lo.off_xc_rank; h->xc_overflow = lo.xc_overflow;
 
     auto put = [&](uint64_t off, const std::vector<int32_t>& v) {
         if (!v.empty()) std::memcpy(base + off, v.data(), 4 * v.size());
@@ -310,6 +330,8 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
     put(lo.off_xc_col, lo.xc_col);
     put(lo.off_xc_ptr, lo.xc_ptr);
     put(lo.off_xc_k, lo.xc_k);
+    put(lo.off_xc_tile_ptr, lo.xc_tile_ptr);
+    put(lo.off_xc_rank, lo.xc_rank);
     {
         uint16_t* xv = (uint16_t*)(base + lo.off_xc_v);
         const uint16_t* Bw = (const uint16_t*)B;
