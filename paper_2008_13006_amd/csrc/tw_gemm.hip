@@ -495,13 +495,39 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
         const int* xptr = (const int*)(p.blob + p.off_xc_ptr);
         const int* xk = (const int*)(p.blob + p.off_xc_k);
         const unsigned short* xv = (const unsigned short*)(p.blob + p.off_xc_v);
+        // The entries of the tile's columns are consecutive in the list.  They are fetched 64 at a time, one per
+        // lane, and handed to the whole wave with v_readlane, so that the loop below waits for memory once per 64
+        // entries and not once per entry; four LDS reads are in flight per lane.
+        const int pv = nx > 0 && lane <= nx ? xptr[x0 + lane] : 0;           // first entry of column lane, lane <= nx
+        const int e_end = nx > 0 ? __builtin_amdgcn_readlane(pv, nx) : 0;
+        int base = -64, kreg = 0;
+        float vreg = 0.f;
+        const unsigned char* arow = at_resident + lane * 2;
+        auto a_of = [&](int e) {                                             // A[row = lane, K row of entry e] (e uniform)
+            const int k = __builtin_amdgcn_readlane(kreg, e - base);
+            return tw_to_f32<DT>(*(const unsigned short*)(arow + (unsigned)k * at_pitch_of<MS>()));
+        };
+        auto v_of = [&](int e) { return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vreg), e - base)); };
         for (int j = 0; j < nx; ++j) {
-            const int e0 = fetch_int(xptr, x0 + j), e1 = fetch_int(xptr, x0 + j + 1);
+            const int e0 = __builtin_amdgcn_readlane(pv, j), e1 = __builtin_amdgcn_readlane(pv, j + 1);
             float sum = 0.f;
-            for (int e = e0; e < e1; ++e) {
-                const int k = fetch_int(xk, e);
-                const float v = tw_to_f32<DT>(xv[e]);
-                sum += v * tw_to_f32<DT>(*(const unsigned short*)(at_resident + (unsigned)k * at_pitch_of<MS>() + lane * 2));
+            int e = e0;
+            while (e < e1) {
+                if (e - base >= 64) {                                        // wave-uniform: the next 64 entries
+                    base = e;
+                    const int mine = base + lane < e_end ? base + lane : e_end - 1;
+                    kreg = xk[mine];
+                    vreg = tw_to_f32<DT>(xv[mine]);
+                }
+                int lim = base + 64 < e1 ? base + 64 : e1;                   // entries of this column inside the batch
+                for (; e + 4 <= lim; e += 4) {
+                    const float a0 = a_of(e), a1 = a_of(e + 1), a2 = a_of(e + 2), a3 = a_of(e + 3);
+                    sum += v_of(e) * a0;
+                    sum += v_of(e + 1) * a1;
+                    sum += v_of(e + 2) * a2;
+                    sum += v_of(e + 3) * a3;
+                }
+                for (; e < lim; ++e) sum += v_of(e) * a_of(e);
             }
             if constexpr (FUSED) {
                 const int n = fetch_int(xcol, x0 + j);
