@@ -137,6 +137,17 @@ struct ARegs {
     tw_u32x4 v[BATCH];
 };
 
+// A 16-byte request for activations.  NTA (compile time, one kernel variant each): with the streaming hint when this
+// workgroup is the only one that reads these rows (one set of tiles per row block: the rows then do not push the
+// packed weights out of the L2; 2 to 6 us on the streamed workloads), plain when the tiles of a row block are split
+// into sets whose workgroups read the same rows one after the other (the later ones then hit in the L2; the skewed
+// FFN-down of BERT-large: 45 us against 49, transposed 41 against 50).
+template <bool NTA>
+__device__ __forceinline__ tw_u32x4 load_a16(const unsigned short* src) {
+    if constexpr (NTA) return tw_load16_stream(src);
+    else return *(const tw_u32x4*)src;
+}
+
 template <int MS, bool PAIR>
 struct ATask {
     int row, oc;      // (first) row of the lane, 16-byte piece of the row
@@ -168,7 +179,7 @@ __device__ __forceinline__ int a_tasks(int kw) {
 }
 
 // requests tasks t0, t0+stride, ... of the block (BATCH requests); stride = number of loading waves
-template <int MS, int BATCH, bool PAIR>
+template <int MS, int BATCH, bool PAIR, bool NTA = true>
 __device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int row0, int k0, int kw, int t0,
                                         int lane_in, int stride = kWaves) {
     const int lane = fresh(lane_in);
@@ -192,7 +203,7 @@ __device__ __forceinline__ void a_issue(const TwGemmParams& p, ARegs<BATCH>& ar,
             const ATask<MS, false> t(t0 + b * stride, kw, lane);
             int grow = row0 + t.row;
             grow = grow < mend ? grow : mend - 1;
-            ar.v[b] = tw_load16_stream(p.A + (long)grow * p.lda + (k0 + t.oc * 8));
+            ar.v[b] = load_a16<NTA>(p.A + (long)grow * p.lda + (k0 + t.oc * 8));
         }
     }
 }
@@ -251,13 +262,13 @@ __device__ __forceinline__ void a_zero_row(const TwGemmParams& p, unsigned char*
 }
 
 // whole block, BATCH requests per wave in flight at a time (12 cover 64 rows x 768 columns)
-template <int MS, int BATCH, bool PAIR>
+template <int MS, int BATCH, bool PAIR, bool NTA = true>
 __device__ __forceinline__ void load_a_block(const TwGemmParams& p, unsigned char* at, int row0, int k0, int kw,
                                              int wave, int lane, int tid) {
     const int tasks = a_tasks<MS, PAIR>(kw);
     for (int t0 = wave; t0 < tasks; t0 += kWaves * (PAIR ? BATCH / 2 : BATCH)) {
         ARegs<BATCH> ar;
-        a_issue<MS, BATCH, PAIR>(p, ar, row0, k0, kw, t0, lane);
+        a_issue<MS, BATCH, PAIR, NTA>(p, ar, row0, k0, kw, t0, lane);
         a_commit<MS, BATCH, PAIR>(p, ar, at, kw, t0, lane);
     }
     a_zero_row(p, at, 32 * MS, tid);
@@ -698,7 +709,7 @@ struct AtTask {
 template <int MS>
 __device__ __forceinline__ int at_tasks(int kw) { return (kw + 64 / (4 * MS) - 1) / (64 / (4 * MS)); }
 
-template <int MS, int BATCH>
+template <int MS, int BATCH, bool NTA = true>
 __device__ __forceinline__ void at_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int m0, int k0, int kw, int t0,
                                          int lane_in, int stride = kWaves) {
     const int lane = fresh(lane_in);
@@ -707,7 +718,7 @@ __device__ __forceinline__ void at_issue(const TwGemmParams& p, ARegs<BATCH>& ar
     for (int b = 0; b < BATCH; ++b) {
         const AtTask<MS> t(t0 + b * stride, kw, lane);
         const int pc = t.pc < pmax ? t.pc : pmax;
-        ar.v[b] = tw_load16_stream(p.A + (long)(k0 + t.krow) * p.lda + (m0 + pc * 8));
+        ar.v[b] = load_a16<NTA>(p.A + (long)(k0 + t.krow) * p.lda + (m0 + pc * 8));
     }
 }
 
@@ -759,13 +770,13 @@ __device__ __forceinline__ void at_commit_rows(const TwGemmParams& p, const AReg
     }
 }
 
-template <int MS, int BATCH>
+template <int MS, int BATCH, bool NTA = true>
 __device__ __forceinline__ void load_at_block(const TwGemmParams& p, unsigned char* at, int m0, int k0, int kw, int wave,
                                               int lane, int tid) {
     const int tasks = at_tasks<MS>(kw);
     for (int t0 = wave; t0 < tasks; t0 += kWaves * BATCH) {
         ARegs<BATCH> ar;
-        at_issue<MS, BATCH>(p, ar, m0, k0, kw, t0, lane);
+        at_issue<MS, BATCH, NTA>(p, ar, m0, k0, kw, t0, lane);
         at_commit<MS, BATCH>(p, ar, at, kw, t0, lane);
     }
     a_zero_row(p, at, 32 * MS, tid);
@@ -779,7 +790,7 @@ __device__ __forceinline__ void load_at_block(const TwGemmParams& p, unsigned ch
 // 8 * (t % 8) .. + 7, columns 64 * (t / 8) .. + 63), but everything that does not depend on the lane is a
 // constant here: one or two row pointers per chunk, one LDS address, immediate offsets (the general code
 // spends about 75 instructions per request on its bookkeeping): 5 % on the FFN-down of BERT-base.
-template <int BATCH, int STRIDE>
+template <int BATCH, int STRIDE, bool NTA = true>
 __device__ __forceinline__ void a_issue_full(const TwGemmParams& p, ARegs<BATCH>& ar, int row0, int k0, int t0, int lane_in) {
     static_assert(STRIDE == 4 || STRIDE == 8, "waves that share a chunk");
     const int lane = fresh(lane_in);
@@ -794,7 +805,7 @@ __device__ __forceinline__ void a_issue_full(const TwGemmParams& p, ARegs<BATCH>
     }
 #pragma unroll
     for (int b = 0; b < BATCH; ++b)
-        ar.v[b] = tw_load16_stream(rp[((b * STRIDE) & 7) / STRIDE] + ((b * STRIDE) >> 3) * 64);
+        ar.v[b] = load_a16<NTA>(rp[((b * STRIDE) & 7) / STRIDE] + ((b * STRIDE) >> 3) * 64);
 }
 template <int BATCH, int STRIDE>
 __device__ __forceinline__ void a_commit_full(const ARegs<BATCH>& ar, unsigned char* at, int t0, int lane_in) {
@@ -811,15 +822,15 @@ __device__ __forceinline__ void a_commit_full(const ARegs<BATCH>& ar, unsigned c
     }
 }
 
-template <int MS, int BATCH, bool TRANS>
+template <int MS, int BATCH, bool TRANS, bool NTA = true>
 __device__ __forceinline__ void stage_issue(const TwGemmParams& p, ARegs<BATCH>& ar, int r0, int k0, int kw, int t0, int lane,
                                             int stride = kWaves) {
     if constexpr (TRANS) {
-        at_issue<MS, BATCH>(p, ar, r0, k0, kw, t0, lane, stride);
+        at_issue<MS, BATCH, NTA>(p, ar, r0, k0, kw, t0, lane, stride);
     } else {
         // (with four loading waves the written-out form measured no faster, 1.6 % slower on the conv workload)
-        if (MS == 2 && stride == 8 && kw == 64 * BATCH) a_issue_full<BATCH, 8>(p, ar, r0, k0, t0, lane);
-        else a_issue<MS, BATCH, kPairStream>(p, ar, r0, k0, kw, t0, lane, stride);
+        if (MS == 2 && stride == 8 && kw == 64 * BATCH) a_issue_full<BATCH, 8, NTA>(p, ar, r0, k0, t0, lane);
+        else a_issue<MS, BATCH, kPairStream, NTA>(p, ar, r0, k0, kw, t0, lane, stride);
     }
 }
 template <int MS, int BATCH, bool TRANS>
@@ -972,7 +983,7 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 //         (Six multiplying and two loading waves were tried for weights of five or six tiles: the two
 //         loading waves cannot keep up with the transposing LDS writes of the row-major boundary, 9 % slower
 //         than MODE 1 on the FFN-down of BERT-base, and no gain on the transposed boundary.)
-template <int DT, int MS, int NCB, int MODE, bool FUSED, bool TRANS>
+template <int DT, int MS, int NCB, int MODE, bool FUSED, bool TRANS, bool NTA = true>
 __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int MSB = MS;                       // 32-row blocks in the workgroup's row block
@@ -1092,7 +1103,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                         if (use_rows)
                             at_issue_rows<PB>(p, ar, r0, c * p.k_chunk, my_rows + c * kListEntries, uni(my_cnt[c]), lw, lane, NLD);
                         else
-                            stage_issue<MSB, PB, TRANS>(p, ar, r0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
+                            stage_issue<MSB, PB, TRANS, NTA>(p, ar, r0, c * p.k_chunk, chunk_width(c), lw, lane, NLD);
                     } else {
 #pragma unroll
                         for (int b = 0; b < PB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
@@ -1216,8 +1227,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             constexpr int AB = 6;    // requests per wave and chunk: 64 rows x 384 columns in 8 waves
             {
                 const int kw = p.K < p.k_chunk ? p.K : p.k_chunk;
-                if constexpr (TRANS) load_at_block<MSB, AB>(p, smem, row0, 0, kw, wave, lane, tid);
-                else load_a_block<MSB, AB, kPairStream>(p, smem, row0, 0, kw, wave, lane, tid);
+                if constexpr (TRANS) load_at_block<MSB, AB, NTA>(p, smem, row0, 0, kw, wave, lane, tid);
+                else load_a_block<MSB, AB, kPairStream, NTA>(p, smem, row0, 0, kw, wave, lane, tid);
                 a_zero_row(p, smem + p.abuf_bytes, BM, tid);
             }
             // Requests run kAhead chunks ahead of the steps: two where the registers allow it (narrow
@@ -1229,7 +1240,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             };
             auto issue_or_zero = [&](ARegs<AB>& ar, int c) {
                 if (c < p.n_chunks) {
-                    stage_issue<MSB, AB, TRANS>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
+                    stage_issue<MSB, AB, TRANS, NTA>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
                 } else {
 #pragma unroll
                     for (int b = 0; b < AB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
@@ -1323,45 +1334,46 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 // beside the host code (-DTW_PART=0), so that a build runs them in parallel; without TW_PART one unit holds
 // everything.  The tables hand out host-side kernel addresses, so no type of this file crosses a unit boundary.
 namespace tw_parts {
-template <int DT, bool FUSED> const void* pick_mode(int mode, int ms, int ncb);     // row-major boundary
-template <int DT, bool FUSED> const void* pick_mode_t(int mode, int ms, int ncb);   // transposed boundary
+// (nta: the streamed kernels' variant whose requests for activations carry the streaming hint)
+template <int DT, bool FUSED> const void* pick_mode(int mode, int ms, int ncb, bool nta);     // row-major boundary
+template <int DT, bool FUSED> const void* pick_mode_t(int mode, int ms, int ncb, bool nta);   // transposed boundary
 }  // namespace tw_parts
 
 #if !defined(TW_PART) || TW_PART != 0
 namespace {
-template <int DT, int MS, int MODE, bool FUSED, bool TRANS>
+template <int DT, int MS, int MODE, bool FUSED, bool TRANS, bool NTA = true>
 const void* pick_ncb(int ncb) {
     switch (ncb) {
-        case 1: return (const void*)tw_gemm_kernel<DT, MS, 1, MODE, FUSED, TRANS>;
-        case 2: return (const void*)tw_gemm_kernel<DT, MS, 2, MODE, FUSED, TRANS>;
-        case 4: return (const void*)tw_gemm_kernel<DT, MS, 4, MODE, FUSED, TRANS>;
+        case 1: return (const void*)tw_gemm_kernel<DT, MS, 1, MODE, FUSED, TRANS, NTA>;
+        case 2: return (const void*)tw_gemm_kernel<DT, MS, 2, MODE, FUSED, TRANS, NTA>;
+        case 4: return (const void*)tw_gemm_kernel<DT, MS, 4, MODE, FUSED, TRANS, NTA>;
         default: return nullptr;
     }
 }
 }  // namespace
 namespace tw_parts {
 template <int DT, bool FUSED>
-const void* pick_mode(int mode, int ms, int ncb) {
+const void* pick_mode(int mode, int ms, int ncb, bool nta) {
     if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, false>(ncb) : pick_ncb<DT, 1, 0, FUSED, false>(ncb);
     if (ms != 2) return nullptr;                  // the streamed kernels take 64-row blocks
-    if (mode == 1) return pick_ncb<DT, 2, 1, FUSED, false>(ncb);
-    return pick_ncb<DT, 2, 2, FUSED, false>(ncb);
+    if (mode == 1) return nta ? pick_ncb<DT, 2, 1, FUSED, false, true>(ncb) : pick_ncb<DT, 2, 1, FUSED, false, false>(ncb);
+    return nta ? pick_ncb<DT, 2, 2, FUSED, false, true>(ncb) : pick_ncb<DT, 2, 2, FUSED, false, false>(ncb);
 }
 // transposed boundary: resident K with blocks of 64 or 32 tokens, streamed K always with 64
 template <int DT, bool FUSED>
-const void* pick_mode_t(int mode, int ms, int ncb) {
+const void* pick_mode_t(int mode, int ms, int ncb, bool nta) {
     if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, true>(ncb) : pick_ncb<DT, 1, 0, FUSED, true>(ncb);
     if (ms != 2) return nullptr;
-    if (mode == 1) return pick_ncb<DT, 2, 1, FUSED, true>(ncb);
-    return pick_ncb<DT, 2, 2, FUSED, true>(ncb);
+    if (mode == 1) return nta ? pick_ncb<DT, 2, 1, FUSED, true, true>(ncb) : pick_ncb<DT, 2, 1, FUSED, true, false>(ncb);
+    return nta ? pick_ncb<DT, 2, 2, FUSED, true, true>(ncb) : pick_ncb<DT, 2, 2, FUSED, true, false>(ncb);
 }
 }  // namespace tw_parts
 #endif
 
 #ifdef TW_PART
 #define TW_TABLES(KW, DT, FUSED)                                            \
-    KW template const void* tw_parts::pick_mode<DT, FUSED>(int, int, int);  \
-    KW template const void* tw_parts::pick_mode_t<DT, FUSED>(int, int, int);
+    KW template const void* tw_parts::pick_mode<DT, FUSED>(int, int, int, bool);  \
+    KW template const void* tw_parts::pick_mode_t<DT, FUSED>(int, int, int, bool);
 #if TW_PART == 0
 TW_TABLES(extern, TW_F16, false) TW_TABLES(extern, TW_F16, true) TW_TABLES(extern, TW_BF16, false) TW_TABLES(extern, TW_BF16, true)
 #elif TW_PART == 1
@@ -1633,15 +1645,15 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
 }
 
 // the kernel for (dtype, mode, MS, NCB, fused epilogue): a host-side address for hipLaunchKernel and hipFuncSetAttribute
-const void* pick_kernel_t(int dt, int mode, int ms, int ncb, bool fused) {
+const void* pick_kernel_t(int dt, int mode, int ms, int ncb, bool fused, bool nta) {
     using namespace tw_parts;
-    if (fused) return dt == TW_F16 ? pick_mode_t<TW_F16, true>(mode, ms, ncb) : pick_mode_t<TW_BF16, true>(mode, ms, ncb);
-    return dt == TW_F16 ? pick_mode_t<TW_F16, false>(mode, ms, ncb) : pick_mode_t<TW_BF16, false>(mode, ms, ncb);
+    if (fused) return dt == TW_F16 ? pick_mode_t<TW_F16, true>(mode, ms, ncb, nta) : pick_mode_t<TW_BF16, true>(mode, ms, ncb, nta);
+    return dt == TW_F16 ? pick_mode_t<TW_F16, false>(mode, ms, ncb, nta) : pick_mode_t<TW_BF16, false>(mode, ms, ncb, nta);
 }
-const void* pick_kernel(int dt, int mode, int ms, int ncb, bool fused) {
+const void* pick_kernel(int dt, int mode, int ms, int ncb, bool fused, bool nta) {
     using namespace tw_parts;
-    if (fused) return dt == TW_F16 ? pick_mode<TW_F16, true>(mode, ms, ncb) : pick_mode<TW_BF16, true>(mode, ms, ncb);
-    return dt == TW_F16 ? pick_mode<TW_F16, false>(mode, ms, ncb) : pick_mode<TW_BF16, false>(mode, ms, ncb);
+    if (fused) return dt == TW_F16 ? pick_mode<TW_F16, true>(mode, ms, ncb, nta) : pick_mode<TW_BF16, true>(mode, ms, ncb, nta);
+    return dt == TW_F16 ? pick_mode<TW_F16, false>(mode, ms, ncb, nta) : pick_mode<TW_BF16, false>(mode, ms, ncb, nta);
 }
 
 // Per-device facts looked up once (the entries are written with the same value by every thread
@@ -1664,7 +1676,7 @@ int device_cus(int dev) {
 }
 
 // The dynamic-LDS limit of a kernel is raised to the hardware maximum once per (device, kernel).
-constexpr int kMaxKernels = 128;
+constexpr int kMaxKernels = 256;
 std::atomic<unsigned> g_lds_set[kMaxDevices][kMaxKernels];
 
 int ensure_lds(int dev, int kernel_id, const void* fn) {
@@ -1808,10 +1820,12 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     int rc = make_plan(h, M, n_cu, pl);
     if (rc) return rc;
     const bool fused = bias != nullptr || act != TW_ACT_NONE;
-    const void* fn = pick_kernel(h->dtype, pl.mode, pl.ms, h->ncb, fused);
+    // streamed K: the activations carry the streaming hint only when one workgroup reads a row block's rows
+    const bool nta = pl.mode == 0 || pl.n_seg == 1;
+    const void* fn = pick_kernel(h->dtype, pl.mode, pl.ms, h->ncb, fused, nta);
     if (!fn) return TW_ERR_UNSUPPORTED;
-    const int variant = pl.mode == 2 ? 4 : 2 * pl.mode + (pl.ms == 2 ? 0 : 1);      // 0, 1, 2, 4
-    const int kernel_id = (fused ? 30 : 0) + (h->dtype == TW_F16 ? 0 : 15) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
+    const int variant = pl.mode == 0 ? (pl.ms == 2 ? 0 : 1) : 2 * pl.mode + (nta ? 0 : 1);   // 0..5
+    const int kernel_id = (fused ? 60 : 0) + (h->dtype == TW_F16 ? 0 : 30) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, fn);
     if (rc) return rc;
 
@@ -1884,10 +1898,11 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     Plan pl;
     int rc = make_plan(h, M, n_cu, pl, /*transposed=*/true);
     if (rc) return rc;
-    const void* fn = pick_kernel_t(h->dtype, pl.mode, pl.ms, h->ncb, fused);
+    const bool nta = pl.mode == 0 || pl.n_seg == 1;
+    const void* fn = pick_kernel_t(h->dtype, pl.mode, pl.ms, h->ncb, fused, nta);
     if (!fn) return TW_ERR_UNSUPPORTED;
-    const int variant = pl.mode == 0 ? (pl.ms == 2 ? 0 : 1) : pl.mode + 1;          // 0..3
-    const int kernel_id = 60 + (fused ? 24 : 0) + (h->dtype == TW_F16 ? 0 : 12) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
+    const int variant = pl.mode == 0 ? (pl.ms == 2 ? 0 : 1) : 2 * pl.mode + (nta ? 0 : 1);   // 0..5
+    const int kernel_id = 120 + (fused ? 60 : 0) + (h->dtype == TW_F16 ? 0 : 30) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, fn);
     if (rc) return rc;
 
