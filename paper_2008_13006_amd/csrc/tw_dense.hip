@@ -49,9 +49,13 @@ struct Staged {
     tw_u32x4 b[4];
 };
 
+template <bool NT = false>
 __device__ __forceinline__ tw_u32x4 load8_guard(const unsigned short* p, int valid) {
     // valid >= 8: one 16-byte load; 0 < valid < 8: element-wise, zero filled; <= 0: zeros
-    if (valid >= 8) return *(const tw_u32x4*)p;
+    if (valid >= 8) {
+        if constexpr (NT) return tw_load16_stream(p);
+        else return *(const tw_u32x4*)p;
+    }
     unsigned short e[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) e[i] = i < valid ? p[i] : (unsigned short)0;
@@ -59,7 +63,8 @@ __device__ __forceinline__ tw_u32x4 load8_guard(const unsigned short* p, int val
                     e[6] | ((unsigned)e[7] << 16)};
 }
 
-template <int MSW>
+// NTA: the activations are read by one column of blocks only (N <= 256), so they carry the streaming hint
+template <int MSW, bool NTA>
 __device__ __forceinline__ void global_fetch(const DenseParams& p, int m0, int n0, int k0, int tid, Staged<MSW>& st) {
     // A tile: 64 * MSW rows x 8 pieces of 16 B; thread handles pieces id = tid + 512*i
 #pragma unroll
@@ -69,7 +74,7 @@ __device__ __forceinline__ void global_fetch(const DenseParams& p, int m0, int n
         int gm = m0 + r;
         gm = gm < p.M ? gm : p.M - 1;
         const int k = k0 + u * 8;
-        st.a[i] = load8_guard(p.A + (long)gm * p.lda + k, p.K - k);
+        st.a[i] = load8_guard<NTA>(p.A + (long)gm * p.lda + k, p.K - k);
     }
     // B tile: 64 rows x 32 pieces
 #pragma unroll
@@ -100,7 +105,7 @@ __device__ __forceinline__ void lds_commit(unsigned char* buf, int tid, const St
     }
 }
 
-template <int DT, int MSW>
+template <int DT, int MSW, bool NTA>
 __global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p) {
     constexpr int BM = bm_of<MSW>(), A_BYTES = a_bytes_of<MSW>(), BUF_BYTES = buf_bytes_of<MSW>();
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p)
 
     const int nk = (p.K + KB - 1) / KB;
     Staged<MSW> st;
-    global_fetch(p, m0, n0, 0, tid, st);
+    global_fetch<MSW, NTA>(p, m0, n0, 0, tid, st);
     lds_commit(smem, tid, st);
     __syncthreads();
 
@@ -135,7 +140,7 @@ __global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p)
         unsigned char* cur = smem + (kt & 1) * BUF_BYTES;
         unsigned char* nxt = smem + ((kt + 1) & 1) * BUF_BYTES;
         const bool more = kt + 1 < nk;
-        if (more) global_fetch(p, m0, n0, (kt + 1) * KB, tid, st);
+        if (more) global_fetch<MSW, NTA>(p, m0, n0, (kt + 1) * KB, tid, st);
 
         const unsigned char* la = cur + (wm * 32 * MSW + l32) * A_PITCH + h * 16;
         // weight operand by transposing reads of the row-major (K-major) B tile: in each 16-lane block,
@@ -177,6 +182,12 @@ __global__ __launch_bounds__(kThreads) void tw_dense_kernel(const DenseParams p)
             tw_store_block<DT, 2>(acc[ms], stage, p.C, p.ldc, m0 + wm * 32 * MSW + ms * 32, p.M, col0, width, lane,
                                   p.bias, p.act, p.stream != 0);
     }
+}
+
+template <int MSW>
+const void* pick(tw_dtype dt, bool nta) {
+    if (dt == TW_F16) return nta ? (const void*)tw_dense_kernel<TW_F16, MSW, true> : (const void*)tw_dense_kernel<TW_F16, MSW, false>;
+    return nta ? (const void*)tw_dense_kernel<TW_BF16, MSW, true> : (const void*)tw_dense_kernel<TW_BF16, MSW, false>;
 }
 
 }  // namespace
@@ -227,13 +238,15 @@ extern "C" int tw_dense_gemm_bias_act(const void* A, int lda, const void* B, int
     if (blocks > 0x7fffffffL) return TW_ERR_UNSUPPORTED;
     const void* fn;
     int lds;
-    if (msw == 4) { fn = dt == TW_F16 ? (const void*)tw_dense_kernel<TW_F16, 4> : (const void*)tw_dense_kernel<TW_BF16, 4>; lds = lds_bytes_of<4>(); }
-    else if (msw == 2) { fn = dt == TW_F16 ? (const void*)tw_dense_kernel<TW_F16, 2> : (const void*)tw_dense_kernel<TW_BF16, 2>; lds = lds_bytes_of<2>(); }
-    else { fn = dt == TW_F16 ? (const void*)tw_dense_kernel<TW_F16, 1> : (const void*)tw_dense_kernel<TW_BF16, 1>; lds = lds_bytes_of<1>(); }
-    static std::atomic<unsigned char> lds_set[64][2][5];
-    if (!lds_set[dev][dt][msw].load(std::memory_order_acquire)) {
+    const bool nta = p.nbn == 1;
+    if (msw == 4) { fn = pick<4>(dt, nta); lds = lds_bytes_of<4>(); }
+    else if (msw == 2) { fn = pick<2>(dt, nta); lds = lds_bytes_of<2>(); }
+    else { fn = pick<1>(dt, nta); lds = lds_bytes_of<1>(); }
+    static std::atomic<unsigned char> lds_set[64][2][10];
+    const int slot = 2 * msw + (nta ? 1 : 0);
+    if (!lds_set[dev][dt][slot].load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return TW_ERR_HIP;
-        lds_set[dev][dt][msw].store(1, std::memory_order_release);
+        lds_set[dev][dt][slot].store(1, std::memory_order_release);
     }
     void* args[] = {(void*)&p};
     return hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(kThreads), args, lds, (hipStream_t)hip_stream) == hipSuccess

@@ -1950,7 +1950,7 @@ __global__ __launch_bounds__(256) void tw_transpose_kernel(const unsigned short*
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int r = (t >> 3) + 32 * i;
-            const tw_u32x4 v = *(const tw_u32x4*)(src + (long)(r0 + r) * lds_ + c0 + 8 * j);
+            const tw_u32x4 v = tw_load16_stream(src + (long)(r0 + r) * lds_ + c0 + 8 * j);   // read once, written once
             const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -1960,7 +1960,9 @@ __global__ __launch_bounds__(256) void tw_transpose_kernel(const unsigned short*
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = (t >> 3) + 32 * i;
-            *(tw_u32x4*)(dst + (long)(c0 + c) * ldd + r0 + 8 * j) = *(const tw_u32x4*)(tile + c * kPitch + j * 16);
+            // (rows of dst on 128-byte boundaries: the eight lanes of a row write a whole line)
+            if (vec == 2) tw_store16_stream(dst + (long)(c0 + c) * ldd + r0 + 8 * j, *(const tw_u32x4*)(tile + c * kPitch + j * 16));
+            else *(tw_u32x4*)tw_opaque(dst + (long)(c0 + c) * ldd + r0 + 8 * j) = *(const tw_u32x4*)(tile + c * kPitch + j * 16);
         }
         return;
     }
@@ -1980,7 +1982,8 @@ extern "C" int tw_transpose(const void* src, int ld_src, int rows, int cols, voi
     if (rows == 0 || cols == 0) return TW_OK;
     const long gx = ((long)cols + 63) / 64, gy = ((long)rows + 63) / 64;
     if (gy > 65535) return TW_ERR_UNSUPPORTED;
-    const int vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0 && (ld_src & 7) == 0 && (ld_dst & 7) == 0;
+    int vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0 && (ld_src & 7) == 0 && (ld_dst & 7) == 0;
+    if (vec && ((uintptr_t)dst & 127) == 0 && (ld_dst & 63) == 0) vec = 2;
     const unsigned short* s_ = (const unsigned short*)src;
     unsigned short* d_ = (unsigned short*)dst;
     long lds2 = ld_src, ldd2 = ld_dst;
