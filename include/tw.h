@@ -134,9 +134,12 @@ int tw_prune(const void* B, int ldb, int K, int N, int G, tw_dtype dt, double co
 
 /* ---- device side ---- */
 
-/* Bytes of device workspace tw_gemm needs for M rows (scheduler counters).  The workspace must be
- * zero before its first use; tw_gemm leaves it zero when the enqueued work has finished, so one
- * zeroed buffer serves any number of calls that do not overlap in time. */
+/* Bytes of device workspace tw_gemm and tw_gemm_t want for M rows: 256 bytes of scheduler counters and, where
+ * the plan for the current GPU splits K (see tw_plan_t.k_parts), the parts' fp32 results behind them.  Only the
+ * first 256 bytes are required: with less than the full size the product runs unsplit (slower for few rows and
+ * a long K, never wrong).  The first 256 bytes must be zero before the first use; tw_gemm leaves them zero when
+ * the enqueued work has finished, so one buffer serves any number of calls that do not overlap in time.  The
+ * rest needs no initialisation. */
 int tw_gemm_workspace(const void* blob_host, int M, size_t* ws_bytes);
 
 /* How tw_gemm (transposed = 0) or tw_gemm_t (transposed != 0) would run this weight on M rows (tokens) on a GPU
@@ -155,7 +158,12 @@ typedef struct tw_plan_t {
     int32_t grid;            /* workgroups launched: min(n_items, n_cu), each pulls items until none is left */
     uint32_t lds_bytes;      /* on-chip memory per workgroup */
     int32_t row_lists;       /* tw_gemm_t, mode 2: the loading waves read only the K rows that the tiles keep */
-    int32_t reserved[7];
+    int32_t k_parts;         /* streamed K, few row blocks: the K chunks are split into this many parts, each a work item
+                                of its own (n_items = n_row_blocks * n_sets * k_parts) whose fp32 results go to the
+                                workspace; a second kernel adds them in the order of the parts.  1: no split.  (What
+                                tw_gemm does with a workspace of tw_gemm_workspace bytes; with a smaller one it
+                                does not split.) */
+    int32_t reserved[6];
 } tw_plan_t;
 /* Errors: TW_ERR_ARG (null pointer, negative M, n_cu <= 0), TW_ERR_BUF (not a blob of this format version),
  * TW_ERR_UNSUPPORTED (what tw_gemm / tw_gemm_t would refuse for this blob and M).  M = 0 or a blob without
@@ -173,8 +181,8 @@ int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transposed, tw_plan
  *              columns); 2-byte aligned rows suffice
  *   workspace  device, >= tw_gemm_workspace bytes, 256-byte aligned, zeroed as described above
  * M >= 0 (M = 0 enqueues nothing).  Calls on one workspace must not overlap in time (use one
- * workspace per stream).  The call enqueues kernels only (one; two for a TEW blob with residual weights in
- * pruned columns) (no memset, no copy, no allocation), so it can be
+ * workspace per stream).  The call enqueues kernels only (one; one more for a split-K plan, one more for a TEW
+ * blob with residual weights in pruned columns) (no memset, no copy, no allocation), so it can be
  * recorded into a HIP graph; the first call that uses a kernel variant on a device raises that kernel's
  * dynamic-LDS limit (a function attribute), so make one call of each kind before a stream capture.  The best speed needs a C base and ldc that are multiples of 64 elements
  * (128-byte lines); any other layout is correct and slower.
@@ -185,15 +193,17 @@ int tw_gemm(const void* blob_host, const void* blob_dev, const void* A, int M, i
             void* C, int ldc, void* workspace, size_t ws_bytes, void* hip_stream);
 
 /* tw_gemm for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
- * capture, tight serving loops, harnesses that forbid hipMalloc.  The scheduler's counters (the scratch memory
- * that tw_gemm takes from the caller's workspace) live in a device array inside the library instead,
- * TW_STATIC_SCRATCH_BYTES per GPU, held until the process ends; the call allocates nothing and frees nothing.
- * It enqueues a one-workgroup kernel that zeroes the counters, then what tw_gemm enqueues.  All calls on one
- * GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads) race and give
- * wrong results; calls on one stream, one after the other, are fine.  Arguments and results as tw_gemm;
- * TW_ERR_UNSUPPORTED if the blob and M need more scratch than the array holds (tw_gemm_workspace says how
- * much; today 256 bytes for every blob and M), TW_ERR_HIP if the array's address cannot be obtained. */
-#define TW_STATIC_SCRATCH_BYTES 4096
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch memory that tw_gemm takes from the
+ * caller's workspace (the scheduler's counters and, for few rows and a long K, the fp32 partial results of a
+ * split-K plan) lives in a device array inside the library instead, TW_STATIC_SCRATCH_BYTES per GPU, held until
+ * the process ends; the call allocates nothing and frees nothing.  It enqueues a one-workgroup kernel that
+ * zeroes the counters, then what tw_gemm enqueues for a workspace of that size: no blob and no M need more than
+ * the counters, and a split-K plan is taken only when its partial results fit the array (tw_gemm_plan's k_parts
+ * is for a workspace of tw_gemm_workspace bytes; with less the product runs with fewer parts or unsplit, never
+ * out of bounds).  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race and give wrong results; calls on one stream, one after the other, are fine.
+ * Arguments, results and errors as tw_gemm; TW_ERR_HIP also if the array's address cannot be obtained. */
+#define TW_STATIC_SCRATCH_BYTES (8u << 20)
 int tw_gemm_static(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
                    void* C, int ldc, void* hip_stream);
 

@@ -23,6 +23,7 @@ SYMBOLS = ["tw_pack_size", "tw_pack", "tw_pack_tew_size", "tw_pack_tew", "tw_res
            "tw_gemm_bias_act", "tw_gemm_t", "tw_gemm_t_bias_act", "tw_transpose", "tw_dense_gemm", "tw_dense_gemm_bias_act", "tw_strerror",
            "tw_version"]
 TW_ACT_NONE, TW_ACT_RELU, TW_ACT_GELU = 0, 1, 2
+TW_STATIC_SCRATCH_BYTES = 8 << 20   # include/tw.h
 _ACT = {None: TW_ACT_NONE, "none": TW_ACT_NONE, "relu": TW_ACT_RELU, "gelu": TW_ACT_GELU}
 
 
@@ -47,7 +48,7 @@ class TwPlan(ctypes.Structure):
     _fields_ = [("mode", ctypes.c_int32), ("rows_per_block", ctypes.c_int32), ("tiles_per_set", ctypes.c_int32),
                 ("n_row_blocks", ctypes.c_int32), ("n_sets", ctypes.c_int32), ("n_items", ctypes.c_int32),
                 ("grid", ctypes.c_int32), ("lds_bytes", ctypes.c_uint32), ("row_lists", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 7)]
+                ("k_parts", ctypes.c_int32), ("reserved", ctypes.c_int32 * 6)]
 
 
 def _load() -> ctypes.CDLL:
@@ -240,7 +241,20 @@ class TwWeight:
         self.dtype = "f16" if self.info["dtype"] == TW_F16 else "bf16"
         self.blob_dev = torch.from_numpy(blob).to(device)
         assert self.blob_dev.data_ptr() % 256 == 0
-        self.workspace = torch.zeros(max(256, tw_gemm_workspace(blob, 1)), dtype=torch.uint8, device=device)
+        self.workspace = torch.zeros(256, dtype=torch.uint8, device=device)
+        self.ws_limit = None        # bytes of workspace handed to the library at most (None: what it asks for)
+        self._retired = []          # outgrown workspaces: kept, kernels already enqueued may still use them
+
+    def workspace_for(self, M: int):
+        """(pointer, bytes) of a zero-initialised workspace of the size the library wants for M rows."""
+        need = max(256, tw_gemm_workspace(self.blob, M))
+        if self.ws_limit is not None:
+            need = max(256, min(need, int(self.ws_limit)))
+        if need > self.workspace.numel():
+            torch = _torch()
+            self._retired.append(self.workspace)
+            self.workspace = torch.zeros(need, dtype=torch.uint8, device=self.workspace.device)
+        return ctypes.c_void_p(self.workspace.data_ptr()), need
 
     @classmethod
     def from_dense(cls, B_bits: np.ndarray, mask: np.ndarray, G: int, dtype: str, device="cuda:0"):
@@ -259,15 +273,15 @@ def tw_gemm(w: TwWeight, A, C=None, stream=None):
     assert C.is_cuda and C.dtype == A.dtype and C.shape == (M, N) and C.stride(1) == 1
     lda = A.stride(0) if M > 1 else max(K, A.stride(0))
     ldc = C.stride(0) if M > 1 else max(N, C.stride(0))
+    ws, ws_bytes = w.workspace_for(M)
     _check(_lib.tw_gemm(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()), ctypes.c_void_p(A.data_ptr()),
-                        M, lda, ctypes.c_void_p(C.data_ptr()), ldc, ctypes.c_void_p(w.workspace.data_ptr()),
-                        w.workspace.numel(), _stream_ptr(stream)), "tw_gemm")
+                        M, lda, ctypes.c_void_p(C.data_ptr()), ldc, ws, ws_bytes, _stream_ptr(stream)), "tw_gemm")
     return C
 
 
 def tw_gemm_static(w: TwWeight, A, C, stream=None):
     """tw_gemm without a workspace and without any allocation: the library's own per-GPU scratch array holds the
-    scheduler's counters.  C must be given (the caller owns every buffer).  Calls must not overlap on one GPU."""
+    scheduler's counters and the partial results of a split-K plan.  C must be given (the caller owns every buffer).  Calls must not overlap on one GPU."""
     assert A.is_cuda and A.dtype == _tdtype(w.dtype) and A.dim() == 2 and A.stride(1) == 1
     M, K = A.shape
     N = w.info["N"]
@@ -302,15 +316,15 @@ def tw_gemm_t_bias_act(w: TwWeight, At, bias=None, act="none", Ct=None, stream=N
     if bias is not None:
         assert bias.is_cuda and bias.dtype == At.dtype and bias.shape == (N,) and bias.stride(0) == 1
         bptr = ctypes.c_void_p(bias.data_ptr())
+    ws, ws_bytes = w.workspace_for(M)
     if bias is None and _act_code(act) == TW_ACT_NONE:
         _check(_lib.tw_gemm_t(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()), ctypes.c_void_p(At.data_ptr()),
-                              M, ldat, ctypes.c_void_p(Ct.data_ptr()), ldct, ctypes.c_void_p(w.workspace.data_ptr()),
-                              w.workspace.numel(), _stream_ptr(stream)), "tw_gemm_t")
+                              M, ldat, ctypes.c_void_p(Ct.data_ptr()), ldct, ws, ws_bytes, _stream_ptr(stream)), "tw_gemm_t")
     else:
         _check(_lib.tw_gemm_t_bias_act(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()),
                                        ctypes.c_void_p(At.data_ptr()), M, ldat, bptr, _act_code(act),
-                                       ctypes.c_void_p(Ct.data_ptr()), ldct, ctypes.c_void_p(w.workspace.data_ptr()),
-                                       w.workspace.numel(), _stream_ptr(stream)), "tw_gemm_t_bias_act")
+                                       ctypes.c_void_p(Ct.data_ptr()), ldct, ws, ws_bytes, _stream_ptr(stream)),
+               "tw_gemm_t_bias_act")
     return Ct
 
 
@@ -354,10 +368,10 @@ def tw_gemm_bias_act(w: TwWeight, A, bias=None, act="none", C=None, stream=None)
         bptr = ctypes.c_void_p(bias.data_ptr())
     lda = A.stride(0) if M > 1 else max(K, A.stride(0))
     ldc = C.stride(0) if M > 1 else max(N, C.stride(0))
+    ws, ws_bytes = w.workspace_for(M)
     _check(_lib.tw_gemm_bias_act(_np_ptr(w.blob), ctypes.c_void_p(w.blob_dev.data_ptr()),
                                  ctypes.c_void_p(A.data_ptr()), M, lda, bptr, _act_code(act),
-                                 ctypes.c_void_p(C.data_ptr()), ldc, ctypes.c_void_p(w.workspace.data_ptr()),
-                                 w.workspace.numel(), _stream_ptr(stream)), "tw_gemm_bias_act")
+                                 ctypes.c_void_p(C.data_ptr()), ldc, ws, ws_bytes, _stream_ptr(stream)), "tw_gemm_bias_act")
     return C
 
 

@@ -71,6 +71,12 @@ struct TwGemmParams {
     int stream_stores;          // rows of the output start on 128-byte boundaries: stores that complete whole lines
                                 // may carry the streaming hint
     unsigned urow_off;          // LDS offset of the loading waves' row lists (transposed, streamed K, few tiles), 0: none
+    // split K (streamed K, wave per tile, few row blocks): the K chunks are cut into n_parts runs of chunks_per_part
+    // and an item is (part, tile set, row block); the tiles' fp32 results go to `partials`
+    // ([part][row block][tile in dispatch order][MS][NCB][4 register groups][64 lanes][4]) and
+    // tw_splitk_reduce_kernel adds them up in the order of the parts and stores C.  n_parts = 1: no split.
+    int n_parts, chunks_per_part;
+    float* partials;
 };
 
 __device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -488,7 +494,10 @@ __device__ __forceinline__ void apply_bias_act(tw_f32x16 (&acc)[MS][NCB], const 
 template <int DT, int MS, int NCB, bool FUSED>
 __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
                                            unsigned char* stage, const unsigned (&dpos)[NCB], int row0, int lane_in,
-                                           const unsigned char* at_resident = nullptr, unsigned short* xbuf = nullptr) {
+                                           const unsigned char* at_resident = nullptr, unsigned short* xbuf = nullptr,
+                                           int pass0 = 0, int pass1 = 4 * MS) {
+    // (pass0, pass1: the passes to run, each eight rows of the block; everything by default.  The second kernel
+    // of a split-K product gives a wave one pass of a tile.)
     const int lane = fresh(lane_in);
     constexpr bool fused = FUSED;
     // Residual-only columns of a TEW blob inside this tile's span (Sec. IV-A "Hybrid Pattern": weights restored in a
@@ -646,10 +655,13 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
             }
         }
         tw_compiler_fence();
-        write_pass(0);
+#pragma unroll
+        for (int P = 0; P < NP; ++P)
+            if (P == pass0) write_pass(P);
         tw_compiler_fence();
 #pragma unroll
         for (int P = 0; P < NP; ++P) {
+            if (P < pass0 || P >= pass1) continue;               // wave-uniform
             tw_i16x4 lo[kWinLines], hi[kWinLines];
 #pragma unroll
             for (int l = 0; l < kWinLines; ++l) {
@@ -659,7 +671,7 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
             const unsigned short eF = *(const unsigned short*)ragF;
             const unsigned short eL = *(const unsigned short*)ragL;
             tw_compiler_fence();
-            if (P + 1 < NP) write_pass(P + 1);
+            if (P + 1 < NP && P + 1 < pass1) write_pass(P + 1);
             tw_compiler_fence();
 #pragma unroll
             for (int l = 0; l < kWinLines; ++l) {
@@ -683,7 +695,7 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
     }
 }
 
-// ---- Transposed boundary (MODE 3): At is K x M, Ct is N x M (Sec. VI "Memory Accesses Coalescing") ----
+// ---- Transposed boundary (TRANS): At is K x M, Ct is N x M (Sec. VI "Memory Accesses Coalescing") ----
 // With the activations stored transposed, a K row of the workgroup's block is 128 contiguous bytes in
 // global memory and goes to its LDS row as it is: the LDS copy needs no transposition, and skipping a
 // pruned K position skips a row, which is what the paper changes the layout for.  A tile's results are
@@ -853,7 +865,10 @@ __device__ __forceinline__ void stage_commit(const TwGemmParams& p, const ARegs<
 // packer's list.
 template <int DT, int MS, int NCB, bool FUSED>
 __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
-                                             unsigned char* stage, const unsigned (&dpos)[NCB], int m0, int lane_in) {
+                                             unsigned char* stage, const unsigned (&dpos)[NCB], int m0, int lane_in,
+                                             int cb0 = 0, int cb1 = NCB) {
+    // (cb0, cb1: the column blocks to store, all by default; the lines of zeros go with column block 0.  The
+    // second kernel of a split-K product gives a wave one column block of a tile.)
     constexpr int PPR = 4 * MS, RPI = 64 / PPR, PITCH = 64 * MS + 8;
     static_assert(32 * PITCH <= (int)kStageBytes, "transposed staging fits the wave's area");
     const int lane = fresh(lane_in);
@@ -886,6 +901,7 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
     };
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
+        if (cb < cb0 || cb >= cb1) continue;                     // wave-uniform
         tw_compiler_fence();
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms)
@@ -907,6 +923,7 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
         }
     }
     tw_compiler_fence();
+    if (cb0 != 0) return;
     // lines of zeros for the pruned columns of the span
     const int* zp = (const int*)(p.blob + p.off_zero_ptr);
     const int* zc = (const int*)(p.blob + p.off_zero_cols);
@@ -983,6 +1000,27 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 //         (Six multiplying and two loading waves were tried for weights of five or six tiles: the two
 //         loading waves cannot keep up with the transposing LDS writes of the row-major boundary, 9 % slower
 //         than MODE 1 on the FFN-down of BERT-base, and no gain on the transposed boundary.)
+// Split K: a wave's fp32 results of its part of the K chunks, as they lie in the registers: piece (ms, cb, q) of
+// lane l (registers 4q .. 4q+3 of acc[ms][cb]) at float offset (((ms * NCB + cb) * 4 + q) * 64 + l) * 4, so that
+// every instruction writes (reads) 1 KB of consecutive memory.  32 KB per tile and part with 128-column tiles.
+typedef float tw_f32x4 __attribute__((ext_vector_type(4)));
+template <int MS, int NCB>
+__device__ __forceinline__ void dump_partial(float* dst, const tw_f32x16 (&acc)[MS][NCB], int lane) {
+    // dst is wave-uniform: said to the compiler, the 32 stores share one vector offset (the lane's) on a scalar
+    // base instead of holding a vector address for every 4 KB of the range
+    const uint64_t a = (uint64_t)dst;
+    unsigned char* base = (unsigned char*)(((uint64_t)(unsigned)uni((int)(a >> 32)) << 32) | (unsigned)uni((int)(unsigned)a));
+    const unsigned voff = (unsigned)lane * 16u;
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(tw_f32x4*)(base + ((ms * NCB + cb) * 4 + q) * 1024 + voff) =
+                    tw_f32x4{acc[ms][cb][4 * q], acc[ms][cb][4 * q + 1], acc[ms][cb][4 * q + 2], acc[ms][cb][4 * q + 3]};
+}
+
 template <int DT, int MS, int NCB, int MODE, bool FUSED, bool TRANS, bool NTA = true>
 __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -1207,14 +1245,46 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             }
         } else {
             // K is streamed in chunks through two LDS buffers: the requests for chunk c+1 go out before
-            // the steps of chunk c and are written to the other buffer after them, one barrier per chunk
-            const int set = item / p.n_mblocks, mb = item - set * p.n_mblocks;
+            // the steps of chunk c and are written to the other buffer after them, one barrier per chunk.
+            // Split K (MODE 3, few row blocks): the item also names a part of the chunks, [c_first, c_first + n_loc),
+            // and a set may have fewer than eight tiles (the other waves then only bring in A); the tiles' fp32
+            // results go to the workspace and a second kernel adds the parts up.  A kernel variant of its own, so
+            // that the unsplit kernel carries none of this.
+            constexpr bool SPLIT = MODE == 3;
+            const int sp_item = item / p.n_mblocks, mb = item - sp_item * p.n_mblocks;
+            const int part = SPLIT ? sp_item / p.n_seg : 0, set = sp_item - part * p.n_seg;
+            const int c_first = SPLIT ? part * p.chunks_per_part : 0;
+            const int n_loc = !SPLIT ? p.n_chunks
+                              : (p.n_chunks - c_first) < p.chunks_per_part ? (p.n_chunks - c_first) : p.chunks_per_part;
             const int row0 = mb * p.row_step;
-            const int ti = set * kWaves + wave;
-            const bool active = ti < p.T;
+            const int ti = set * (SPLIT ? p.tiles_per_set : kWaves) + wave;
+            const bool active = (!SPLIT || wave < p.tiles_per_set) && ti < p.T;
             const TileU d = fetch_tile(p, active ? ti : 0);
-            unsigned dpos[NCB];
+            constexpr int AB = 6;    // requests per wave and chunk: 64 rows x 384 columns in 8 waves
+            // (chunk j of the item is chunk c_first + j of K and lives in LDS buffer j % 2)
+            auto chunk_width = [&](int j) {
+                const int k0 = (c_first + j) * p.k_chunk;
+                return (p.K - k0) < p.k_chunk ? (p.K - k0) : p.k_chunk;
+            };
+            auto issue_or_zero = [&](ARegs<AB>& ar, int j) {
+                if (j < n_loc) {
+                    stage_issue<MSB, AB, TRANS, NTA>(p, ar, row0, (c_first + j) * p.k_chunk, chunk_width(j), wave, lane);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < AB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
+                }
+            };
+            auto commit = [&](const ARegs<AB>& ar, int j) {
+                if (j < n_loc) stage_commit<MSB, AB, TRANS>(p, ar, smem + (j & 1) * p.abuf_bytes, chunk_width(j), wave, lane);
+            };
             {
+                const int kw = chunk_width(0);
+                if constexpr (TRANS) load_at_block<MSB, AB, NTA>(p, smem, row0, c_first * p.k_chunk, kw, wave, lane, tid);
+                else load_a_block<MSB, AB, kPairStream, NTA>(p, smem, row0, c_first * p.k_chunk, kw, wave, lane, tid);
+                a_zero_row(p, smem + p.abuf_bytes, BM, tid);
+            }
+            unsigned dpos[NCB];
+            if constexpr (!SPLIT) {
                 const unsigned* dp = (const unsigned*)(p.blob + p.off_dpos) + ((long)d.tile * 32 + (lane & 31)) * NCB;
 #pragma unroll
                 for (int cb = 0; cb < NCB; ++cb) dpos[cb] = dp[cb];
@@ -1224,30 +1294,12 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             const int* sp = step_ptr + d.step_ptr;
             const unsigned char* gt = p.blob + p.off_goff + (long)d.first_step * 32;
             const unsigned char* bt = p.blob + p.off_bvals + (long)d.first_step * NCB * 1024;
-            constexpr int AB = 6;    // requests per wave and chunk: 64 rows x 384 columns in 8 waves
-            {
-                const int kw = p.K < p.k_chunk ? p.K : p.k_chunk;
-                if constexpr (TRANS) load_at_block<MSB, AB, NTA>(p, smem, row0, 0, kw, wave, lane, tid);
-                else load_a_block<MSB, AB, kPairStream, NTA>(p, smem, row0, 0, kw, wave, lane, tid);
-                a_zero_row(p, smem + p.abuf_bytes, BM, tid);
-            }
             // Requests run kAhead chunks ahead of the steps: two where the registers allow it (narrow
             // tiles), so that a chunk is always on its way from memory, else one.
             constexpr int kAhead = (MS * NCB <= 4) ? 2 : 1;
-            auto chunk_width = [&](int c) {
-                const int k0 = c * p.k_chunk;
-                return (p.K - k0) < p.k_chunk ? (p.K - k0) : p.k_chunk;
-            };
-            auto issue_or_zero = [&](ARegs<AB>& ar, int c) {
-                if (c < p.n_chunks) {
-                    stage_issue<MSB, AB, TRANS, NTA>(p, ar, row0, c * p.k_chunk, chunk_width(c), wave, lane);
-                } else {
-#pragma unroll
-                    for (int b = 0; b < AB; ++b) ar.v[b] = tw_u32x4{0u, 0u, 0u, 0u};   // defined on every path
-                }
-            };
             // first steps of chunk c (b0), c+1 (b1) and c+2 (b2), read one chunk ahead with scalar loads
-            int b0 = fetch_int(sp, 0), b1 = fetch_int(sp, 1), b2 = fetch_int(sp, p.n_chunks < 2 ? p.n_chunks : 2);
+            int b0 = fetch_int(sp, c_first), b1 = fetch_int(sp, c_first + 1),
+                b2 = fetch_int(sp, c_first + 2 < p.n_chunks ? c_first + 2 : p.n_chunks);
             // the first steps of a chunk are requested at the end of the previous chunk's steps, so they arrive
             // while the chunk after it is written to LDS and the workgroup meets at the barrier
             StepRegs<NCB> rg;
@@ -1263,25 +1315,23 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                         for (int cb = 0; cb < NCB; ++cb) rg.bq[i][cb] = tw_u16x8{0, 0, 0, 0, 0, 0, 0, 0};
                 }
             };
-            auto steps_of = [&](int c) {
+            auto steps_of = [&](int j) {
+                const int c = c_first + j;
                 if (active && b0 < b1)
-                    run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
-                if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
+                    run_steps<DT, MS, NCB>(acc, rg, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
+                if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
                 b0 = b1; b1 = b2;
                 b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
-                if (c + 1 < p.n_chunks) prefetch_steps(b0, b1); else prefetch_steps(0, 0);
+                if (j + 1 < n_loc) prefetch_steps(b0, b1); else prefetch_steps(0, 0);
             };
             prefetch_steps(b0, b1);
-            auto commit = [&](const ARegs<AB>& ar, int c) {
-                if (c < p.n_chunks) stage_commit<MSB, AB, TRANS>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), wave, lane);
-            };
             if constexpr (kAhead == 1) {
                 __syncthreads();
-                for (int c = 0; c < p.n_chunks; ++c) {
+                for (int j = 0; j < n_loc; ++j) {
                     ARegs<AB> ar;
-                    issue_or_zero(ar, c + 1);
-                    steps_of(c);
-                    commit(ar, c + 1);
+                    issue_or_zero(ar, j + 1);
+                    steps_of(j);
+                    commit(ar, j + 1);
                     __syncthreads();
                 }
             } else {
@@ -1290,22 +1340,26 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 ARegs<AB> ar0, ar1;
                 issue_or_zero(ar1, 1);
                 __syncthreads();
-                for (int c = 0; c < p.n_chunks; c += 2) {
-                    issue_or_zero(ar0, c + 2);
-                    steps_of(c);
-                    commit(ar1, c + 1);
+                for (int j = 0; j < n_loc; j += 2) {
+                    issue_or_zero(ar0, j + 2);
+                    steps_of(j);
+                    commit(ar1, j + 1);
                     __syncthreads();
-                    if (c + 1 < p.n_chunks) {
-                        issue_or_zero(ar1, c + 3);
-                        steps_of(c + 1);
-                        commit(ar0, c + 2);
+                    if (j + 1 < n_loc) {
+                        issue_or_zero(ar1, j + 3);
+                        steps_of(j + 1);
+                        commit(ar0, j + 2);
                     }
                     __syncthreads();
                 }
             }
             if (active) {
-                if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
-                else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                if constexpr (SPLIT) {
+                    dump_partial<MS, NCB>(p.partials + ((((long)part * p.n_mblocks + mb) * p.T + ti) * (long)(MS * NCB * 1024)), acc, lane);
+                } else {
+                    if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                }
             }
         }
     }
@@ -1327,6 +1381,71 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
     }
 }
 
+// Second kernel of a split-K product.  A workgroup is one wave and takes one piece of one (row block, tile): on the
+// row-major boundary one pass of the tile's epilogue (eight rows, all column blocks), on the transposed boundary
+// one column block (all 64 tokens).  It adds that piece's partial results of all parts in the order of the parts
+// (a fixed order: the result does not depend on which workgroup of the first kernel finished first) and stores it
+// through the epilogue of the main kernel (column scatter, zeros of pruned columns, fused bias and activation).
+// The pieces are this small because a compute unit brings in only about 16 KB per microsecond from memory (its
+// queue of outstanding misses times the latency): a wave that summed a whole tile (32 KB per part) would take as
+// long as the chunks it saves.
+template <int DT, int NCB, bool FUSED, bool TRANS>
+__global__ __launch_bounds__(64) void tw_splitk_reduce_kernel(const TwGemmParams p) {
+    constexpr int MS = 2;
+    constexpr int SUB = TRANS ? NCB : 4 * MS;               // pieces per tile
+    constexpr int NL = TRANS ? 4 * MS : NCB;                // 1 KB loads per piece and part
+    __shared__ __attribute__((aligned(16))) unsigned char stage[kStageBytes];
+    const int lane = threadIdx.x & 63;
+    const int unit = (int)blockIdx.x;                       // ((row block * T) + tile) * SUB + piece
+    const int sub = unit % SUB, mt = unit / SUB;
+    const int mb = mt / p.T, ti = mt - mb * p.T;
+    const int row0 = mb * p.row_step;
+    const TileU d = fetch_tile(p, ti);
+    const long part_stride = (long)p.n_mblocks * p.T * (MS * NCB * 1024);
+    const float* src = p.partials + ((long)mb * p.T + ti) * (long)(MS * NCB * 1024) + lane * 4;
+    // load i of the piece: row-major (ms, q) = sub, cb = i; transposed cb = sub, (ms, q) = i
+    int off[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int msq = TRANS ? i : sub, cb = TRANS ? sub : i;
+        off[i] = (((msq >> 2) * NCB + cb) * 4 + (msq & 3)) * 256;
+    }
+    // (the first part is requested before anything waits for the tile's descriptor)
+    tw_f32x4 s[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) s[i] = *(const tw_f32x4*)(src + off[i]);
+    unsigned dpos[NCB];
+    {
+        const unsigned* dp = (const unsigned*)(p.blob + p.off_dpos) + ((long)d.tile * 32 + (lane & 31)) * NCB;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) dpos[cb] = dp[cb];
+    }
+#pragma unroll 2
+    for (int part = 1; part < p.n_parts; ++part) {
+        tw_f32x4 v[NL];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) v[i] = *(const tw_f32x4*)(src + part * part_stride + off[i]);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) s[i] += v[i];
+    }
+    tw_f32x16 acc[MS][NCB];
+    zero_acc<MS, NCB>(acc);
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int msq = 4 * ms + q;
+                if ((TRANS ? cb : msq) == sub) {            // wave-uniform
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[ms][cb][4 * q + e] = s[TRANS ? msq : cb][e];
+                }
+            }
+    if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, sub, sub + 1);
+    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, nullptr, sub, sub + 1);
+}
+
 }  // namespace
 
 // ---- kernel tables
@@ -1337,6 +1456,7 @@ namespace tw_parts {
 // (nta: the streamed kernels' variant whose requests for activations carry the streaming hint)
 template <int DT, bool FUSED> const void* pick_mode(int mode, int ms, int ncb, bool nta);     // row-major boundary
 template <int DT, bool FUSED> const void* pick_mode_t(int mode, int ms, int ncb, bool nta);   // transposed boundary
+template <int DT, bool FUSED> const void* pick_reduce(int ncb, bool transposed);               // second kernel of split K
 }  // namespace tw_parts
 
 #if !defined(TW_PART) || TW_PART != 0
@@ -1357,6 +1477,10 @@ const void* pick_mode(int mode, int ms, int ncb, bool nta) {
     if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, false>(ncb) : pick_ncb<DT, 1, 0, FUSED, false>(ncb);
     if (ms != 2) return nullptr;                  // the streamed kernels take 64-row blocks
     if (mode == 1) return nta ? pick_ncb<DT, 2, 1, FUSED, false, true>(ncb) : pick_ncb<DT, 2, 1, FUSED, false, false>(ncb);
+    if (mode == 3) {                              // split K: the epilogue is the second kernel's, so only the plain variant exists
+        if constexpr (!FUSED) return nta ? pick_ncb<DT, 2, 3, false, false, true>(ncb) : pick_ncb<DT, 2, 3, false, false, false>(ncb);
+        else return nullptr;
+    }
     return nta ? pick_ncb<DT, 2, 2, FUSED, false, true>(ncb) : pick_ncb<DT, 2, 2, FUSED, false, false>(ncb);
 }
 // transposed boundary: resident K with blocks of 64 or 32 tokens, streamed K always with 64
@@ -1365,7 +1489,20 @@ const void* pick_mode_t(int mode, int ms, int ncb, bool nta) {
     if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, true>(ncb) : pick_ncb<DT, 1, 0, FUSED, true>(ncb);
     if (ms != 2) return nullptr;
     if (mode == 1) return nta ? pick_ncb<DT, 2, 1, FUSED, true, true>(ncb) : pick_ncb<DT, 2, 1, FUSED, true, false>(ncb);
+    if (mode == 3) {
+        if constexpr (!FUSED) return nta ? pick_ncb<DT, 2, 3, false, true, true>(ncb) : pick_ncb<DT, 2, 3, false, true, false>(ncb);
+        else return nullptr;
+    }
     return nta ? pick_ncb<DT, 2, 2, FUSED, true, true>(ncb) : pick_ncb<DT, 2, 2, FUSED, true, false>(ncb);
+}
+template <int DT, bool FUSED>
+const void* pick_reduce(int ncb, bool transposed) {
+    switch (ncb) {
+        case 1: return transposed ? (const void*)tw_splitk_reduce_kernel<DT, 1, FUSED, true> : (const void*)tw_splitk_reduce_kernel<DT, 1, FUSED, false>;
+        case 2: return transposed ? (const void*)tw_splitk_reduce_kernel<DT, 2, FUSED, true> : (const void*)tw_splitk_reduce_kernel<DT, 2, FUSED, false>;
+        case 4: return transposed ? (const void*)tw_splitk_reduce_kernel<DT, 4, FUSED, true> : (const void*)tw_splitk_reduce_kernel<DT, 4, FUSED, false>;
+        default: return nullptr;
+    }
 }
 }  // namespace tw_parts
 #endif
@@ -1373,7 +1510,8 @@ const void* pick_mode_t(int mode, int ms, int ncb, bool nta) {
 #ifdef TW_PART
 #define TW_TABLES(KW, DT, FUSED)                                            \
     KW template const void* tw_parts::pick_mode<DT, FUSED>(int, int, int, bool);  \
-    KW template const void* tw_parts::pick_mode_t<DT, FUSED>(int, int, int, bool);
+    KW template const void* tw_parts::pick_mode_t<DT, FUSED>(int, int, int, bool); \
+    KW template const void* tw_parts::pick_reduce<DT, FUSED>(int, bool);
 #if TW_PART == 0
 TW_TABLES(extern, TW_F16, false) TW_TABLES(extern, TW_F16, true) TW_TABLES(extern, TW_BF16, false) TW_TABLES(extern, TW_BF16, true)
 #elif TW_PART == 1
@@ -1548,9 +1686,24 @@ struct Plan {
     unsigned at_pitch, abuf_bytes, stage_off, misc_off, lds_bytes;
     unsigned urow_off;   // transposed boundary, loading waves: LDS offset of their row lists (0: whole chunks are read)
     unsigned xbuf_off;   // row-major boundary, K resident, TEW blob with residual-only columns: LDS offset of the waves' areas for them
+    int n_parts, chunks_per_part;   // split K (see TwGemmParams); n_parts = 1: none
+    size_t partial_bytes;           // workspace the parts' fp32 results take, behind the counters
 };
 
+
 constexpr unsigned kLdsLimit = 160 * 1024;
+// Estimates of the planner for streamed K when a launch has fewer items than compute units, in microseconds
+// (fitted to the FFN-down of BERT-base and of BERT-large and to a lowered convolution, K = 2304 .. 4096 in 6 to 11
+// chunks, M = 64 .. 6000, both boundaries).  Unsplit: kItemUs for the launch and the start of an item, then per
+// chunk in sequence kChunkUs (what it takes a compute unit to bring in 64 rows x 384 columns of A; kChunkUsT on
+// the transposed boundary, where whole rows go to LDS; kNarrowChunk of it for tiles of at most 64 columns, whose
+// requests run two chunks ahead).  Split: kSplitItemUs (nothing overlaps the first chunk), a chunk takes longer
+// the more workgroups stream at once (1 + kLoadedChunk at a full round), the tiles' partial results leave a
+// compute unit at kCuStoreBytesPerUs; the second kernel costs kReduceUs plus, per wave that a compute unit gets,
+// kReduceWaveUs and its loads at kCuLoadBytesPerUs.  A split must promise kSplitMargin of the unsplit time or less.
+constexpr double kItemUs = 4.5, kChunkUs = 3.3, kChunkUsT = 2.8, kNarrowChunk = 0.85, kSplitItemUs = 5.5,
+                 kLoadedChunk = 0.4, kCuStoreBytesPerUs = 38e3, kReduceUs = 2.5, kReduceWaveUs = 0.25,
+                 kCuLoadBytesPerUs = 24e3, kSplitMargin = 0.9;
 
 unsigned at_bytes(int msb, int k_chunk) {
     const unsigned pitch = 64u * msb + 8u;
@@ -1560,7 +1713,7 @@ unsigned lds_need(int msb, int k_chunk, int buffers) {
     return buffers * at_bytes(msb, k_chunk) + kWaves * kStageBytes + 16u;
 }
 
-int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = false) {
+int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = false, size_t ws_avail = ~(size_t)0) {
     const bool resident = h->n_chunks == 1;
     const int buffers = resident ? 1 : 2;
     if (lds_need(1, h->k_chunk, buffers) > kLdsLimit) return TW_ERR_UNSUPPORTED;
@@ -1597,6 +1750,9 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
             pl.mode = 2;
             tpw = kWaves / 2;
             while (tpw > 1 && items_for(2, tpw, nmb, nseg) < n_cu) tpw >>= 1;
+            // (an item takes about as long with fewer tiles, its time is the time to bring A in: one round of
+            // workgroups that leaves compute units idle beats two rounds)
+            if (tpw < kWaves / 2 && items_for(2, tpw, nmb, nseg) > n_cu) tpw <<= 1;
         }
     }
     if (!resident && msb != 2) return TW_ERR_UNSUPPORTED;   // (the streamed kernels take 64-row blocks; 384-row chunks fit)
@@ -1641,6 +1797,49 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
         const unsigned need = (kWaves / 2) * (unsigned)h->n_chunks * (8 * 12 + 2) * 2;
         if (pl.lds_bytes + need <= kLdsLimit) { pl.urow_off = pl.lds_bytes; pl.lds_bytes += need; }
     }
+    // Split K.  With streamed K and few row blocks the plan above leaves most compute units idle while each
+    // workgroup walks all chunks in sequence, and a compute unit brings A in at about 16 KB per microsecond only
+    // (its queue of outstanding misses times the memory latency), 3 us per chunk.  The alternative: MODE 1 with
+    // the chunks cut into parts of equal length and the tiles into sets of `tpw`, an item per (part, set, row
+    // block), all in one round; the tiles' fp32 results go to the workspace and a second kernel adds them in a
+    // fixed order and stores C.  Both the number of parts and the tiles per set are chosen by the estimate below;
+    // the split is taken when its estimate is lower and the caller's workspace holds the partial results.
+    pl.n_parts = 1; pl.chunks_per_part = h->n_chunks; pl.partial_bytes = 0;
+    if (!resident && msb == 2 && h->n_chunks >= 2) {
+        const long nmb1 = (M + 63) / 64;
+        const size_t tile_bytes = (size_t)2 * h->ncb * 4096;          // fp32 results of a tile: 64 rows x G columns
+        const int sub = transposed ? h->ncb : 8;                      // pieces of a tile in the second kernel
+        const long units2 = nmb1 * T * sub;
+        const double rounds0 = (double)((items + n_cu - 1) / n_cu);
+        const double chunk_us = transposed ? kChunkUsT : kChunkUs;
+        double best = rounds0 * (kItemUs + h->n_chunks * chunk_us * (h->ncb <= 2 ? kNarrowChunk : 1.0));
+        int best_cpp = 0, best_tpw = 0;
+        for (int sets = 1; sets <= T; ++sets) {
+            const int tpw1 = (T + sets - 1) / sets;
+            if (tpw1 > kWaves || (sets > 1 && (T + sets - 2) / (sets - 1) == tpw1)) continue;   // (as many tiles per set with fewer sets)
+            for (int cpp = h->n_chunks - 1; cpp >= 1; --cpp) {
+                const int parts = (h->n_chunks + cpp - 1) / cpp;
+                if (nmb1 * sets * parts > n_cu) break;
+                if (cpp > 1 && (h->n_chunks + cpp - 2) / (cpp - 1) == parts) continue;   // a shorter part with as many parts follows
+                const size_t bytes = (size_t)parts * nmb1 * T * tile_bytes;
+                if (256 + bytes > ws_avail) continue;
+                const double waves2 = (double)((units2 + n_cu - 1) / n_cu);     // of the second kernel, per compute unit
+                const double loaded = 1.0 + kLoadedChunk * (double)(nmb1 * sets * parts) / n_cu;
+                const double cost = kSplitItemUs + cpp * chunk_us * loaded + tpw1 * (double)tile_bytes / kCuStoreBytesPerUs +
+                                    kReduceUs + waves2 * (kReduceWaveUs + parts * (double)(tile_bytes / sub) / kCuLoadBytesPerUs);
+                if (cost < kSplitMargin * best) { best = cost / kSplitMargin; best_cpp = cpp; best_tpw = tpw1; }
+            }
+        }
+        if (best_cpp > 0) {
+            pl.mode = 1; pl.tiles_per_set = best_tpw; pl.row_step = 64; pl.urow_off = 0;
+            pl.chunks_per_part = best_cpp;
+            pl.n_parts = (h->n_chunks + best_cpp - 1) / best_cpp;
+            pl.n_mblocks = (int)nmb1; pl.n_seg = (T + best_tpw - 1) / best_tpw;
+            pl.n_items = (int)(nmb1 * pl.n_seg * pl.n_parts);
+            pl.partial_bytes = (size_t)pl.n_parts * nmb1 * T * tile_bytes;
+            pl.lds_bytes = pl.misc_off + 16u;
+        }
+    }
     return TW_OK;
 }
 
@@ -1654,6 +1853,12 @@ const void* pick_kernel(int dt, int mode, int ms, int ncb, bool fused, bool nta)
     using namespace tw_parts;
     if (fused) return dt == TW_F16 ? pick_mode<TW_F16, true>(mode, ms, ncb, nta) : pick_mode<TW_BF16, true>(mode, ms, ncb, nta);
     return dt == TW_F16 ? pick_mode<TW_F16, false>(mode, ms, ncb, nta) : pick_mode<TW_BF16, false>(mode, ms, ncb, nta);
+}
+
+const void* pick_reduce_kernel(int dt, int ncb, bool fused, bool transposed) {
+    using namespace tw_parts;
+    if (fused) return dt == TW_F16 ? pick_reduce<TW_F16, true>(ncb, transposed) : pick_reduce<TW_BF16, true>(ncb, transposed);
+    return dt == TW_F16 ? pick_reduce<TW_F16, false>(ncb, transposed) : pick_reduce<TW_BF16, false>(ncb, transposed);
 }
 
 // Per-device facts looked up once (the entries are written with the same value by every thread
@@ -1693,7 +1898,19 @@ extern "C" int tw_gemm_workspace(const void* blob_host, int M, size_t* ws_bytes)
     if (!blob_host || !ws_bytes || M < 0) return TW_ERR_ARG;
     const TwHeader* h = (const TwHeader*)blob_host;
     if (h->magic != TW_MAGIC || h->version != TW_FORMAT_VERSION) return TW_ERR_BUF;
-    *ws_bytes = 256;
+    // the counters, and behind them the partial results of a split-K plan (the larger of the two boundaries'), as
+    // planned for the current GPU (256 compute units when there is none to ask)
+    size_t need = 256;
+    if (M > 0 && h->T > 0 && h->n_chunks > 1) {
+        int n_cu = 256;
+        const int dev = current_device();
+        if (dev >= 0 && device_cus(dev) > 0) n_cu = device_cus(dev);
+        for (int tr = 0; tr < 2; ++tr) {
+            Plan pl;
+            if (make_plan(h, M, n_cu, pl, tr != 0) == TW_OK && 256 + pl.partial_bytes > need) need = 256 + pl.partial_bytes;
+        }
+    }
+    *ws_bytes = need;
     return TW_OK;
 }
 
@@ -1715,6 +1932,7 @@ extern "C" int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transpos
     plan->grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     plan->lds_bytes = pl.lds_bytes;
     plan->row_lists = pl.urow_off != 0;
+    plan->k_parts = pl.n_parts;
     return TW_OK;
 }
 
@@ -1741,7 +1959,9 @@ int check_gemm_args(const void* blob_host, const void* blob_dev, const void* A, 
 }
 
 // ---- scratch memory of the entry point that allocates nothing and takes no workspace (tw_gemm_static) ----
-// The scheduler's counters live in this array instead of a buffer of the caller.  Every GPU holds its own
+// The scheduler's counters (its first 256 bytes) and the fp32 partial results of a split-K plan (the rest; the
+// planner takes a split only if they fit) live in this array instead of a buffer of the caller.  Only the counters
+// need a defined start value; the partial results are written before they are read.  Every GPU holds its own
 // copy at its own address; host code must use the address that hipGetSymbolAddress returns with that GPU
 // current (the array's name is only a host-side stand-in), so it is looked up once per device and kept.
 __device__ __align__(256) unsigned char tw_static_scratch[TW_STATIC_SCRATCH_BYTES];
@@ -1766,14 +1986,10 @@ __global__ void tw_clear_kernel(unsigned* w, int n) {
 
 extern "C" int tw_gemm_static(const void* blob_host, const void* blob_dev, const void* A, int M, int lda, void* C,
                               int ldc, void* hip_stream) {
-    size_t need = 0;
-    int rc = tw_gemm_workspace(blob_host, M < 0 ? 0 : M, &need);
-    if (rc) return rc;
-    if (need > TW_STATIC_SCRATCH_BYTES) return TW_ERR_UNSUPPORTED;     // more scratch than the array holds
     const int dev = current_device();
     if (dev < 0) return TW_ERR_HIP;
     void* scratch = nullptr;
-    rc = static_scratch(dev, &scratch);
+    int rc = static_scratch(dev, &scratch);
     if (rc) return rc;
     rc = check_gemm_args(blob_host, blob_dev, A, M, lda, nullptr, TW_ACT_NONE, C, ldc, scratch, TW_STATIC_SCRATCH_BYTES);
     if (rc) return rc;
@@ -1817,14 +2033,22 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     const int n_cu = device_cus(dev);
     if (n_cu <= 0) return TW_ERR_HIP;
     Plan pl;
-    int rc = make_plan(h, M, n_cu, pl);
+    int rc = make_plan(h, M, n_cu, pl, false, ws_bytes);
     if (rc) return rc;
-    const bool fused = bias != nullptr || act != TW_ACT_NONE;
+    const bool split = pl.n_parts > 1;
+    const bool fused_epilogue = bias != nullptr || act != TW_ACT_NONE;
+    const bool fused = fused_epilogue && !split;      // split K: the epilogue is the second kernel's
     // streamed K: the activations carry the streaming hint only when one workgroup reads a row block's rows
     const bool nta = pl.mode == 0 || pl.n_seg == 1;
-    const void* fn = pick_kernel(h->dtype, pl.mode, pl.ms, h->ncb, fused, nta);
+    const int kmode = split ? 3 : pl.mode;             // the kernel's MODE
+    const void* fn = pick_kernel(h->dtype, kmode, pl.ms, h->ncb, fused, nta);
     if (!fn) return TW_ERR_UNSUPPORTED;
-    const int variant = pl.mode == 0 ? (pl.ms == 2 ? 0 : 1) : 2 * pl.mode + (nta ? 0 : 1);   // 0..5
+    const void* fn_reduce = nullptr;
+    if (split) {
+        fn_reduce = pick_reduce_kernel(h->dtype, h->ncb, fused_epilogue, false);
+        if (!fn_reduce) return TW_ERR_UNSUPPORTED;
+    }
+    const int variant = kmode == 0 ? (pl.ms == 2 ? 0 : 1) : 2 * kmode + (nta ? 0 : 1);   // 0..7
     const int kernel_id = (fused ? 60 : 0) + (h->dtype == TW_F16 ? 0 : 30) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, fn);
     if (rc) return rc;
@@ -1849,9 +2073,15 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.stream_stores = ((uintptr_t)C & 127) == 0 && (ldc & 63) == 0;
     p.off_xc_tile_ptr = h->off_xc_tile_ptr; p.off_xc_col = h->off_xc_col; p.off_xc_ptr = h->off_xc_ptr;
     p.off_xc_k = h->off_xc_k; p.off_xc_v = h->off_xc_v; p.xbuf_off = pl.xbuf_off;
+    p.n_parts = pl.n_parts; p.chunks_per_part = pl.chunks_per_part;
+    p.partials = (float*)((unsigned char*)workspace + 256);
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     void* args[] = {(void*)&p};
     if (hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, pl.lds_bytes, stream) != hipSuccess) return TW_ERR_HIP;
+    if (split) {
+        const long units = (long)pl.n_mblocks * h->T * 8;                 // a wave per pass of a tile
+        if (hipLaunchKernel(fn_reduce, dim3((unsigned)units), dim3(64), args, 0, stream) != hipSuccess) return TW_ERR_HIP;
+    }
     return launch_xcols(h, blob_dev, A, lda, C, ldc, M, bias, (int)act, false, stream, pl.xbuf_off != 0);
 }
 
@@ -1867,7 +2097,7 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     if (!blob_host || !blob_dev || !At || !Ct || !workspace || M < 0) return TW_ERR_ARG;
     if (act != TW_ACT_NONE && act != TW_ACT_RELU && act != TW_ACT_GELU) return TW_ERR_ARG;
     if (((uintptr_t)bias & 1) != 0) return TW_ERR_ALIGN;
-    const bool fused = bias != nullptr || act != TW_ACT_NONE;
+    const bool fused_epilogue = bias != nullptr || act != TW_ACT_NONE;
     const TwHeader* h = (const TwHeader*)blob_host;
     if (h->magic != TW_MAGIC || h->version != TW_FORMAT_VERSION) return TW_ERR_BUF;
     if (ws_bytes < 256) return TW_ERR_BUF;
@@ -1896,12 +2126,20 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     const int n_cu = device_cus(dev);
     if (n_cu <= 0) return TW_ERR_HIP;
     Plan pl;
-    int rc = make_plan(h, M, n_cu, pl, /*transposed=*/true);
+    int rc = make_plan(h, M, n_cu, pl, /*transposed=*/true, ws_bytes);
     if (rc) return rc;
+    const bool split = pl.n_parts > 1;
+    const bool fused = fused_epilogue && !split;      // split K: the epilogue is the second kernel's
     const bool nta = pl.mode == 0 || pl.n_seg == 1;
-    const void* fn = pick_kernel_t(h->dtype, pl.mode, pl.ms, h->ncb, fused, nta);
+    const int kmode = split ? 3 : pl.mode;             // the kernel's MODE
+    const void* fn = pick_kernel_t(h->dtype, kmode, pl.ms, h->ncb, fused, nta);
     if (!fn) return TW_ERR_UNSUPPORTED;
-    const int variant = pl.mode == 0 ? (pl.ms == 2 ? 0 : 1) : 2 * pl.mode + (nta ? 0 : 1);   // 0..5
+    const void* fn_reduce = nullptr;
+    if (split) {
+        fn_reduce = pick_reduce_kernel(h->dtype, h->ncb, fused_epilogue, true);
+        if (!fn_reduce) return TW_ERR_UNSUPPORTED;
+    }
+    const int variant = kmode == 0 ? (pl.ms == 2 ? 0 : 1) : 2 * kmode + (nta ? 0 : 1);   // 0..7
     const int kernel_id = 120 + (fused ? 60 : 0) + (h->dtype == TW_F16 ? 0 : 30) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, fn);
     if (rc) return rc;
@@ -1927,10 +2165,16 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_xc_tile_ptr = h->off_xc_tile_ptr; p.off_xc_col = h->off_xc_col; p.off_xc_ptr = h->off_xc_ptr;
     p.off_xc_k = h->off_xc_k; p.off_xc_v = h->off_xc_v; p.xbuf_off = 0;
     p.stream_stores = ((uintptr_t)Ct & 127) == 0 && (ldct & 63) == 0;
+    p.n_parts = pl.n_parts; p.chunks_per_part = pl.chunks_per_part;
+    p.partials = (float*)((unsigned char*)workspace + 256);
     const unsigned lds_bytes = pl.lds_bytes;
     const int grid = pl.n_items < n_cu ? pl.n_items : n_cu;
     void* args[] = {(void*)&p};
     if (hipLaunchKernel(fn, dim3(grid), dim3(kThreads), args, lds_bytes, stream) != hipSuccess) return TW_ERR_HIP;
+    if (split) {
+        const long units = (long)pl.n_mblocks * h->T * h->ncb;            // a wave per column block of a tile
+        if (hipLaunchKernel(fn_reduce, dim3((unsigned)units), dim3(64), args, 0, stream) != hipSuccess) return TW_ERR_HIP;
+    }
     return launch_xcols(h, blob_dev, At, ldat, Ct, ldct, M, bias, (int)act, true, stream);
 }
 

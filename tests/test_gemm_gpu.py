@@ -860,16 +860,21 @@ def test_random_big_shapes_on_sampled_rows(tw, seed):
 # result is exact in the storage type while |C| stays below 2^11 (fp16) or 2^8 (bf16); the cases assert that.
 # The shapes are chosen for the plan they give on 256 compute units; the plan is asserted.
 EXACT = [
-    # name, M, K, N, G, dtype, col_prune, keep, expected (mode, rows_per_block, tiles_per_set) row-major / transposed
-    ("resident_32rows", 150, 256, 384, 128, "f16", 0.05, ("upow", 0.1, 0.6), (0, 32, 0), (0, 32, 0)),
-    ("resident_64rows", 8192, 256, 390, 128, "f16", 0.05, ("upow", 0.1, 0.6), (0, 64, 0), (0, 64, 0)),
-    ("resident_64rows_bf16", 8192, 96, 200, 64, "bf16", 0.1, ("upow", 0.1, 0.5), (0, 64, 0), (0, 64, 0)),
-    ("resident_lowered_blocks", 17000, 256, 250, 128, "f16", 0.0, ("upow", 0.1, 0.6), (0, 40, 0), (0, 64, 0)),
-    ("streamed_wave_per_tile", 16384, 1600, 380, 64, "f16", 0.05, ("upow", 0.02, 0.15), (1, 64, 8), (1, 64, 8)),
-    ("streamed_sets_of_4", 16400, 1600, 250, 64, "f16", 0.0, ("upow", 0.02, 0.15), (2, 40, 4), (2, 64, 4)),
-    ("streamed_sets_of_2", 8192, 1700, 256, 64, "f16", 0.0, ("upow", 0.02, 0.15), (2, 64, 2), (2, 64, 2)),
-    ("streamed_sets_of_1", 4096, 1600, 128, 32, "f16", 0.0, ("upow", 0.02, 0.15), (2, 64, 1), (2, 64, 1)),
-    ("streamed_bf16", 16384, 1600, 256, 64, "bf16", 0.0, ("upow", 0.01, 0.04), (2, 64, 4), (2, 64, 4)),
+    # name, M, K, N, G, dtype, col_prune, keep, expected (mode, rows_per_block, tiles_per_set, k_parts) row-major / transposed
+    ("resident_32rows", 150, 256, 384, 128, "f16", 0.05, ("upow", 0.1, 0.6), (0, 32, 0, 1), (0, 32, 0, 1)),
+    ("resident_64rows", 8192, 256, 390, 128, "f16", 0.05, ("upow", 0.1, 0.6), (0, 64, 0, 1), (0, 64, 0, 1)),
+    ("resident_64rows_bf16", 8192, 96, 200, 64, "bf16", 0.1, ("upow", 0.1, 0.5), (0, 64, 0, 1), (0, 64, 0, 1)),
+    ("resident_lowered_blocks", 17000, 256, 250, 128, "f16", 0.0, ("upow", 0.1, 0.6), (0, 40, 0, 1), (0, 64, 0, 1)),
+    ("streamed_wave_per_tile", 16384, 1600, 380, 64, "f16", 0.05, ("upow", 0.02, 0.15), (1, 64, 8, 1), (1, 64, 8, 1)),
+    ("streamed_sets_of_4", 16400, 1600, 250, 64, "f16", 0.0, ("upow", 0.02, 0.15), (2, 40, 4, 1), (2, 64, 4, 1)),
+    ("streamed_sets_of_2", 8192, 1700, 256, 64, "f16", 0.0, ("upow", 0.02, 0.15), (2, 64, 2, 1), (2, 64, 2, 1)),
+    ("streamed_sets_of_1", 4096, 1600, 128, 32, "f16", 0.0, ("upow", 0.02, 0.15), (2, 64, 1, 1), (2, 64, 1, 1)),
+    ("streamed_bf16", 16384, 1600, 256, 64, "bf16", 0.0, ("upow", 0.01, 0.04), (2, 64, 4, 1), (2, 64, 4, 1)),
+    # split K: few row blocks and a streamed K; the parts' partial results go through the workspace
+    ("split_one_row_block", 64, 3072, 768, 128, "f16", 0.0, ("upow", 0.02, 0.15), (1, 64, 1, 8), (1, 64, 1, 8)),
+    ("split_sets_apart", 512, 3072, 768, 128, "f16", 0.05, ("upow", 0.02, 0.15), (1, 64, 2, 8), (1, 64, 2, 8)),
+    ("split_bf16_ragged_chunk", 700, 2000, 300, 64, "bf16", 0.0, ("upow", 0.01, 0.04), (1, 64, 2, 6), (1, 64, 2, 6)),
+    ("split_g32_parts_of_two", 1100, 1600, 250, 32, "f16", 0.1, ("upow", 0.02, 0.15), (1, 64, 4, 5), (1, 64, 4, 5)),
 ]
 
 
@@ -884,8 +889,8 @@ def test_integer_inputs_bit_exact_per_mode(tw, case):
     pl, plt = tw.tw_gemm_plan(blob, M, n_cu=n_cu), tw.tw_gemm_plan(blob, M, n_cu=n_cu, transposed=True)
     _say(f"exact {name}: M={M} K={K} N={N} G={G} {dtype} T={tw.tw_info(blob)['T']} plan {pl} / transposed {plt}")
     if n_cu == 256:
-        assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"]) == plan_n
-        assert (plt["mode"], plt["rows_per_block"], plt["tiles_per_set"]) == plan_t
+        assert (pl["mode"], pl["rows_per_block"], pl["tiles_per_set"], pl["k_parts"]) == plan_n
+        assert (plt["mode"], plt["rows_per_block"], plt["tiles_per_set"], plt["k_parts"]) == plan_t
     ref = tw_ref.masked_gemm(w.A, w.B, w.mask, dtype)
     limit = 2048 if dtype == "f16" else 256
     assert np.max(np.abs(ref)) <= limit, "the case must stay exactly representable"
@@ -895,6 +900,16 @@ def test_integer_inputs_bit_exact_per_mode(tw, case):
     tw.tw_gemm(wt, A, C)
     torch.cuda.synchronize()
     assert np.array_equal(_to_f64(C), ref), "tw_gemm differs from the oracle in some bit"
+    if pl["k_parts"] > 1:
+        # the same product with the counters' 256 bytes of workspace only: no split, a different kernel plan
+        assert tw.tw_gemm_workspace(blob, M) > 256
+        wu = tw.TwWeight(blob)
+        wu.ws_limit = 256
+        Cu = torch.full((M, N), float("nan"), dtype=A.dtype, device="cuda:0")
+        tw.tw_gemm(wu, A, Cu)
+        torch.cuda.synchronize()
+        assert wu.workspace.numel() == 256 and torch.equal(C, Cu), "split and unsplit plans differ on exact inputs"
+        del Cu
     del C
     At = _device_At(tw, w.A, dtype)
     ldct = (M + 7) // 8 * 8 + 8
@@ -926,6 +941,75 @@ def test_integer_inputs_bit_exact_per_mode(tw, case):
         Cet = tw.tw_gemm_t(wte, _device_At(tw, w.A, dtype))
         torch.cuda.synchronize()
         assert np.array_equal(_to_f64(Cet).T, ref_e), "tw_gemm_t on the TEW blob differs from the oracle in some bit"
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ split K: few rows, streamed K
+@pytest.mark.parametrize("M", [64, 512, 2048, 1000])
+def test_split_k_small_batches_of_the_ffn_down(tw, M):
+    """FFN-down of BERT-base (K = 3072 in eight chunks, the c3 workload's weight and value distributions) at batch
+    sizes that leave most compute units without a row block: the K chunks are split over workgroups, the parts'
+    fp32 results go through the workspace and a second kernel adds them in a fixed order.  Every element of C
+    against the oracle on both boundaries, with the fused epilogue and with a TEW residual; repeated calls are
+    bit-identical (no atomics on floating point); a workspace that is too small for the parts falls back to
+    the unsplit plan instead of failing."""
+    import dataclasses
+    base = W.CONFIGS["c3_bert_base_layer"][3]
+    spec = dataclasses.replace(base, name=f"{base.name}_M{M}", M=M)
+    w = W.generate(spec)
+    dtype = spec.dtype
+    wt = tw.TwWeight.from_dense(w.B, w.mask, spec.G, dtype)
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    pl, plt = tw.tw_gemm_plan(wt.blob, M, n_cu=n_cu), tw.tw_gemm_plan(wt.blob, M, n_cu=n_cu, transposed=True)
+    need = tw.tw_gemm_workspace(wt.blob, M)
+    _say(f"split K {spec.name}: K={spec.K} N={spec.N} T={wt.info['T']} plan {pl} / transposed {plt}, workspace {need} bytes")
+    if n_cu == 256:
+        assert pl["k_parts"] > 1 and plt["k_parts"] > 1 and pl["mode"] == 1 and pl["n_items"] <= n_cu
+        tile_bytes = 64 * spec.G * 4
+        assert need == 256 + max(pl["k_parts"], plt["k_parts"]) * pl["n_row_blocks"] * wt.info["T"] * tile_bytes
+    A = _device_A(tw, w.A, dtype)
+    C = torch.full((M, spec.N), float("nan"), dtype=A.dtype, device="cuda:0")
+    tw.tw_gemm(wt, A, C)
+    torch.cuda.synchronize()
+    assert wt.workspace.numel() == need
+    err = _compare_whole(C, w.A, w.B, w.mask, dtype, what=spec.name)
+    assert wt.workspace.view(torch.int32)[:4].cpu().tolist() == [0, 0, 0, 0]
+    for _ in range(3):
+        assert torch.equal(C, tw.tw_gemm(wt, A)), "two calls of a split-K plan differ in some bit"
+    # transposed boundary
+    At = _device_At(tw, w.A, dtype)
+    Ct = tw.tw_gemm_t(wt, At)
+    torch.cuda.synchronize()
+    errt = _compare_whole(Ct, w.A, w.B, w.mask, dtype, transposed=True, what=spec.name + " transposed")
+    assert torch.equal(Ct, tw.tw_gemm_t(wt, At))
+    # fused bias + GELU in the second kernel's epilogue, both boundaries
+    bbits = _bias_bits(spec.N, dtype, 77 + M)
+    bias = tw.bits_to_tensor(bbits, dtype)
+    bias64 = tw_ref.decode(bbits, dtype)
+    post = lambda ref: tw_ref.bias_act(ref, bias64, "gelu")
+    Cf = tw.tw_gemm_bias_act(wt, A, bias, "gelu")
+    Cft = tw.tw_gemm_t_bias_act(wt, At, bias, "gelu")
+    torch.cuda.synchronize()
+    _compare_whole(Cf, w.A, w.B, w.mask, dtype, what=spec.name + " gelu", post=post)
+    _compare_whole(Cft, w.A, w.B, w.mask, dtype, transposed=True, what=spec.name + " gelu transposed", post=post)
+    # too little workspace for the parts: the unsplit plan, same tolerance
+    wu = tw.TwWeight(wt.blob)
+    wu.ws_limit = 4096
+    Cu = tw.tw_gemm(wu, A)
+    torch.cuda.synchronize()
+    assert wu.workspace.numel() <= 4096
+    _compare_whole(Cu, w.A, w.B, w.mask, dtype, what=spec.name + " small workspace")
+    # the hybrid: residual weights inside the tiles' columns (added per chunk by the part that holds the chunk)
+    # and in pruned columns (the pass of their own runs behind the second kernel)
+    ew = tw.tw_restore_ew(w.B, w.mask, 0.01, dtype)
+    union = (w.mask | ew).astype(np.uint8)
+    wte = tw.TwWeight(tw.tw_pack_tew(w.B, w.mask, ew, spec.G, dtype))
+    Ce = tw.tw_gemm(wte, A)
+    Cet = tw.tw_gemm_t(wte, At)
+    torch.cuda.synchronize()
+    _compare_whole(Ce, w.A, w.B, union, dtype, what=spec.name + " TEW")
+    _compare_whole(Cet, w.A, w.B, union, dtype, transposed=True, what=spec.name + " TEW transposed")
+    _say(f"split K {spec.name}: rel err {err:.3e} / transposed {errt:.3e}")
     torch.cuda.empty_cache()
 
 

@@ -372,8 +372,13 @@ def test_plan_limits_and_errors():
                     assert 32 <= pl["rows_per_block"] <= 64 and pl["rows_per_block"] % 8 == 0
                     assert pl["rows_per_block"] in (32, 64) or not tr
                     assert pl["n_row_blocks"] == (M + pl["rows_per_block"] - 1) // pl["rows_per_block"]
-                    assert pl["n_items"] == pl["n_row_blocks"] * pl["n_sets"] and pl["grid"] == min(pl["n_items"], n_cu)
+                    assert pl["n_items"] == pl["n_row_blocks"] * pl["n_sets"] * pl["k_parts"]
+                    assert pl["grid"] == min(pl["n_items"], n_cu)
                     assert (pl["mode"] == 0) == (K <= 1536)
+                    n_chunks = (K + 383) // 384
+                    assert 1 <= pl["k_parts"] <= n_chunks and (pl["k_parts"] == 1 or pl["mode"] == 1)
+                    if pl["k_parts"] > 1:                      # split K: only to fill idle compute units
+                        assert pl["n_items"] <= n_cu and pl["rows_per_block"] == 64
                     if pl["mode"] != 0:
                         T = tw.tw_info(blob)["T"]
                         assert pl["n_sets"] == (T + pl["tiles_per_set"] - 1) // pl["tiles_per_set"]
