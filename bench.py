@@ -106,7 +106,7 @@ def per_launch_stats(torch, fn, n_sets: int, steps: int):
 
 
 def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = True, n_sets=None,
-               with_warm: bool = False, with_steady: bool = False, settle: int = 0):
+               with_warm: bool = False, with_steady: bool = False, settle: int = 0, with_unsplit: bool = False):
     w = W.generate(spec)
     t0 = time.perf_counter()
     blob = tw.tw_pack(w.B, w.mask, spec.G, spec.dtype)
@@ -145,6 +145,13 @@ def bench_gemm(torch, tw, W, spec, steps: int, warmup: int, with_dense: bool = T
                sparsity=w.info["sparsity"], tw_ms=cold_ms, tw_ms_warm=warm_ms, tw_ms_median=med_ms,
                tw_ms_min=min_ms, tw_wall_ms=cold_wall, pack_ms=pack_ms, n_buffer_sets=n_sets, tw_t_ms=t_ms,
                tw_ms_steady=steady_ms)
+    if with_unsplit:  # the same launches with the counters' 256 bytes of workspace only: no split-K plan
+        wu = tw.TwWeight(blob)
+        wu.ws_limit = 256
+        u_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wu, As[i], Cs[i]), n_sets, steps, warmup)
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        out.update(tw_ms_unsplit=u_ms, plan=tw.tw_gemm_plan(blob, M, n_cu=n_cu),
+                   plan_t=tw.tw_gemm_plan(blob, M, n_cu=n_cu, transposed=True), workspace_bytes=tw.tw_gemm_workspace(blob, M))
     nz_flops = W.nonzero_flops(w.mask, M)
     dense_flops = 2.0 * M * spec.K * spec.N
     abytes = algorithmic_bytes(info, M)
@@ -262,6 +269,9 @@ def main() -> int:
     ap.add_argument("--transposed", action="store_true", help="with --pmc-calibration: launch tw_gemm_t instead of tw_gemm")
     ap.add_argument("--pmc-sweep", action="store_true", help="counter runs of the sparsity sweep (G = 128)")
     ap.add_argument("--source-hash", action="store_true", help="print the hash that the counter summaries record")
+    ap.add_argument("--small-batch", type=int, default=0, metavar="M",
+                    help="time only the FFN-down of BERT-base (K = 3072, streamed) on M rows: the split-K plan, the "
+                         "unsplit plan and the dense GEMMs; prints its own JSON line")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="counter runs: launch only a copy kernel of known size, then the tw_gemm steps")
     args = ap.parse_args()
@@ -280,6 +290,14 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     spec = W.CONFIGS["c2_bert_base_ffn_up"][0]
+    if args.small_batch > 0:
+        import dataclasses
+        s_ = dataclasses.replace(W.CONFIGS["c3_bert_base_layer"][3], M=args.small_batch)
+        r, _, _ = bench_gemm(torch, tw, W, s_, args.steps, args.warmup, n_sets=16, with_unsplit=True, settle=100)
+        print(json.dumps({"workload": f"c3 {s_.name} at M={s_.M}", "tw_ms": r["tw_ms"], "tw_ms_unsplit": r["tw_ms_unsplit"],
+                          "tw_t_ms": r["tw_t_ms"], "dense_ms": r["dense_ms"], "vendor_dense_ms": r["torch_matmul_ms"],
+                          "plan": r["plan"], "plan_t": r["plan_t"], "workspace_bytes": r["workspace_bytes"]}), flush=True)
+        return 0
     if args.pmc_sweep:
         return pmc_sweep(torch, tw, W)
     if args.pmc_calibration:
@@ -366,6 +384,20 @@ def main() -> int:
             print(f"[report] TEW on c2, delta {delta:.3f} ({int(wte.info['ew_nnz'])} residual weights): tw_gemm {a_ms*1e3:.1f} us, "
                   f"tw_gemm_t {b_ms*1e3:.1f} us", file=sys.stderr, flush=True)
         del Ats, Cts
+        # Few rows and a streamed K (the GEMMs with K > 1536 at serving batch sizes): split-K plans against the
+        # unsplit plan and the dense GEMMs
+        import dataclasses
+        for cfg, idx in (("c3_bert_base_layer", 3), ("c4_bert_large_skewed", 1), ("c5_conv_im2col", 0)):
+            for Ms in (64, 512, 2048):
+                s_ = dataclasses.replace(W.CONFIGS[cfg][idx], M=Ms)
+                r, _, _ = bench_gemm(torch, tw, W, s_, max(50, args.steps // 2), 10, n_sets=16, with_unsplit=True)
+                r["config"] = "small_batch"
+                r["of"] = cfg
+                rows.append(r)
+                print(f"[report] small batch {cfg}/{s_.name} M={Ms}: tw {r['tw_ms']*1e3:.1f} us (k_parts {r['plan']['k_parts']}, "
+                      f"unsplit {r['tw_ms_unsplit']*1e3:.1f} us)  tw_t {r['tw_t_ms']*1e3:.1f} us  dense {r['dense_ms']*1e3:.1f} us  "
+                      f"vendor dense {r['torch_matmul_ms']*1e3:.1f} us", file=sys.stderr, flush=True)
+                torch.cuda.empty_cache()
         # The four weight GEMMs of a BERT-base layer chained on one stream (QKV, attention output on a strided view,
         # FFN-up with bias + GELU, FFN-down), launch by launch and as one HIP graph: at small M the launches bound it.
         for Ml in (512, 16384):

@@ -244,10 +244,13 @@ class TwWeight:
         self.workspace = torch.zeros(256, dtype=torch.uint8, device=device)
         self.ws_limit = None        # bytes of workspace handed to the library at most (None: what it asks for)
         self._retired = []          # outgrown workspaces: kept, kernels already enqueued may still use them
+        self._ws_need = {}          # M -> bytes the library wants (asked once per M)
 
     def workspace_for(self, M: int):
         """(pointer, bytes) of a zero-initialised workspace of the size the library wants for M rows."""
-        need = max(256, tw_gemm_workspace(self.blob, M))
+        need = self._ws_need.get(M)
+        if need is None:
+            need = self._ws_need[M] = max(256, tw_gemm_workspace(self.blob, M))
         if self.ws_limit is not None:
             need = max(256, min(need, int(self.ws_limit)))
         if need > self.workspace.numel():

@@ -1277,7 +1277,14 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             auto commit = [&](const ARegs<AB>& ar, int j) {
                 if (j < n_loc) stage_commit<MSB, AB, TRANS>(p, ar, smem + (j & 1) * p.abuf_bytes, chunk_width(j), wave, lane);
             };
-            {
+            // Split K: the item's first chunk is requested before anything waits for the tile's descriptor (the
+            // descriptor, the table of first steps and the first packed weights are three dependent round trips to
+            // memory, and an item is only a few chunks long); written to LDS below, behind the first requests for
+            // packed weights.  (Not in the unsplit kernel: the registers it takes there cost more than it gains.)
+            ARegs<AB> first;
+            if constexpr (SPLIT) {
+                issue_or_zero(first, 0);
+            } else {
                 const int kw = chunk_width(0);
                 if constexpr (TRANS) load_at_block<MSB, AB, NTA>(p, smem, row0, c_first * p.k_chunk, kw, wave, lane, tid);
                 else load_a_block<MSB, AB, kPairStream, NTA>(p, smem, row0, c_first * p.k_chunk, kw, wave, lane, tid);
@@ -1325,6 +1332,11 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (j + 1 < n_loc) prefetch_steps(b0, b1); else prefetch_steps(0, 0);
             };
             prefetch_steps(b0, b1);
+            if constexpr (SPLIT) {
+                commit(first, 0);
+                a_zero_row(p, smem, BM, tid);
+                a_zero_row(p, smem + p.abuf_bytes, BM, tid);
+            }
             if constexpr (kAhead == 1) {
                 __syncthreads();
                 for (int j = 0; j < n_loc; ++j) {
