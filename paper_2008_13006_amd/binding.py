@@ -232,7 +232,10 @@ def tw_gemm_workspace(blob: np.ndarray, M: int) -> int:
 
 
 class TwWeight:
-    """A packed weight resident on one GPU: host blob, device copy and a zeroed workspace."""
+    """A packed weight resident on one GPU: host blob, device copy and a workspace (zeroed scheduler counters and,
+    for few rows and a long K, room for the partial results of a split-K plan).  The library's rule applies:
+    calls on ONE workspace must not overlap in time, so launches of one weight that may run concurrently (two
+    streams) need a TwWeight each: `sibling()` gives another one on the same device copy of the blob."""
 
     def __init__(self, blob: np.ndarray, device="cuda:0"):
         torch = _torch()
@@ -245,6 +248,15 @@ class TwWeight:
         self.ws_limit = None        # bytes of workspace handed to the library at most (None: what it asks for)
         self._retired = []          # outgrown workspaces: kept, kernels already enqueued may still use them
         self._ws_need = {}          # M -> bytes the library wants (asked once per M)
+
+    def sibling(self):
+        """Another TwWeight on the same host and device copy of the blob, with a workspace of its own."""
+        torch = _torch()
+        other = object.__new__(TwWeight)
+        other.blob, other.info, other.dtype, other.blob_dev = self.blob, self.info, self.dtype, self.blob_dev
+        other.workspace = torch.zeros(256, dtype=torch.uint8, device=self.workspace.device)
+        other.ws_limit, other._retired, other._ws_need = self.ws_limit, [], {}
+        return other
 
     def workspace_for(self, M: int):
         """(pointer, bytes) of a zero-initialised workspace of the size the library wants for M rows."""

@@ -190,6 +190,34 @@ def test_tw_gemm_is_deterministic_and_workspace_reusable(tw):
     assert torch.equal(C1, C2) and torch.equal(C1, C3)
 
 
+def test_two_streams_with_a_workspace_each(tw):
+    """Launches of one weight on two streams that may overlap: a TwWeight (a workspace) per stream on one device copy
+    of the blob; a resident-K weight with more items than compute units (the counters are in use) and a split-K plan
+    (the workspace holds partial results)."""
+    for name, M, K, N, G in (("two_streams_resident", 20000, 256, 512, 128), ("two_streams_split", 512, 2304, 512, 128)):
+        spec = W.small_spec(name, M=M, K=K, N=N, G=G, dtype="f16", col_prune=0.05, keep=("upow", 0.1, 0.5), seed_offset=9900 + K)
+        w = W.generate(spec)
+        w0 = tw.TwWeight.from_dense(w.B, w.mask, G, "f16")
+        w1 = w0.sibling()
+        assert w1.blob_dev.data_ptr() == w0.blob_dev.data_ptr() and w1.workspace.data_ptr() != w0.workspace.data_ptr()
+        A = _device_A(tw, w.A, "f16")
+        ref = tw.tw_gemm(w0, A)
+        torch.cuda.synchronize()
+        s0, s1 = torch.cuda.Stream(), torch.cuda.Stream()
+        outs = [[], []]
+        for rep in range(6):
+            for wt, st, o in ((w0, s0, outs[0]), (w1, s1, outs[1])):
+                with torch.cuda.stream(st):
+                    o.append(tw.tw_gemm(wt, A, stream=st))
+        torch.cuda.synchronize()
+        for o in outs[0] + outs[1]:
+            assert torch.equal(o, ref)
+        for wt in (w0, w1):
+            assert wt.workspace.view(torch.int32)[:4].cpu().tolist() == [0, 0, 0, 0]
+        _say(f"{name}: 2 x 6 launches on two streams, all equal to the single-stream result")
+    torch.cuda.empty_cache()
+
+
 def test_tw_gemm_strided_output(tw):
     _say("tw_gemm into a strided C")
     spec = W.small_spec("ldc", M=50, K=128, N=200, G=64, dtype="f16", col_prune=0.1, seed_offset=9900)
