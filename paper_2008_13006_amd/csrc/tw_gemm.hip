@@ -1826,7 +1826,7 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
         const double chunk_us = transposed ? kChunkUsT : kChunkUs;
         double best = rounds0 * (kItemUs + h->n_chunks * chunk_us * (h->ncb <= 2 ? kNarrowChunk : 1.0));
         int best_cpp = 0, best_tpw = 0;
-        for (int sets = 1; sets <= T; ++sets) {
+        for (int sets = 1; sets <= T && nmb1 * sets * 2 <= n_cu; ++sets) {   // (at least two parts in one round)
             const int tpw1 = (T + sets - 1) / sets;
             if (tpw1 > kWaves || (sets > 1 && (T + sets - 2) / (sets - 1) == tpw1)) continue;   // (as many tiles per set with fewer sets)
             for (int cpp = h->n_chunks - 1; cpp >= 1; --cpp) {
