@@ -151,10 +151,11 @@ typedef struct tw_plan_t {
                                 2: K streamed, four waves multiply (a tile each), four only load A */
     int32_t rows_per_block;  /* rows of A (tokens) of a work item: 64 or 32; tw_gemm may take a multiple of 8
                                 between them so that the row blocks fill the last round of workgroups */
-    int32_t tiles_per_set;   /* streamed K: tiles a workgroup holds (8 or 4); 0 with mode 0 */
+    int32_t tiles_per_set;   /* streamed K: tiles a workgroup holds (mode 1: 8; mode 2: 4, 2 or 1; a split-K plan: 1 to 8);
+                                0 with mode 0 */
     int32_t n_row_blocks;    /* ceil(M / rows_per_block) */
     int32_t n_sets;          /* mode 0: workgroups that share the tiles of a row block; else sets of tiles */
-    int32_t n_items;         /* work items = n_row_blocks * n_sets */
+    int32_t n_items;         /* work items = n_row_blocks * n_sets * k_parts */
     int32_t grid;            /* workgroups launched: min(n_items, n_cu), each pulls items until none is left */
     uint32_t lds_bytes;      /* on-chip memory per workgroup */
     int32_t row_lists;       /* tw_gemm_t, mode 2: the loading waves read only the K rows that the tiles keep */
@@ -179,7 +180,8 @@ int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transposed, tw_plan
  *              M x lda elements (what lies between K and that multiple is read and ignored)
  *   C          device, M x N, ldc >= N; EVERY element of C[0:M, 0:N] is written (zeros in pruned
  *              columns); 2-byte aligned rows suffice
- *   workspace  device, >= tw_gemm_workspace bytes, 256-byte aligned, zeroed as described above
+ *   workspace  device, at least 256 bytes (tw_gemm_workspace bytes for the fastest plan), 256-byte aligned, its
+ *              first 256 bytes zeroed as described above
  * M >= 0 (M = 0 enqueues nothing).  Calls on one workspace must not overlap in time (use one
  * workspace per stream).  The call enqueues kernels only (one; one more for a split-K plan, one more for a TEW
  * blob with residual weights in pruned columns) (no memset, no copy, no allocation), so it can be
@@ -187,7 +189,7 @@ int tw_gemm_plan(const void* blob_host, int M, int n_cu, int transposed, tw_plan
  * dynamic-LDS limit (a function attribute), so make one call of each kind before a stream capture.  The best speed needs a C base and ldc that are multiples of 64 elements
  * (128-byte lines); any other layout is correct and slower.
  * Errors: TW_ERR_ARG (null pointer, negative M, lda/ldc too small), TW_ERR_BUF (not a blob of this
- * format version, workspace too small), TW_ERR_ALIGN, TW_ERR_UNSUPPORTED (more than 2^31 work items),
+ * format version, workspace below 256 bytes), TW_ERR_ALIGN, TW_ERR_UNSUPPORTED (more than 2^31 work items),
  * TW_ERR_HIP (the launch failed); nothing is enqueued when an error is returned. */
 int tw_gemm(const void* blob_host, const void* blob_dev, const void* A, int M, int lda,
             void* C, int ldc, void* workspace, size_t ws_bytes, void* hip_stream);
