@@ -1701,7 +1701,18 @@ __global__ __launch_bounds__(256) void tw_xcol_t_kernel(const XcolParams p) {
     for (int j = blockIdx.y; j < p.n_cols; j += gridDim.y) {
         if (p.rank[j] < p.skip_below) continue;
         float acc = 0.f;
-        for (int e = p.ptr[j]; e < p.ptr[j + 1]; ++e)
+        int e = p.ptr[j];
+        const int e1 = p.ptr[j + 1];
+        // eight requests in flight per thread (one at a time, a column's 40 entries were 40 round trips to memory);
+        // the products are added in the order of the entries either way
+        for (; e + 8 <= e1; e += 8) {
+            unsigned short a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] = p.A[(long)p.k[e + u] * p.lda + m];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += tw_to_f32<DT>(p.v[e + u]) * tw_to_f32<DT>(a[u]);
+        }
+        for (; e < e1; ++e)
             acc += tw_to_f32<DT>(p.v[e]) * tw_to_f32<DT>(p.A[(long)p.k[e] * p.lda + m]);
         const int n = p.col[j];
         const float b = p.bias ? tw_to_f32<DT>(p.bias[n]) : 0.f;
