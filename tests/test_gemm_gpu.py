@@ -883,6 +883,35 @@ def test_random_big_shapes_on_sampled_rows(tw, seed):
     torch.cuda.empty_cache()
 
 
+def test_a_million_rows_byte_offsets_beyond_2_31(tw):
+    """The largest launch of the suite: 1 048 583 rows (a ragged last block, 16 385 row blocks: 65 rounds of
+    workgroups through the item counter), C of 2.3 GB so that byte offsets into C and into Ct pass 2^31.  Every
+    element against the oracle, both boundaries."""
+    M, K, N, G = 1048583, 64, 1100, 128
+    spec = W.small_spec("million_rows", M=M, K=K, N=N, G=G, dtype="f16", col_prune=0.4, keep=("upow", 0.2, 0.5),
+                        seed_offset=31000)
+    w = W.generate(spec)
+    wt = tw.TwWeight.from_dense(w.B, w.mask, G, "f16")
+    A = _device_A(tw, w.A, "f16")
+    C = torch.full((M, N), float("nan"), dtype=A.dtype, device="cuda:0")
+    assert C.numel() * 2 > 2 ** 31
+    tw.tw_gemm(wt, A, C)
+    At = _device_At(tw, w.A, "f16")
+    Ct = tw.tw_gemm_t(wt, At)
+    torch.cuda.synchronize()
+    assert wt.workspace.view(torch.int32)[:4].cpu().tolist() == [0, 0, 0, 0]
+    worst = worst_t = 0.0
+    chunk = 65536
+    for r0 in range(0, M, chunk):                      # the oracle once per block of rows, both outputs against it
+        r1 = min(M, r0 + chunk)
+        ref = tw_ref.masked_gemm(np.ascontiguousarray(w.A[r0:r1]), w.B, w.mask, "f16")
+        worst = max(worst, _assert_close(_to_f64(C[r0:r1]), ref, "f16", f"million rows {r0}..{r1}"))
+        worst_t = max(worst_t, _assert_close(_to_f64(Ct[:, r0:r1]).T, ref, "f16", f"million rows transposed {r0}..{r1}"))
+    _say(f"million rows: rel err {worst:.3e} / transposed {worst_t:.3e}")
+    del C, Ct, At, A
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ integer inputs: bit for bit, per kernel mode
 # A in {-3..3}, B in {-2..2}: every product and every partial sum is an integer that fp32 holds exactly, and the
 # result is exact in the storage type while |C| stays below 2^11 (fp16) or 2^8 (bf16); the cases assert that.
