@@ -1043,6 +1043,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
     ARegs<12> pre0, pre1;
     bool preloaded = false;
     int lists_of = -1;               // loading waves: the set whose row lists are in LDS
+    int par = 0;                     // MODE 2: chunk c of the item lives in LDS buffer (c + par) % 2 (see the ring below)
     for (int turn = 0;; ++turn) {
         if (tid == 0) {
             misc[0] = my_next;
@@ -1136,8 +1137,21 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                         if (lane == 0) my_cnt[c] = gc[c];
                     }
                 };
+                // Across items: the ring of chunks (chunk c in LDS buffer (c + par) % 2, waiting in register set c % 2)
+                // runs on into the NEXT item of the workgroup when that item has the same set of tiles: ring positions
+                // n_chunks, n_chunks + 1, .. are its chunks 0, 1, ..  They are requested during this item's last chunks
+                // and its chunk 0 is written to LDS while the multiplying waves work on this item's last chunk (the
+                // buffers alternate, so that buffer is free), which is the state that start_item would otherwise only
+                // begin to build when this item's steps are over.  With an odd number of chunks the buffers (`par`) and
+                // the register sets change roles from one item to the next.
+                // (`cross`, `nrow0`: set after the item's first barrier, where thread 0 has said which item comes next.)
+                const bool ring = p.n_chunks >= 3;
+                bool cross = false;
+                int nrow0 = 0;
                 auto issue_or_zero = [&](ARegs<PB>& ar, int c, int r0) {
-                    if (c < p.n_chunks) {
+                    const bool into_next = c >= p.n_chunks && cross && c - p.n_chunks < p.n_chunks;
+                    if (c < p.n_chunks || into_next) {
+                        if (into_next) { c -= p.n_chunks; r0 = nrow0; }
                         if (use_rows)
                             at_issue_rows<PB>(p, ar, r0, c * p.k_chunk, my_rows + c * kListEntries, uni(my_cnt[c]), lw, lane, NLD);
                         else
@@ -1148,12 +1162,14 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     }
                 };
                 auto commit = [&](const ARegs<PB>& ar, int c) {
-                    if (c < p.n_chunks) {
+                    const bool into_next = c >= p.n_chunks && cross && c - p.n_chunks < p.n_chunks;
+                    if (c < p.n_chunks || into_next) {
+                        unsigned char* buf = smem + ((c + par) & 1) * p.abuf_bytes;          // by ring position
+                        if (into_next) c -= p.n_chunks;
                         if (use_rows)
-                            at_commit_rows<PB>(p, ar, smem + (c & 1) * p.abuf_bytes, my_rows + c * kListEntries, uni(my_cnt[c]), lw,
-                                               lane, NLD);
+                            at_commit_rows<PB>(p, ar, buf, my_rows + c * kListEntries, uni(my_cnt[c]), lw, lane, NLD);
                         else
-                            stage_commit<MSB, PB, TRANS>(p, ar, smem + (c & 1) * p.abuf_bytes, chunk_width(c), lw, lane, NLD);
+                            stage_commit<MSB, PB, TRANS>(p, ar, buf, chunk_width(c), lw, lane, NLD);
                     }
                 };
                 // chunk j waits in register set j % 2; the loop is unrolled by two so that the sets are
@@ -1172,6 +1188,11 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     start_item(row0);
                 }
                 __syncthreads();
+                if (ring) {
+                    const int nxt = misc[2];
+                    cross = nxt < p.n_items && nxt / p.n_mblocks == set;
+                    nrow0 = (nxt % p.n_mblocks) * p.row_step;
+                }
                 for (int c = 0; c < p.n_chunks; c += 2) {
                     commit(ar1, c + 1);
                     issue_or_zero(ar1, c + 3, row0);
@@ -1182,12 +1203,18 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     }
                     __syncthreads();
                 }
-                // the multiplying waves are through with both buffers and have said which item comes next:
-                // its first chunks are brought in while they store this item's tiles
+                // the multiplying waves are through with both buffers; the next item's first chunks are brought in
+                // while they store this item's tiles, unless the ring has done that already
                 __syncthreads();
                 const int nxt = misc[2];
                 preloaded = nxt < p.n_items;
-                if (preloaded) {
+                par ^= p.n_chunks & 1;
+                if (preloaded && cross) {
+                    if (p.n_chunks & 1) {        // ring positions n+1 and n+2 are the next item's chunks 1 and 2: sets 1 and 0 there
+#pragma unroll
+                        for (int b = 0; b < PB; ++b) { const tw_u32x4 t = ar0.v[b]; ar0.v[b] = ar1.v[b]; ar1.v[b] = t; }
+                    }
+                } else if (preloaded) {
                     const int nset = nxt / p.n_mblocks;
                     if (use_rows && nset != lists_of) { load_lists(nset); lists_of = nset; }
                     start_item((nxt % p.n_mblocks) * p.row_step);
@@ -1220,15 +1247,17 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     }
                 };
                 auto steps_of = [&](int c) {
+                    const unsigned char* buf = smem + ((c + par) & 1) * p.abuf_bytes;
                     if (active && b0 < b1)
-                        run_steps<DT, MS, NCB>(acc, rg, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
-                    if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (c & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
+                        run_steps<DT, MS, NCB>(acc, rg, buf, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
+                    if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, buf, at_pitch_of<MS>(), lane);
                     // on to chunk c+1
                     b0 = b1; b1 = b2;
                     b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
                     if (c + 1 < p.n_chunks) prefetch_steps(b0, b1); else prefetch_steps(0, 0);
                 };
                 prefetch_steps(b0, b1);
+                if (tid == 0) misc[2] = my_next;   // the loading waves look one item ahead (requested at the top of this turn)
                 __syncthreads();
                 for (int c = 0; c < p.n_chunks; c += 2) {
                     steps_of(c);
@@ -1236,8 +1265,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     if (c + 1 < p.n_chunks) steps_of(c + 1);
                     __syncthreads();
                 }
-                if (tid == 0) misc[2] = my_next;   // requested at the start of the item: here by now
                 __syncthreads();
+                par ^= p.n_chunks & 1;
                 if (active) {
                     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
                     else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
