@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define TW_MAGIC 0x31425754u /* "TWB1" */
-#define TW_FORMAT_VERSION 12
+#define TW_FORMAT_VERSION 13
 
 // MFMA step geometry the packed values are laid out for: one step contracts 16 kept rows
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
@@ -52,13 +52,20 @@ struct TwHeader {
                              //   and per chunk, the chunk-local K rows that any tile of the set keeps (in its tile-wise
                              //   pattern or in its element-wise residual), ascending
     uint64_t off_ucnt;       // int32 [n_sets][n_chunks]: their number
-    // element-wise residual of the TEW hybrid (Sec. IV-A): the weights kept outside the tile-wise pattern, per
-    // tile and K chunk as planes of G entries (one per packed column): plane e of a (tile, chunk) holds every
-    // column's e-th residual entry inside that chunk,
-    int64_t ew_nnz;          //   number of residual weights (0: none)
-    uint64_t off_ew_ptr;     //   int32 [T*n_chunks+1]: first plane of every (tile, chunk), tiles in canonical order
-    uint64_t off_ew_k;       //   uint16 [planes][G]: chunk-local K row of the entry; k_chunk (the zero row) where a column has fewer
-    uint64_t off_ew_v;       //   16-bit [planes][G]: its weight; 0 for padding
+    // element-wise residual of the TEW hybrid (Sec. IV-A): the weights kept outside the tile-wise pattern, in the
+    // tile's kept columns.  They are multiplied on the matrix cores like the tile itself, column block by column
+    // block: per (tile, K chunk, column block) the K rows in which any of the block's 32 columns has a residual
+    // weight, 16 to a step (in fours that a transposing LDS read takes from different banks, as far as such fours
+    // go), with the block's weights of those rows (zero where there is none).  A residual step of a (tile, chunk)
+    // is one such step of every column block; blocks with fewer rows are padded (zero row, weight 0).
+    int64_t ew_nnz;          //   number of residual weights (0: none), those of off_xc_* included
+    uint64_t off_ew_ptr;     //   int32 [T*n_chunks+1]: first residual step of every (tile, chunk), tiles in canonical order
+    uint64_t off_ew_goff;    //   uint16 [rsteps][8][ncb][2]: chunk-local K row of slot 8*h + 4*r + q of column block cb at
+                             //   [4*h + q][cb][r] (a lane reads the indices of all its column blocks in one piece);
+                             //   k_chunk (the zero row) for unused slots
+    uint64_t off_ew_b;       //   16-bit [rsteps][ncb][64][8]: the weights, per column block laid out like a step of bvals
+    uint64_t off_ew_mask;    //   uint32 [rsteps][ncb][16]: bit n of word s: slot s of the block holds a residual weight of
+                             //   packed column 32*cb + n (host side: a stored weight may be zero)
     // residual weights in columns that the tile-wise pattern prunes altogether: stored by column (the CSC form the
     // paper names for the element-wise part, Sec. IV-A) and added by a pass of their own after the tiles' kernel
     uint64_t off_xc_col;     //   int32 [xc_n]: original column, ascending
@@ -67,12 +74,17 @@ struct TwHeader {
     uint64_t off_xc_v;       //   16-bit [entries]: its weight
     uint64_t off_xc_tile_ptr;//   int32 [T+1]: the columns of the list that lie in the span of tile t (canonical order) are
                              //   [xc_tile_ptr[t], xc_tile_ptr[t+1]) (the list is ascending and spans are disjoint)
-    uint64_t off_xc_rank;    //   int32 [xc_n]: position of the column among those of its tile; the kernel with K resident
-                             //   adds the first TW_XC_INLINE of a tile in that tile's epilogue, the rest (and everything
-                             //   in the other kernel modes) goes to the pass of its own
+    uint64_t off_xc_rank;    //   int32 [xc_n]: position of the column among those of its tile; on the row-major boundary
+                             //   the tile adds the first TW_XC_INLINE itself (see off_xm_ptr), the rest (and everything
+                             //   on the transposed boundary and in a split-K plan) goes to the pass of its own
     int32_t xc_overflow;     //   columns with rank >= TW_XC_INLINE
     int32_t reserved1;
-    uint8_t pad[384 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 20 - 4 * 2];
+    // the first TW_XC_INLINE residual-only columns of every tile once more, as one column block for the matrix
+    // cores (packed column j = the tile's j-th such column), in steps like those of off_ew_goff / off_ew_b
+    uint64_t off_xm_ptr;     //   int32 [T*n_chunks+1]: first step of every (tile, chunk), tiles in canonical order
+    uint64_t off_xm_goff;    //   uint16 [steps][16]: chunk-local K rows, slot order of off_goff; k_chunk for unused slots
+    uint64_t off_xm_b;       //   16-bit [steps][64][8]: the weights
+    uint8_t pad[384 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 21 - 4 * 2 - 8 * 3];
 };
 static_assert(sizeof(TwHeader) == 384, "header is 384 bytes");
 
@@ -103,7 +115,8 @@ struct TwSchedDesc {
     int32_t tile;        // canonical tile number (selects the dpos table)
     int32_t step_ptr;    // row of the step_ptr table (int32 units)
     int32_t first_step;  // first step in the goff / bvals tables
-    int32_t reserved;
+    int32_t xc;          // residual-only columns in the tile's span (TEW): xc_tile_ptr[tile] in the low 26 bits, above
+                         //   them min(their number, TW_XC_INLINE)
 };
 
 // Chunking policy: the whole K extent of a 32-row block stays resident in LDS when it fits next to

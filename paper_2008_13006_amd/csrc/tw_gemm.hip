@@ -43,6 +43,7 @@ constexpr int kIdxAhead = 6;  // steps the K indices are requested ahead (they f
                               // runs one step ahead of the MFMAs)
 
 typedef short tw_i16x4 __attribute__((ext_vector_type(4)));
+typedef float tw_f32x4 __attribute__((ext_vector_type(4)));
 
 struct TwGemmParams {
     const unsigned char* blob;  // device copy
@@ -63,7 +64,7 @@ struct TwGemmParams {
     unsigned stage_off;         // LDS offset of the per-wave staging areas
     unsigned misc_off;          // LDS offset of two ints (item, tile counter)
     uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_zero_ptr, off_zero_cols, off_urow, off_ucnt;
-    uint64_t off_ew_ptr, off_ew_k, off_ew_v;
+    uint64_t off_ew_ptr, off_ew_goff, off_ew_b, off_xm_ptr, off_xm_goff, off_xm_b;
     int has_ew;                 // the blob carries an element-wise residual (TEW)
     uint64_t off_xc_tile_ptr, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v;
     unsigned xbuf_off;          // LDS offset of the per-wave areas for residual-only columns (TEW), 0: the tiles' kernel
@@ -101,7 +102,7 @@ __device__ __forceinline__ int fresh(int x) {
 // outstanding vector stores.  The compiler places the wait at the first use, so a descriptor requested
 // early arrives while other work runs.
 struct TileU {
-    int w, span_start, span_w, nsteps, tile, step_ptr, first_step;
+    int w, span_start, span_w, nsteps, tile, step_ptr, first_step, xc;
 };
 typedef const __attribute__((address_space(4))) int* tw_const_int_ptr;
 __device__ __forceinline__ TileU fetch_tile(const TwGemmParams& p, int ti) {
@@ -111,7 +112,7 @@ __device__ __forceinline__ TileU fetch_tile(const TwGemmParams& p, int ti) {
     tw_const_int_ptr d = (tw_const_int_ptr)ua;
     TileU u;
     u.w = d[0]; u.span_start = d[1]; u.span_w = d[2]; u.nsteps = d[3];
-    u.tile = d[4]; u.step_ptr = d[5]; u.first_step = d[6];
+    u.tile = d[4]; u.step_ptr = d[5]; u.first_step = d[6]; u.xc = d[7];
     return u;
 }
 
@@ -495,67 +496,17 @@ template <int DT, int MS, int NCB, bool FUSED>
 __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
                                            unsigned char* stage, const unsigned (&dpos)[NCB], int row0, int lane_in,
                                            const unsigned char* at_resident = nullptr, unsigned short* xbuf = nullptr,
+                                           const int* xcols = nullptr,
                                            int pass0 = 0, int pass1 = 4 * MS) {
     // (pass0, pass1: the passes to run, each eight rows of the block; everything by default.  The second kernel
     // of a split-K product gives a wave one pass of a tile.)
     const int lane = fresh(lane_in);
     constexpr bool fused = FUSED;
     // Residual-only columns of a TEW blob inside this tile's span (Sec. IV-A "Hybrid Pattern": weights restored in a
-    // column that the tile-wise pattern pruned altogether).  With K resident the tile that owns the span computes
-    // them here, from the LDS copy of A, lane = row: C[row, n] = sum_e v_e * A[row, k_e]; the results wait in
-    // `xbuf` ([column][row], 16-bit) and every pass puts its eight rows of them into the staging window, where the
-    // pruned columns otherwise read back as zeros - so they leave with the tile's own stores.
-    int nx = 0, x0 = 0;
-    if (xbuf != nullptr) {                                   // wave-uniform
-        const int* xtp = (const int*)(p.blob + p.off_xc_tile_ptr);
-        x0 = fetch_int(xtp, d.tile);
-        nx = fetch_int(xtp, d.tile + 1) - x0;
-        nx = nx < TW_XC_INLINE ? nx : TW_XC_INLINE;
-        const int* xcol = (const int*)(p.blob + p.off_xc_col);
-        const int* xptr = (const int*)(p.blob + p.off_xc_ptr);
-        const int* xk = (const int*)(p.blob + p.off_xc_k);
-        const unsigned short* xv = (const unsigned short*)(p.blob + p.off_xc_v);
-        // The entries of the tile's columns are consecutive in the list.  They are fetched 64 at a time, one per
-        // lane, and handed to the whole wave with v_readlane, so that the loop below waits for memory once per 64
-        // entries and not once per entry; four LDS reads are in flight per lane.
-        const int pv = nx > 0 && lane <= nx ? xptr[x0 + lane] : 0;           // first entry of column lane, lane <= nx
-        const int e_end = nx > 0 ? __builtin_amdgcn_readlane(pv, nx) : 0;
-        int base = -64, kreg = 0;
-        float vreg = 0.f;
-        const unsigned char* arow = at_resident + lane * 2;
-        auto a_of = [&](int e) {                                             // A[row = lane, K row of entry e] (e uniform)
-            const int k = __builtin_amdgcn_readlane(kreg, e - base);
-            return tw_to_f32<DT>(*(const unsigned short*)(arow + (unsigned)k * at_pitch_of<MS>()));
-        };
-        auto v_of = [&](int e) { return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vreg), e - base)); };
-        for (int j = 0; j < nx; ++j) {
-            const int e0 = __builtin_amdgcn_readlane(pv, j), e1 = __builtin_amdgcn_readlane(pv, j + 1);
-            float sum = 0.f;
-            int e = e0;
-            while (e < e1) {
-                if (e - base >= 64) {                                        // wave-uniform: the next 64 entries
-                    base = e;
-                    const int mine = base + lane < e_end ? base + lane : e_end - 1;
-                    kreg = xk[mine];
-                    vreg = tw_to_f32<DT>(xv[mine]);
-                }
-                int lim = base + 64 < e1 ? base + 64 : e1;                   // entries of this column inside the batch
-                for (; e + 4 <= lim; e += 4) {
-                    const float a0 = a_of(e), a1 = a_of(e + 1), a2 = a_of(e + 2), a3 = a_of(e + 3);
-                    sum += v_of(e) * a0;
-                    sum += v_of(e + 1) * a1;
-                    sum += v_of(e + 2) * a2;
-                    sum += v_of(e + 3) * a3;
-                }
-                for (; e < lim; ++e) sum += v_of(e) * a_of(e);
-            }
-            if constexpr (FUSED) {
-                const int n = fetch_int(xcol, x0 + j);
-                sum = tw_activate(sum + (p.bias != nullptr ? tw_to_f32<DT>(p.bias[n]) : 0.f), p.act);
-            }
-            xbuf[j * 64 + lane] = tw_cvt<DT>(sum);
-        }
-    }
+    // column that the tile-wise pattern pruned altogether).  With K resident the tile that owns the span has computed
+    // them (xc_columns) into `xbuf` (16-bit, [column][row % 8][row / 8]); every pass puts its eight rows of them into the staging
+    // window, where the pruned columns otherwise read back as zeros - so they leave with the tile's own stores.
+    const int nx = xbuf != nullptr ? (int)((unsigned)d.xc >> 26) : 0;   // wave-uniform
     EpiBias<NCB> eb;
     if constexpr (FUSED) {
         fetch_epi_bias<DT, NCB>(p, d, dpos, eb, lane);
@@ -612,9 +563,15 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
             xpos[g] = nullptr;
             const int j = 8 * g + (lane >> 3);
             if (j < nx) {
-                const unsigned rel = (unsigned)(((const int*)(p.blob + p.off_xc_col))[x0 + j] - win0);
+                const unsigned rel = (unsigned)(xcols[g] - win0);
                 if (rel < (unsigned)kWinCols) xpos[g] = stage + ((lane >> 2) & 1) * kPlaneBytes + rel * 8u + (lane & 3) * 2;
             }
+        }
+        tw_u32x4 xq[TW_XC_INLINE / 8];                       // this lane's row of its columns, all passes
+#pragma unroll
+        for (int g = 0; g < TW_XC_INLINE / 8; ++g) {
+            xq[g] = tw_u32x4{0u, 0u, 0u, 0u};
+            if (nx > 0) xq[g] = *(const tw_u32x4*)(xbuf + (8 * g + (lane >> 3)) * 64 + (lane & 7) * 8);
         }
         auto write_pass = [&](int P) {
             const int ms = P >> 2, q = P & 3;
@@ -629,7 +586,7 @@ __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d
 #pragma unroll
                 for (int g = 0; g < TW_XC_INLINE / 8; ++g)
                     if (xpos[g] != nullptr)
-                        *(unsigned short*)xpos[g] = xbuf[(8 * g + (lane >> 3)) * 64 + 8 * P + (lane & 7)];
+                        *(unsigned short*)xpos[g] = (unsigned short)(xq[g][P >> 1] >> (16 * (P & 1)));
             }
         };
 
@@ -939,48 +896,6 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
     }
 }
 
-// Element-wise residual of the TEW hybrid (Sec. IV-A): the weights kept outside the tile-wise pattern are
-// added to the tile's accumulators after the MFMA steps, by linearity.  The paper runs this part as a
-// separate sparse product on the scalar cores; here it rides on the LDS copy of A: a lane owns a packed
-// column, so for each of that column's residual entries (K row k, weight v) it reads the column's 32*MS
-// activations of row k from LDS (8-byte pieces: four consecutive rows of the block) and adds v * A.
-// Entries come in planes of G (one per packed column, padded with weight 0 at the zero row).
-template <int DT, int MS, int NCB>
-__device__ __forceinline__ void add_ew_residual(const TwGemmParams& p, int tile, int chunk, tw_f32x16 (&acc)[MS][NCB],
-                                                const unsigned char* at, unsigned at_pitch, int lane_in) {
-    const int lane = fresh(lane_in);
-    const int n = lane & 31, h = lane >> 5;
-    const int* ep = (const int*)(p.blob + p.off_ew_ptr);
-    const int pi = tile * p.n_chunks + chunk;      // planes of this tile inside this K chunk (`at` holds the chunk)
-    const int e0 = fetch_int(ep, pi), e1 = fetch_int(ep, pi + 1);
-    const unsigned short* ek = (const unsigned short*)(p.blob + p.off_ew_k) + n;
-    const unsigned short* ev = (const unsigned short*)(p.blob + p.off_ew_v) + n;
-    constexpr int G = 32 * NCB;
-    for (int e = e0; e < e1; ++e) {
-        unsigned k[NCB];
-        float v[NCB];
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-            k[cb] = ek[(long)e * G + 32 * cb];
-            v[cb] = tw_to_f32<DT>(ev[(long)e * G + 32 * cb]);
-        }
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-            const unsigned char* row = at + k[cb] * at_pitch + 8 * h;
-#pragma unroll
-            for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const tw_u32x2 a = *(const tw_u32x2*)(row + (32 * ms + 8 * q) * 2);
-                    acc[ms][cb][4 * q + 0] += v[cb] * tw_to_f32<DT>((unsigned short)a.x);
-                    acc[ms][cb][4 * q + 1] += v[cb] * tw_to_f32<DT>((unsigned short)(a.x >> 16));
-                    acc[ms][cb][4 * q + 2] += v[cb] * tw_to_f32<DT>((unsigned short)a.y);
-                    acc[ms][cb][4 * q + 3] += v[cb] * tw_to_f32<DT>((unsigned short)(a.y >> 16));
-                }
-        }
-    }
-}
-
 template <int MS, int NCB>
 __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 #pragma unroll
@@ -989,6 +904,261 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[ms][cb][r] = 0.f;
+}
+
+// Element-wise residual of the TEW hybrid (Sec. IV-A): the weights kept outside the tile-wise pattern, in the
+// tile's kept columns, are added to the tile's accumulators after the tile's own steps, by linearity.  The paper
+// runs this part as a separate sparse product on the scalar cores; here it runs on the matrix cores out of the
+// same LDS copy of A: per column block of 32 columns the packer lists the K rows in which the block has residual
+// weights, 16 to a step, with the block's weights of those rows (mostly zeros).  One residual step is one such
+// step of every column block: NCB gathers of A (each block has its own rows), NCB pieces of weights, MS * NCB
+// MFMAs.  At 1 % of the weights a block of 32 columns touches about a quarter of the K rows, so the residual
+// costs about as many MFMAs as the tile itself, where one fused multiply-add per row and weight on the vector
+// units cost five times that.
+// Same pipeline as run_steps: weights kDepth steps ahead, K rows kIdx steps ahead, the gather kRing - 1 column
+// blocks ahead of the MFMAs that use it.
+// Steps [s0, s1), not empty, of the tables `goff` (uint16 [steps][8][NCB][2]) and `bw` (16-bit [steps][NCB][64][8]).
+template <int NCB>
+struct BlockRegs {
+    static constexpr int kDepth = 2, kIdx = NCB <= 2 ? 6 : 3;
+    unsigned kk[kIdx][NCB];
+    tw_u16x8 bq[kDepth][NCB];
+};
+template <int NCB>
+__device__ __forceinline__ void block_load_k(BlockRegs<NCB>& r, int slot, const unsigned char* gk, int s, int last) {
+    s = s < last ? s : last;
+    const unsigned char* q = gk + (long)s * (32 * NCB);
+    if constexpr (NCB == 4) {
+        const tw_u32x4 t = *(const tw_u32x4*)q;
+        r.kk[slot][0] = t.x; r.kk[slot][1] = t.y; r.kk[slot][2] = t.z; r.kk[slot][3] = t.w;
+    } else if constexpr (NCB == 2) {
+        const tw_u32x2 t = *(const tw_u32x2*)q;
+        r.kk[slot][0] = t.x; r.kk[slot][1] = t.y;
+    } else {
+        r.kk[slot][0] = *(const unsigned*)q;
+    }
+}
+// Requests the first steps of [s0, s1) (not empty).  The requests keep this order (first needed first): a wait for
+// the first one must not wait for them all, and the loop's wait counts are the weaker of what its entry and its
+// back edge allow.
+template <int NCB>
+__device__ __forceinline__ void request_block_steps(BlockRegs<NCB>& r, const unsigned char* goff, const unsigned char* bw,
+                                                    int s0, int s1, int lane_in) {
+    const int lane = fresh(lane_in);
+    const unsigned char* gk = goff + ((lane >> 5) * 4 + ((lane & 15) >> 2)) * (NCB * 4);
+    const unsigned char* bl = bw + lane * 16;
+    const int last = s1 - 1;
+#pragma unroll
+    for (int i = 0; i < BlockRegs<NCB>::kIdx; ++i) {
+        block_load_k<NCB>(r, i, gk, s0 + i, last);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < BlockRegs<NCB>::kDepth; ++i) {
+        const int s = s0 + i < last ? s0 + i : last;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            r.bq[i][cb] = *(const tw_u16x8*)(bl + ((long)s * NCB + cb) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+// Expects the first steps in `r` (request_block_steps).
+template <int DT, int MS, int NCB>
+__device__ __forceinline__ void run_block_steps(tw_f32x16 (&acc)[MS][NCB], BlockRegs<NCB>& r, const unsigned char* at,
+                                                unsigned at_pitch, const unsigned char* goff, const unsigned char* bw,
+                                                int s0, int s1, int lane_in) {
+    const int lane = fresh(lane_in);
+    const int h = lane >> 5, j = lane & 15;
+    const unsigned lanebase = (unsigned)(((lane >> 4) & 1) * 16 + (j & 3) * 4) * 2;
+    const unsigned char* gk = goff + (h * 4 + (j >> 2)) * (NCB * 4);   // this lane's K rows of a step
+    const unsigned char* bl = bw + lane * 16;
+    const int last = s1 - 1;
+    constexpr int kDepth = BlockRegs<NCB>::kDepth, kIdx = BlockRegs<NCB>::kIdx, kUnroll = 6;
+    auto& kk = r.kk;
+    auto& bq = r.bq;
+    auto load_k = [&](int slot, int s) { block_load_k<NCB>(r, slot, gk, s, last); };
+    auto gather = [&](tw_u16x8 (&a)[MS], unsigned k2) {
+        const unsigned a0 = (k2 & 0xFFFFu) * at_pitch + lanebase;
+        const unsigned a1 = (k2 >> 16) * at_pitch + lanebase;
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms) {
+            const tw_i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) tw_i16x4*)(at + a0 + ms * 64));
+            const tw_i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) tw_i16x4*)(at + a1 + ms * 64));
+            a[ms] = tw_u16x8{(unsigned short)lo4[0], (unsigned short)lo4[1], (unsigned short)lo4[2],
+                             (unsigned short)lo4[3], (unsigned short)hi4[0], (unsigned short)hi4[1],
+                             (unsigned short)hi4[2], (unsigned short)hi4[3]};
+        }
+    };
+    constexpr int kRing = 2;   // (four buffers, the gather three column blocks ahead: no faster, 16 registers more)
+    static_assert((kUnroll * NCB) % kRing == 0 && (kRing - 1 + NCB - 1) / NCB < kIdx, "ring of gather buffers");
+    tw_u16x8 a[kRing][MS];
+#pragma unroll
+    for (int m = 0; m < kRing; ++m)
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms) a[m][ms] = tw_u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int m = 0; m < kRing - 1; ++m) gather(a[m], kk[m / NCB][m % NCB]);
+    auto step = [&](int i, int s) {
+        const int sb = (s + kDepth) < last ? (s + kDepth) : last;
+        const unsigned char* bnext = bl + ((long)sb * NCB) * 1024;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            const int m = i * NCB + cb, ahead = cb + kRing - 1;
+            gather(a[(m + kRing - 1) % kRing], kk[(i + ahead / NCB) % kIdx][ahead % NCB]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms)
+                acc[ms][cb] = tw_mfma<DT>(a[m % kRing][ms], bq[i % kDepth][cb], acc[ms][cb]);
+            __builtin_amdgcn_sched_barrier(0);
+            bq[i % kDepth][cb] = *(const tw_u16x8*)(bnext + cb * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        load_k(i % kIdx, s + kIdx);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int s = s0;
+    for (; s + kUnroll <= s1; s += kUnroll) {
+#pragma unroll
+        for (int i = 0; i < kUnroll; ++i) step(i, s + i);
+    }
+    const int rest = s1 - s;
+#pragma unroll
+    for (int i = 0; i < kUnroll - 1; ++i)
+        if (i < rest) step(i, s + i);
+}
+
+template <int DT, int MS, int NCB>
+__device__ __forceinline__ void add_ew_residual(const TwGemmParams& p, int tile, int chunk, tw_f32x16 (&acc)[MS][NCB],
+                                                const unsigned char* at, unsigned at_pitch, int lane) {
+    const int* ep = (const int*)(p.blob + p.off_ew_ptr);
+    const int pi = tile * p.n_chunks + chunk;      // residual steps of this tile inside this K chunk (`at` holds the chunk)
+    const int s0 = fetch_int(ep, pi), s1 = fetch_int(ep, pi + 1);
+    if (s0 != s1) {
+        BlockRegs<NCB> r;
+        request_block_steps<NCB>(r, p.blob + p.off_ew_goff, p.blob + p.off_ew_b, s0, s1, lane);
+        run_block_steps<DT, MS, NCB>(acc, r, at, at_pitch, p.blob + p.off_ew_goff, p.blob + p.off_ew_b, s0, s1, lane);
+    }
+}
+
+// Residual-only columns inside a tile's span (weights restored in a column that the tile-wise pattern pruned
+// altogether), row-major boundary: the first TW_XC_INLINE of a tile are multiplied like one more column block
+// (packed column j = the tile's j-th such column; per K chunk the steps hold the K rows in which any of them has a
+// weight) and put into `xbuf` (16-bit, [column][row % 8][row / 8]: the eight rows that one lane of the epilogue
+// puts into the staging window, one per pass, lie side by side; act(. + bias) applied if FUSED), from where the
+// tile's epilogue takes them.  With K streamed their fp32 sums wait between the chunks in the wave's staging
+// area, which only the epilogue uses otherwise.
+struct XcSteps {
+    int s0, s1;
+    BlockRegs<1> r;
+};
+__device__ __forceinline__ int xc_count(const TileU& d) { return (int)((unsigned)d.xc >> 26); }
+// original column of the tile's residual-only columns l / 8 and l / 8 + 8 for lane l (what the epilogue needs)
+__device__ __forceinline__ void xc_column_numbers(const TwGemmParams& p, const TileU& d, int (&col)[TW_XC_INLINE / 8], int lane) {
+    const int x0 = d.xc & 0x3FFFFFF, nx = xc_count(d);
+    const int* xcol = (const int*)(p.blob + p.off_xc_col);
+#pragma unroll
+    for (int g = 0; g < TW_XC_INLINE / 8; ++g) {
+        col[g] = 0;
+        const int j = 8 * g + (fresh(lane) >> 3);
+        if (nx > 0) col[g] = xcol[x0 + (j < nx ? j : nx - 1)];   // wave-uniform condition
+    }
+}
+__device__ __forceinline__ void xc_request(const TwGemmParams& p, const TileU& d, int chunk, XcSteps& x, int lane) {
+    x.s0 = x.s1 = 0;
+    if (xc_count(d) == 0) return;                            // wave-uniform
+    const int* xp = (const int*)(p.blob + p.off_xm_ptr) + d.tile * p.n_chunks + chunk;
+    x.s0 = fetch_int(xp, 0);
+    x.s1 = fetch_int(xp, 1);
+    if (x.s0 != x.s1) request_block_steps<1>(x.r, p.blob + p.off_xm_goff, p.blob + p.off_xm_b, x.s0, x.s1, lane);
+}
+template <int DT, int MS, bool FUSED>
+__device__ __forceinline__ void xc_store(const TwGemmParams& p, const TileU& d, const tw_f32x16 (&acc)[MS][1],
+                                         unsigned short* xbuf, int lane) {
+    const int n = lane & 31, h = lane >> 5;
+    if (n < xc_count(d)) {
+        float bias = 0.f;
+        if constexpr (FUSED)
+            if (p.bias != nullptr) bias = tw_to_f32<DT>(p.bias[((const int*)(p.blob + p.off_xc_col))[(d.xc & 0x3FFFFFF) + n]]);
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {                    // rows 32*ms + 8*q + 4*h + i, q = 0..3
+                float v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v[q] = acc[ms][0][4 * q + i];
+                    if constexpr (FUSED) v[q] = tw_activate(v[q] + bias, p.act);
+                }
+                tw_u32x2 o;
+                o.x = (unsigned)tw_cvt<DT>(v[0]) | ((unsigned)tw_cvt<DT>(v[1]) << 16);
+                o.y = (unsigned)tw_cvt<DT>(v[2]) | ((unsigned)tw_cvt<DT>(v[3]) << 16);
+                *(tw_u32x2*)(xbuf + n * 64 + (4 * h + i) * 8 + 4 * ms) = o;
+            }
+    }
+}
+// K resident: everything at once
+template <int DT, int MS, bool FUSED>
+__device__ __forceinline__ void xc_columns(const TwGemmParams& p, const TileU& d, XcSteps& x, const unsigned char* at,
+                                           unsigned at_pitch, unsigned short* xbuf, int lane) {
+    if (xc_count(d) == 0) return;                            // wave-uniform
+    tw_f32x16 acc[MS][1];
+    zero_acc<MS, 1>(acc);
+    if (x.s0 != x.s1)
+        run_block_steps<DT, MS, 1>(acc, x.r, at, at_pitch, p.blob + p.off_xm_goff, p.blob + p.off_xm_b, x.s0, x.s1, lane);
+    xc_store<DT, MS, FUSED>(p, d, acc, xbuf, lane);
+}
+// K streamed: the sums of the 16 columns between chunks, fp32, piece (ms, q) of lane (h, n < 16) at float offset
+// (((4 * ms + q) * 32 + 16 * h + n) * 4 of `area` (4 KB with 64 rows)
+static_assert(TW_XC_INLINE == 16 && 2 * 4 * 32 * 16 <= (int)kStageBytes, "partial sums of the residual-only columns fit the staging area");
+template <int MS>
+__device__ __forceinline__ void xc_zero_partial(const TileU& d, unsigned char* area, int lane) {
+    if (xc_count(d) == 0) return;                            // wave-uniform
+#pragma unroll
+    for (int i = 0; i < MS * 2; ++i) *(tw_u32x4*)(area + (i * 64 + lane) * 16) = tw_u32x4{0u, 0u, 0u, 0u};
+}
+template <int MS>
+__device__ __forceinline__ void xc_load_partial(tw_f32x16 (&acc)[MS][1], const unsigned char* area, int lane) {
+    zero_acc<MS, 1>(acc);
+    const int n = lane & 31, h = lane >> 5;
+    if (n < 16) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const tw_f32x4 v = *(const tw_f32x4*)(area + (((4 * ms + q) * 32 + 16 * h + n) * 16));
+                acc[ms][0][4 * q + 0] = v.x; acc[ms][0][4 * q + 1] = v.y; acc[ms][0][4 * q + 2] = v.z; acc[ms][0][4 * q + 3] = v.w;
+            }
+    }
+}
+template <int DT, int MS>
+__device__ __forceinline__ void xc_chunk(const TwGemmParams& p, const TileU& d, int chunk, const unsigned char* at,
+                                         unsigned at_pitch, unsigned char* area, int lane) {
+    XcSteps x;
+    xc_request(p, d, chunk, x, lane);
+    if (x.s0 == x.s1) return;                                // wave-uniform
+    tw_f32x16 acc[MS][1];
+    xc_load_partial<MS>(acc, area, lane);
+    run_block_steps<DT, MS, 1>(acc, x.r, at, at_pitch, p.blob + p.off_xm_goff, p.blob + p.off_xm_b, x.s0, x.s1, lane);
+    const int n = lane & 31, h = lane >> 5;
+    if (n < 16) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(tw_f32x4*)(area + (((4 * ms + q) * 32 + 16 * h + n) * 16)) =
+                    tw_f32x4{acc[ms][0][4 * q + 0], acc[ms][0][4 * q + 1], acc[ms][0][4 * q + 2], acc[ms][0][4 * q + 3]};
+    }
+}
+template <int DT, int MS, bool FUSED>
+__device__ __forceinline__ void xc_finish(const TwGemmParams& p, const TileU& d, const unsigned char* area,
+                                          unsigned short* xbuf, int lane) {
+    if (xc_count(d) == 0) return;                            // wave-uniform
+    tw_f32x16 acc[MS][1];
+    xc_load_partial<MS>(acc, area, lane);
+    xc_store<DT, MS, FUSED>(p, d, acc, xbuf, lane);
 }
 
 // MODE 0: the K extent of a row block of 32*MS rows is resident in LDS, waves pull whole tiles.
@@ -1003,7 +1173,6 @@ __device__ __forceinline__ void zero_acc(tw_f32x16 (&acc)[MS][NCB]) {
 // Split K: a wave's fp32 results of its part of the K chunks, as they lie in the registers: piece (ms, cb, q) of
 // lane l (registers 4q .. 4q+3 of acc[ms][cb]) at float offset (((ms * NCB + cb) * 4 + q) * 64 + l) * 4, so that
 // every instruction writes (reads) 1 KB of consecutive memory.  32 KB per tile and part with 128-column tiles.
-typedef float tw_f32x4 __attribute__((ext_vector_type(4)));
 template <int MS, int NCB>
 __device__ __forceinline__ void dump_partial(float* dst, const tw_f32x16 (&acc)[MS][NCB], int lane) {
     // dst is wave-uniform: said to the compiler, the 32 stores share one vector offset (the lane's) on a scalar
@@ -1083,17 +1252,30 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
 #pragma unroll
                     for (int cb = 0; cb < NCB; ++cb) dpos[cb] = dp[cb];
                 }
+                // residual-only columns of the tile's span (TEW): multiplied first, while the tile's own first
+                // operands are on their way (their requests come first, so the wait for them is the shorter one)
+                unsigned short* xbuf = nullptr;
+                XcSteps xs;
+                int xcols[TW_XC_INLINE / 8];
+                if constexpr (!TRANS) {
+                    if (p.xbuf_off != 0) {
+                        xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
+                        xc_column_numbers(p, d, xcols, lane);
+                        xc_request(p, d, 0, xs, lane);
+                    }
+                }
                 StepRegs<NCB> rg;
                 prefetch_first_steps<NCB>(rg, p.blob + p.off_goff + (long)d.first_step * 32,
                                           p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
+                if constexpr (!TRANS)
+                    if (xbuf != nullptr) xc_columns<DT, MS, FUSED>(p, d, xs, smem, at_pitch_of<MS>(), xbuf, lane);
                 tw_f32x16 acc[MS][NCB];
                 zero_acc<MS, NCB>(acc);
                 run_steps<DT, MS, NCB>(acc, rg, smem, at_pitch_of<MS>(), p.blob + p.off_goff + (long)d.first_step * 32,
                                            p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
                 if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, at_pitch_of<MS>(), lane);
                 if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
-                else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, smem,
-                                                    p.xbuf_off != 0 ? (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64) : nullptr);
+                else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, smem, xbuf, xcols);
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
         } else if constexpr (MODE == 2) {
@@ -1228,6 +1410,16 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 }
                 tw_f32x16 acc[MS][NCB];
                 zero_acc<MS, NCB>(acc);
+                // residual-only columns of the tile's span (TEW): their sums wait in the staging area between chunks
+                unsigned short* xbuf = nullptr;
+                int xcols[TW_XC_INLINE / 8];
+                if constexpr (!TRANS) {
+                    if (p.xbuf_off != 0 && active) {
+                        xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
+                        xc_column_numbers(p, d, xcols, lane);
+                        xc_zero_partial<MS>(d, stage, lane);
+                    }
+                }
                 // the first steps of a chunk are requested at the end of the previous chunk's steps, so
                 // they arrive while the workgroup meets at the barrier
                 StepRegs<NCB> rg;
@@ -1251,6 +1443,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     if (active && b0 < b1)
                         run_steps<DT, MS, NCB>(acc, rg, buf, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
                     if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, buf, at_pitch_of<MS>(), lane);
+                    if constexpr (!TRANS)
+                        if (xbuf != nullptr) xc_chunk<DT, MS>(p, d, c, buf, at_pitch_of<MS>(), stage, lane);
                     // on to chunk c+1
                     b0 = b1; b1 = b2;
                     b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
@@ -1268,8 +1462,12 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 __syncthreads();
                 par ^= p.n_chunks & 1;
                 if (active) {
-                    if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
-                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                    if constexpr (TRANS) {
+                        store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                    } else {
+                        if (xbuf != nullptr) xc_finish<DT, MS, FUSED>(p, d, stage, xbuf, lane);
+                        store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, xbuf, xcols);
+                    }
                 }
             }
         } else {
@@ -1327,6 +1525,17 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             }
             tw_f32x16 acc[MS][NCB];
             zero_acc<MS, NCB>(acc);
+            // residual-only columns of the tile's span (TEW): their sums wait in the staging area between chunks
+            // (a split-K plan leaves them to the pass of their own)
+            unsigned short* xbuf = nullptr;
+            int xcols[TW_XC_INLINE / 8];
+            if constexpr (!TRANS && !SPLIT) {
+                if (p.xbuf_off != 0 && active) {
+                    xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
+                    xc_column_numbers(p, d, xcols, lane);
+                    xc_zero_partial<MS>(d, stage, lane);
+                }
+            }
             const int* sp = step_ptr + d.step_ptr;
             const unsigned char* gt = p.blob + p.off_goff + (long)d.first_step * 32;
             const unsigned char* bt = p.blob + p.off_bvals + (long)d.first_step * NCB * 1024;
@@ -1356,6 +1565,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (active && b0 < b1)
                     run_steps<DT, MS, NCB>(acc, rg, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
                 if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
+                if constexpr (!TRANS && !SPLIT)
+                    if (xbuf != nullptr) xc_chunk<DT, MS>(p, d, c, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), stage, lane);
                 b0 = b1; b1 = b2;
                 b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
                 if (j + 1 < n_loc) prefetch_steps(b0, b1); else prefetch_steps(0, 0);
@@ -1398,8 +1609,12 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if constexpr (SPLIT) {
                     dump_partial<MS, NCB>(p.partials + ((((long)part * p.n_mblocks + mb) * p.T + ti) * (long)(MS * NCB * 1024)), acc, lane);
                 } else {
-                    if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
-                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                    if constexpr (TRANS) {
+                        store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                    } else {
+                        if (xbuf != nullptr) xc_finish<DT, MS, FUSED>(p, d, stage, xbuf, lane);
+                        store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, xbuf, xcols);
+                    }
                 }
             }
         }
@@ -1484,7 +1699,7 @@ __global__ __launch_bounds__(64) void tw_splitk_reduce_kernel(const TwGemmParams
                 }
             }
     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, sub, sub + 1);
-    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, nullptr, sub, sub + 1);
+    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, nullptr, nullptr, sub, sub + 1);
 }
 
 }  // namespace
@@ -1888,7 +2103,7 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     // from lists they hold in LDS.  (The blob's row lists are per set of TW_SET_TILES(T) tiles: with other sets
     // the loading waves bring in whole chunks.)
     pl.xbuf_off = 0;
-    if (!transposed && resident && h->xc_n > 0) {
+    if (!transposed && h->xc_n > 0) {
         const unsigned need = kWaves * TW_XC_INLINE * 64 * 2;
         if (pl.lds_bytes + need <= kLdsLimit) { pl.xbuf_off = pl.lds_bytes; pl.lds_bytes += need; }
     }
@@ -1904,8 +2119,10 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     // block), all in one round; the tiles' fp32 results go to the workspace and a second kernel adds them in a
     // fixed order and stores C.  Both the number of parts and the tiles per set are chosen by the estimate below;
     // the split is taken when its estimate is lower and the caller's workspace holds the partial results.
+    // (Not where the tiles add the residual-only columns of a TEW blob themselves: a split leaves those to the pass
+    // of their own, which reads all of A once more - 92 against 46 us on the FFN-down of BERT-base at 512 rows.)
     pl.n_parts = 1; pl.chunks_per_part = h->n_chunks; pl.partial_bytes = 0;
-    if (!resident && msb == 2 && h->n_chunks >= 2) {
+    if (!resident && msb == 2 && h->n_chunks >= 2 && pl.xbuf_off == 0) {
         const long nmb1 = (M + 63) / 64;
         const size_t tile_bytes = (size_t)2 * h->ncb * 4096;          // fp32 results of a tile: 64 rows x G columns
         const int sub = transposed ? h->ncb : 8;                      // pieces of a tile in the second kernel
@@ -1931,7 +2148,7 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
             }
         }
         if (best_cpp > 0) {
-            pl.mode = 1; pl.tiles_per_set = best_tpw; pl.row_step = 64; pl.urow_off = 0;
+            pl.mode = 1; pl.tiles_per_set = best_tpw; pl.row_step = 64; pl.urow_off = 0; pl.xbuf_off = 0;
             pl.chunks_per_part = best_cpp;
             pl.n_parts = (h->n_chunks + best_cpp - 1) / best_cpp;
             pl.n_mblocks = (int)nmb1; pl.n_seg = (T + best_tpw - 1) / best_tpw;
@@ -2169,7 +2386,8 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt; p.urow_off = 0;
-    p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
+    p.off_ew_ptr = h->off_ew_ptr; p.off_ew_goff = h->off_ew_goff; p.off_ew_b = h->off_ew_b; p.has_ew = h->ew_nnz > 0;
+    p.off_xm_ptr = h->off_xm_ptr; p.off_xm_goff = h->off_xm_goff; p.off_xm_b = h->off_xm_b;
     p.stream_stores = ((uintptr_t)C & 127) == 0 && (ldc & 63) == 0;
     p.off_xc_tile_ptr = h->off_xc_tile_ptr; p.off_xc_col = h->off_xc_col; p.off_xc_ptr = h->off_xc_ptr;
     p.off_xc_k = h->off_xc_k; p.off_xc_v = h->off_xc_v; p.xbuf_off = pl.xbuf_off;
@@ -2260,7 +2478,8 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_dpos = h->off_dpos; p.off_bvals = h->off_bvals;
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt;
-    p.off_ew_ptr = h->off_ew_ptr; p.off_ew_k = h->off_ew_k; p.off_ew_v = h->off_ew_v; p.has_ew = h->ew_nnz > 0;
+    p.off_ew_ptr = h->off_ew_ptr; p.off_ew_goff = h->off_ew_goff; p.off_ew_b = h->off_ew_b; p.has_ew = h->ew_nnz > 0;
+    p.off_xm_ptr = h->off_xm_ptr; p.off_xm_goff = h->off_xm_goff; p.off_xm_b = h->off_xm_b;
     p.urow_off = pl.urow_off;
     p.off_xc_tile_ptr = h->off_xc_tile_ptr; p.off_xc_col = h->off_xc_col; p.off_xc_ptr = h->off_xc_ptr;
     p.off_xc_k = h->off_xc_k; p.off_xc_v = h->off_xc_v; p.xbuf_off = 0;

@@ -30,11 +30,12 @@ struct Layout {
     int64_t total_steps = 0;
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
         off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, off_zero_ptr,
-        off_zero_cols, off_urow, off_ucnt, off_ew_ptr, off_ew_k, off_ew_v, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v, off_xc_tile_ptr, off_xc_rank, bytes;
+        off_zero_cols, off_urow, off_ucnt, off_ew_ptr, off_ew_goff, off_ew_b, off_ew_mask, off_xm_ptr, off_xm_goff, off_xm_b, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v, off_xc_tile_ptr, off_xc_rank, bytes;
     int64_t ew_nnz = 0;
-    std::vector<int32_t> ew_ptr;   // planes per (tile, chunk), prefix sums
+    std::vector<int32_t> ew_ptr;   // residual steps per (tile, chunk), prefix sums
     // residual weights in columns without tile-wise weights, by column
     std::vector<int32_t> xc_col, xc_ptr, xc_k, xc_tile_ptr, xc_rank;
+    std::vector<int32_t> xm_ptr;   // K resident: steps of every tile's first TW_XC_INLINE such columns, prefix sums
     int32_t xc_overflow = 0;
 };
 
@@ -85,6 +86,57 @@ int analyse(const uint8_t* mask, int K, int N, int G, Tiling& tl) {
         tl.nnz += (int64_t)(tl.tile_col_ptr[t + 1] - tl.tile_col_ptr[t]) *
                   (tl.tile_row_ptr[t + 1] - tl.tile_row_ptr[t]);
     return TW_OK;
+}
+
+// K rows of [k0, k1) in which one of the packed columns [c_lo, c_hi) of the tiling has a residual weight (kept by
+// `ew`, not by the tile-wise mask), ascending; returns the number of such weights.
+int64_t residual_rows(const Tiling& tl, const uint8_t* mask, const uint8_t* ew, int N, int c_lo, int c_hi, int k0,
+                      int k1, std::vector<int32_t>& rows) {
+    rows.clear();
+    int64_t cnt = 0;
+    for (int k = k0; k < k1; ++k) {
+        int here = 0;
+        for (int c = c_lo; c < c_hi; ++c) {
+            const size_t i = (size_t)k * N + tl.col_idx[c];
+            here += ew[i] != 0 && mask[i] == 0;
+        }
+        if (here) rows.push_back(k);
+        cnt += here;
+    }
+    return cnt;
+}
+
+// Order of a column block's residual rows inside its steps.  A transposing LDS read of the kernel serves four
+// contraction slots (4*i .. 4*i+3 of a step) per 32 lanes, 64 bytes of each row; rows of the LDS copy of A are
+// 8 bytes more than a multiple of 128 bytes apart, so the four pieces cover the 64 banks once exactly when the four
+// K rows agree modulo 8 and differ in (k / 8) modulo 4.  Rows are dealt out in such fours as far as they go; the
+// rest follows in ascending order.  `base` is the first row of the chunk (LDS rows are chunk-local).
+void order_residual_rows(std::vector<int32_t>& rows, int base) {
+    std::vector<int32_t> bucket[32], out, rest;
+    for (int32_t k : rows) bucket[(k - base) & 31].push_back(k);
+    for (int c = 0; c < 8; ++c) {
+        size_t n = rows.size();
+        for (int i = 0; i < 4; ++i) n = std::min(n, bucket[c + 8 * i].size());
+        for (size_t j = 0; j < n; ++j)
+            for (int i = 0; i < 4; ++i) out.push_back(bucket[c + 8 * i][j]);
+        for (int i = 0; i < 4; ++i) rest.insert(rest.end(), bucket[c + 8 * i].begin() + n, bucket[c + 8 * i].end());
+    }
+    std::sort(rest.begin(), rest.end());
+    out.insert(out.end(), rest.begin(), rest.end());
+    rows.swap(out);
+}
+
+// K rows of [k0, k1) in which one of the first TW_XC_INLINE residual-only columns of tile t has a weight, in the
+// order of order_residual_rows.
+void inline_xc_rows(const Layout& lo, int t, int k0, int k1, std::vector<int32_t>& rows) {
+    rows.clear();
+    const int x0 = lo.xc_tile_ptr[t], x1 = std::min(lo.xc_tile_ptr[t + 1], x0 + TW_XC_INLINE);
+    for (int j = x0; j < x1; ++j)
+        for (int32_t q = lo.xc_ptr[j]; q < lo.xc_ptr[j + 1]; ++q)
+            if (lo.xc_k[q] >= k0 && lo.xc_k[q] < k1) rows.push_back(lo.xc_k[q]);
+    std::sort(rows.begin(), rows.end());
+    rows.erase(std::unique(rows.begin(), rows.end()), rows.end());
+    order_residual_rows(rows, k0);
 }
 
 void plan(const Tiling& tl, int K, int G, Layout& lo, const uint8_t* mask = nullptr, const uint8_t* ew = nullptr, int N = 0) {
@@ -141,30 +193,28 @@ void plan(const Tiling& tl, int K, int G, Layout& lo, const uint8_t* mask = null
         lo.off_urow = take(2 * (n_sets * lo.n_chunks * (size_t)lo.k_chunk + 1), 16);
     }
     {
-        // residual planes per (tile, chunk): the largest number of residual entries that any of the tile's
-        // columns has inside the chunk
+        // residual steps per (tile, chunk): what the column block with the most residual rows in the chunk needs
         const int nc = lo.n_chunks;
         lo.ew_ptr.assign((size_t)T * nc + 1, 0);
         lo.ew_nnz = 0;
         if (ew) {
+            std::vector<int32_t> rows;
             for (int t = 0; t < T; ++t)
                 for (int ch = 0; ch < nc; ++ch) {
                     const int k0 = ch * lo.k_chunk, k1 = std::min(K, k0 + lo.k_chunk);
-                    int emax = 0;
-                    for (int c = tl.tile_col_ptr[t]; c < tl.tile_col_ptr[t + 1]; ++c) {
-                        const int n = tl.col_idx[c];
-                        int cnt = 0;
-                        for (int k = k0; k < k1; ++k) cnt += ew[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0;
-                        lo.ew_nnz += cnt;
-                        emax = std::max(emax, cnt);
+                    int smax = 0;
+                    for (int c = tl.tile_col_ptr[t]; c < tl.tile_col_ptr[t + 1]; c += TW_COLBLK) {
+                        lo.ew_nnz += residual_rows(tl, mask, ew, N, c, std::min(c + TW_COLBLK, tl.tile_col_ptr[t + 1]), k0, k1, rows);
+                        smax = std::max(smax, ((int)rows.size() + TW_KSTEP - 1) / TW_KSTEP);
                     }
-                    lo.ew_ptr[(size_t)t * nc + ch + 1] = lo.ew_ptr[(size_t)t * nc + ch] + emax;
+                    lo.ew_ptr[(size_t)t * nc + ch + 1] = lo.ew_ptr[(size_t)t * nc + ch] + smax;
                 }
         }
-        const size_t planes = (size_t)lo.ew_ptr[(size_t)T * nc];
+        const size_t rsteps = (size_t)lo.ew_ptr[(size_t)T * nc];
         lo.off_ew_ptr = take(4 * ((size_t)T * nc + 1), 16);
-        lo.off_ew_k = take(2 * (planes * G + 1), 16);
-        lo.off_ew_v = take(2 * (planes * G + 1), 16);
+        lo.off_ew_goff = take(2 * 16 * (rsteps * lo.ncb + 1), 256);
+        lo.off_ew_b = take(2 * 512 * (rsteps * lo.ncb) + 16, 256);
+        lo.off_ew_mask = take(4 * 16 * (rsteps * lo.ncb) + 16, 16);
         // residual weights in columns that keep no tile-wise weight
         lo.xc_ptr.assign(1, 0);
         if (ew) {
@@ -198,6 +248,19 @@ void plan(const Tiling& tl, int K, int G, Layout& lo, const uint8_t* mask = null
             lo.xc_tile_ptr[T] = (int32_t)j;
             if (T == 0) lo.xc_overflow = (int32_t)lo.xc_col.size();
         }
+        lo.xm_ptr.assign((size_t)T * lo.n_chunks + 1, 0);
+        {
+            std::vector<int32_t> rows;
+            for (int t = 0; t < T; ++t)
+                for (int ch = 0; ch < lo.n_chunks; ++ch) {
+                    inline_xc_rows(lo, t, ch * lo.k_chunk, std::min(K, (ch + 1) * lo.k_chunk), rows);
+                    const size_t i = (size_t)t * lo.n_chunks + ch;
+                    lo.xm_ptr[i + 1] = lo.xm_ptr[i] + ((int32_t)rows.size() + TW_KSTEP - 1) / TW_KSTEP;
+                }
+        }
+        lo.off_xm_ptr = take(4 * lo.xm_ptr.size(), 16);
+        lo.off_xm_goff = take(2 * 16 * ((size_t)lo.xm_ptr.back() + 1), 256);
+        lo.off_xm_b = take(2 * 512 * (size_t)lo.xm_ptr.back() + 16, 256);
         lo.off_xc_tile_ptr = take(4 * ((size_t)T + 1), 16);
         lo.off_xc_rank = take(4 * (lo.xc_rank.size() + 1), 16);
         lo.off_xc_col = take(4 * (lo.xc_col.size() + 1), 16);
@@ -242,6 +305,7 @@ extern "C" int tw_pack_tew_size(const uint8_t* mask, const uint8_t* ew_mask, int
     if (rc) return rc;
     Layout lo;
     plan(tl, K, G, lo, mask, ew_mask, N);
+    if (lo.xc_col.size() >= (1u << 26)) return TW_ERR_UNSUPPORTED;   // TwSchedDesc::xc holds 26 bits of the list position
     *blob_bytes = (size_t)lo.bytes;
     return TW_OK;
 }
@@ -263,6 +327,7 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
     if (rc) return rc;
     Layout lo;
     plan(tl, K, G, lo, mask, ew_mask, N);
+    if (lo.xc_col.size() >= (1u << 26)) return TW_ERR_UNSUPPORTED;
     if (blob_bytes < lo.bytes) return TW_ERR_BUF;
 
     uint8_t* base = (uint8_t*)blob;
@@ -284,7 +349,9 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
     h->off_sched_desc = lo.off_sched_desc;
     h->off_zero_ptr = lo.off_zero_ptr; h->off_zero_cols = lo.off_zero_cols;
     h->off_urow = lo.off_urow; h->off_ucnt = lo.off_ucnt;
-    h->ew_nnz = lo.ew_nnz; h->off_ew_ptr = lo.off_ew_ptr; h->off_ew_k = lo.off_ew_k; h->off_ew_v = lo.off_ew_v;
+    h->ew_nnz = lo.ew_nnz; h->off_ew_ptr = lo.off_ew_ptr; h->off_ew_goff = lo.off_ew_goff; h->off_ew_b = lo.off_ew_b;
+    h->off_ew_mask = lo.off_ew_mask;
+    h->off_xm_ptr = lo.off_xm_ptr; h->off_xm_goff = lo.off_xm_goff; h->off_xm_b = lo.off_xm_b;
     h->xc_n = (int32_t)lo.xc_col.size();
     h->off_xc_col = lo.off_xc_col; h->off_xc_ptr = lo.off_xc_ptr; h->off_xc_k = lo.off_xc_k; h->off_xc_v = lo.off_xc_v;
     h->off_xc_tile_ptr = lo.off_xc_tile_ptr; h->off_xc_rank = lo.off_xc_rank; h->xc_overflow = lo.xc_overflow;
@@ -299,28 +366,39 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
     put(lo.off_tile_span, tl.tile_span);
     put(lo.off_step_ptr, lo.step_ptr);
 
-    // element-wise residual, planes of G entries per (tile, chunk)
+    // element-wise residual in the tiles' kept columns: steps of 16 rows per column block
     put(lo.off_ew_ptr, lo.ew_ptr);
     if (ew_mask && lo.ew_ptr[(size_t)tl.T * lo.n_chunks] > 0) {
-        uint16_t* ek = (uint16_t*)(base + lo.off_ew_k);
-        uint16_t* ev = (uint16_t*)(base + lo.off_ew_v);
+        uint16_t* eg = (uint16_t*)(base + lo.off_ew_goff);
+        uint16_t* eb = (uint16_t*)(base + lo.off_ew_b);
+        uint32_t* em = (uint32_t*)(base + lo.off_ew_mask);
         const uint16_t* Bw = (const uint16_t*)B;
-        const int nc = lo.n_chunks;
+        const int nc = lo.n_chunks, ncb = lo.ncb;
+        const size_t minis = (size_t)lo.ew_ptr[(size_t)tl.T * nc] * ncb;
+        for (size_t i = 0; i < minis * 16; ++i) eg[i] = (uint16_t)lo.k_chunk;   // weights and mask words are zero already
+        std::vector<int32_t> rows;
         for (int t = 0; t < tl.T; ++t) {
-            const int c0 = tl.tile_col_ptr[t], w = tl.tile_col_ptr[t + 1] - c0;
-            for (int e = lo.ew_ptr[(size_t)t * nc]; e < lo.ew_ptr[(size_t)(t + 1) * nc]; ++e)
-                for (int c = 0; c < G; ++c) { ek[(size_t)e * G + c] = (uint16_t)lo.k_chunk; ev[(size_t)e * G + c] = 0; }
+            const int c0 = tl.tile_col_ptr[t], c1 = tl.tile_col_ptr[t + 1];
             for (int ch = 0; ch < nc; ++ch) {
                 const int k0 = ch * lo.k_chunk, k1 = std::min(K, k0 + lo.k_chunk);
-                for (int c = 0; c < w; ++c) {
-                    const int n = tl.col_idx[c0 + c];
-                    int e = lo.ew_ptr[(size_t)t * nc + ch];
-                    for (int k = k0; k < k1; ++k)
-                        if (ew_mask[(size_t)k * N + n] != 0 && mask[(size_t)k * N + n] == 0) {
-                            ek[(size_t)e * G + c] = (uint16_t)(k - k0);
-                            ev[(size_t)e * G + c] = Bw[(size_t)k * ldb + n];
-                            ++e;
+                const size_t rs0 = (size_t)lo.ew_ptr[(size_t)t * nc + ch];
+                for (int cb = 0; c0 + cb * TW_COLBLK < c1; ++cb) {
+                    const int cl = c0 + cb * TW_COLBLK, chi = std::min(cl + TW_COLBLK, c1);
+                    residual_rows(tl, mask, ew_mask, N, cl, chi, k0, k1, rows);
+                    order_residual_rows(rows, k0);
+                    for (size_t j = 0; j < rows.size(); ++j) {
+                        const int k = rows[j];
+                        const size_t rs = rs0 + j / 16;
+                        const int kl = (int)(j % 16), half = kl / 8, e = kl % 8;
+                        eg[((rs * 8 + half * 4 + (e & 3)) * ncb + cb) * 2 + (e >> 2)] = (uint16_t)(k - k0);
+                        for (int c = cl; c < chi; ++c) {
+                            const size_t i = (size_t)k * N + tl.col_idx[c];
+                            if (ew_mask[i] == 0 || mask[i] != 0) continue;
+                            const int n = c - cl;
+                            eb[((rs * ncb + cb) * 64 + 32 * half + n) * 8 + e] = Bw[(size_t)k * ldb + tl.col_idx[c]];
+                            em[(rs * ncb + cb) * 16 + kl] |= 1u << n;
                         }
+                    }
                 }
             }
         }
@@ -338,6 +416,38 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
         for (size_t j = 0; j < lo.xc_col.size(); ++j)
             for (int32_t e = lo.xc_ptr[j]; e < lo.xc_ptr[j + 1]; ++e)
                 xv[e] = Bw[(size_t)lo.xc_k[e] * ldb + lo.xc_col[j]];
+    }
+
+    // the tiles' first residual-only columns as a column block for the matrix cores, chunk by chunk
+    put(lo.off_xm_ptr, lo.xm_ptr);
+    if (lo.xm_ptr.back() > 0) {
+        uint16_t* xg = (uint16_t*)(base + lo.off_xm_goff);
+        uint16_t* xb = (uint16_t*)(base + lo.off_xm_b);
+        const uint16_t* Bw = (const uint16_t*)B;
+        for (size_t i = 0; i < (size_t)lo.xm_ptr.back() * 16; ++i) xg[i] = (uint16_t)lo.k_chunk;
+        std::vector<int32_t> rows, slot_of(K, -1);
+        for (int t = 0; t < tl.T; ++t)
+            for (int ch = 0; ch < lo.n_chunks; ++ch) {
+                const int k0 = ch * lo.k_chunk, k1 = std::min(K, k0 + lo.k_chunk);
+                const size_t first = (size_t)lo.xm_ptr[(size_t)t * lo.n_chunks + ch];
+                inline_xc_rows(lo, t, k0, k1, rows);
+                for (size_t j = 0; j < rows.size(); ++j) {
+                    slot_of[rows[j]] = (int32_t)j;
+                    const size_t st = first + j / 16;
+                    const int kl = (int)(j % 16), half = kl / 8, e = kl % 8;
+                    xg[st * 16 + (half * 4 + (e & 3)) * 2 + (e >> 2)] = (uint16_t)(rows[j] - k0);
+                }
+                const int x0 = lo.xc_tile_ptr[t], x1 = std::min(lo.xc_tile_ptr[t + 1], x0 + TW_XC_INLINE);
+                for (int c = x0; c < x1; ++c)
+                    for (int32_t q = lo.xc_ptr[c]; q < lo.xc_ptr[c + 1]; ++q) {
+                        const int k = lo.xc_k[q];
+                        if (k < k0 || k >= k1) continue;
+                        const int j = slot_of[k];
+                        const size_t st = first + j / 16;
+                        const int kl = j % 16, half = kl / 8, e = kl % 8;
+                        xb[(st * 64 + 32 * half + (c - x0)) * 8 + e] = Bw[(size_t)k * ldb + lo.xc_col[c]];
+                    }
+            }
     }
 
     // pruned columns inside every span
@@ -467,7 +577,8 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
         const TwTileDesc& d = desc[dispatch[i]];
         sd[i].w = d.w; sd[i].span_start = d.span_start; sd[i].span_w = d.span_w; sd[i].nsteps = d.nsteps;
         sd[i].tile = dispatch[i]; sd[i].step_ptr = d.step_ptr; sd[i].first_step = d.first_step;
-        sd[i].reserved = 0;
+        const int32_t x0 = lo.xc_tile_ptr[dispatch[i]], nx = lo.xc_tile_ptr[dispatch[i] + 1] - x0;
+        sd[i].xc = (int32_t)((uint32_t)x0 | (uint32_t)std::min(nx, TW_XC_INLINE) << 26);
     }
     return TW_OK;
 }
@@ -532,21 +643,27 @@ extern "C" int tw_unpack(const void* blob, void* B_out, int ldb, uint8_t* mask_o
     // the element-wise residual: part of the weights the GEMM multiplies by
     if (h->ew_nnz > 0) {
         const int32_t* ep = (const int32_t*)(base + h->off_ew_ptr);
-        const uint16_t* ek = (const uint16_t*)(base + h->off_ew_k);
-        const uint16_t* ev = (const uint16_t*)(base + h->off_ew_v);
-        const int nc = h->n_chunks;
+        const uint16_t* eg = (const uint16_t*)(base + h->off_ew_goff);
+        const uint16_t* eb = (const uint16_t*)(base + h->off_ew_b);
+        const uint32_t* em = (const uint32_t*)(base + h->off_ew_mask);
+        const int nc = h->n_chunks, ncb = h->ncb;
         for (int t = 0; t < T; ++t) {
-            const int c0 = tcp[t], w = tcp[t + 1] - c0;
+            const int c0 = tcp[t];
             for (int ch = 0; ch < nc; ++ch)
-                for (int e = ep[(size_t)t * nc + ch]; e < ep[(size_t)t * nc + ch + 1]; ++e)
-                    for (int c = 0; c < w; ++c) {
-                        const int kl = ek[(size_t)e * h->G + c];
-                        if (kl >= h->k_chunk) continue;     // padding
-                        const int k = ch * h->k_chunk + kl;
-                        const int n = col_idx[c0 + c];
-                        if (mask_out) mask_out[(size_t)k * N + n] = 1;
-                        if (Bo) Bo[(size_t)k * ldb + n] = ev[(size_t)e * h->G + c];
-                    }
+                for (size_t rs = (size_t)ep[(size_t)t * nc + ch]; rs < (size_t)ep[(size_t)t * nc + ch + 1]; ++rs)
+                    for (int cb = 0; cb < ncb; ++cb)
+                        for (int kl = 0; kl < 16; ++kl) {
+                            const uint32_t bits = em[(rs * ncb + cb) * 16 + kl];
+                            if (bits == 0) continue;
+                            const int half = kl / 8, e = kl % 8;
+                            const int k = ch * h->k_chunk + eg[((rs * 8 + half * 4 + (e & 3)) * ncb + cb) * 2 + (e >> 2)];
+                            for (int n = 0; n < 32; ++n) {
+                                if (!((bits >> n) & 1u)) continue;
+                                const int col = col_idx[c0 + cb * TW_COLBLK + n];
+                                if (mask_out) mask_out[(size_t)k * N + col] = 1;
+                                if (Bo) Bo[(size_t)k * ldb + col] = eb[((rs * ncb + cb) * 64 + 32 * half + n) * 8 + e];
+                            }
+                        }
         }
         const int32_t* xcol = (const int32_t*)(base + h->off_xc_col);
         const int32_t* xptr = (const int32_t*)(base + h->off_xc_ptr);

@@ -1057,13 +1057,16 @@ def test_split_k_small_batches_of_the_ffn_down(tw, M):
     assert wu.workspace.numel() <= 4096
     _compare_whole(Cu, w.A, w.B, w.mask, dtype, what=spec.name + " small workspace")
     # the hybrid: residual weights inside the tiles' columns (added per chunk by the part that holds the chunk)
-    # and in pruned columns (the pass of their own runs behind the second kernel)
+    # and in pruned columns (transposed: the pass of their own runs behind the second kernel; row-major: the
+    # tiles add them themselves, which takes an unsplit plan)
     ew = tw.tw_restore_ew(w.B, w.mask, 0.01, dtype)
     union = (w.mask | ew).astype(np.uint8)
     wte = tw.TwWeight(tw.tw_pack_tew(w.B, w.mask, ew, spec.G, dtype))
     Ce = tw.tw_gemm(wte, A)
     Cet = tw.tw_gemm_t(wte, At)
     torch.cuda.synchronize()
+    assert wte.info["ew_nnz"] > 0 and tw.tw_gemm_plan(wte.blob, M, n_cu=n_cu, transposed=True)["k_parts"] == plt["k_parts"]
+    assert tw.tw_gemm_plan(wte.blob, M, n_cu=n_cu)["k_parts"] == 1
     _compare_whole(Ce, w.A, w.B, union, dtype, what=spec.name + " TEW")
     _compare_whole(Cet, w.A, w.B, union, dtype, transposed=True, what=spec.name + " TEW transposed")
     _say(f"split K {spec.name}: rel err {err:.3e} / transposed {errt:.3e}")

@@ -276,6 +276,13 @@ def test_tew_pack_round_trip_and_errors():
     union = (w.mask | ew).astype(np.uint8)
     assert np.array_equal(mu, union)
     assert np.array_equal(Bu, tw_ref.masked_weight_bits(w.B, union))
+    # a restored weight whose value is zero is still part of the mask (the residual is stored as blocks of
+    # weights for the matrix cores, most of them zero: which of them are weights is recorded apart)
+    Bz = w.B.copy()
+    kz, nz = np.argwhere((ew != 0) & w.mask.any(axis=0)[None, :])[5]
+    Bz[kz, nz] = 0
+    Buz, muz = tw.tw_unpack(tw.tw_pack_tew(Bz, w.mask, ew, spec.G, "f16"))
+    assert np.array_equal(muz, union) and np.array_equal(Buz, tw_ref.masked_weight_bits(Bz, union))
     # entries that the tile-wise pattern keeps anyway are ignored
     blob2 = tw.tw_pack_tew(w.B, w.mask, (ew | w.mask).astype(np.uint8), spec.G, "f16")
     assert tw.tw_info(blob2)["ew_nnz"] == int(ew.sum())
