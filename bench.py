@@ -383,7 +383,25 @@ def main() -> int:
                          "ew_nnz": int(wte.info["ew_nnz"]), "tw_ms": a_ms, "tw_t_ms": b_ms})
             print(f"[report] TEW on c2, delta {delta:.3f} ({int(wte.info['ew_nnz'])} residual weights): tw_gemm {a_ms*1e3:.1f} us, "
                   f"tw_gemm_t {b_ms*1e3:.1f} us", file=sys.stderr, flush=True)
-        del Ats, Cts
+        del Ats, Cts, As, Cs
+        # the same with a streamed K: the FFN-down of BERT-base (K = 3072 in eight chunks)
+        spec_d = W.CONFIGS["c3_bert_base_layer"][3]
+        wd = W.generate(spec_d)
+        Ad = [tw.bits_to_tensor(wd.A, spec_d.dtype)]
+        Ad += [Ad[0].clone() for _ in range(n_sets - 1)]
+        Adt = [tw.tw_transpose(a).contiguous() for a in Ad]
+        Cd = [torch.empty((spec_d.M, spec_d.N), dtype=td, device="cuda:0") for _ in range(n_sets)]
+        Cdt = [torch.empty((spec_d.N, spec_d.M), dtype=td, device="cuda:0") for _ in range(n_sets)]
+        for delta in (0.0, 0.01):
+            ew = tw.tw_restore_ew(wd.B, wd.mask, delta, spec_d.dtype)
+            wte = tw.TwWeight(tw.tw_pack_tew(wd.B, wd.mask, ew, spec_d.G, spec_d.dtype))
+            a_ms, _ = time_launches(torch, lambda i: tw.tw_gemm(wte, Ad[i], Cd[i]), n_sets, st, 5)
+            b_ms, _ = time_launches(torch, lambda i: tw.tw_gemm_t(wte, Adt[i], Cdt[i]), n_sets, st, 5)
+            rows.append({"config": "tew_ffn_down", "name": f"ffn_down_3072x768 delta={delta}", "delta": delta,
+                         "ew_nnz": int(wte.info["ew_nnz"]), "tw_ms": a_ms, "tw_t_ms": b_ms})
+            print(f"[report] TEW on the FFN-down of c3 (streamed K), delta {delta:.3f} ({int(wte.info['ew_nnz'])} residual weights): "
+                  f"tw_gemm {a_ms*1e3:.1f} us, tw_gemm_t {b_ms*1e3:.1f} us", file=sys.stderr, flush=True)
+        del Ad, Adt, Cd, Cdt
         # Few rows and a streamed K (the GEMMs with K > 1536 at serving batch sizes): split-K plans against the
         # unsplit plan and the dense GEMMs
         import dataclasses
