@@ -98,8 +98,8 @@ int tw_pack(const void* B, int ldb, const uint8_t* mask, int K, int N, int G, tw
  * (the K rows that the block touches, 16 to a step, with the block's weights of those rows) and multiplied on
  * the matrix cores inside the tiles' kernel; residual weights in a column that the tile-wise pattern prunes
  * altogether are stored by column (the CSC form the paper names) and added by a second, small kernel that
- * tw_gemm enqueues behind the first, or (row-major boundary, K resident in LDS, up to 16 such columns per tile)
- * by the tile that owns the span.  ew_mask = NULL is tw_pack. */
+ * tw_gemm enqueues behind the first, or (up to 16 such columns per tile, no split-K plan) by the tile that owns
+ * the span.  ew_mask = NULL is tw_pack. */
 int tw_pack_tew_size(const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G, tw_dtype dt,
                      size_t* blob_bytes);
 int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const uint8_t* ew_mask, int K, int N, int G,

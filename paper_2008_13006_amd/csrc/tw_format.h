@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define TW_MAGIC 0x31425754u /* "TWB1" */
-#define TW_FORMAT_VERSION 13
+#define TW_FORMAT_VERSION 14
 
 // MFMA step geometry the packed values are laid out for: one step contracts 16 kept rows
 // (v_mfma_f32_32x32x16) against column blocks of 32 columns.
@@ -50,7 +50,7 @@ struct TwHeader {
     uint64_t off_urow;       // streamed K only: uint16 [n_sets][n_chunks][k_chunk]: per set of tiles that a
                              //   workgroup of the streamed kernel holds (TW_SET_TILES(T) tiles in dispatch order)
                              //   and per chunk, the chunk-local K rows that any tile of the set keeps (in its tile-wise
-                             //   pattern or in its element-wise residual), ascending
+                             //   pattern, in its element-wise residual or in the residual-only columns it adds itself), ascending
     uint64_t off_ucnt;       // int32 [n_sets][n_chunks]: their number
     // element-wise residual of the TEW hybrid (Sec. IV-A): the weights kept outside the tile-wise pattern, in the
     // tile's kept columns.  They are multiplied on the matrix cores like the tile itself, column block by column
@@ -74,9 +74,9 @@ struct TwHeader {
     uint64_t off_xc_v;       //   16-bit [entries]: its weight
     uint64_t off_xc_tile_ptr;//   int32 [T+1]: the columns of the list that lie in the span of tile t (canonical order) are
                              //   [xc_tile_ptr[t], xc_tile_ptr[t+1]) (the list is ascending and spans are disjoint)
-    uint64_t off_xc_rank;    //   int32 [xc_n]: position of the column among those of its tile; on the row-major boundary
-                             //   the tile adds the first TW_XC_INLINE itself (see off_xm_ptr), the rest (and everything
-                             //   on the transposed boundary and in a split-K plan) goes to the pass of its own
+    uint64_t off_xc_rank;    //   int32 [xc_n]: position of the column among those of its tile; the tile adds the first
+                             //   TW_XC_INLINE itself (see off_xm_ptr), the rest (and everything in a split-K plan) goes
+                             //   to the pass of its own
     int32_t xc_overflow;     //   columns with rank >= TW_XC_INLINE
     int32_t reserved1;
     // the first TW_XC_INLINE residual-only columns of every tile once more, as one column block for the matrix
@@ -84,7 +84,9 @@ struct TwHeader {
     uint64_t off_xm_ptr;     //   int32 [T*n_chunks+1]: first step of every (tile, chunk), tiles in canonical order
     uint64_t off_xm_goff;    //   uint16 [steps][16]: chunk-local K rows, slot order of off_goff; k_chunk for unused slots
     uint64_t off_xm_b;       //   16-bit [steps][64][8]: the weights
-    uint8_t pad[384 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 21 - 4 * 2 - 8 * 3];
+    uint64_t off_zero_xc;    // int8 [], parallel to zero_cols: position of the column among the residual-only columns of
+                             //   its tile if the tile adds it itself (0 .. TW_XC_INLINE-1), else -1
+    uint8_t pad[384 - 4 * 2 - 4 * 6 - 8 * 2 - 4 * 4 - 8 - 8 * 6 - 8 * 21 - 4 * 2 - 8 * 4];
 };
 static_assert(sizeof(TwHeader) == 384, "header is 384 bytes");
 

@@ -64,7 +64,7 @@ struct TwGemmParams {
     unsigned stage_off;         // LDS offset of the per-wave staging areas
     unsigned misc_off;          // LDS offset of two ints (item, tile counter)
     uint64_t off_sched_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_zero_ptr, off_zero_cols, off_urow, off_ucnt;
-    uint64_t off_ew_ptr, off_ew_goff, off_ew_b, off_xm_ptr, off_xm_goff, off_xm_b;
+    uint64_t off_ew_ptr, off_ew_goff, off_ew_b, off_xm_ptr, off_xm_goff, off_xm_b, off_zero_xc;
     int has_ew;                 // the blob carries an element-wise residual (TEW)
     uint64_t off_xc_tile_ptr, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v;
     unsigned xbuf_off;          // LDS offset of the per-wave areas for residual-only columns (TEW), 0: the tiles' kernel
@@ -823,7 +823,7 @@ __device__ __forceinline__ void stage_commit(const TwGemmParams& p, const ARegs<
 template <int DT, int MS, int NCB, bool FUSED>
 __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
                                              unsigned char* stage, const unsigned (&dpos)[NCB], int m0, int lane_in,
-                                             int cb0 = 0, int cb1 = NCB) {
+                                             int cb0 = 0, int cb1 = NCB, const unsigned short* xbuf = nullptr) {
     // (cb0, cb1: the column blocks to store, all by default; the lines of zeros go with column block 0.  The
     // second kernel of a split-K product gives a wave one column block of a tile.)
     constexpr int PPR = 4 * MS, RPI = 64 / PPR, PITCH = 64 * MS + 8;
@@ -885,8 +885,15 @@ __device__ __forceinline__ void store_tile_t(const TwGemmParams& p, const TileU&
     const int* zp = (const int*)(p.blob + p.off_zero_ptr);
     const int* zc = (const int*)(p.blob + p.off_zero_cols);
     const int z0 = fetch_int(zp, d.tile), z1 = fetch_int(zp, d.tile + 1);
+    // (`xbuf`: the rows of the span's residual-only columns that this tile has multiplied itself, [column][token])
+    const signed char* zx = (const signed char*)(p.blob + p.off_zero_xc);
     for (int j = z0 + rr; j < z1; j += RPI) {
         const int col = zc[j];
+        const int xs = xbuf != nullptr ? (int)zx[j] : -1;
+        if (xs >= 0) {
+            put_piece((long)col, *(const tw_u32x4*)(xbuf + xs * 64 + 8 * pc));
+            continue;
+        }
         unsigned v = 0u;
         if constexpr (FUSED) {   // a pruned column holds act(bias) for every token
             const unsigned hv = tw_cvt<DT>(tw_activate(p.bias != nullptr ? tw_to_f32<DT>(p.bias[col]) : 0.f, p.act));
@@ -1099,8 +1106,35 @@ __device__ __forceinline__ void xc_store(const TwGemmParams& p, const TileU& d, 
             }
     }
 }
-// K resident: everything at once
+// Transposed boundary: a column is a row of Ct, `xbuf` is [column][token] and the epilogue writes its rows in place
+// of the lines of zeros.
 template <int DT, int MS, bool FUSED>
+__device__ __forceinline__ void xc_store_t(const TwGemmParams& p, const TileU& d, const tw_f32x16 (&acc)[MS][1],
+                                           unsigned short* xbuf, int lane) {
+    const int n = lane & 31, h = lane >> 5;
+    if (n < xc_count(d)) {
+        float bias = 0.f;
+        if constexpr (FUSED)
+            if (p.bias != nullptr) bias = tw_to_f32<DT>(p.bias[((const int*)(p.blob + p.off_xc_col))[(d.xc & 0x3FFFFFF) + n]]);
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {                    // tokens 32*ms + 8*q + 4*h .. + 3
+                float v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    v[i] = acc[ms][0][4 * q + i];
+                    if constexpr (FUSED) v[i] = tw_activate(v[i] + bias, p.act);
+                }
+                tw_u32x2 o;
+                o.x = (unsigned)tw_cvt<DT>(v[0]) | ((unsigned)tw_cvt<DT>(v[1]) << 16);
+                o.y = (unsigned)tw_cvt<DT>(v[2]) | ((unsigned)tw_cvt<DT>(v[3]) << 16);
+                *(tw_u32x2*)(xbuf + n * 64 + 32 * ms + 8 * q + 4 * h) = o;
+            }
+    }
+}
+// K resident: everything at once
+template <int DT, int MS, bool FUSED, bool TRANS>
 __device__ __forceinline__ void xc_columns(const TwGemmParams& p, const TileU& d, XcSteps& x, const unsigned char* at,
                                            unsigned at_pitch, unsigned short* xbuf, int lane) {
     if (xc_count(d) == 0) return;                            // wave-uniform
@@ -1108,7 +1142,8 @@ __device__ __forceinline__ void xc_columns(const TwGemmParams& p, const TileU& d
     zero_acc<MS, 1>(acc);
     if (x.s0 != x.s1)
         run_block_steps<DT, MS, 1>(acc, x.r, at, at_pitch, p.blob + p.off_xm_goff, p.blob + p.off_xm_b, x.s0, x.s1, lane);
-    xc_store<DT, MS, FUSED>(p, d, acc, xbuf, lane);
+    if constexpr (TRANS) xc_store_t<DT, MS, FUSED>(p, d, acc, xbuf, lane);
+    else xc_store<DT, MS, FUSED>(p, d, acc, xbuf, lane);
 }
 // K streamed: the sums of the 16 columns between chunks, fp32, piece (ms, q) of lane (h, n < 16) at float offset
 // (((4 * ms + q) * 32 + 16 * h + n) * 4 of `area` (4 KB with 64 rows)
@@ -1152,13 +1187,14 @@ __device__ __forceinline__ void xc_chunk(const TwGemmParams& p, const TileU& d, 
                     tw_f32x4{acc[ms][0][4 * q + 0], acc[ms][0][4 * q + 1], acc[ms][0][4 * q + 2], acc[ms][0][4 * q + 3]};
     }
 }
-template <int DT, int MS, bool FUSED>
+template <int DT, int MS, bool FUSED, bool TRANS>
 __device__ __forceinline__ void xc_finish(const TwGemmParams& p, const TileU& d, const unsigned char* area,
                                           unsigned short* xbuf, int lane) {
     if (xc_count(d) == 0) return;                            // wave-uniform
     tw_f32x16 acc[MS][1];
     xc_load_partial<MS>(acc, area, lane);
-    xc_store<DT, MS, FUSED>(p, d, acc, xbuf, lane);
+    if constexpr (TRANS) xc_store_t<DT, MS, FUSED>(p, d, acc, xbuf, lane);
+    else xc_store<DT, MS, FUSED>(p, d, acc, xbuf, lane);
 }
 
 // MODE 0: the K extent of a row block of 32*MS rows is resident in LDS, waves pull whole tiles.
@@ -1257,24 +1293,21 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 unsigned short* xbuf = nullptr;
                 XcSteps xs;
                 int xcols[TW_XC_INLINE / 8];
-                if constexpr (!TRANS) {
-                    if (p.xbuf_off != 0) {
-                        xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
-                        xc_column_numbers(p, d, xcols, lane);
-                        xc_request(p, d, 0, xs, lane);
-                    }
+                if (p.xbuf_off != 0) {
+                    xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
+                    if constexpr (!TRANS) xc_column_numbers(p, d, xcols, lane);
+                    xc_request(p, d, 0, xs, lane);
                 }
                 StepRegs<NCB> rg;
                 prefetch_first_steps<NCB>(rg, p.blob + p.off_goff + (long)d.first_step * 32,
                                           p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
-                if constexpr (!TRANS)
-                    if (xbuf != nullptr) xc_columns<DT, MS, FUSED>(p, d, xs, smem, at_pitch_of<MS>(), xbuf, lane);
+                if (xbuf != nullptr) xc_columns<DT, MS, FUSED, TRANS>(p, d, xs, smem, at_pitch_of<MS>(), xbuf, lane);
                 tw_f32x16 acc[MS][NCB];
                 zero_acc<MS, NCB>(acc);
                 run_steps<DT, MS, NCB>(acc, rg, smem, at_pitch_of<MS>(), p.blob + p.off_goff + (long)d.first_step * 32,
                                            p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
                 if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, at_pitch_of<MS>(), lane);
-                if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
+                if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, 0, NCB, xbuf);
                 else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, smem, xbuf, xcols);
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
@@ -1413,12 +1446,10 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 // residual-only columns of the tile's span (TEW): their sums wait in the staging area between chunks
                 unsigned short* xbuf = nullptr;
                 int xcols[TW_XC_INLINE / 8];
-                if constexpr (!TRANS) {
-                    if (p.xbuf_off != 0 && active) {
-                        xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
-                        xc_column_numbers(p, d, xcols, lane);
-                        xc_zero_partial<MS>(d, stage, lane);
-                    }
+                if (p.xbuf_off != 0 && active) {
+                    xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
+                    if constexpr (!TRANS) xc_column_numbers(p, d, xcols, lane);
+                    xc_zero_partial<MS>(d, stage, lane);
                 }
                 // the first steps of a chunk are requested at the end of the previous chunk's steps, so
                 // they arrive while the workgroup meets at the barrier
@@ -1443,8 +1474,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     if (active && b0 < b1)
                         run_steps<DT, MS, NCB>(acc, rg, buf, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
                     if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, buf, at_pitch_of<MS>(), lane);
-                    if constexpr (!TRANS)
-                        if (xbuf != nullptr) xc_chunk<DT, MS>(p, d, c, buf, at_pitch_of<MS>(), stage, lane);
+                    if (xbuf != nullptr) xc_chunk<DT, MS>(p, d, c, buf, at_pitch_of<MS>(), stage, lane);
                     // on to chunk c+1
                     b0 = b1; b1 = b2;
                     b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
@@ -1462,12 +1492,9 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 __syncthreads();
                 par ^= p.n_chunks & 1;
                 if (active) {
-                    if constexpr (TRANS) {
-                        store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
-                    } else {
-                        if (xbuf != nullptr) xc_finish<DT, MS, FUSED>(p, d, stage, xbuf, lane);
-                        store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, xbuf, xcols);
-                    }
+                    if (xbuf != nullptr) xc_finish<DT, MS, FUSED, TRANS>(p, d, stage, xbuf, lane);
+                    if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, 0, NCB, xbuf);
+                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, xbuf, xcols);
                 }
             }
         } else {
@@ -1529,10 +1556,10 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             // (a split-K plan leaves them to the pass of their own)
             unsigned short* xbuf = nullptr;
             int xcols[TW_XC_INLINE / 8];
-            if constexpr (!TRANS && !SPLIT) {
+            if constexpr (!SPLIT) {
                 if (p.xbuf_off != 0 && active) {
                     xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
-                    xc_column_numbers(p, d, xcols, lane);
+                    if constexpr (!TRANS) xc_column_numbers(p, d, xcols, lane);
                     xc_zero_partial<MS>(d, stage, lane);
                 }
             }
@@ -1565,7 +1592,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (active && b0 < b1)
                     run_steps<DT, MS, NCB>(acc, rg, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
                 if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
-                if constexpr (!TRANS && !SPLIT)
+                if constexpr (!SPLIT)
                     if (xbuf != nullptr) xc_chunk<DT, MS>(p, d, c, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), stage, lane);
                 b0 = b1; b1 = b2;
                 b2 = fetch_int(sp, c + 3 < p.n_chunks ? c + 3 : p.n_chunks);
@@ -1609,12 +1636,9 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if constexpr (SPLIT) {
                     dump_partial<MS, NCB>(p.partials + ((((long)part * p.n_mblocks + mb) * p.T + ti) * (long)(MS * NCB * 1024)), acc, lane);
                 } else {
-                    if constexpr (TRANS) {
-                        store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane);
-                    } else {
-                        if (xbuf != nullptr) xc_finish<DT, MS, FUSED>(p, d, stage, xbuf, lane);
-                        store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, xbuf, xcols);
-                    }
+                    if (xbuf != nullptr) xc_finish<DT, MS, FUSED, TRANS>(p, d, stage, xbuf, lane);
+                    if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, 0, NCB, xbuf);
+                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, xbuf, xcols);
                 }
             }
         }
@@ -2103,7 +2127,7 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     // from lists they hold in LDS.  (The blob's row lists are per set of TW_SET_TILES(T) tiles: with other sets
     // the loading waves bring in whole chunks.)
     pl.xbuf_off = 0;
-    if (!transposed && h->xc_n > 0) {
+    if (h->xc_n > 0) {
         const unsigned need = kWaves * TW_XC_INLINE * 64 * 2;
         if (pl.lds_bytes + need <= kLdsLimit) { pl.xbuf_off = pl.lds_bytes; pl.lds_bytes += need; }
     }
@@ -2122,7 +2146,7 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     // (Not where the tiles add the residual-only columns of a TEW blob themselves: a split leaves those to the pass
     // of their own, which reads all of A once more - 92 against 46 us on the FFN-down of BERT-base at 512 rows.)
     pl.n_parts = 1; pl.chunks_per_part = h->n_chunks; pl.partial_bytes = 0;
-    if (!resident && msb == 2 && h->n_chunks >= 2 && pl.xbuf_off == 0) {
+    if (!resident && msb == 2 && h->n_chunks >= 2 && (pl.xbuf_off == 0 || transposed)) {
         const long nmb1 = (M + 63) / 64;
         const size_t tile_bytes = (size_t)2 * h->ncb * 4096;          // fp32 results of a tile: 64 rows x G columns
         const int sub = transposed ? h->ncb : 8;                      // pieces of a tile in the second kernel
@@ -2387,7 +2411,7 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt; p.urow_off = 0;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_goff = h->off_ew_goff; p.off_ew_b = h->off_ew_b; p.has_ew = h->ew_nnz > 0;
-    p.off_xm_ptr = h->off_xm_ptr; p.off_xm_goff = h->off_xm_goff; p.off_xm_b = h->off_xm_b;
+    p.off_xm_ptr = h->off_xm_ptr; p.off_xm_goff = h->off_xm_goff; p.off_xm_b = h->off_xm_b; p.off_zero_xc = h->off_zero_xc;
     p.stream_stores = ((uintptr_t)C & 127) == 0 && (ldc & 63) == 0;
     p.off_xc_tile_ptr = h->off_xc_tile_ptr; p.off_xc_col = h->off_xc_col; p.off_xc_ptr = h->off_xc_ptr;
     p.off_xc_k = h->off_xc_k; p.off_xc_v = h->off_xc_v; p.xbuf_off = pl.xbuf_off;
@@ -2479,10 +2503,10 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     p.off_zero_ptr = h->off_zero_ptr; p.off_zero_cols = h->off_zero_cols;
     p.off_urow = h->off_urow; p.off_ucnt = h->off_ucnt;
     p.off_ew_ptr = h->off_ew_ptr; p.off_ew_goff = h->off_ew_goff; p.off_ew_b = h->off_ew_b; p.has_ew = h->ew_nnz > 0;
-    p.off_xm_ptr = h->off_xm_ptr; p.off_xm_goff = h->off_xm_goff; p.off_xm_b = h->off_xm_b;
+    p.off_xm_ptr = h->off_xm_ptr; p.off_xm_goff = h->off_xm_goff; p.off_xm_b = h->off_xm_b; p.off_zero_xc = h->off_zero_xc;
     p.urow_off = pl.urow_off;
     p.off_xc_tile_ptr = h->off_xc_tile_ptr; p.off_xc_col = h->off_xc_col; p.off_xc_ptr = h->off_xc_ptr;
-    p.off_xc_k = h->off_xc_k; p.off_xc_v = h->off_xc_v; p.xbuf_off = 0;
+    p.off_xc_k = h->off_xc_k; p.off_xc_v = h->off_xc_v; p.xbuf_off = pl.xbuf_off;
     p.stream_stores = ((uintptr_t)Ct & 127) == 0 && (ldct & 63) == 0;
     p.n_parts = pl.n_parts; p.chunks_per_part = pl.chunks_per_part;
     p.partials = (float*)((unsigned char*)workspace + 256);
@@ -2494,7 +2518,7 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
         const long units = (long)pl.n_mblocks * h->T * h->ncb;            // a wave per column block of a tile
         if (hipLaunchKernel(fn_reduce, dim3((unsigned)units), dim3(64), args, 0, stream) != hipSuccess) return TW_ERR_HIP;
     }
-    return launch_xcols(h, blob_dev, At, ldat, Ct, ldct, M, bias, (int)act, true, stream);
+    return launch_xcols(h, blob_dev, At, ldat, Ct, ldct, M, bias, (int)act, true, stream, pl.xbuf_off != 0);
 }
 
 // ---- the transposes at the two ends of a network that runs on the transposed boundary (Sec. VI) ----

@@ -30,7 +30,7 @@ struct Layout {
     int64_t total_steps = 0;
     uint64_t off_col_idx, off_tile_col_ptr, off_tile_row_ptr, off_row_idx, off_tile_span,
         off_sched_order, off_tile_desc, off_step_ptr, off_goff, off_dpos, off_bvals, off_sched_desc, off_zero_ptr,
-        off_zero_cols, off_urow, off_ucnt, off_ew_ptr, off_ew_goff, off_ew_b, off_ew_mask, off_xm_ptr, off_xm_goff, off_xm_b, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v, off_xc_tile_ptr, off_xc_rank, bytes;
+        off_zero_cols, off_zero_xc, off_urow, off_ucnt, off_ew_ptr, off_ew_goff, off_ew_b, off_ew_mask, off_xm_ptr, off_xm_goff, off_xm_b, off_xc_col, off_xc_ptr, off_xc_k, off_xc_v, off_xc_tile_ptr, off_xc_rank, bytes;
     int64_t ew_nnz = 0;
     std::vector<int32_t> ew_ptr;   // residual steps per (tile, chunk), prefix sums
     // residual weights in columns without tile-wise weights, by column
@@ -186,6 +186,7 @@ void plan(const Tiling& tl, int K, int G, Layout& lo, const uint8_t* mask = null
         if (T > 0) n_zero = (size_t)tl.tile_span[T] - tl.col_idx.size();
         lo.off_zero_ptr = take(4 * (size_t)(T + 1), 16);
         lo.off_zero_cols = take(4 * (n_zero + 1), 16);
+        lo.off_zero_xc = take(n_zero + 1, 16);
     }
     {
         const size_t n_sets = lo.n_chunks > 1 && T > 0 ? (size_t)(T + TW_SET_TILES(T) - 1) / TW_SET_TILES(T) : 0;
@@ -347,7 +348,7 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
     h->off_tile_desc = lo.off_tile_desc; h->off_step_ptr = lo.off_step_ptr;
     h->off_goff = lo.off_goff; h->off_dpos = lo.off_dpos; h->off_bvals = lo.off_bvals;
     h->off_sched_desc = lo.off_sched_desc;
-    h->off_zero_ptr = lo.off_zero_ptr; h->off_zero_cols = lo.off_zero_cols;
+    h->off_zero_ptr = lo.off_zero_ptr; h->off_zero_cols = lo.off_zero_cols; h->off_zero_xc = lo.off_zero_xc;
     h->off_urow = lo.off_urow; h->off_ucnt = lo.off_ucnt;
     h->ew_nnz = lo.ew_nnz; h->off_ew_ptr = lo.off_ew_ptr; h->off_ew_goff = lo.off_ew_goff; h->off_ew_b = lo.off_ew_b;
     h->off_ew_mask = lo.off_ew_mask;
@@ -463,6 +464,18 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
         }
         put(lo.off_zero_ptr, zptr);
         put(lo.off_zero_cols, zcols);
+        // which of them hold residual weights that the owning tile adds itself (both lists ascend)
+        int8_t* zx = (int8_t*)(base + lo.off_zero_xc);
+        for (int t = 0; t < tl.T; ++t) {
+            int x = lo.xc_tile_ptr[t];
+            for (int32_t j = zptr[t]; j < zptr[t + 1]; ++j) {
+                zx[j] = -1;
+                if (x < lo.xc_tile_ptr[t + 1] && lo.xc_col[x] == zcols[j]) {
+                    if (x - lo.xc_tile_ptr[t] < TW_XC_INLINE) zx[j] = (int8_t)(x - lo.xc_tile_ptr[t]);
+                    ++x;
+                }
+            }
+        }
     }
 
     // schedule: heaviest tile (most kept rows) first, ties keep tile order
@@ -561,6 +574,9 @@ extern "C" int tw_pack_tew(const void* B, int ldb, const uint8_t* mask, const ui
                         for (int k = 0; k < K; ++k)
                             if (ew_mask[(size_t)k * N + n] != 0) need[k] = 1;
                     }
+                // and those of the residual-only columns in its span that the tile adds itself
+                for (int x = lo.xc_tile_ptr[t]; x < std::min(lo.xc_tile_ptr[t + 1], lo.xc_tile_ptr[t] + TW_XC_INLINE); ++x)
+                    for (int32_t q = lo.xc_ptr[x]; q < lo.xc_ptr[x + 1]; ++q) need[lo.xc_k[q]] = 1;
             }
             for (int c = 0; c < lo.n_chunks; ++c) {
                 uint16_t* out = urow + ((size_t)st * lo.n_chunks + c) * lo.k_chunk;

@@ -1073,6 +1073,45 @@ def test_split_k_small_batches_of_the_ffn_down(tw, M):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("K", [300, 1700], ids=["k_resident", "k_streamed_ragged_chunk"])
+def test_tew_many_residual_only_columns_per_tile_bit_exact(tw, K):
+    """Tiles whose spans hold more residual-only columns than a tile adds itself (16): the first 16 leave with the
+    tile's stores (row-major: through the staging window; transposed: in place of the lines of zeros), the others
+    in the pass of their own; with a residual inside the kept columns as well, K resident and streamed (five
+    chunks, the last one ragged; the columns' sums then wait in LDS between chunks); several row blocks with a
+    ragged last one; integers, bit for bit, both boundaries and the fused epilogue."""
+    spec = W.small_spec(f"xcols_many_{K}", M=205, K=K, N=300, G=64, dtype="f16", col_prune=0.45, keep=("upow", 0.1, 0.5),
+                        a_dist="smallint", seed_offset=4242)
+    w = W.generate(spec)
+    rng = np.random.default_rng(17)
+    alive = w.mask.any(axis=0)
+    pruned = np.flatnonzero(~alive)
+    ew = np.zeros_like(w.mask)
+    for n in pruned:
+        ew[rng.choice(spec.K, size=int(rng.integers(1, 12)), replace=False), n] = 1
+    kept_res = (rng.random(w.mask.shape) < 0.02) & (w.mask == 0) & alive[None, :]
+    ew |= kept_res.astype(np.uint8)
+    wt = tw.TwWeight(tw.tw_pack_tew(w.B, w.mask, ew, spec.G, "f16"))
+    span = wt.info["tile_span"]
+    per_tile = np.histogram(pruned, bins=span)[0]
+    assert per_tile.max() > 16 and wt.info["ew_nnz"] == int(ew.sum())
+    pl, plt = tw.tw_gemm_plan(wt.blob, spec.M), tw.tw_gemm_plan(wt.blob, spec.M, transposed=True)
+    _say(f"{spec.name}: residual-only columns per tile {per_tile.tolist()}, plan {pl} / {plt}")
+    assert (pl["mode"] == 0) == (K <= 1536) and pl["k_parts"] == 1
+    bias_i = rng.integers(-5, 6, size=spec.N).astype(np.float32)
+    bias = tw.bits_to_tensor(W.f32_to_bits(bias_i, "f16"), "f16")
+    A, At = _device_A(tw, w.A, "f16"), _device_At(tw, w.A, "f16")
+    ref = tw_ref.masked_gemm(w.A, w.B, (w.mask | ew).astype(np.uint8), "f16")
+    ref_r = tw_ref.bias_act(ref, bias_i.astype(np.float64), "relu")
+    C, Ct = tw.tw_gemm(wt, A), tw.tw_gemm_t(wt, At)
+    Cf, Cft = tw.tw_gemm_bias_act(wt, A, bias, "relu"), tw.tw_gemm_t_bias_act(wt, At, bias, "relu")
+    torch.cuda.synchronize()
+    assert np.abs(ref).max() < 2048                      # fp16 holds every result exactly
+    assert np.array_equal(_to_f64(C), ref) and np.array_equal(_to_f64(Ct).T, ref)
+    assert np.array_equal(_to_f64(Cf), ref_r) and np.array_equal(_to_f64(Cft).T, ref_r)
+    assert np.any(ref[:, pruned] != 0)
+
+
 def test_tew_residual_only_in_pruned_columns_bit_exact(tw):
     """A weight whose tile-wise pattern is EMPTY plus a residual (every column is of the kind that runs in the
     pass of its own), and one whose residual lies only in the pruned columns; integers, bit for bit, both boundaries
