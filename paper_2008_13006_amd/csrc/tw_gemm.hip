@@ -495,7 +495,7 @@ __device__ __forceinline__ void apply_bias_act(tw_f32x16 (&acc)[MS][NCB], const 
 template <int DT, int MS, int NCB, bool FUSED>
 __device__ __forceinline__ void store_tile(const TwGemmParams& p, const TileU& d, tw_f32x16 (&acc)[MS][NCB],
                                            unsigned char* stage, const unsigned (&dpos)[NCB], int row0, int lane_in,
-                                           const unsigned char* at_resident = nullptr, unsigned short* xbuf = nullptr,
+                                           unsigned short* xbuf = nullptr,
                                            const int* xcols = nullptr,
                                            int pass0 = 0, int pass1 = 4 * MS) {
     // (pass0, pass1: the passes to run, each eight rows of the block; everything by default.  The second kernel
@@ -1308,7 +1308,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                                            p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
                 if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, at_pitch_of<MS>(), lane);
                 if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, 0, NCB, xbuf);
-                else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, smem, xbuf, xcols);
+                else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, xbuf, xcols);
             }
             __syncthreads();  // everyone is done with the LDS copy of A and with misc[]
         } else if constexpr (MODE == 2) {
@@ -1494,7 +1494,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 if (active) {
                     if (xbuf != nullptr) xc_finish<DT, MS, FUSED, TRANS>(p, d, stage, xbuf, lane);
                     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, 0, NCB, xbuf);
-                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, xbuf, xcols);
+                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, xbuf, xcols);
                 }
             }
         } else {
@@ -1638,7 +1638,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 } else {
                     if (xbuf != nullptr) xc_finish<DT, MS, FUSED, TRANS>(p, d, stage, xbuf, lane);
                     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, 0, NCB, xbuf);
-                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, xbuf, xcols);
+                    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, xbuf, xcols);
                 }
             }
         }
@@ -1723,7 +1723,7 @@ __global__ __launch_bounds__(64) void tw_splitk_reduce_kernel(const TwGemmParams
                 }
             }
     if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, sub, sub + 1);
-    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, nullptr, nullptr, sub, sub + 1);
+    else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, nullptr, nullptr, sub, sub + 1);
 }
 
 }  // namespace
