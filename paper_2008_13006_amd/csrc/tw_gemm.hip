@@ -2126,15 +2126,16 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
     // Transposed boundary, at most four tiles, streamed: the loading waves read only the K rows the tiles keep,
     // from lists they hold in LDS.  (The blob's row lists are per set of TW_SET_TILES(T) tiles: with other sets
     // the loading waves bring in whole chunks.)
-    pl.xbuf_off = 0;
-    if (h->xc_n > 0) {
-        const unsigned need = kWaves * TW_XC_INLINE * 64 * 2;
-        if (pl.lds_bytes + need <= kLdsLimit) { pl.xbuf_off = pl.lds_bytes; pl.lds_bytes += need; }
-    }
     pl.urow_off = 0;
     if (transposed && pl.mode == 2 && T <= kWaves / 2 && tpw == kWaves / 2) {
         const unsigned need = (kWaves / 2) * (unsigned)h->n_chunks * (8 * 12 + 2) * 2;
         if (pl.lds_bytes + need <= kLdsLimit) { pl.urow_off = pl.lds_bytes; pl.lds_bytes += need; }
+    }
+    // per-wave areas for the residual-only columns that the tiles add themselves (TEW), if there is room left
+    pl.xbuf_off = 0;
+    if (h->xc_n > 0) {
+        const unsigned need = kWaves * TW_XC_INLINE * 64 * 2;
+        if (pl.lds_bytes + need <= kLdsLimit) { pl.xbuf_off = pl.lds_bytes; pl.lds_bytes += need; }
     }
     // Split K.  With streamed K and few row blocks the plan above leaves most compute units idle while each
     // workgroup walks all chunks in sequence, and a compute unit brings A in at about 16 KB per microsecond only

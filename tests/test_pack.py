@@ -347,6 +347,18 @@ def test_plan_of_the_paper_shaped_workloads():
     assert plt["row_lists"] == 1 and plt["lds_bytes"] > pl["lds_bytes"]
     spec, inf, plt = _plan("c4_bert_large_skewed", 1, transposed=True)
     assert plt["mode"] == 2 and plt["n_sets"] == 2 and plt["row_lists"] == 0     # the lists are per set of eight tiles
+    # the hybrid on the same shape, with residual weights in pruned columns: the row lists keep their place in LDS
+    # (the per-wave areas for those columns come after them, if there is room), and nothing outgrows the LDS
+    spec = W.CONFIGS["c5_conv_im2col"][0]
+    w = W.generate(spec, with_A=False)
+    mask = w.mask.copy()
+    mask[:, -8:] = 0                                          # the last tile loses eight columns: T stays 4
+    ew = tw.tw_restore_ew(w.B, mask, 0.01, spec.dtype)
+    assert ew[:, -8:].any() and tw.tw_info(tw.tw_pack(w.B, mask, spec.G, spec.dtype))["T"] == 4
+    blob = tw.tw_pack_tew(w.B, mask, ew, spec.G, spec.dtype)
+    ple, plet = tw.tw_gemm_plan(blob, spec.M), tw.tw_gemm_plan(blob, spec.M, transposed=True)
+    assert plet["row_lists"] == 1 and plet["mode"] == 2 and ple["mode"] == 2
+    assert max(ple["lds_bytes"], plet["lds_bytes"]) <= 160 * 1024 and ple["lds_bytes"] > pl["lds_bytes"]
 
 
 def test_plan_fills_the_last_round_on_the_row_major_boundary():
