@@ -26,10 +26,10 @@ def needs_build() -> bool:
     return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
 
 
-# (source, -D flags, object): tw_gemm.hip is compiled as its host code (part 0) and four groups of kernels
-# (parts 1..4: fp16 / bf16 x plain / fused epilogue), all at once
+# (source, -D flags, object): tw_gemm.hip is compiled as its host code (part 0) and eight groups of kernels
+# (parts 1..4: fp16 / bf16 x plain / fused epilogue; 5..8: the same with the code for TEW blobs), all at once
 UNITS = [("tw_pack.cpp", [], "tw_pack.cpp.o"), ("tw_dense.hip", [], "tw_dense.hip.o")] + [
-    ("tw_gemm.hip", [f"-DTW_PART={i}"], f"tw_gemm.part{i}.o") for i in range(5)]
+    ("tw_gemm.hip", [f"-DTW_PART={i}"], f"tw_gemm.part{i}.o") for i in range(9)]
 
 
 def build(force: bool = True, verbose: bool = False) -> str:

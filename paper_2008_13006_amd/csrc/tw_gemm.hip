@@ -1226,9 +1226,13 @@ __device__ __forceinline__ void dump_partial(float* dst, const tw_f32x16 (&acc)[
                     tw_f32x4{acc[ms][cb][4 * q], acc[ms][cb][4 * q + 1], acc[ms][cb][4 * q + 2], acc[ms][cb][4 * q + 3]};
 }
 
-template <int DT, int MS, int NCB, int MODE, bool FUSED, bool TRANS, bool NTA = true>
+// EW: the variant for TEW blobs.  The code of the element-wise residual costs the kernels without it 1 to 2.5 %
+// (registers: the widest variants sit at the limit of 256), so blobs without a residual run kernels without it.
+template <int DT, int MS, int NCB, int MODE, bool FUSED, bool TRANS, bool NTA = true, bool EW = false>
 __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const bool has_ew = EW && p.has_ew != 0;
+    const unsigned xbuf_off = EW ? p.xbuf_off : 0u;
     constexpr int MSB = MS;                       // 32-row blocks in the workgroup's row block
     constexpr int BM = 32 * MSB;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1293,8 +1297,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 unsigned short* xbuf = nullptr;
                 XcSteps xs;
                 int xcols[TW_XC_INLINE / 8];
-                if (p.xbuf_off != 0) {
-                    xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
+                if (xbuf_off != 0) {
+                    xbuf = (unsigned short*)(smem + xbuf_off) + wave * (TW_XC_INLINE * 64);
                     if constexpr (!TRANS) xc_column_numbers(p, d, xcols, lane);
                     xc_request(p, d, 0, xs, lane);
                 }
@@ -1306,7 +1310,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 zero_acc<MS, NCB>(acc);
                 run_steps<DT, MS, NCB>(acc, rg, smem, at_pitch_of<MS>(), p.blob + p.off_goff + (long)d.first_step * 32,
                                            p.blob + p.off_bvals + (long)d.first_step * NCB * 1024, 0, d.nsteps, lane);
-                if (p.has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, at_pitch_of<MS>(), lane);
+                if (has_ew) add_ew_residual<DT, MS, NCB>(p, d.tile, 0, acc, smem, at_pitch_of<MS>(), lane);
                 if constexpr (TRANS) store_tile_t<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, 0, NCB, xbuf);
                 else store_tile<DT, MS, NCB, FUSED>(p, d, acc, stage, dpos, row0, lane, xbuf, xcols);
             }
@@ -1446,8 +1450,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 // residual-only columns of the tile's span (TEW): their sums wait in the staging area between chunks
                 unsigned short* xbuf = nullptr;
                 int xcols[TW_XC_INLINE / 8];
-                if (p.xbuf_off != 0 && active) {
-                    xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
+                if (xbuf_off != 0 && active) {
+                    xbuf = (unsigned short*)(smem + xbuf_off) + wave * (TW_XC_INLINE * 64);
                     if constexpr (!TRANS) xc_column_numbers(p, d, xcols, lane);
                     xc_zero_partial<MS>(d, stage, lane);
                 }
@@ -1473,7 +1477,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                     const unsigned char* buf = smem + ((c + par) & 1) * p.abuf_bytes;
                     if (active && b0 < b1)
                         run_steps<DT, MS, NCB>(acc, rg, buf, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
-                    if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, buf, at_pitch_of<MS>(), lane);
+                    if (has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, buf, at_pitch_of<MS>(), lane);
                     if (xbuf != nullptr) xc_chunk<DT, MS>(p, d, c, buf, at_pitch_of<MS>(), stage, lane);
                     // on to chunk c+1
                     b0 = b1; b1 = b2;
@@ -1557,8 +1561,8 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
             unsigned short* xbuf = nullptr;
             int xcols[TW_XC_INLINE / 8];
             if constexpr (!SPLIT) {
-                if (p.xbuf_off != 0 && active) {
-                    xbuf = (unsigned short*)(smem + p.xbuf_off) + wave * (TW_XC_INLINE * 64);
+                if (xbuf_off != 0 && active) {
+                    xbuf = (unsigned short*)(smem + xbuf_off) + wave * (TW_XC_INLINE * 64);
                     if constexpr (!TRANS) xc_column_numbers(p, d, xcols, lane);
                     xc_zero_partial<MS>(d, stage, lane);
                 }
@@ -1591,7 +1595,7 @@ __global__ __launch_bounds__(kThreads) void tw_gemm_kernel(const TwGemmParams p)
                 const int c = c_first + j;
                 if (active && b0 < b1)
                     run_steps<DT, MS, NCB>(acc, rg, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), gt, bt, b0, b1, lane);
-                if (p.has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
+                if (has_ew && active) add_ew_residual<DT, MS, NCB>(p, d.tile, c, acc, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), lane);
                 if constexpr (!SPLIT)
                     if (xbuf != nullptr) xc_chunk<DT, MS>(p, d, c, smem + (j & 1) * p.abuf_bytes, at_pitch_of<MS>(), stage, lane);
                 b0 = b1; b1 = b2;
@@ -1729,51 +1733,52 @@ __global__ __launch_bounds__(64) void tw_splitk_reduce_kernel(const TwGemmParams
 }  // namespace
 
 // ---- kernel tables
-// The kernels can be compiled as four translation units (-DTW_PART=1..4: fp16 / bf16 x plain / fused epilogue)
-// beside the host code (-DTW_PART=0), so that a build runs them in parallel; without TW_PART one unit holds
+// The kernels can be compiled as eight translation units (-DTW_PART=1..4: fp16 / bf16 x plain / fused epilogue, 5..8:
+// the same for TEW blobs) beside the host code (-DTW_PART=0), so that a build runs them in parallel; without TW_PART one unit holds
 // everything.  The tables hand out host-side kernel addresses, so no type of this file crosses a unit boundary.
 namespace tw_parts {
 // (nta: the streamed kernels' variant whose requests for activations carry the streaming hint)
-template <int DT, bool FUSED> const void* pick_mode(int mode, int ms, int ncb, bool nta);     // row-major boundary
-template <int DT, bool FUSED> const void* pick_mode_t(int mode, int ms, int ncb, bool nta);   // transposed boundary
+// (EW: the variant with the code of the element-wise residual, for TEW blobs)
+template <int DT, bool FUSED, bool EW> const void* pick_mode(int mode, int ms, int ncb, bool nta);     // row-major boundary
+template <int DT, bool FUSED, bool EW> const void* pick_mode_t(int mode, int ms, int ncb, bool nta);   // transposed boundary
 template <int DT, bool FUSED> const void* pick_reduce(int ncb, bool transposed);               // second kernel of split K
 }  // namespace tw_parts
 
 #if !defined(TW_PART) || TW_PART != 0
 namespace {
-template <int DT, int MS, int MODE, bool FUSED, bool TRANS, bool NTA = true>
+template <int DT, int MS, int MODE, bool FUSED, bool TRANS, bool EW, bool NTA = true>
 const void* pick_ncb(int ncb) {
     switch (ncb) {
-        case 1: return (const void*)tw_gemm_kernel<DT, MS, 1, MODE, FUSED, TRANS, NTA>;
-        case 2: return (const void*)tw_gemm_kernel<DT, MS, 2, MODE, FUSED, TRANS, NTA>;
-        case 4: return (const void*)tw_gemm_kernel<DT, MS, 4, MODE, FUSED, TRANS, NTA>;
+        case 1: return (const void*)tw_gemm_kernel<DT, MS, 1, MODE, FUSED, TRANS, NTA, EW>;
+        case 2: return (const void*)tw_gemm_kernel<DT, MS, 2, MODE, FUSED, TRANS, NTA, EW>;
+        case 4: return (const void*)tw_gemm_kernel<DT, MS, 4, MODE, FUSED, TRANS, NTA, EW>;
         default: return nullptr;
     }
 }
 }  // namespace
 namespace tw_parts {
-template <int DT, bool FUSED>
+template <int DT, bool FUSED, bool EW>
 const void* pick_mode(int mode, int ms, int ncb, bool nta) {
-    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, false>(ncb) : pick_ncb<DT, 1, 0, FUSED, false>(ncb);
+    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, false, EW>(ncb) : pick_ncb<DT, 1, 0, FUSED, false, EW>(ncb);
     if (ms != 2) return nullptr;                  // the streamed kernels take 64-row blocks
-    if (mode == 1) return nta ? pick_ncb<DT, 2, 1, FUSED, false, true>(ncb) : pick_ncb<DT, 2, 1, FUSED, false, false>(ncb);
+    if (mode == 1) return nta ? pick_ncb<DT, 2, 1, FUSED, false, EW, true>(ncb) : pick_ncb<DT, 2, 1, FUSED, false, EW, false>(ncb);
     if (mode == 3) {                              // split K: the epilogue is the second kernel's, so only the plain variant exists
-        if constexpr (!FUSED) return nta ? pick_ncb<DT, 2, 3, false, false, true>(ncb) : pick_ncb<DT, 2, 3, false, false, false>(ncb);
+        if constexpr (!FUSED) return nta ? pick_ncb<DT, 2, 3, false, false, EW, true>(ncb) : pick_ncb<DT, 2, 3, false, false, EW, false>(ncb);
         else return nullptr;
     }
-    return nta ? pick_ncb<DT, 2, 2, FUSED, false, true>(ncb) : pick_ncb<DT, 2, 2, FUSED, false, false>(ncb);
+    return nta ? pick_ncb<DT, 2, 2, FUSED, false, EW, true>(ncb) : pick_ncb<DT, 2, 2, FUSED, false, EW, false>(ncb);
 }
 // transposed boundary: resident K with blocks of 64 or 32 tokens, streamed K always with 64
-template <int DT, bool FUSED>
+template <int DT, bool FUSED, bool EW>
 const void* pick_mode_t(int mode, int ms, int ncb, bool nta) {
-    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, true>(ncb) : pick_ncb<DT, 1, 0, FUSED, true>(ncb);
+    if (mode == 0) return ms == 2 ? pick_ncb<DT, 2, 0, FUSED, true, EW>(ncb) : pick_ncb<DT, 1, 0, FUSED, true, EW>(ncb);
     if (ms != 2) return nullptr;
-    if (mode == 1) return nta ? pick_ncb<DT, 2, 1, FUSED, true, true>(ncb) : pick_ncb<DT, 2, 1, FUSED, true, false>(ncb);
+    if (mode == 1) return nta ? pick_ncb<DT, 2, 1, FUSED, true, EW, true>(ncb) : pick_ncb<DT, 2, 1, FUSED, true, EW, false>(ncb);
     if (mode == 3) {
-        if constexpr (!FUSED) return nta ? pick_ncb<DT, 2, 3, false, true, true>(ncb) : pick_ncb<DT, 2, 3, false, true, false>(ncb);
+        if constexpr (!FUSED) return nta ? pick_ncb<DT, 2, 3, false, true, EW, true>(ncb) : pick_ncb<DT, 2, 3, false, true, EW, false>(ncb);
         else return nullptr;
     }
-    return nta ? pick_ncb<DT, 2, 2, FUSED, true, true>(ncb) : pick_ncb<DT, 2, 2, FUSED, true, false>(ncb);
+    return nta ? pick_ncb<DT, 2, 2, FUSED, true, EW, true>(ncb) : pick_ncb<DT, 2, 2, FUSED, true, EW, false>(ncb);
 }
 template <int DT, bool FUSED>
 const void* pick_reduce(int ncb, bool transposed) {
@@ -1788,22 +1793,31 @@ const void* pick_reduce(int ncb, bool transposed) {
 #endif
 
 #ifdef TW_PART
-#define TW_TABLES(KW, DT, FUSED)                                            \
-    KW template const void* tw_parts::pick_mode<DT, FUSED>(int, int, int, bool);  \
-    KW template const void* tw_parts::pick_mode_t<DT, FUSED>(int, int, int, bool); \
-    KW template const void* tw_parts::pick_reduce<DT, FUSED>(int, bool);
+#define TW_TABLES_EW(KW, DT, FUSED, EW)                                          \
+    KW template const void* tw_parts::pick_mode<DT, FUSED, EW>(int, int, int, bool);  \
+    KW template const void* tw_parts::pick_mode_t<DT, FUSED, EW>(int, int, int, bool);
+#define TW_TABLES_REDUCE(KW, DT, FUSED) KW template const void* tw_parts::pick_reduce<DT, FUSED>(int, bool);
+#define TW_TABLES_ALL(KW, DT, FUSED) TW_TABLES_EW(KW, DT, FUSED, false) TW_TABLES_EW(KW, DT, FUSED, true) TW_TABLES_REDUCE(KW, DT, FUSED)
 #if TW_PART == 0
-TW_TABLES(extern, TW_F16, false) TW_TABLES(extern, TW_F16, true) TW_TABLES(extern, TW_BF16, false) TW_TABLES(extern, TW_BF16, true)
+TW_TABLES_ALL(extern, TW_F16, false) TW_TABLES_ALL(extern, TW_F16, true) TW_TABLES_ALL(extern, TW_BF16, false) TW_TABLES_ALL(extern, TW_BF16, true)
 #elif TW_PART == 1
-TW_TABLES(, TW_F16, false)
+TW_TABLES_EW(, TW_F16, false, false) TW_TABLES_REDUCE(, TW_F16, false)
 #elif TW_PART == 2
-TW_TABLES(, TW_F16, true)
+TW_TABLES_EW(, TW_F16, true, false) TW_TABLES_REDUCE(, TW_F16, true)
 #elif TW_PART == 3
-TW_TABLES(, TW_BF16, false)
+TW_TABLES_EW(, TW_BF16, false, false) TW_TABLES_REDUCE(, TW_BF16, false)
 #elif TW_PART == 4
-TW_TABLES(, TW_BF16, true)
+TW_TABLES_EW(, TW_BF16, true, false) TW_TABLES_REDUCE(, TW_BF16, true)
+#elif TW_PART == 5
+TW_TABLES_EW(, TW_F16, false, true)
+#elif TW_PART == 6
+TW_TABLES_EW(, TW_F16, true, true)
+#elif TW_PART == 7
+TW_TABLES_EW(, TW_BF16, false, true)
+#elif TW_PART == 8
+TW_TABLES_EW(, TW_BF16, true, true)
 #else
-#error "TW_PART is 0 (host code) or 1..4 (kernels)"
+#error "TW_PART is 0 (host code) or 1..8 (kernels)"
 #endif
 #endif
 
@@ -2186,17 +2200,25 @@ int make_plan(const TwHeader* h, int M, int n_cu, Plan& pl, bool transposed = fa
 }
 
 // the kernel for (dtype, mode, MS, NCB, fused epilogue): a host-side address for hipLaunchKernel and hipFuncSetAttribute
-const void* pick_kernel_t(int dt, int mode, int ms, int ncb, bool fused, bool nta) {
+template <bool EW>
+const void* pick_kernel_t_of(int dt, int mode, int ms, int ncb, bool fused, bool nta) {
     using namespace tw_parts;
-    if (fused) return dt == TW_F16 ? pick_mode_t<TW_F16, true>(mode, ms, ncb, nta) : pick_mode_t<TW_BF16, true>(mode, ms, ncb, nta);
-    return dt == TW_F16 ? pick_mode_t<TW_F16, false>(mode, ms, ncb, nta) : pick_mode_t<TW_BF16, false>(mode, ms, ncb, nta);
+    if (fused) return dt == TW_F16 ? pick_mode_t<TW_F16, true, EW>(mode, ms, ncb, nta) : pick_mode_t<TW_BF16, true, EW>(mode, ms, ncb, nta);
+    return dt == TW_F16 ? pick_mode_t<TW_F16, false, EW>(mode, ms, ncb, nta) : pick_mode_t<TW_BF16, false, EW>(mode, ms, ncb, nta);
 }
-const void* pick_kernel(int dt, int mode, int ms, int ncb, bool fused, bool nta) {
+template <bool EW>
+const void* pick_kernel_of(int dt, int mode, int ms, int ncb, bool fused, bool nta) {
     using namespace tw_parts;
-    if (fused) return dt == TW_F16 ? pick_mode<TW_F16, true>(mode, ms, ncb, nta) : pick_mode<TW_BF16, true>(mode, ms, ncb, nta);
-    return dt == TW_F16 ? pick_mode<TW_F16, false>(mode, ms, ncb, nta) : pick_mode<TW_BF16, false>(mode, ms, ncb, nta);
+    if (fused) return dt == TW_F16 ? pick_mode<TW_F16, true, EW>(mode, ms, ncb, nta) : pick_mode<TW_BF16, true, EW>(mode, ms, ncb, nta);
+    return dt == TW_F16 ? pick_mode<TW_F16, false, EW>(mode, ms, ncb, nta) : pick_mode<TW_BF16, false, EW>(mode, ms, ncb, nta);
 }
-
+// (ew: the blob carries an element-wise residual)
+const void* pick_kernel_t(int dt, int mode, int ms, int ncb, bool fused, bool nta, bool ew) {
+    return ew ? pick_kernel_t_of<true>(dt, mode, ms, ncb, fused, nta) : pick_kernel_t_of<false>(dt, mode, ms, ncb, fused, nta);
+}
+const void* pick_kernel(int dt, int mode, int ms, int ncb, bool fused, bool nta, bool ew) {
+    return ew ? pick_kernel_of<true>(dt, mode, ms, ncb, fused, nta) : pick_kernel_of<false>(dt, mode, ms, ncb, fused, nta);
+}
 const void* pick_reduce_kernel(int dt, int ncb, bool fused, bool transposed) {
     using namespace tw_parts;
     if (fused) return dt == TW_F16 ? pick_reduce<TW_F16, true>(ncb, transposed) : pick_reduce<TW_BF16, true>(ncb, transposed);
@@ -2223,7 +2245,7 @@ int device_cus(int dev) {
 }
 
 // The dynamic-LDS limit of a kernel is raised to the hardware maximum once per (device, kernel).
-constexpr int kMaxKernels = 256;
+constexpr int kMaxKernels = 512;
 std::atomic<unsigned> g_lds_set[kMaxDevices][kMaxKernels];
 
 int ensure_lds(int dev, int kernel_id, const void* fn) {
@@ -2383,7 +2405,7 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
     // streamed K: the activations carry the streaming hint only when one workgroup reads a row block's rows
     const bool nta = pl.mode == 0 || pl.n_seg == 1;
     const int kmode = split ? 3 : pl.mode;             // the kernel's MODE
-    const void* fn = pick_kernel(h->dtype, kmode, pl.ms, h->ncb, fused, nta);
+    const void* fn = pick_kernel(h->dtype, kmode, pl.ms, h->ncb, fused, nta, h->ew_nnz > 0);
     if (!fn) return TW_ERR_UNSUPPORTED;
     const void* fn_reduce = nullptr;
     if (split) {
@@ -2391,7 +2413,7 @@ extern "C" int tw_gemm_bias_act(const void* blob_host, const void* blob_dev, con
         if (!fn_reduce) return TW_ERR_UNSUPPORTED;
     }
     const int variant = kmode == 0 ? (pl.ms == 2 ? 0 : 1) : 2 * kmode + (nta ? 0 : 1);   // 0..7
-    const int kernel_id = (fused ? 60 : 0) + (h->dtype == TW_F16 ? 0 : 30) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
+    const int kernel_id = (h->ew_nnz > 0 ? 240 : 0) + (fused ? 60 : 0) + (h->dtype == TW_F16 ? 0 : 30) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, fn);
     if (rc) return rc;
 
@@ -2475,7 +2497,7 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
     const bool fused = fused_epilogue && !split;      // split K: the epilogue is the second kernel's
     const bool nta = pl.mode == 0 || pl.n_seg == 1;
     const int kmode = split ? 3 : pl.mode;             // the kernel's MODE
-    const void* fn = pick_kernel_t(h->dtype, kmode, pl.ms, h->ncb, fused, nta);
+    const void* fn = pick_kernel_t(h->dtype, kmode, pl.ms, h->ncb, fused, nta, h->ew_nnz > 0);
     if (!fn) return TW_ERR_UNSUPPORTED;
     const void* fn_reduce = nullptr;
     if (split) {
@@ -2483,7 +2505,7 @@ extern "C" int tw_gemm_t_bias_act(const void* blob_host, const void* blob_dev, c
         if (!fn_reduce) return TW_ERR_UNSUPPORTED;
     }
     const int variant = kmode == 0 ? (pl.ms == 2 ? 0 : 1) : 2 * kmode + (nta ? 0 : 1);   // 0..7
-    const int kernel_id = 120 + (fused ? 60 : 0) + (h->dtype == TW_F16 ? 0 : 30) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
+    const int kernel_id = (h->ew_nnz > 0 ? 240 : 0) + 120 + (fused ? 60 : 0) + (h->dtype == TW_F16 ? 0 : 30) + 3 * variant + (h->ncb == 4 ? 0 : h->ncb == 2 ? 1 : 2);
     rc = ensure_lds(dev, kernel_id, fn);
     if (rc) return rc;
 
