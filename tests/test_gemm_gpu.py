@@ -1073,13 +1073,14 @@ def test_split_k_small_batches_of_the_ffn_down(tw, M):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("K", [300, 1700], ids=["k_resident", "k_streamed_ragged_chunk"])
+@pytest.mark.parametrize("K", [300, 1536, 1700], ids=["k_resident", "k_resident_no_lds_left", "k_streamed_ragged_chunk"])
 def test_tew_many_residual_only_columns_per_tile_bit_exact(tw, K):
     """Tiles whose spans hold more residual-only columns than a tile adds itself (16): the first 16 leave with the
     tile's stores (row-major: through the staging window; transposed: in place of the lines of zeros), the others
     in the pass of their own; with a residual inside the kept columns as well, K resident and streamed (five
     chunks, the last one ragged; the columns' sums then wait in LDS between chunks); several row blocks with a
-    ragged last one; integers, bit for bit, both boundaries and the fused epilogue."""
+    ragged last one; integers, bit for bit, both boundaries and the fused epilogue.  K = 1536 is the largest resident K:
+    its LDS copy of A leaves no room for the waves' areas for these columns, so all of them take the pass of their own."""
     spec = W.small_spec(f"xcols_many_{K}", M=205, K=K, N=300, G=64, dtype="f16", col_prune=0.45, keep=("upow", 0.1, 0.5),
                         a_dist="smallint", seed_offset=4242)
     w = W.generate(spec)
@@ -1098,6 +1099,8 @@ def test_tew_many_residual_only_columns_per_tile_bit_exact(tw, K):
     pl, plt = tw.tw_gemm_plan(wt.blob, spec.M), tw.tw_gemm_plan(wt.blob, spec.M, transposed=True)
     _say(f"{spec.name}: residual-only columns per tile {per_tile.tolist()}, plan {pl} / {plt}")
     assert (pl["mode"] == 0) == (K <= 1536) and pl["k_parts"] == 1
+    if K == 1536:
+        assert pl["lds_bytes"] + 8 * 16 * 64 * 2 > 160 * 1024      # no room for eight waves x 16 columns x 64 rows
     bias_i = rng.integers(-5, 6, size=spec.N).astype(np.float32)
     bias = tw.bits_to_tensor(W.f32_to_bits(bias_i, "f16"), "f16")
     A, At = _device_A(tw, w.A, "f16"), _device_At(tw, w.A, "f16")
