@@ -1115,6 +1115,50 @@ def test_tew_many_residual_only_columns_per_tile_bit_exact(tw, K):
     assert np.any(ref[:, pruned] != 0)
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_tew_random_shapes_bit_exact(tw, seed):
+    """Seeded random hybrids (shape, granularity, dtype, share of pruned columns, share of restored weights; every
+    third one with residual weights in ALL pruned columns), integer data: tw_unpack gives the union back, and both
+    boundaries with and without the fused epilogue equal the oracle bit for bit.  Cases whose results an output
+    element cannot hold exactly are skipped."""
+    rng = np.random.default_rng(1000 + seed)
+    checked = 0
+    for case in range(16):
+        G = int(rng.choice([32, 64, 128]))
+        K = int(rng.choice([40, 200, 520, 1000, 1536, 1544, 1704, 2400]))
+        N = int(rng.integers(G, 5 * G + 40))
+        M = int(rng.choice([1, 31, 64, 100, 200, 333, 700, 1500]))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        cp = float(rng.choice([0.0, 0.1, 0.3, 0.5]))
+        delta = float(rng.choice([0.005, 0.02, 0.05]))
+        spec = W.small_spec(f"tew_random_{seed}_{case}", M=M, K=K, N=N, G=G, dtype=dtype, col_prune=cp,
+                            keep=("upow", 0.05, 0.5), a_dist="smallint", seed_offset=60000 + 100 * seed + case)
+        w = W.generate(spec)
+        ew = tw.tw_restore_ew(w.B, w.mask, delta, dtype)
+        if case % 3 == 0:
+            for n in np.flatnonzero(~w.mask.any(axis=0)):
+                ew[rng.choice(K, size=int(rng.integers(1, 9)), replace=False), n] = 1
+        _say(f"TEW random {seed}/{case}: M={M} K={K} N={N} G={G} {dtype} col_prune={cp} delta={delta} residual {int(ew.sum())}")
+        wt = tw.TwWeight(tw.tw_pack_tew(w.B, w.mask, ew, G, dtype))
+        union = (w.mask | ew).astype(np.uint8)
+        Bu, mu = tw.tw_unpack(wt.blob)
+        assert np.array_equal(mu, union) and np.array_equal(Bu, tw_ref.masked_weight_bits(w.B, union))
+        bias_i = rng.integers(-3, 4, size=N).astype(np.float32)
+        ref = tw_ref.masked_gemm(w.A, w.B, union, dtype)
+        ref_r = tw_ref.bias_act(ref, bias_i.astype(np.float64), "relu")
+        if max(np.abs(ref).max(), np.abs(ref_r).max()) >= (2048 if dtype == "f16" else 256):
+            continue
+        A, At = _device_A(tw, w.A, dtype), _device_At(tw, w.A, dtype)
+        bias = tw.bits_to_tensor(W.f32_to_bits(bias_i, dtype), dtype)
+        C, Ct = tw.tw_gemm(wt, A), tw.tw_gemm_t(wt, At)
+        Cf, Cft = tw.tw_gemm_bias_act(wt, A, bias, "relu"), tw.tw_gemm_t_bias_act(wt, At, bias, "relu")
+        torch.cuda.synchronize()
+        assert np.array_equal(_to_f64(C), ref) and np.array_equal(_to_f64(Ct).T, ref), (seed, case)
+        assert np.array_equal(_to_f64(Cf), ref_r) and np.array_equal(_to_f64(Cft).T, ref_r), (seed, case)
+        checked += 1
+    assert checked >= 6
+
+
 def test_tew_residual_only_in_pruned_columns_bit_exact(tw):
     """A weight whose tile-wise pattern is EMPTY plus a residual (every column is of the kind that runs in the
     pass of its own), and one whose residual lies only in the pruned columns; integers, bit for bit, both boundaries
